@@ -1,0 +1,277 @@
+"""Count Sketch / Sketched-SGD reference ("oracle") -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+
+Plain, slow, single-threaded CPU code in fp64 that computes what the data-parallel
+hot path of Sketched-SGD computes, step by step, in the paper's order and notation:
+
+    Alg. 4 (App. C)   init / update / estimate of a Count Sketch
+    Sec. 3, App. C    mergeability: S(g1) + S(g2) = S(g1 + g2)
+    Alg. 3 (Sec. 5.1) worker sketches -> (1/W) sum -> recover top-k -> second round of
+                      exact values; momentum u <- m u + g and error accumulation v <- v + u,
+                      here held as their sketches (linear images), see SketchSpaceState
+    Sec. 5.2          "query every coordinate, then choose the largest"
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import this module.
+It imports nothing from the HIP package and the HIP package imports nothing from here.
+The inner loops live in cs_oracle.c (compiled with gcc); everything that has a textbook
+routine (sort, sum, fancy indexing) is written with numpy.
+
+Every function here is pinned by tests/test_oracle_pins.py to something other than
+itself (dense-matrix product on tiny inputs, linearity, closed-form row variance, AMS
+special case, planted-sparse recovery, numpy's stable argsort, a dense-state twin of the
+sketch-space state).  Nothing in this file is "parity unpinned"; the one free choice
+(the value fed back in sketch space, SketchSpaceState.feedback) is a documented reading,
+pinned internally by the dense-state twin.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "cs_oracle.c")
+_LIB = os.path.join(_HERE, "libcs_oracle.so")
+
+P61 = (1 << 61) - 1
+MAX_R = 64
+
+
+def build(force: bool = False) -> str:
+    """Compile cs_oracle.c with gcc into libcs_oracle.so (next to this file)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-Wall", "-Wextra", "-shared", "-fPIC", "-o", _LIB, _SRC]
+        )
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+    return _lib
+
+
+def _p(arr, ctype):
+    return arr.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+def splitmix64(seed: int, n: int) -> np.ndarray:
+    out = np.zeros(n, dtype=np.uint64)
+    _load().cso_splitmix64(ctypes.c_uint64(seed), ctypes.c_int(n), _p(out, ctypes.c_uint64))
+    return out
+
+
+class SketchOracle:
+    """Count Sketch with r rows and c columns (Alg. 4), fp64 counters, 0-based indices."""
+
+    def __init__(self, r: int, c: int, seed: int):
+        if not (1 <= r <= MAX_R) or r % 2 == 0:
+            raise ValueError("r must be odd and in [1, 64] (the median of Alg. 4 needs a middle)")
+        if not (1 <= c < (1 << 32)):
+            raise ValueError("c must be in [1, 2^32)")
+        self.r, self.c, self.seed = int(r), int(c), int(seed)
+        self.a = np.zeros(r, dtype=np.uint64)
+        self.b = np.zeros(r, dtype=np.uint64)
+        self.as_ = np.zeros(r, dtype=np.uint64)
+        self.bs = np.zeros(r, dtype=np.uint64)
+        _load().cso_derive_params(
+            ctypes.c_uint64(self.seed), ctypes.c_int(r),
+            _p(self.a, ctypes.c_uint64), _p(self.b, ctypes.c_uint64),
+            _p(self.as_, ctypes.c_uint64), _p(self.bs, ctypes.c_uint64))
+
+    # -- plumbing ---------------------------------------------------------
+    def _hp(self):
+        return (ctypes.c_int(self.r), ctypes.c_uint32(self.c),
+                _p(self.a, ctypes.c_uint64), _p(self.b, ctypes.c_uint64),
+                _p(self.as_, ctypes.c_uint64), _p(self.bs, ctypes.c_uint64))
+
+    def zeros(self) -> np.ndarray:
+        """Alg. 4 init: the r x c table of counters, all zero."""
+        return np.zeros((self.r, self.c), dtype=np.float64)
+
+    def _check_table(self, T):
+        assert T.dtype == np.float64 and T.shape == (self.r, self.c) and T.flags.c_contiguous
+
+    # -- hashes -----------------------------------------------------------
+    def hash(self, idx):
+        """bucket[j, t] = h_j(idx[t]) (uint32), sign[j, t] = s_j(idx[t]) (int8, +1/-1)."""
+        idx = np.ascontiguousarray(idx, dtype=np.int64)
+        n = idx.size
+        bucket = np.zeros((self.r, n), dtype=np.uint32)
+        sign = np.zeros((self.r, n), dtype=np.int8)
+        _load().cso_hash(*self._hp(), _p(idx, ctypes.c_int64), ctypes.c_int64(n),
+                         _p(bucket, ctypes.c_uint32), _p(sign, ctypes.c_int8))
+        return bucket, sign
+
+    # -- update -----------------------------------------------------------
+    def accumulate(self, T, g, i0: int = 0, scale: float = 1.0):
+        """T[j, h_j(i0+t)] += scale * s_j(i0+t) * g[t] for every t, j (Alg. 4 update)."""
+        self._check_table(T)
+        g = np.ascontiguousarray(g)
+        if g.dtype == np.float32:
+            fn, ct = _load().cso_accumulate_f32, ctypes.c_float
+        elif g.dtype == np.float64:
+            fn, ct = _load().cso_accumulate_f64, ctypes.c_double
+        else:
+            raise TypeError("g must be float32 or float64")
+        fn(*self._hp(), _p(T, ctypes.c_double), _p(g, ct), ctypes.c_int64(g.size),
+           ctypes.c_int64(i0), ctypes.c_double(scale))
+        return T
+
+    def accumulate_sparse(self, T, idx, val, scale: float = 1.0):
+        self._check_table(T)
+        idx = np.ascontiguousarray(idx, dtype=np.int64)
+        val = np.ascontiguousarray(val, dtype=np.float64)
+        assert idx.size == val.size
+        _load().cso_accumulate_sparse(*self._hp(), _p(T, ctypes.c_double),
+                                      _p(idx, ctypes.c_int64), _p(val, ctypes.c_double),
+                                      ctypes.c_int64(idx.size), ctypes.c_double(scale))
+        return T
+
+    def sketch(self, g, i0: int = 0, scale: float = 1.0):
+        return self.accumulate(self.zeros(), g, i0, scale)
+
+    # -- query ------------------------------------------------------------
+    def estimate(self, T, d: int, i0: int = 0) -> np.ndarray:
+        """est[t] = median_j s_j(i0+t) * T[j, h_j(i0+t)] for t in [0, d) (Alg. 4 estimate)."""
+        self._check_table(T)
+        est = np.zeros(d, dtype=np.float64)
+        _load().cso_estimate(*self._hp(), _p(T, ctypes.c_double), ctypes.c_int64(d),
+                             ctypes.c_int64(i0), _p(est, ctypes.c_double))
+        return est
+
+    def estimate_sparse(self, T, idx) -> np.ndarray:
+        self._check_table(T)
+        idx = np.ascontiguousarray(idx, dtype=np.int64)
+        out = np.zeros(idx.size, dtype=np.float64)
+        _load().cso_estimate_sparse(*self._hp(), _p(T, ctypes.c_double),
+                                    _p(idx, ctypes.c_int64), ctypes.c_int64(idx.size),
+                                    _p(out, ctypes.c_double))
+        return out
+
+    def row_estimates(self, T, d: int, i0: int = 0) -> np.ndarray:
+        """rows[j, t] = s_j(i0+t) * T[j, h_j(i0+t)]: the r values whose median is the estimate."""
+        self._check_table(T)
+        rows = np.zeros((self.r, d), dtype=np.float64)
+        _load().cso_row_estimates(*self._hp(), _p(T, ctypes.c_double), ctypes.c_int64(d),
+                                  ctypes.c_int64(i0), _p(rows, ctypes.c_double))
+        return rows
+
+
+# ---------------------------------------------------------------------------
+# parameter-server side: merge, selection, second round
+# ---------------------------------------------------------------------------
+def merge(tables, alpha: float = 1.0, beta: float = 0.0, dst=None) -> np.ndarray:
+    """beta * dst + alpha * sum_w tables[w]  (Alg. 3: S_t = (1/W) sum_i S_t^i, alpha = 1/W)."""
+    acc = np.zeros_like(np.asarray(tables[0], dtype=np.float64))
+    for T in tables:
+        acc = acc + np.asarray(T, dtype=np.float64)
+    out = alpha * acc
+    if dst is not None and beta != 0.0:
+        out = out + beta * np.asarray(dst, dtype=np.float64)
+    return out
+
+
+def topk(est, k: int) -> np.ndarray:
+    """Indices of the k entries of largest magnitude (Sec. 4: "largest gradient elements by
+    magnitude"; Sec. 5.2), equal magnitudes resolved towards the lower index, returned in
+    ascending index order.  Written as the definition: stable sort by descending |est|."""
+    mag = np.abs(np.asarray(est, dtype=np.float64))
+    order = np.argsort(-mag, kind="stable")
+    return np.sort(order[:k]).astype(np.int64)
+
+
+def topk_threshold(est, k: int) -> np.ndarray:
+    """Same result as topk() without the full sort (for d ~ 1e8): theta = k-th largest
+    magnitude; everything above theta, then the lowest-index entries equal to theta."""
+    mag = np.abs(np.asarray(est, dtype=np.float64))
+    d = mag.size
+    theta = np.partition(mag, d - k)[d - k]
+    above = np.flatnonzero(mag > theta)
+    ties = np.flatnonzero(mag == theta)[: k - above.size]
+    return np.sort(np.concatenate([above, ties])).astype(np.int64)
+
+
+def gather_exact(vecs, idx, alpha: float = 1.0) -> np.ndarray:
+    """Second round (Alg. 1 step 5, Alg. 3 "query all workers for exact values ... store the
+    sum"): alpha * sum_w vecs[w][idx]."""
+    idx = np.asarray(idx, dtype=np.int64)
+    acc = np.zeros(idx.size, dtype=np.float64)
+    for v in vecs:
+        acc = acc + np.asarray(v)[idx].astype(np.float64)
+    return alpha * acc
+
+
+def compression_factor(d: int, sketch_cells: int, P: int, k: int) -> float:
+    """Sec. 5.3: 2d / (|S| + Pk + k)."""
+    return 2.0 * d / (sketch_cells + P * k + k)
+
+
+# ---------------------------------------------------------------------------
+# momentum and error feedback (Alg. 3), two forms
+# ---------------------------------------------------------------------------
+class DenseState:
+    """Alg. 3 with the W workers' u^i, v^i replaced by their means (every update of u, v is
+    linear and identical on all workers, so the mean obeys the same recursion):
+        u <- m u + gbar ;  v <- v + u ;  select idx from the sketch of v ;
+        then subtract the fed-back values at idx.
+    Exists to pin SketchSpaceState through S(v) == S_v, S(u) == S_u (linearity)."""
+
+    def __init__(self, d: int, rho: float):
+        self.u = np.zeros(d, dtype=np.float64)
+        self.v = np.zeros(d, dtype=np.float64)
+        self.rho = float(rho)
+
+    def momentum(self, gbar):
+        self.u = self.rho * self.u + np.asarray(gbar, dtype=np.float64)
+        self.v = self.v + self.u
+
+    def feedback(self, idx, delta_v, delta_u):
+        self.v[idx] -= delta_v
+        self.u[idx] -= delta_u
+
+
+class SketchSpaceState:
+    """Momentum and error accumulation of Alg. 3 kept as sketches S_u = S(u), S_v = S(v).
+
+    Reading (the paper keeps u, v dense on each worker; the benchmark definition asks for
+    them "in sketch space"): by linearity of S,
+        S_u <- rho S_u + S_t          (image of  u <- m u + g)
+        S_v <- S_v + S_u              (image of  v <- v + u)
+        est = estimate(S_v) ; idx = top-k |est|
+        Delta = est[idx]      ; S_v <- S_v - S(Delta at idx)     (error feedback: what was
+                                                                  applied leaves the residual)
+        uhat = estimate(S_u, idx) ; S_u <- S_u - S(uhat at idx)  (momentum factor masking:
+                                                                  "u, v <- 0" on updated coords,
+                                                                  as far as a sketch can say)
+    rho is the fp32 value of the momentum constant, as the device receives it."""
+
+    def __init__(self, sk: SketchOracle, rho: float):
+        self.sk = sk
+        self.rho = float(np.float32(rho))
+        self.S_u = sk.zeros()
+        self.S_v = sk.zeros()
+
+    def momentum(self, S_t):
+        self.S_u = self.rho * self.S_u + S_t
+        self.S_v = self.S_v + self.S_u
+
+    def select(self, d: int, k: int, big: bool = False):
+        est = self.sk.estimate(self.S_v, d)
+        idx = topk_threshold(est, k) if big else topk(est, k)
+        return est, idx
+
+    def feedback(self, idx):
+        """Returns (Delta, uhat) and removes their sketches from S_v, S_u."""
+        delta = self.sk.estimate_sparse(self.S_v, idx)
+        uhat = self.sk.estimate_sparse(self.S_u, idx)
+        self.sk.accumulate_sparse(self.S_v, idx, delta, scale=-1.0)
+        self.sk.accumulate_sparse(self.S_u, idx, uhat, scale=-1.0)
+        return delta, uhat
