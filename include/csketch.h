@@ -1,0 +1,186 @@
+/*
+ * csketch.h -- C ABI of the Count Sketch hot path of Sketched-SGD for AMD MI355X (gfx950).
+ *
+ * What the library computes (paper = "Communication-efficient Distributed SGD with
+ * Sketching", arXiv 1903.04488):
+ *   - Count Sketch update / estimate                      App. C, Alg. 4
+ *   - merge of workers' sketches, S = (1/W) sum_i S^i     Sec. 3; Alg. 2 "Aggregate sketches";
+ *                                                         Alg. 3 "Aggregate sketches"
+ *   - recovery of the largest coordinates by querying     Sec. 5.2; Alg. 3 "Recover the top-Pk
+ *     every coordinate and keeping the k largest          coordinates"
+ *   - second round: exact values of the chosen            Sec. 4; Alg. 1 "second round of
+ *     coordinates, summed over workers                    communication"; Alg. 3 "Query all workers"
+ *   - momentum and error accumulation (Alg. 3 "Momentum", "Error accumulation", and the
+ *     zeroing of u, v on updated coordinates) held as sketches, which is possible because
+ *     the sketch is linear (Sec. 3).
+ *
+ * Conventions
+ *   - Every function returns CS_OK (0) or a negative cs_status; none throws, exits or prints.
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
+ *     ordinary host memory.  The library allocates no device memory and keeps no state:
+ *     cs_params is a plain struct, immutable after cs_params_init, so calls are re-entrant.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Kernels are
+ *     enqueued on it and the call returns without synchronising.  Launch failures are
+ *     reported as CS_EHIP; faults inside a kernel surface at the caller's next synchronise.
+ *   - A sketch table is float[r][c], row-major, contiguous.  Coordinates are 0-based int64.
+ *   - Device data are not validated: NaN / Inf propagate.  In cs_heavy_hitters_topk a NaN
+ *     magnitude orders above every finite value (comparison is on the bit pattern).
+ *   - fp32 atomic adds make sketch cells depend on summation order in the last bits; every
+ *     other output is a deterministic function of its inputs.
+ *
+ * Hash family (Alg. 4 "init sign hashes and bucket hashes"; the family itself is fixed by
+ * the benchmark definition): with p = 2^61 - 1,
+ *     h_j(i) = ((a_j  * i + b_j ) mod p) mod c                       bucket of row j
+ *     s_j(i) = +1 if ((a'_j * i + b'_j) mod p) is even, -1 if odd     sign of row j
+ * The 4r constants are drawn, in the order a_0, b_0, a'_0, b'_0, a_1, ..., from the
+ * SplitMix64 generator started at `seed`:  a = 1 + z mod (p - 1),  b = z mod p.
+ */
+#ifndef CSKETCH_H
+#define CSKETCH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CS_MAX_R 16          /* covers the paper's largest sketch (15 rows, Table 1) */
+#define CS_MAX_LANES 64      /* wavefront width; size of the per-row lane-offset tables */
+
+typedef enum cs_status {
+    CS_OK = 0,
+    CS_EINVAL = -1,       /* bad argument (null pointer, size out of range, even r, ...) */
+    CS_EWORKSPACE = -2,   /* workspace smaller than cs_topk_workspace_bytes() says */
+    CS_EHIP = -3          /* a HIP runtime call or kernel launch failed */
+} cs_status;
+
+/* Traversal of one row (derived from a_j and c; does not change any result).  Because the
+ * bucket hash is affine mod p, coordinates i, i + D, i + 2D, ... fall into buckets that
+ * advance by a constant (a*D mod p) mod c, plus one for every wrap around p.  D is chosen
+ * so that this advance is at most a few buckets: a group of lanes that takes coordinates D
+ * apart then touches neighbouring cells of the row, and its atomic adds / gathers share
+ * cache lines. */
+typedef struct cs_row_plan {
+    uint64_t D;           /* lane stride in coordinates, >= 1 */
+    uint64_t AD;          /* (a_j  * D) mod p */
+    uint64_t ADs;         /* (a'_j * D) mod p */
+    int32_t  step;        /* bucket advance per lane: (AD mod c) folded into (-c/2, c/2] */
+    int32_t  reserved;
+} cs_row_plan;
+
+typedef struct cs_params {
+    uint32_t r;                 /* rows, odd, 1..CS_MAX_R */
+    uint32_t c;                 /* columns, 1..2^31 */
+    uint32_t c_pow2;            /* 1 if c is a power of two (fast bucket extraction) */
+    uint32_t lanes;             /* lanes per traversal group (16, 32 or 64) */
+    uint64_t seed;
+    uint64_t a[CS_MAX_R], b[CS_MAX_R];     /* bucket hashes */
+    uint64_t as[CS_MAX_R], bs[CS_MAX_R];   /* sign hashes */
+    cs_row_plan plan[CS_MAX_R];
+} cs_params;
+
+/* Alg. 4 init: fills *p for an r x c sketch from `seed` (host, no GPU needed).
+ * `d_hint` is the vector length the sketch will mostly be used with (0 = unknown); it only
+ * steers the traversal plan.  CS_EINVAL: p null, r even or outside 1..CS_MAX_R, c == 0,
+ * c > 2^31 or r * c >= 2^32 (a 16 GiB table). */
+int cs_params_init(cs_params* p, uint32_t r, uint32_t c, uint64_t seed, int64_t d_hint);
+
+/* Parity hook: bucket[j*n + t] = h_j(idx[t]) and sign[j*n + t] = s_j(idx[t]) (+1 / -1),
+ * computed on the device with the same code path the kernels use.
+ * idx, bucket, sign: device.  0 <= idx[t] < 2^61.  n >= 0. */
+int cs_hash_debug(const cs_params* p, const int64_t* idx, int64_t n,
+                  uint32_t* bucket, int8_t* sign, void* stream);
+
+/* Same for the contiguous range i0 .. i0+n-1, computed through the incremental hash state
+ * of the streaming kernels (the traversal plan's order), so that path is bit-checked too. */
+int cs_hash_debug_range(const cs_params* p, int64_t i0, int64_t n,
+                        uint32_t* bucket, int8_t* sign, void* stream);
+
+/* S = 0.  S: device float[r][c]. */
+int cs_sketch_zero(const cs_params* p, float* S, void* stream);
+
+/* Alg. 4 update applied to a dense vector (Alg. 3 "Compute sketch S^i of v^i"):
+ *     S[j][h_j(i0 + t)] += scale * s_j(i0 + t) * g[t]      for t in [0, d), j in [0, r)
+ * S: device float[r][c], accumulated into (not cleared).  g: device float[d].
+ * i0 = global index of g[0] (>= 0, i0 + d <= 2^61).  d >= 0 (0 is a no-op). */
+int cs_sketch_accumulate(const cs_params* p, float* S, const float* g, int64_t d,
+                         int64_t i0, float scale, void* stream);
+
+/* The same update for W workers at once, worker w's vector into worker w's table; hashes
+ * are evaluated once per coordinate and shared by all workers (they use the same seed).
+ * S_w, g_w: HOST arrays of W device pointers (float[r][c] and float[d] each). W >= 1. */
+int cs_sketch_accumulate_batch(const cs_params* p, float* const* S_w, const float* const* g_w,
+                               int32_t W, int64_t d, int64_t i0, float scale, void* stream);
+
+/* Alg. 4 update for a list of (index, value) pairs:
+ *     S[j][h_j(idx[t])] += scale * s_j(idx[t]) * val[t]
+ * idx: device int64[n] (0 <= idx[t] < 2^61, repeats allowed and summed), val: device float[n]. */
+int cs_sketch_accumulate_sparse(const cs_params* p, float* S, const int64_t* idx,
+                                const float* val, int64_t n, float scale, void* stream);
+
+/* Mergeability (Sec. 3; Alg. 3 "S_t = (1/W) sum_i S_t^i"):
+ *     dst = beta * dst + alpha * sum_{w<W} src[w]
+ * dst: device float[r][c]; with beta == 0 it is not read.  src: HOST array of W device
+ * pointers; dst may not alias any src[w] unless W == 1.  The sum over w is taken in
+ * ascending w in fp32. */
+int cs_sketch_merge(const cs_params* p, float* dst, float beta, const float* const* src,
+                    int32_t W, float alpha, void* stream);
+
+/* y = a * x + b * y over a whole table (device float[r][c] each; x may equal y). */
+int cs_sketch_axpby(const cs_params* p, float* y, float a, const float* x, float b,
+                    void* stream);
+
+/* Momentum and error accumulation of Alg. 3 in sketch space, one pass:
+ *     S_u = rho * S_u + S_t ;   S_v = S_v + S_u
+ * (the images under the sketch of  u <- m u + g  and  v <- v + u). All device float[r][c]. */
+int cs_sketch_momentum(const cs_params* p, float* S_u, float* S_v, const float* S_t,
+                       float rho, void* stream);
+
+/* Alg. 4 estimate of every coordinate of a range (Sec. 5.2 "query the sketch for every
+ * gradient coordinate"):
+ *     est[t] = median_{j<r} s_j(i0 + t) * S[j][h_j(i0 + t)]       t in [0, d)
+ * S: device float[r][c]; est: device float[d].
+ * rows_ws: device scratch of cs_estimate_workspace_bytes(p, d) bytes (may be NULL when that
+ * size is 0).  */
+int cs_estimate_workspace_bytes(const cs_params* p, int64_t d, size_t* bytes);
+int cs_sketch_estimate(const cs_params* p, const float* S, int64_t d, int64_t i0,
+                       float* est, void* rows_ws, size_t ws_bytes, void* stream);
+
+/* Alg. 4 estimate of listed coordinates: out[t] = median_j s_j(idx[t]) * S[j][h_j(idx[t])].
+ * idx: device int64[n]; out: device float[n]. */
+int cs_sketch_estimate_sparse(const cs_params* p, const float* S, const int64_t* idx,
+                              int64_t n, float* out, void* stream);
+
+/* "...and then choose the largest elements" (Sec. 5.2): the k indices t in [0, d) with the
+ * largest |est[t]|; equal magnitudes are resolved towards the lower index; the result is in
+ * ascending index order.  idx_out: device int64[k] (index t, NOT offset by any i0);
+ * val_out: device float[k], val_out[n] = est[idx_out[n]] (may be NULL).
+ * workspace: device, at least cs_topk_workspace_bytes(d, k) bytes, contents irrelevant on
+ * entry.  1 <= k <= d. */
+int cs_topk_workspace_bytes(int64_t d, int64_t k, size_t* bytes);
+int cs_heavy_hitters_topk(const float* est, int64_t d, int64_t k,
+                          int64_t* idx_out, float* val_out,
+                          void* workspace, size_t ws_bytes, void* stream);
+
+/* Second round (Sec. 4; Alg. 3 "Query all workers for exact values ...; store the sum"):
+ *     out[n] = alpha * sum_{w<W} vec[w][idx[n]]          (sum in ascending w, fp32)
+ * vec: HOST array of W device pointers to float vectors; idx: device int64[k] with every
+ * idx[n] inside the vectors; out: device float[k]. */
+int cs_gather_exact(const float* const* vec, int32_t W, const int64_t* idx, int64_t k,
+                    float alpha, float* out, void* stream);
+
+/* Error feedback / momentum masking in sketch space (Alg. 2 "Error accumulation",
+ * Alg. 3 "u, v <- 0 for all updated coordinates", as far as a sketch can express them):
+ *     val[n] = estimate(S, idx[n])   for all n, from the table as it is on entry, then
+ *     S     -= sketch of the k-sparse vector (idx, val)
+ * S: device float[r][c]; idx: device int64[k], distinct; val: device float[k] (output). */
+int cs_sketch_feedback(const cs_params* p, float* S, const int64_t* idx, int64_t k,
+                       float* val, void* stream);
+
+const char* cs_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CSKETCH_H */

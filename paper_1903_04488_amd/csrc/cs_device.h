@@ -1,0 +1,92 @@
+// Device-side arithmetic shared by the kernels: hashing modulo the Mersenne prime
+// p = 2^61 - 1 kept in registers, and a few wavefront helpers.  gfx950 only.
+//
+// Hash family (Alg. 4 "init sign hashes and bucket hashes" of the paper's App. C):
+//     h_j(i) = ((a_j * i + b_j) mod p) mod c,     s_j(i) = +1 / -1 by the parity of
+//     ((a'_j * i + b'_j) mod p).
+// A hash value x in [0, p) is carried as y = x + 1 in [1, p].  In that form "add a constant
+// A in [0, p) modulo p" needs no comparison: t = y + A < 2^62, and x + A >= p exactly when
+// bit 61 of t is set, in which case subtracting p = 2^61 - 1 is "clear bit 61, add 1":
+//     y' = (t & p) + (t >> 61).
+// The streaming kernels use this to step a thread's hash state from coordinate i to i + D
+// with two 64-bit adds, a shift and a mask instead of a 61 x 61 bit multiplication; the
+// results are bit-identical to the definition because the identity holds over the integers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "csketch.h"
+
+namespace cs {
+
+constexpr uint64_t kP61 = (1ull << 61) - 1;
+constexpr int kBlock = 256;                 // threads per workgroup (4 wavefronts)
+
+// s < 2^63  ->  s mod p in [0, p)
+__host__ __device__ __forceinline__ uint64_t reduce_p(uint64_t s) {
+    s = (s & kP61) + (s >> 61);             // <= p + 3
+    s = (s & kP61) + (s >> 61);             // <= p
+    return s == kP61 ? 0 : s;
+}
+
+__device__ __forceinline__ uint64_t mulhi64(uint64_t a, uint64_t b) { return __umul64hi(a, b); }
+
+// (a * i) mod p for a, i < 2^61.  a*i = hi * 2^64 + lo with 2^64 = 8 (mod p), 2^61 = 1 (mod p).
+__device__ __forceinline__ uint64_t mulmod_p(uint64_t a, uint64_t i) {
+    const uint64_t lo = a * i;
+    const uint64_t hi = mulhi64(a, i);                    // < 2^58
+    return reduce_p((hi << 3) + (lo >> 61) + (lo & kP61)); // < 2^61 + 8 + 2^61
+}
+
+// y-form state of  (a * i + b) mod p
+__device__ __forceinline__ uint64_t hash_state(uint64_t a, uint64_t b, uint64_t i) {
+    return reduce_p(mulmod_p(a, i) + b) + 1;
+}
+
+// state of coordinate i  ->  state of coordinate i + D, where A = (a * D) mod p
+__device__ __forceinline__ uint64_t hash_advance(uint64_t y, uint64_t A) {
+    const uint64_t t = y + A;
+    return (t & kP61) + (t >> 61);
+}
+
+template <bool POW2>
+__device__ __forceinline__ uint32_t bucket_of(uint64_t y, uint32_t c) {
+    if (POW2) return (static_cast<uint32_t>(y) - 1u) & (c - 1u);
+    return static_cast<uint32_t>((y - 1) % c);
+}
+
+// 0x80000000 when s = -1 (x odd, i.e. y even), 0 when s = +1: XOR it into a float's bits.
+__device__ __forceinline__ uint32_t sign_flip_of(uint64_t y) {
+    return (~static_cast<uint32_t>(y)) << 31;
+}
+
+__device__ __forceinline__ float apply_sign(float v, uint32_t flip) {
+    return __uint_as_float(__float_as_uint(v) ^ flip);
+}
+
+// fp32 add into global memory, result not needed: one hardware global_atomic_add_f32.
+__device__ __forceinline__ void atomic_add_noret(float* addr, float v) {
+    __hip_atomic_fetch_add(addr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// median of an odd number R of floats held in registers (compile-time R): odd-even
+// transposition sort, fully unrolled, then the middle element.
+template <int R>
+__device__ __forceinline__ float median_odd(float (&v)[R]) {
+    if (R == 1) return v[0];
+    if (R == 3) return fmaxf(fminf(v[0], v[1]), fminf(fmaxf(v[0], v[1]), v[2]));
+#pragma unroll
+    for (int pass = 0; pass < R; ++pass) {
+#pragma unroll
+        for (int x = pass & 1; x + 1 < R; x += 2) {
+            const float lo = fminf(v[x], v[x + 1]);
+            const float hi = fmaxf(v[x], v[x + 1]);
+            v[x] = lo;
+            v[x + 1] = hi;
+        }
+    }
+    return v[R / 2];
+}
+
+}  // namespace cs

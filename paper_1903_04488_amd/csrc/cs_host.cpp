@@ -1,0 +1,99 @@
+// Host-only part of the library: Alg. 4 "init" (drawing the hash constants from the seed),
+// the per-row traversal plan, and status strings.  No GPU is touched here.
+#include <stdint.h>
+#include <string.h>
+
+#include "csketch.h"
+
+namespace {
+
+constexpr uint64_t kP61 = (1ull << 61) - 1;
+typedef unsigned __int128 u128;
+
+// SplitMix64 (Steele, Lea, Flood 2014): the generator that the hash constants are drawn from.
+uint64_t splitmix64(uint64_t* s) {
+    uint64_t z = (*s += 0x9E3779B97F4A7C15ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+uint64_t mulmod(uint64_t a, uint64_t b) { return (uint64_t)(((u128)a * b) % kP61); }
+
+// Lane stride for one row.
+//
+// Along coordinates i, i + D, i + 2D, ... the hash value moves by AD = a*D mod p each time,
+// and the bucket (value mod c, c | 2^61 so p = -1 mod c) by (AD mod c) plus 1 whenever the
+// value wraps past p: on average by  sigma(D) = (AD mod c) + AD / p  buckets, read as a
+// signed number in (-c/2, c/2].  We want the smallest D whose |sigma| is at most
+// `max_adv` buckets, so that `lanes` lanes taking coordinates D apart touch a contiguous
+// stretch of about lanes * |sigma| cells.  D is capped by the vector length: a group of
+// lanes spans lanes * D coordinates.  A brute-force scan over D is cheap (one 64-bit add
+// per candidate) and runs once per sketch.
+void plan_row(cs_row_plan* rp, uint64_t a, uint64_t as, uint32_t c, bool pow2,
+              uint64_t d_cap, double max_adv) {
+    rp->D = 1;
+    if (pow2 && c >= 64 && d_cap > 1) {
+        uint64_t x = 0;                      // (a * D) mod p
+        const double inv_p = 1.0 / (double)kP61;
+        for (uint64_t D = 1; D <= d_cap; ++D) {
+            x += a;
+            if (x >= kP61) x -= kP61;
+            double adv = (double)(x & (c - 1)) + (double)x * inv_p;   // [0, c + 1)
+            if (adv > 0.5 * c) adv -= (double)c;
+            if (adv < 0) adv = -adv;
+            if (adv <= max_adv) { rp->D = D; break; }
+        }
+    }
+    rp->AD = mulmod(a, rp->D);
+    rp->ADs = mulmod(as, rp->D);
+    int64_t step = (int64_t)(rp->AD % c);
+    if (step > (int64_t)(c / 2)) step -= (int64_t)c;
+    rp->step = (int32_t)step;
+    rp->reserved = 0;
+}
+
+}  // namespace
+
+extern "C" int cs_params_init(cs_params* p, uint32_t r, uint32_t c, uint64_t seed,
+                              int64_t d_hint) {
+    if (!p) return CS_EINVAL;
+    if (r == 0 || r > CS_MAX_R || (r & 1u) == 0) return CS_EINVAL;
+    if (c == 0 || c > (1u << 31)) return CS_EINVAL;
+    if ((uint64_t)r * c > 0xffffffffull) return CS_EINVAL;   // cell indices are 32-bit
+    if (d_hint < 0) return CS_EINVAL;
+    memset(p, 0, sizeof(*p));
+    p->r = r;
+    p->c = c;
+    p->c_pow2 = (c & (c - 1)) == 0 ? 1u : 0u;
+    p->seed = seed;
+    uint64_t st = seed;
+    for (uint32_t j = 0; j < r; ++j) {
+        p->a[j] = 1 + splitmix64(&st) % (kP61 - 1);
+        p->b[j] = splitmix64(&st) % kP61;
+        p->as[j] = 1 + splitmix64(&st) % (kP61 - 1);
+        p->bs[j] = splitmix64(&st) % kP61;
+    }
+    // Traversal plan.  A group of `lanes` lanes covers lanes * D coordinates, so D is kept
+    // below d / lanes (with d unknown, below c: Dirichlet's bound guarantees |sigma| <= 1 for
+    // some D <= c).
+    p->lanes = 64;
+    uint64_t d_cap = c;
+    if (d_hint > 0) {
+        uint64_t lim = (uint64_t)d_hint / p->lanes;
+        if (lim < d_cap) d_cap = lim;
+    }
+    for (uint32_t j = 0; j < r; ++j)
+        plan_row(&p->plan[j], p->a[j], p->as[j], c, p->c_pow2 != 0, d_cap, 1.0);
+    return CS_OK;
+}
+
+extern "C" const char* cs_status_string(int status) {
+    switch (status) {
+        case CS_OK: return "ok";
+        case CS_EINVAL: return "invalid argument";
+        case CS_EWORKSPACE: return "workspace too small";
+        case CS_EHIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}

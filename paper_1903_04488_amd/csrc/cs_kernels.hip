@@ -1,0 +1,468 @@
+// Kernels and C ABI of the Count Sketch hot path (gfx950).  See include/csketch.h for what
+// every entry point computes and which passage of the paper defines it.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cs_device.h"
+#include "csketch.h"
+
+namespace cs {
+
+// ---------------------------------------------------------------------------------------
+// launch helpers
+// ---------------------------------------------------------------------------------------
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP; }
+
+inline bool params_ok(const cs_params* p) {
+    return p && p->r >= 1 && p->r <= CS_MAX_R && (p->r & 1u) && p->c >= 1 && p->c <= (1u << 31);
+}
+
+// number of workgroups for a grid-stride kernel over n items: enough to fill 256 CUs a few
+// times over, never more than the items need.
+inline unsigned grid_for(int64_t n, int per_block = kBlock, int max_blocks = 256 * 16) {
+    int64_t b = (n + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    if (b > max_blocks) b = max_blocks;
+    return static_cast<unsigned>(b);
+}
+
+// Dispatch on the (odd) row count and on "c is a power of two" so that the hash state of all
+// rows lives in registers and loops over rows are unrolled.
+#define CS_DISPATCH_R(p, CALL)                                                     \
+    do {                                                                           \
+        const bool pow2__ = (p)->c_pow2 != 0;                                      \
+        switch ((p)->r) {                                                          \
+            case 1: if (pow2__) { CALL(1, true); } else { CALL(1, false); } break;   \
+            case 3: if (pow2__) { CALL(3, true); } else { CALL(3, false); } break;   \
+            case 5: if (pow2__) { CALL(5, true); } else { CALL(5, false); } break;   \
+            case 7: if (pow2__) { CALL(7, true); } else { CALL(7, false); } break;   \
+            case 9: if (pow2__) { CALL(9, true); } else { CALL(9, false); } break;   \
+            case 11: if (pow2__) { CALL(11, true); } else { CALL(11, false); } break; \
+            case 13: if (pow2__) { CALL(13, true); } else { CALL(13, false); } break; \
+            case 15: if (pow2__) { CALL(15, true); } else { CALL(15, false); } break; \
+            default: return CS_EINVAL;                                             \
+        }                                                                          \
+    } while (0)
+
+// ---------------------------------------------------------------------------------------
+// hash parity hooks
+// ---------------------------------------------------------------------------------------
+template <bool POW2>
+__global__ void __launch_bounds__(kBlock)
+k_hash_list(cs_params p, const int64_t* __restrict__ idx, int64_t n,
+            uint32_t* __restrict__ bucket, int8_t* __restrict__ sign) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < n; t += stride) {
+        const uint64_t i = static_cast<uint64_t>(idx[t]);
+        for (uint32_t j = 0; j < p.r; ++j) {
+            const uint64_t yb = hash_state(p.a[j], p.b[j], i);
+            const uint64_t ys = hash_state(p.as[j], p.bs[j], i);
+            bucket[static_cast<size_t>(j) * n + t] = bucket_of<POW2>(yb, p.c);
+            sign[static_cast<size_t>(j) * n + t] = sign_flip_of(ys) ? -1 : 1;
+        }
+    }
+}
+
+// Streaming hash state of all R rows for one thread: start at coordinate `first`, then step
+// by `stride` coordinates at a time.
+template <int R>
+struct RowStates {
+    uint64_t yb[R], ys[R];    // y-form states of the bucket and sign hashes
+    uint64_t Ab[R], As[R];    // (a_j * stride) mod p, (a'_j * stride) mod p
+
+    __device__ __forceinline__ void init(const cs_params& p, uint64_t first, uint64_t stride) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            yb[j] = hash_state(p.a[j], p.b[j], first);
+            ys[j] = hash_state(p.as[j], p.bs[j], first);
+            Ab[j] = mulmod_p(p.a[j], stride);
+            As[j] = mulmod_p(p.as[j], stride);
+        }
+    }
+    __device__ __forceinline__ void advance() {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            yb[j] = hash_advance(yb[j], Ab[j]);
+            ys[j] = hash_advance(ys[j], As[j]);
+        }
+    }
+};
+
+template <int R, bool POW2>
+__global__ void __launch_bounds__(kBlock)
+k_hash_range(cs_params p, int64_t i0, int64_t n, uint32_t* __restrict__ bucket,
+             int8_t* __restrict__ sign) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (t >= n) return;
+    RowStates<R> st;
+    st.init(p, static_cast<uint64_t>(i0 + t), static_cast<uint64_t>(stride));
+    for (; t < n; t += stride) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            bucket[static_cast<size_t>(j) * n + t] = bucket_of<POW2>(st.yb[j], p.c);
+            sign[static_cast<size_t>(j) * n + t] = sign_flip_of(st.ys[j]) ? -1 : 1;
+        }
+        st.advance();
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// sketch_accumulate: Alg. 4 update over a dense vector
+// ---------------------------------------------------------------------------------------
+constexpr int kMaxBatch = 32;   // workers per launch of the batched kernels
+
+struct BatchPtrs {
+    float* S[kMaxBatch];
+    const float* g[kMaxBatch];
+};
+
+// One thread per coordinate, grid-stride; the gradient is read coalesced, the r updates go
+// out as fp32 atomics.  With NW > 1 the same hash values serve NW workers.
+template <int R, bool POW2>
+__global__ void __launch_bounds__(kBlock)
+k_accumulate(cs_params p, BatchPtrs ptrs, int nw, int64_t d, int64_t i0, float scale) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (t >= d) return;
+    RowStates<R> st;
+    st.init(p, static_cast<uint64_t>(i0 + t), static_cast<uint64_t>(stride));
+    const uint32_t c = p.c;
+    for (; t < d; t += stride) {
+        uint32_t cell[R], flip[R];
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            cell[j] = static_cast<uint32_t>(j) * c + bucket_of<POW2>(st.yb[j], c);
+            flip[j] = sign_flip_of(st.ys[j]);
+        }
+        for (int w = 0; w < nw; ++w) {
+            const float v = scale * ptrs.g[w][t];
+            float* S = ptrs.S[w];
+#pragma unroll
+            for (int j = 0; j < R; ++j) atomic_add_noret(S + cell[j], apply_sign(v, flip[j]));
+        }
+        st.advance();
+    }
+}
+
+template <bool POW2>
+__global__ void __launch_bounds__(kBlock)
+k_accumulate_sparse(cs_params p, float* __restrict__ S, const int64_t* __restrict__ idx,
+                    const float* __restrict__ val, int64_t n, float scale) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < n; t += stride) {
+        const uint64_t i = static_cast<uint64_t>(idx[t]);
+        const float v = scale * val[t];
+        for (uint32_t j = 0; j < p.r; ++j) {
+            const uint64_t yb = hash_state(p.a[j], p.b[j], i);
+            const uint64_t ys = hash_state(p.as[j], p.bs[j], i);
+            atomic_add_noret(S + static_cast<size_t>(j) * p.c + bucket_of<POW2>(yb, p.c),
+                             apply_sign(v, sign_flip_of(ys)));
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// table-wide elementwise kernels: zero, merge, axpby, momentum
+// ---------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kBlock) k_fill_zero(float* __restrict__ S, int64_t n) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < n; t += stride)
+        S[t] = 0.0f;
+}
+
+constexpr int kMaxMerge = 128;   // source tables per launch of the merge kernel
+
+struct MergePtrs {
+    const float* src[kMaxMerge];
+};
+
+// dst = beta * dst + alpha * (src[0] + src[1] + ...), the sum taken in ascending order.
+__global__ void __launch_bounds__(kBlock)
+k_merge(float* __restrict__ dst, float beta, MergePtrs ptrs, int nw, float alpha, int64_t n) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < n; t += stride) {
+        float s = ptrs.src[0][t];
+        for (int w = 1; w < nw; ++w) s += ptrs.src[w][t];
+        const float base = (beta == 0.0f) ? 0.0f : beta * dst[t];
+        dst[t] = base + alpha * s;
+    }
+}
+
+__global__ void __launch_bounds__(kBlock)
+k_axpby(float* __restrict__ y, float a, const float* __restrict__ x, float b, int64_t n) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < n; t += stride) {
+        const float by = (b == 0.0f) ? 0.0f : b * y[t];
+        y[t] = a * x[t] + by;
+    }
+}
+
+__global__ void __launch_bounds__(kBlock)
+k_momentum(float* __restrict__ Su, float* __restrict__ Sv, const float* __restrict__ St,
+           float rho, int64_t n) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < n; t += stride) {
+        const float u = rho * Su[t] + St[t];
+        Su[t] = u;
+        Sv[t] = Sv[t] + u;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// sketch_estimate: Alg. 4 estimate
+// ---------------------------------------------------------------------------------------
+template <int R, bool POW2>
+__global__ void __launch_bounds__(kBlock)
+k_estimate(cs_params p, const float* __restrict__ S, int64_t d, int64_t i0,
+           float* __restrict__ est) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (t >= d) return;
+    RowStates<R> st;
+    st.init(p, static_cast<uint64_t>(i0 + t), static_cast<uint64_t>(stride));
+    const uint32_t c = p.c;
+    for (; t < d; t += stride) {
+        float v[R];
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const float cellv = S[static_cast<size_t>(j) * c + bucket_of<POW2>(st.yb[j], c)];
+            v[j] = apply_sign(cellv, sign_flip_of(st.ys[j]));
+        }
+        est[t] = median_odd<R>(v);
+        st.advance();
+    }
+}
+
+template <int R, bool POW2>
+__global__ void __launch_bounds__(kBlock)
+k_estimate_sparse(cs_params p, const float* __restrict__ S, const int64_t* __restrict__ idx,
+                  int64_t n, float* __restrict__ out) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < n; t += stride) {
+        const uint64_t i = static_cast<uint64_t>(idx[t]);
+        float v[R];
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const uint64_t yb = hash_state(p.a[j], p.b[j], i);
+            const uint64_t ys = hash_state(p.as[j], p.bs[j], i);
+            v[j] = apply_sign(S[static_cast<size_t>(j) * p.c + bucket_of<POW2>(yb, p.c)],
+                              sign_flip_of(ys));
+        }
+        out[t] = median_odd<R>(v);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// gather_exact: second round
+// ---------------------------------------------------------------------------------------
+struct GatherPtrs {
+    const float* vec[kMaxBatch];
+};
+
+__global__ void __launch_bounds__(kBlock)
+k_gather(GatherPtrs ptrs, int nw, const int64_t* __restrict__ idx, int64_t k, float alpha,
+         float* __restrict__ out, int first_chunk, int last_chunk) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    for (int64_t n = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; n < k; n += stride) {
+        const int64_t i = idx[n];
+        float s = first_chunk ? 0.0f : out[n];
+        for (int w = 0; w < nw; ++w) s += ptrs.vec[w][i];
+        out[n] = last_chunk ? alpha * s : s;
+    }
+}
+
+}  // namespace cs
+
+using namespace cs;
+
+// =========================================================================================
+// C ABI
+// =========================================================================================
+extern "C" int cs_hash_debug(const cs_params* p, const int64_t* idx, int64_t n,
+                             uint32_t* bucket, int8_t* sign, void* stream) {
+    if (!params_ok(p) || n < 0) return CS_EINVAL;
+    if (n == 0) return CS_OK;
+    if (!idx || !bucket || !sign) return CS_EINVAL;
+    if (p->c_pow2)
+        k_hash_list<true><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(*p, idx, n, bucket, sign);
+    else
+        k_hash_list<false><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(*p, idx, n, bucket, sign);
+    return launch_status();
+}
+
+extern "C" int cs_hash_debug_range(const cs_params* p, int64_t i0, int64_t n,
+                                   uint32_t* bucket, int8_t* sign, void* stream) {
+    if (!params_ok(p) || n < 0 || i0 < 0 || i0 > (int64_t)kP61 - n) return CS_EINVAL;
+    if (n == 0) return CS_OK;
+    if (!bucket || !sign) return CS_EINVAL;
+    // a small grid on purpose: every thread takes several strided steps
+    const unsigned grid = grid_for(n, kBlock * 8, 64);
+#define CALL(R_, P2_) \
+    k_hash_range<R_, P2_><<<grid, kBlock, 0, as_stream(stream)>>>(*p, i0, n, bucket, sign)
+    CS_DISPATCH_R(p, CALL);
+#undef CALL
+    return launch_status();
+}
+
+extern "C" int cs_sketch_zero(const cs_params* p, float* S, void* stream) {
+    if (!params_ok(p) || !S) return CS_EINVAL;
+    const int64_t n = static_cast<int64_t>(p->r) * p->c;
+    k_fill_zero<<<grid_for(n), kBlock, 0, as_stream(stream)>>>(S, n);
+    return launch_status();
+}
+
+static int accumulate_launch(const cs_params* p, const BatchPtrs& ptrs, int nw, int64_t d,
+                             int64_t i0, float scale, void* stream) {
+    // at least ~8 coordinates per thread so the per-thread hash set-up is amortised
+    const unsigned grid = grid_for(d, kBlock * 8, 256 * 8);
+#define CALL(R_, P2_) \
+    k_accumulate<R_, P2_><<<grid, kBlock, 0, as_stream(stream)>>>(*p, ptrs, nw, d, i0, scale)
+    CS_DISPATCH_R(p, CALL);
+#undef CALL
+    return launch_status();
+}
+
+extern "C" int cs_sketch_accumulate(const cs_params* p, float* S, const float* g, int64_t d,
+                                    int64_t i0, float scale, void* stream) {
+    if (!params_ok(p) || d < 0 || i0 < 0 || i0 > (int64_t)kP61 - d) return CS_EINVAL;
+    if (d == 0) return CS_OK;
+    if (!S || !g) return CS_EINVAL;
+    BatchPtrs ptrs{};
+    ptrs.S[0] = S;
+    ptrs.g[0] = g;
+    return accumulate_launch(p, ptrs, 1, d, i0, scale, stream);
+}
+
+extern "C" int cs_sketch_accumulate_batch(const cs_params* p, float* const* S_w,
+                                          const float* const* g_w, int32_t W, int64_t d,
+                                          int64_t i0, float scale, void* stream) {
+    if (!params_ok(p) || W < 1 || d < 0 || i0 < 0 || i0 > (int64_t)kP61 - d) return CS_EINVAL;
+    if (!S_w || !g_w) return CS_EINVAL;
+    for (int w = 0; w < W; ++w)
+        if (!S_w[w] || (!g_w[w] && d > 0)) return CS_EINVAL;
+    if (d == 0) return CS_OK;
+    for (int w0 = 0; w0 < W; w0 += kMaxBatch) {
+        const int nw = (W - w0 < kMaxBatch) ? (W - w0) : kMaxBatch;
+        BatchPtrs ptrs{};
+        for (int w = 0; w < nw; ++w) {
+            ptrs.S[w] = S_w[w0 + w];
+            ptrs.g[w] = g_w[w0 + w];
+        }
+        const int rc = accumulate_launch(p, ptrs, nw, d, i0, scale, stream);
+        if (rc != CS_OK) return rc;
+    }
+    return CS_OK;
+}
+
+extern "C" int cs_sketch_accumulate_sparse(const cs_params* p, float* S, const int64_t* idx,
+                                           const float* val, int64_t n, float scale,
+                                           void* stream) {
+    if (!params_ok(p) || n < 0) return CS_EINVAL;
+    if (n == 0) return CS_OK;
+    if (!S || !idx || !val) return CS_EINVAL;
+    if (p->c_pow2)
+        k_accumulate_sparse<true><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(*p, S, idx, val, n, scale);
+    else
+        k_accumulate_sparse<false><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(*p, S, idx, val, n, scale);
+    return launch_status();
+}
+
+extern "C" int cs_sketch_merge(const cs_params* p, float* dst, float beta,
+                               const float* const* src, int32_t W, float alpha, void* stream) {
+    if (!params_ok(p) || !dst || !src || W < 1) return CS_EINVAL;
+    for (int w = 0; w < W; ++w)
+        if (!src[w] || (W > 1 && src[w] == dst)) return CS_EINVAL;
+    const int64_t n = static_cast<int64_t>(p->r) * p->c;
+    // More sources than one launch takes: later launches add their share on top (beta = 1).
+    for (int w0 = 0; w0 < W; w0 += kMaxMerge) {
+        const int nw = (W - w0 < kMaxMerge) ? (W - w0) : kMaxMerge;
+        MergePtrs ptrs{};
+        for (int w = 0; w < nw; ++w) ptrs.src[w] = src[w0 + w];
+        k_merge<<<grid_for(n), kBlock, 0, as_stream(stream)>>>(dst, w0 == 0 ? beta : 1.0f, ptrs,
+                                                               nw, alpha, n);
+        if (launch_status() != CS_OK) return CS_EHIP;
+    }
+    return CS_OK;
+}
+
+extern "C" int cs_sketch_axpby(const cs_params* p, float* y, float a, const float* x, float b,
+                               void* stream) {
+    if (!params_ok(p) || !y || !x) return CS_EINVAL;
+    const int64_t n = static_cast<int64_t>(p->r) * p->c;
+    k_axpby<<<grid_for(n), kBlock, 0, as_stream(stream)>>>(y, a, x, b, n);
+    return launch_status();
+}
+
+extern "C" int cs_sketch_momentum(const cs_params* p, float* S_u, float* S_v, const float* S_t,
+                                  float rho, void* stream) {
+    if (!params_ok(p) || !S_u || !S_v || !S_t) return CS_EINVAL;
+    const int64_t n = static_cast<int64_t>(p->r) * p->c;
+    k_momentum<<<grid_for(n), kBlock, 0, as_stream(stream)>>>(S_u, S_v, S_t, rho, n);
+    return launch_status();
+}
+
+extern "C" int cs_estimate_workspace_bytes(const cs_params* p, int64_t d, size_t* bytes) {
+    if (!params_ok(p) || d < 0 || !bytes) return CS_EINVAL;
+    *bytes = 0;
+    return CS_OK;
+}
+
+extern "C" int cs_sketch_estimate(const cs_params* p, const float* S, int64_t d, int64_t i0,
+                                  float* est, void* rows_ws, size_t ws_bytes, void* stream) {
+    (void)rows_ws;
+    (void)ws_bytes;
+    if (!params_ok(p) || d < 0 || i0 < 0 || i0 > (int64_t)kP61 - d) return CS_EINVAL;
+    if (d == 0) return CS_OK;
+    if (!S || !est) return CS_EINVAL;
+    const unsigned grid = grid_for(d, kBlock * 8, 256 * 8);
+#define CALL(R_, P2_) \
+    k_estimate<R_, P2_><<<grid, kBlock, 0, as_stream(stream)>>>(*p, S, d, i0, est)
+    CS_DISPATCH_R(p, CALL);
+#undef CALL
+    return launch_status();
+}
+
+extern "C" int cs_sketch_estimate_sparse(const cs_params* p, const float* S, const int64_t* idx,
+                                         int64_t n, float* out, void* stream) {
+    if (!params_ok(p) || n < 0) return CS_EINVAL;
+    if (n == 0) return CS_OK;
+    if (!S || !idx || !out) return CS_EINVAL;
+#define CALL(R_, P2_) \
+    k_estimate_sparse<R_, P2_><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(*p, S, idx, n, out)
+    CS_DISPATCH_R(p, CALL);
+#undef CALL
+    return launch_status();
+}
+
+extern "C" int cs_gather_exact(const float* const* vec, int32_t W, const int64_t* idx, int64_t k,
+                               float alpha, float* out, void* stream) {
+    if (!vec || W < 1 || k < 0) return CS_EINVAL;
+    for (int w = 0; w < W; ++w)
+        if (!vec[w]) return CS_EINVAL;
+    if (k == 0) return CS_OK;
+    if (!idx || !out) return CS_EINVAL;
+    for (int w0 = 0; w0 < W; w0 += kMaxBatch) {
+        const int nw = (W - w0 < kMaxBatch) ? (W - w0) : kMaxBatch;
+        GatherPtrs ptrs{};
+        for (int w = 0; w < nw; ++w) ptrs.vec[w] = vec[w0 + w];
+        k_gather<<<grid_for(k), kBlock, 0, as_stream(stream)>>>(ptrs, nw, idx, k, alpha, out,
+                                                                w0 == 0, w0 + nw == W);
+        if (launch_status() != CS_OK) return CS_EHIP;
+    }
+    return CS_OK;
+}
+
+extern "C" int cs_sketch_feedback(const cs_params* p, float* S, const int64_t* idx, int64_t k,
+                                  float* val, void* stream) {
+    if (!params_ok(p) || k < 0) return CS_EINVAL;
+    if (k == 0) return CS_OK;
+    if (!S || !idx || !val) return CS_EINVAL;
+    // all k estimates are taken from the table as it is on entry (first kernel), and only
+    // then is the sketch of (idx, val) subtracted (second kernel, same stream).
+    int rc = cs_sketch_estimate_sparse(p, S, idx, k, val, stream);
+    if (rc != CS_OK) return rc;
+    return cs_sketch_accumulate_sparse(p, S, idx, val, k, -1.0f, stream);
+}

@@ -1,0 +1,310 @@
+// heavy_hitters_topk: "query the sketch for every gradient coordinate, and then choose the
+// largest elements" (Sec. 5.2 of the paper) -- the selection half.
+//
+// Exact radix select on the 31-bit magnitude key  bits(est) & 0x7fffffff  (monotone in |est|
+// for IEEE binary32): three histogram passes (11 + 10 + 10 bits) find the key theta of the
+// k-th largest magnitude and how many entries equal to theta are still needed; an ordered
+// compaction (per-block counts, scan over blocks, write) then emits, in ascending index
+// order, every index with key > theta plus the lowest-index entries with key == theta.
+// Everything is integer work, so the result is a deterministic function of est.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cs_device.h"
+#include "csketch.h"
+
+namespace cs {
+
+constexpr int kBins = 2048;           // bins of the widest pass
+constexpr int kItems = 4;             // consecutive elements per thread in a tile
+constexpr int kTile = kBlock * kItems;
+constexpr int kMaxSelBlocks = 4096;   // blocks of the count / write passes
+
+struct TopkSel {
+    uint32_t prefix;      // key bits fixed so far (after pass n: the top 11, 21, 31 bits)
+    uint32_t pad;
+    uint64_t k_rem;       // how many of the entries sharing `prefix` are still wanted
+};
+
+// workspace layout (all 8-byte aligned)
+struct TopkWs {
+    uint64_t hist[3][kBins];
+    TopkSel sel;
+    uint64_t gt[kMaxSelBlocks];     // per block: entries with key > theta  -> exclusive scan
+    uint64_t eq[kMaxSelBlocks];     // per block: entries with key == theta -> exclusive scan
+};
+
+__device__ __forceinline__ uint32_t key_of(float v) { return __float_as_uint(v) & 0x7fffffffu; }
+
+__global__ void __launch_bounds__(kBlock) k_topk_clear(TopkWs* ws, uint64_t k) {
+    for (int t = threadIdx.x; t < 3 * kBins; t += kBlock) (&ws->hist[0][0])[t] = 0;
+    if (threadIdx.x == 0) {
+        ws->sel.prefix = 0;
+        ws->sel.pad = 0;
+        ws->sel.k_rem = k;
+    }
+}
+
+// PASS 0: bin = key >> 20 (2048 bins); PASS 1: entries with key >> 20 == prefix, bin = bits
+// 19..10; PASS 2: entries with key >> 10 == prefix, bin = bits 9..0.
+template <int PASS>
+__global__ void __launch_bounds__(kBlock)
+k_topk_hist(const float* __restrict__ est, int64_t d, TopkWs* ws) {
+    __shared__ uint32_t lh[kBins];
+    constexpr int nb = (PASS == 0) ? 2048 : 1024;
+    for (int t = threadIdx.x; t < nb; t += kBlock) lh[t] = 0;
+    __syncthreads();
+    const uint32_t prefix = ws->sel.prefix;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < d; t += stride) {
+        const uint32_t key = key_of(est[t]);
+        if (PASS == 0) {
+            atomicAdd(&lh[key >> 20], 1u);
+        } else if (PASS == 1) {
+            if ((key >> 20) == prefix) atomicAdd(&lh[(key >> 10) & 1023u], 1u);
+        } else {
+            if ((key >> 10) == prefix) atomicAdd(&lh[key & 1023u], 1u);
+        }
+    }
+    __syncthreads();
+    for (int t = threadIdx.x; t < nb; t += kBlock) {
+        const uint32_t v = lh[t];
+        if (v) atomicAdd(reinterpret_cast<unsigned long long*>(&ws->hist[PASS][t]),
+                         static_cast<unsigned long long>(v));
+    }
+}
+
+// One workgroup: walk the histogram of this pass from the top bin down to the bin that holds
+// the k_rem-th largest entry; append that bin to the prefix, and drop from k_rem the entries
+// in higher bins (they are all selected).
+template <int PASS>
+__global__ void __launch_bounds__(kBlock) k_topk_find(TopkWs* ws) {
+    constexpr int nb = (PASS == 0) ? 2048 : 1024;
+    constexpr int per = nb / kBlock;              // bins per thread: 8 or 4
+    __shared__ uint64_t seg[kBlock];
+    const uint64_t* h = ws->hist[PASS];
+    const uint64_t k_rem = ws->sel.k_rem;
+    const uint32_t prefix = ws->sel.prefix;
+    uint64_t mine = 0;
+    for (int q = 0; q < per; ++q) mine += h[threadIdx.x * per + q];
+    seg[threadIdx.x] = mine;
+    __syncthreads();
+    uint64_t above = 0;                            // entries in bins above my segment
+    for (int u = threadIdx.x + 1; u < kBlock; ++u) above += seg[u];
+    __syncthreads();
+    if (above < k_rem && k_rem <= above + mine) {  // true for exactly one thread
+        uint64_t acc = above;
+        for (int q = per - 1; q >= 0; --q) {
+            const int bin = threadIdx.x * per + q;
+            const uint64_t cnt = h[bin];
+            if (k_rem <= acc + cnt) {
+                constexpr int bits = (PASS == 0) ? 11 : 10;
+                ws->sel.prefix = (PASS == 0) ? static_cast<uint32_t>(bin)
+                                             : ((prefix << bits) | static_cast<uint32_t>(bin));
+                ws->sel.k_rem = k_rem - acc;
+                break;
+            }
+            acc += cnt;
+        }
+    }
+}
+
+// flags of one element against theta, packed: low 16 bits count "greater", high 16 "equal"
+__device__ __forceinline__ uint32_t classify(uint32_t key, uint32_t theta) {
+    return (key > theta ? 1u : 0u) | (key == theta ? 0x10000u : 0u);
+}
+
+// inclusive scan of a packed counter over the workgroup; returns the inclusive value and
+// writes the workgroup total to *total.  `lds` holds one word per wavefront.
+__device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, uint32_t* lds, uint32_t* total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t up = __shfl_up(v, off, 64);
+        if (lane >= off) v += up;
+    }
+    if (lane == 63) lds[wave] = v;
+    __syncthreads();
+    uint32_t before = 0, all = 0;
+#pragma unroll
+    for (int wv = 0; wv < kBlock / 64; ++wv) {
+        const uint32_t s = lds[wv];
+        if (wv < wave) before += s;
+        all += s;
+    }
+    __syncthreads();
+    *total = all;
+    return v + before;
+}
+
+template <bool VEC>
+__device__ __forceinline__ void load_items(const float* __restrict__ est, int64_t base, int64_t d,
+                                           float (&v)[kItems], int& nvalid) {
+    // base = index of this thread's first element
+    if (VEC && base + kItems <= d) {
+        const float4 q = *reinterpret_cast<const float4*>(est + base);
+        v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+        nvalid = kItems;
+        return;
+    }
+    nvalid = 0;
+#pragma unroll
+    for (int q = 0; q < kItems; ++q) {
+        if (base + q < d) { v[q] = est[base + q]; nvalid = q + 1; } else { v[q] = 0.0f; }
+    }
+}
+
+// per block: how many entries of its chunk are above / equal to theta
+template <bool VEC>
+__global__ void __launch_bounds__(kBlock)
+k_topk_count(const float* __restrict__ est, int64_t d, int64_t chunk, TopkWs* ws) {
+    __shared__ uint32_t lds[kBlock / 64];
+    const uint32_t theta = ws->sel.prefix;
+    const int64_t lo = static_cast<int64_t>(blockIdx.x) * chunk;
+    const int64_t hi = (lo + chunk < d) ? lo + chunk : d;
+    uint64_t n_gt = 0, n_eq = 0;
+    for (int64_t tile = lo; tile < hi; tile += kTile) {
+        float v[kItems];
+        int nvalid;
+        load_items<VEC>(est, tile + static_cast<int64_t>(threadIdx.x) * kItems, hi, v, nvalid);
+        uint32_t c = 0;
+#pragma unroll
+        for (int q = 0; q < kItems; ++q)
+            if (q < nvalid) c += classify(key_of(v[q]), theta);
+        uint32_t total;
+        block_inclusive_scan(c, lds, &total);
+        n_gt += total & 0xffffu;
+        n_eq += total >> 16;
+    }
+    if (threadIdx.x == 0) {
+        ws->gt[blockIdx.x] = n_gt;
+        ws->eq[blockIdx.x] = n_eq;
+    }
+}
+
+// one workgroup: exclusive scan of the per-block counts, in place
+__global__ void __launch_bounds__(kBlock) k_topk_scan(TopkWs* ws, int nblocks) {
+    __shared__ uint64_t part_gt[kBlock], part_eq[kBlock];
+    constexpr int per = kMaxSelBlocks / kBlock;     // 16 consecutive blocks per thread
+    uint64_t g[per], e[per], sg = 0, se = 0;
+    for (int q = 0; q < per; ++q) {
+        const int b = threadIdx.x * per + q;
+        g[q] = (b < nblocks) ? ws->gt[b] : 0;
+        e[q] = (b < nblocks) ? ws->eq[b] : 0;
+        sg += g[q];
+        se += e[q];
+    }
+    part_gt[threadIdx.x] = sg;
+    part_eq[threadIdx.x] = se;
+    __syncthreads();
+    uint64_t bg = 0, be = 0;
+    for (int u = 0; u < static_cast<int>(threadIdx.x); ++u) { bg += part_gt[u]; be += part_eq[u]; }
+    for (int q = 0; q < per; ++q) {
+        const int b = threadIdx.x * per + q;
+        if (b < nblocks) { ws->gt[b] = bg; ws->eq[b] = be; }
+        bg += g[q];
+        be += e[q];
+    }
+}
+
+// ordered compaction: index t is selected when key > theta, or key == theta and fewer than
+// need_eq equal entries precede it; its output slot is (#greater before t) + min(#equal
+// before t, need_eq), which is its rank among the selected in ascending index order.
+template <bool VEC>
+__global__ void __launch_bounds__(kBlock)
+k_topk_write(const float* __restrict__ est, int64_t d, int64_t chunk, const TopkWs* ws,
+             int64_t k, int64_t* __restrict__ idx_out, float* __restrict__ val_out) {
+    __shared__ uint32_t lds[kBlock / 64];
+    const uint32_t theta = ws->sel.prefix;
+    const uint64_t need_eq = ws->sel.k_rem;
+    uint64_t gt_before = ws->gt[blockIdx.x];
+    uint64_t eq_before = ws->eq[blockIdx.x];
+    const int64_t lo = static_cast<int64_t>(blockIdx.x) * chunk;
+    const int64_t hi = (lo + chunk < d) ? lo + chunk : d;
+    for (int64_t tile = lo; tile < hi; tile += kTile) {
+        float v[kItems];
+        int nvalid;
+        const int64_t base = tile + static_cast<int64_t>(threadIdx.x) * kItems;
+        load_items<VEC>(est, base, hi, v, nvalid);
+        uint32_t c = 0;
+#pragma unroll
+        for (int q = 0; q < kItems; ++q)
+            if (q < nvalid) c += classify(key_of(v[q]), theta);
+        uint32_t total;
+        const uint32_t incl = block_inclusive_scan(c, lds, &total);
+        if (c) {
+            uint64_t g = gt_before + ((incl - c) & 0xffffu);
+            uint64_t e = eq_before + ((incl - c) >> 16);
+#pragma unroll
+            for (int q = 0; q < kItems; ++q) {
+                if (q >= nvalid) break;
+                const uint32_t key = key_of(v[q]);
+                const bool is_gt = key > theta, is_eq = key == theta;
+                if (is_gt || (is_eq && e < need_eq)) {
+                    const uint64_t slot = g + (e < need_eq ? e : need_eq);
+                    if (slot < static_cast<uint64_t>(k)) {
+                        idx_out[slot] = base + q;
+                        if (val_out) val_out[slot] = v[q];
+                    }
+                }
+                g += is_gt;
+                e += is_eq;
+            }
+        }
+        gt_before += total & 0xffffu;
+        eq_before += total >> 16;
+    }
+}
+
+}  // namespace cs
+
+using namespace cs;
+
+static void topk_geometry(int64_t d, int* nblocks, int64_t* chunk) {
+    int64_t tiles = (d + kTile - 1) / kTile;
+    int64_t nb = tiles < kMaxSelBlocks ? tiles : kMaxSelBlocks;
+    if (nb < 1) nb = 1;
+    int64_t tiles_per_block = (tiles + nb - 1) / nb;
+    *chunk = tiles_per_block * kTile;
+    *nblocks = static_cast<int>((d + *chunk - 1) / *chunk);
+    if (*nblocks < 1) *nblocks = 1;
+}
+
+extern "C" int cs_topk_workspace_bytes(int64_t d, int64_t k, size_t* bytes) {
+    if (!bytes || d < 1 || k < 1 || k > d) return CS_EINVAL;
+    *bytes = sizeof(TopkWs);
+    return CS_OK;
+}
+
+extern "C" int cs_heavy_hitters_topk(const float* est, int64_t d, int64_t k, int64_t* idx_out,
+                                     float* val_out, void* workspace, size_t ws_bytes,
+                                     void* stream) {
+    if (d < 1 || k < 1 || k > d || !est || !idx_out || !workspace) return CS_EINVAL;
+    if (reinterpret_cast<uintptr_t>(workspace) % 8 != 0) return CS_EINVAL;
+    if (ws_bytes < sizeof(TopkWs)) return CS_EWORKSPACE;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    TopkWs* ws = static_cast<TopkWs*>(workspace);
+    const unsigned hgrid = static_cast<unsigned>(
+        (d + kBlock * 16 - 1) / (kBlock * 16) < 2048 ? (d + kBlock * 16 - 1) / (kBlock * 16) : 2048);
+    k_topk_clear<<<1, kBlock, 0, s>>>(ws, static_cast<uint64_t>(k));
+    k_topk_hist<0><<<hgrid, kBlock, 0, s>>>(est, d, ws);
+    k_topk_find<0><<<1, kBlock, 0, s>>>(ws);
+    k_topk_hist<1><<<hgrid, kBlock, 0, s>>>(est, d, ws);
+    k_topk_find<1><<<1, kBlock, 0, s>>>(ws);
+    k_topk_hist<2><<<hgrid, kBlock, 0, s>>>(est, d, ws);
+    k_topk_find<2><<<1, kBlock, 0, s>>>(ws);
+    int nblocks;
+    int64_t chunk;
+    topk_geometry(d, &nblocks, &chunk);
+    const bool vec = reinterpret_cast<uintptr_t>(est) % 16 == 0;
+    if (vec) {
+        k_topk_count<true><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws);
+        k_topk_scan<<<1, kBlock, 0, s>>>(ws, nblocks);
+        k_topk_write<true><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, k, idx_out, val_out);
+    } else {
+        k_topk_count<false><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws);
+        k_topk_scan<<<1, kBlock, 0, s>>>(ws, nblocks);
+        k_topk_write<false><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, k, idx_out, val_out);
+    }
+    return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
+}

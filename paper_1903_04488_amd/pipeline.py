@@ -1,0 +1,84 @@
+"""One pass of the hot path on one GPU: buffers and the order of library calls, nothing else.
+
+Per step (Alg. 3 of the paper, with the W workers simulated on the one device):
+    worker sketches   S^w = S(g^w)                cs_sketch_accumulate_batch
+    aggregate         S_t = (1/W) sum_w S^w       cs_sketch_merge
+    momentum, error   S_u = rho S_u + S_t ; S_v += S_u      cs_sketch_momentum   (stateful only)
+    query all         est = estimate(S_v or S_t)  cs_sketch_estimate
+    choose largest    idx = top-k |est|           cs_heavy_hitters_topk
+    second round      x = (1/W) sum_w g^w[idx]    cs_gather_exact
+    feedback          S_v -= S(est[idx]) ; S_u -= S(estimate(S_u, idx))   cs_sketch_feedback (stateful)
+Every arithmetic step runs inside libcsketch.so; this class only owns tensors.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+
+
+class HotPath:
+    def __init__(self, d: int, W: int, r: int, c: int, k: int, seed: int,
+                 rho: float | None = None, device="cuda:0"):
+        self.d, self.W, self.r, self.c, self.k = d, W, r, c, k
+        self.rho = rho
+        self.device = torch.device(device)
+        self.params = B.cs_params_init(r, c, seed, d)
+        f32 = dict(dtype=torch.float32, device=self.device)
+        self.S_w = [torch.zeros(r, c, **f32) for _ in range(W)]
+        self.S_t = torch.zeros(r, c, **f32)
+        self.S_u = torch.zeros(r, c, **f32) if rho is not None else None
+        self.S_v = torch.zeros(r, c, **f32) if rho is not None else None
+        self.est = torch.empty(d, **f32)
+        self.idx = torch.empty(k, dtype=torch.int64, device=self.device)
+        self.est_at_idx = torch.empty(k, **f32)
+        self.x = torch.empty(k, **f32)
+        self.delta = torch.empty(k, **f32)
+        self.uhat = torch.empty(k, **f32)
+        self.topk_ws = torch.empty(B.cs_topk_workspace_bytes(d, k), dtype=torch.uint8,
+                                   device=self.device)
+        n_est = B.cs_estimate_workspace_bytes(self.params, d)
+        self.est_ws = (torch.empty(n_est, dtype=torch.uint8, device=self.device)
+                       if n_est else None)
+
+    # individual stages (bench.py times them separately) ---------------------------------
+    def accumulate(self, g_w):
+        for S in self.S_w:
+            B.cs_sketch_zero(self.params, S)
+        B.cs_sketch_accumulate_batch(self.params, self.S_w, g_w)
+
+    def merge(self):
+        B.cs_sketch_merge(self.params, self.S_t, self.S_w, alpha=1.0 / self.W, beta=0.0)
+
+    def momentum(self):
+        if self.rho is not None:
+            B.cs_sketch_momentum(self.params, self.S_u, self.S_v, self.S_t, self.rho)
+
+    def query_table(self):
+        return self.S_v if self.rho is not None else self.S_t
+
+    def estimate(self):
+        B.cs_sketch_estimate(self.params, self.query_table(), self.est, 0, self.est_ws)
+
+    def topk(self):
+        B.cs_heavy_hitters_topk(self.est, self.k, self.idx, self.est_at_idx, self.topk_ws)
+
+    def gather(self, g_w):
+        B.cs_gather_exact(g_w, self.idx, self.x, alpha=1.0 / self.W)
+
+    def feedback(self):
+        if self.rho is not None:
+            B.cs_sketch_feedback(self.params, self.S_v, self.idx, self.delta)
+            B.cs_sketch_feedback(self.params, self.S_u, self.idx, self.uhat)
+
+    def step(self, g_w):
+        """g_w: list of W fp32[d] device tensors.  Returns (idx, x): chosen coordinates
+        (ascending) and their exact mean over workers."""
+        self.accumulate(g_w)
+        self.merge()
+        self.momentum()
+        self.estimate()
+        self.topk()
+        self.gather(g_w)
+        self.feedback()
+        return self.idx, self.x

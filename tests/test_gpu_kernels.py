@@ -1,0 +1,277 @@
+"""Kernel-by-kernel parity of the HIP library (through its C ABI) against the CPU reference.
+Integer results (hash buckets, signs, selected indices) must be bit-exact; a median picks one
+of its inputs, so estimates computed from the same fp32 table must be bit-exact too; sums
+(sketch cells, merges, gathers) must be within the stated fp32 tolerance."""
+import numpy as np
+import pytest
+import torch
+
+import paper_1903_04488_amd as cs
+from oracle import cs_oracle as orc
+from parity_util import assert_cells_close, assert_values_close
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.to(DEV)
+
+
+def ref_table_from_device(S):
+    return S.detach().cpu().numpy().astype(np.float64)
+
+
+SHAPES = [  # (r, c, seed)
+    (5, 1 << 15, 190304489),
+    (7, 1 << 19, 190304493),
+    (5, 1 << 20, 190304492),
+    (15, 180000, 77),        # the paper's non-power-of-two column count, 15 rows
+    (7, 40, 5),              # MNIST-sized sketch of App. E
+    (1, 1 << 10, 3),
+    (3, 1, 4),               # c = 1: AMS rows
+]
+
+
+# ------------------------------------------------------------------------------ hashing
+@pytest.mark.parametrize("r,c,seed", SHAPES)
+def test_hash_list_bit_exact(r, c, seed):
+    p = cs.cs_params_init(r, c, seed)
+    sk = orc.SketchOracle(r, c, seed)
+    rng = np.random.default_rng(seed)
+    idx = np.concatenate([
+        np.array([0, 1, 2, 63, 64, 65, 255, 256, (1 << 20) - 1, 10**8 - 1, (1 << 32) - 1,
+                  1 << 32, (1 << 40) + 12345, (1 << 61) - 1], dtype=np.int64),
+        rng.integers(0, 1 << 61, size=5000), rng.integers(0, 1 << 27, size=5000)])
+    n = idx.size
+    bucket = torch.empty(r * n, dtype=torch.int32, device=DEV)
+    sign = torch.empty(r * n, dtype=torch.int8, device=DEV)
+    cs.cs_hash_debug(p, dev(idx), bucket, sign)
+    rb, rs = sk.hash(idx)
+    np.testing.assert_array_equal(bucket.cpu().numpy().view(np.uint32).reshape(r, n), rb)
+    np.testing.assert_array_equal(sign.cpu().numpy().reshape(r, n), rs)
+
+
+def test_hash_edge_constants_bit_exact():
+    P = (1 << 61) - 1
+    c = 1 << 15
+    p = cs.cs_params_init(5, c, 5)
+    sk = orc.SketchOracle(5, c, 5)
+    i_star = 123456789
+    a3 = 987654321987654321 % P
+    edge = [(1, 0), (P - 1, P - 1), (1, P - 1), (P - 1, 0), (a3, (-a3 * i_star) % P)]
+    for j, (a, b) in enumerate(edge):
+        p.a[j] = p.as_[j] = a
+        p.b[j] = p.bs[j] = b
+        sk.a[j] = sk.as_[j] = a
+        sk.b[j] = sk.bs[j] = b
+    idx = np.array([0, 1, 2, i_star - 1, i_star, i_star + 1, (1 << 32) - 1, P - 1, P], dtype=np.int64)
+    n = idx.size
+    bucket = torch.empty(5 * n, dtype=torch.int32, device=DEV)
+    sign = torch.empty(5 * n, dtype=torch.int8, device=DEV)
+    cs.cs_hash_debug(p, dev(idx), bucket, sign)
+    rb, rs = sk.hash(idx)
+    np.testing.assert_array_equal(bucket.cpu().numpy().view(np.uint32).reshape(5, n), rb)
+    np.testing.assert_array_equal(sign.cpu().numpy().reshape(5, n), rs)
+
+
+@pytest.mark.parametrize("r,c,seed", SHAPES[:4])
+@pytest.mark.parametrize("i0,n", [(0, 1 << 20), (12345678901, 300001), (0, 1), (7, 63)])
+def test_hash_range_incremental_state_bit_exact(r, c, seed, i0, n):
+    p = cs.cs_params_init(r, c, seed, n)
+    sk = orc.SketchOracle(r, c, seed)
+    bucket = torch.empty(r * n, dtype=torch.int32, device=DEV)
+    sign = torch.empty(r * n, dtype=torch.int8, device=DEV)
+    cs.cs_hash_debug_range(p, i0, n, bucket, sign)
+    rb, rs = sk.hash(np.arange(i0, i0 + n, dtype=np.int64))
+    np.testing.assert_array_equal(bucket.cpu().numpy().view(np.uint32).reshape(r, n), rb)
+    np.testing.assert_array_equal(sign.cpu().numpy().reshape(r, n), rs)
+
+
+# ------------------------------------------------------------------------------ accumulate
+@pytest.mark.parametrize("r,c,seed", SHAPES)
+@pytest.mark.parametrize("d,i0,scale", [(1_000_003, 0, 1.0), (70_001, 5_000_000_000, -0.25), (1, 9, 3.0)])
+def test_accumulate_dense(r, c, seed, d, i0, scale):
+    p = cs.cs_params_init(r, c, seed, d)
+    sk = orc.SketchOracle(r, c, seed)
+    rng = np.random.default_rng(d)
+    g = (rng.standard_normal(d) * 0.01).astype(np.float32)
+    g[rng.integers(0, d, size=min(d, 50))] += 1.0
+    S = torch.full((r, c), 0.5, dtype=torch.float32, device=DEV)     # accumulates, does not clear
+    cs.cs_sketch_accumulate(p, S, dev(g), i0=i0, scale=scale)
+    ref = sk.accumulate(np.full((r, c), 0.5), g, i0=i0, scale=scale)
+    assert_cells_close(S.cpu().numpy(), ref)
+
+
+def test_accumulate_empty_is_noop():
+    p = cs.cs_params_init(5, 64, 1)
+    S = torch.ones(5, 64, dtype=torch.float32, device=DEV)
+    cs.cs_sketch_accumulate(p, S, torch.empty(0, dtype=torch.float32, device=DEV))
+    assert (S == 1).all()
+
+
+@pytest.mark.parametrize("W", [1, 3, 33])
+def test_accumulate_batch(W):
+    r, c, seed, d = 5, 1 << 12, 11, 200_003
+    p = cs.cs_params_init(r, c, seed, d)
+    sk = orc.SketchOracle(r, c, seed)
+    rng = np.random.default_rng(W)
+    gs = [(rng.standard_normal(d) * 0.01).astype(np.float32) for _ in range(W)]
+    S_w = [torch.zeros(r, c, dtype=torch.float32, device=DEV) for _ in range(W)]
+    cs.cs_sketch_accumulate_batch(p, S_w, [dev(g) for g in gs], i0=17, scale=0.5)
+    for w in range(W):
+        assert_cells_close(S_w[w].cpu().numpy(), sk.sketch(gs[w], i0=17, scale=0.5), what=f"worker {w}")
+
+
+@pytest.mark.parametrize("r,c,seed", SHAPES[:5])
+def test_accumulate_sparse_with_repeats(r, c, seed):
+    p = cs.cs_params_init(r, c, seed)
+    sk = orc.SketchOracle(r, c, seed)
+    rng = np.random.default_rng(1)
+    n = 10_007
+    idx = rng.integers(0, 1 << 40, size=n)
+    idx[::10] = idx[0]                                   # repeated index: values add up
+    val = rng.standard_normal(n).astype(np.float32)
+    S = torch.zeros(r, c, dtype=torch.float32, device=DEV)
+    cs.cs_sketch_accumulate_sparse(p, S, dev(idx), dev(val), scale=-2.0)
+    ref = sk.accumulate_sparse(sk.zeros(), idx, val.astype(np.float64), scale=-2.0)
+    assert_cells_close(S.cpu().numpy(), ref)
+
+
+# ------------------------------------------------------------------------------ table ops
+@pytest.mark.parametrize("W", [1, 5, 130])
+def test_merge_axpby_momentum_zero(W):
+    r, c = 5, 3001
+    p = cs.cs_params_init(r, c, 1)
+    rng = np.random.default_rng(W)
+    tabs = [rng.standard_normal((r, c)).astype(np.float32) for _ in range(W)]
+    dst0 = rng.standard_normal((r, c)).astype(np.float32)
+    dst = dev(dst0)
+    cs.cs_sketch_merge(p, dst, [dev(t) for t in tabs], alpha=1.0 / W, beta=0.0)
+    assert_cells_close(dst.cpu().numpy(), orc.merge(tabs, alpha=1.0 / W))
+    dst = dev(dst0)
+    cs.cs_sketch_merge(p, dst, [dev(t) for t in tabs], alpha=0.5, beta=-2.0)
+    assert_cells_close(dst.cpu().numpy(), orc.merge(tabs, alpha=0.5, beta=-2.0, dst=dst0))
+    # beta = 0 must not read dst (NaN there must not leak)
+    dst = torch.full((r, c), float("nan"), dtype=torch.float32, device=DEV)
+    cs.cs_sketch_merge(p, dst, [dev(t) for t in tabs], alpha=1.0, beta=0.0)
+    assert torch.isfinite(dst).all()
+
+    x, y = tabs[0], dst0
+    yd = dev(y)
+    cs.cs_sketch_axpby(p, yd, 0.75, dev(x), -1.5)
+    assert_cells_close(yd.cpu().numpy(), 0.75 * x.astype(np.float64) - 1.5 * y)
+
+    su, sv, st = dev(tabs[0]), dev(dst0), dev(tabs[-1])
+    cs.cs_sketch_momentum(p, su, sv, st, 0.9)
+    rho = float(np.float32(0.9))
+    u_ref = rho * tabs[0].astype(np.float64) + tabs[-1]
+    assert_cells_close(su.cpu().numpy(), u_ref)
+    assert_cells_close(sv.cpu().numpy(), dst0.astype(np.float64) + u_ref)
+
+    cs.cs_sketch_zero(p, su)
+    assert (su == 0).all()
+
+
+# ------------------------------------------------------------------------------ estimate
+@pytest.mark.parametrize("r,c,seed", SHAPES)
+@pytest.mark.parametrize("d,i0", [(1_000_003, 0), (4097, 3_000_000_000)])
+def test_estimate_bit_exact_from_same_table(r, c, seed, d, i0):
+    p = cs.cs_params_init(r, c, seed, d)
+    sk = orc.SketchOracle(r, c, seed)
+    T32 = (np.random.default_rng(seed).standard_normal((r, c))).astype(np.float32)
+    S = dev(T32)
+    est = torch.empty(d, dtype=torch.float32, device=DEV)
+    n_ws = cs.cs_estimate_workspace_bytes(p, d)
+    ws = torch.empty(n_ws, dtype=torch.uint8, device=DEV) if n_ws else None
+    cs.cs_sketch_estimate(p, S, est, i0=i0, workspace=ws)
+    ref = sk.estimate(T32.astype(np.float64), d, i0=i0)
+    np.testing.assert_array_equal(est.cpu().numpy(), ref.astype(np.float32))
+    # listed coordinates
+    idx = np.random.default_rng(1).integers(i0, i0 + d, size=777)
+    out = torch.empty(777, dtype=torch.float32, device=DEV)
+    cs.cs_sketch_estimate_sparse(p, S, dev(idx), out)
+    np.testing.assert_array_equal(out.cpu().numpy(), ref[idx - i0].astype(np.float32))
+
+
+# ------------------------------------------------------------------------------ top-k
+def run_topk(est32, k):
+    d = est32.size
+    est = dev(est32)
+    idx = torch.empty(k, dtype=torch.int64, device=DEV)
+    val = torch.empty(k, dtype=torch.float32, device=DEV)
+    ws = torch.empty(cs.cs_topk_workspace_bytes(d, k), dtype=torch.uint8, device=DEV)
+    ws.fill_(0xAB)      # contents on entry must not matter
+    cs.cs_heavy_hitters_topk(est, k, idx, val, ws)
+    return idx.cpu().numpy(), val.cpu().numpy()
+
+
+@pytest.mark.parametrize("d,k", [(1, 1), (5, 5), (1000, 1), (1023, 37), (1025, 1025), (4096, 256),
+                                 (1_000_003, 1000), (1_000_003, 999_999), (5_000_011, 50_000)])
+@pytest.mark.parametrize("kind", ["gauss", "ties", "zeros"])
+def test_topk_exact(d, k, kind):
+    rng = np.random.default_rng(d + k)
+    if kind == "gauss":
+        est = (rng.standard_normal(d) * 0.01).astype(np.float32)
+    elif kind == "ties":                       # heavy ties, both signs, signed zeros
+        est = (np.round(rng.standard_normal(d) * 3) / 4).astype(np.float32)
+        est[::7] *= -1
+    else:
+        est = np.zeros(d, dtype=np.float32)
+        est[1::2] = -0.0
+    want = orc.topk_threshold(est, k) if d > (1 << 18) else orc.topk(est, k)
+    idx, val = run_topk(est, k)
+    np.testing.assert_array_equal(idx, want)
+    np.testing.assert_array_equal(val.view(np.uint32), est[want].view(np.uint32))
+
+
+def test_topk_extreme_values_and_unaligned_input():
+    d, k = 100_003, 10
+    est = (np.random.default_rng(0).standard_normal(d)).astype(np.float32)
+    est[17] = np.float32(3.4e38)
+    est[99_999] = -np.float32(3.4e38)
+    est[5] = np.float32(1e-45)                  # subnormal: smallest positive key
+    base = torch.empty(d + 1, dtype=torch.float32, device=DEV)
+    base[1:] = dev(est)
+    view = base[1:]                             # 4-byte aligned only
+    idx = torch.empty(k, dtype=torch.int64, device=DEV)
+    val = torch.empty(k, dtype=torch.float32, device=DEV)
+    ws = torch.empty(cs.cs_topk_workspace_bytes(d, k), dtype=torch.uint8, device=DEV)
+    cs.cs_heavy_hitters_topk(view, k, idx, val, ws)
+    want = orc.topk(est, k)
+    np.testing.assert_array_equal(idx.cpu().numpy(), want)
+    assert 17 in want and 99_999 in want
+
+
+# ------------------------------------------------------------------------------ gather / feedback
+@pytest.mark.parametrize("W", [1, 4, 70])
+def test_gather_exact(W):
+    d, k = 300_007, 5000
+    rng = np.random.default_rng(W)
+    vecs = [rng.standard_normal(d).astype(np.float32) for _ in range(W)]
+    idx = np.sort(rng.choice(d, k, replace=False))
+    out = torch.empty(k, dtype=torch.float32, device=DEV)
+    cs.cs_gather_exact([dev(v) for v in vecs], dev(idx), out, alpha=1.0 / W)
+    ref = orc.gather_exact(vecs, idx, 1.0 / W)
+    scale = 1.0 / np.sqrt(W)
+    assert_values_close(out.cpu().numpy(), ref, scale)
+
+
+def test_feedback_removes_estimated_values():
+    r, c, seed, d, k = 5, 1 << 12, 21, 1 << 16, 300
+    p = cs.cs_params_init(r, c, seed, d)
+    sk = orc.SketchOracle(r, c, seed)
+    rng = np.random.default_rng(2)
+    T32 = rng.standard_normal((r, c)).astype(np.float32)
+    idx = np.sort(rng.choice(d, k, replace=False))
+    S = dev(T32)
+    val = torch.empty(k, dtype=torch.float32, device=DEV)
+    cs.cs_sketch_feedback(p, S, dev(idx), val)
+    T = T32.astype(np.float64)
+    ref_val = sk.estimate_sparse(T, idx)
+    np.testing.assert_array_equal(val.cpu().numpy(), ref_val.astype(np.float32))
+    sk.accumulate_sparse(T, idx, ref_val, scale=-1.0)
+    assert_cells_close(S.cpu().numpy(), T)
