@@ -23,28 +23,39 @@ uint64_t mulmod(uint64_t a, uint64_t b) { return (uint64_t)(((u128)a * b) % kP61
 // Lane stride for one row.
 //
 // Along coordinates i, i + D, i + 2D, ... the hash value moves by AD = a*D mod p each time,
-// and the bucket (value mod c, c | 2^61 so p = -1 mod c) by (AD mod c) plus 1 whenever the
-// value wraps past p: on average by  sigma(D) = (AD mod c) + AD / p  buckets, read as a
-// signed number in (-c/2, c/2].  We want the smallest D whose |sigma| is at most
-// `max_adv` buckets, so that `lanes` lanes taking coordinates D apart touch a contiguous
-// stretch of about lanes * |sigma| cells.  D is capped by the vector length: a group of
-// lanes spans lanes * D coordinates.  A brute-force scan over D is cheap (one 64-bit add
-// per candidate) and runs once per sketch.
-void plan_row(cs_row_plan* rp, uint64_t a, uint64_t as, uint32_t c, bool pow2,
-              uint64_t d_cap, double max_adv) {
-    rp->D = 1;
-    if (pow2 && c >= 64 && d_cap > 1) {
-        uint64_t x = 0;                      // (a * D) mod p
+// and the bucket (value mod c; c | 2^61 so p = -1 mod c) by (AD mod c), plus 1 whenever the
+// value wraps past p: on average by  sigma(D) = (AD mod c) + AD / p  buckets, read as a signed
+// number in (-c/2, c/2].  64 lanes taking coordinates D apart touch a stretch of about
+// 64 |sigma| cells, i.e. about 4 |sigma| + 1 requests of 64 bytes.  A super-tile is 64 D
+// coordinates, so lanes idle when 64 D does not divide into the vector length d.  The plan
+// minimises (requests per wavefront) x (idle-lane overhead) over all D by brute force: one
+// 64-bit add per candidate, once per sketch.
+void plan_row(cs_row_plan* rp, uint64_t a, uint64_t as, uint32_t c, bool pow2, uint64_t d_hint) {
+    uint64_t best_D = 1;
+    if (pow2 && c >= 64) {
+        const uint64_t d_eff = d_hint ? d_hint : 64ull * c;
+        uint64_t d_max = d_eff / 8;                     // at least 8 of 64 lanes busy
+        if (d_max > 4ull * c) d_max = 4ull * c;
+        double best_cost = 1e300, best_adv = 1e300;
+        uint64_t x = 0;                                 // (a * D) mod p
         const double inv_p = 1.0 / (double)kP61;
-        for (uint64_t D = 1; D <= d_cap; ++D) {
+        for (uint64_t D = 1; D <= d_max; ++D) {
             x += a;
             if (x >= kP61) x -= kP61;
             double adv = (double)(x & (c - 1)) + (double)x * inv_p;   // [0, c + 1)
             if (adv > 0.5 * c) adv -= (double)c;
             if (adv < 0) adv = -adv;
-            if (adv <= max_adv) { rp->D = D; break; }
+            if (adv >= best_adv) continue;              // only record-breaking advances matter
+            best_adv = adv;
+            double req = 4.0 * adv + 1.0;
+            if (req > 64.0) req = 64.0;
+            const uint64_t span = 64 * D;
+            const double waste = (double)(((d_eff + span - 1) / span) * span) / (double)d_eff;
+            const double cost = req * waste;
+            if (cost < best_cost) { best_cost = cost; best_D = D; }
         }
     }
+    rp->D = best_D;
     rp->AD = mulmod(a, rp->D);
     rp->ADs = mulmod(as, rp->D);
     int64_t step = (int64_t)(rp->AD % c);
@@ -74,17 +85,9 @@ extern "C" int cs_params_init(cs_params* p, uint32_t r, uint32_t c, uint64_t see
         p->as[j] = 1 + splitmix64(&st) % (kP61 - 1);
         p->bs[j] = splitmix64(&st) % kP61;
     }
-    // Traversal plan.  A group of `lanes` lanes covers lanes * D coordinates, so D is kept
-    // below d / lanes (with d unknown, below c: Dirichlet's bound guarantees |sigma| <= 1 for
-    // some D <= c).
     p->lanes = 64;
-    uint64_t d_cap = c;
-    if (d_hint > 0) {
-        uint64_t lim = (uint64_t)d_hint / p->lanes;
-        if (lim < d_cap) d_cap = lim;
-    }
     for (uint32_t j = 0; j < r; ++j)
-        plan_row(&p->plan[j], p->a[j], p->as[j], c, p->c_pow2 != 0, d_cap, 1.0);
+        plan_row(&p->plan[j], p->a[j], p->as[j], c, p->c_pow2 != 0, (uint64_t)d_hint);
     return CS_OK;
 }
 

@@ -1,0 +1,30 @@
+// Declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "csketch.h"
+
+namespace cs {
+
+constexpr int kMaxBatch = 32;   // workers per launch of the batched update kernels
+
+// kernel argument block: worker w's table and vector
+struct LatticePtrs {
+    float* S[kMaxBatch];
+    const float* g[kMaxBatch];
+};
+
+// True when the stride-aligned traversal is used for vectors of length d with this sketch
+// (power-of-two c, a stride found for every row, d large enough to fill tiles).
+bool lattice_applies(const cs_params* p, int64_t d);
+
+int launch_accumulate_lattice(const cs_params* p, const LatticePtrs& ptrs, int nw, int64_t d,
+                              int64_t i0, float scale, hipStream_t stream);
+int launch_estimate_lattice(const cs_params* p, const float* S, int64_t d, int64_t i0,
+                            float* est, float* rows, hipStream_t stream);
+int launch_hash_range_lattice(const cs_params* p, int64_t i0, int64_t n, uint32_t* bucket,
+                              int8_t* sign, hipStream_t stream);
+
+}  // namespace cs

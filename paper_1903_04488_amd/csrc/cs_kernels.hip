@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include "cs_device.h"
+#include "cs_internal.h"
 #include "csketch.h"
 
 namespace cs {
@@ -112,12 +113,7 @@ k_hash_range(cs_params p, int64_t i0, int64_t n, uint32_t* __restrict__ bucket,
 // ---------------------------------------------------------------------------------------
 // sketch_accumulate: Alg. 4 update over a dense vector
 // ---------------------------------------------------------------------------------------
-constexpr int kMaxBatch = 32;   // workers per launch of the batched kernels
-
-struct BatchPtrs {
-    float* S[kMaxBatch];
-    const float* g[kMaxBatch];
-};
+using BatchPtrs = LatticePtrs;
 
 // One thread per coordinate, grid-stride; the gradient is read coalesced, the r updates go
 // out as fp32 atomics.  With NW > 1 the same hash values serve NW workers.
@@ -298,6 +294,7 @@ extern "C" int cs_hash_debug_range(const cs_params* p, int64_t i0, int64_t n,
     if (!params_ok(p) || n < 0 || i0 < 0 || i0 > (int64_t)kP61 - n) return CS_EINVAL;
     if (n == 0) return CS_OK;
     if (!bucket || !sign) return CS_EINVAL;
+    if (lattice_applies(p, n)) return launch_hash_range_lattice(p, i0, n, bucket, sign, as_stream(stream));
     // a small grid on purpose: every thread takes several strided steps
     const unsigned grid = grid_for(n, kBlock * 8, 64);
 #define CALL(R_, P2_) \
@@ -316,6 +313,8 @@ extern "C" int cs_sketch_zero(const cs_params* p, float* S, void* stream) {
 
 static int accumulate_launch(const cs_params* p, const BatchPtrs& ptrs, int nw, int64_t d,
                              int64_t i0, float scale, void* stream) {
+    if (lattice_applies(p, d))
+        return launch_accumulate_lattice(p, ptrs, nw, d, i0, scale, as_stream(stream));
     // at least ~8 coordinates per thread so the per-thread hash set-up is amortised
     const unsigned grid = grid_for(d, kBlock * 8, 256 * 8);
 #define CALL(R_, P2_) \
@@ -406,17 +405,22 @@ extern "C" int cs_sketch_momentum(const cs_params* p, float* S_u, float* S_v, co
 
 extern "C" int cs_estimate_workspace_bytes(const cs_params* p, int64_t d, size_t* bytes) {
     if (!params_ok(p) || d < 0 || !bytes) return CS_EINVAL;
-    *bytes = 0;
+    // the stride-aligned path stores the r signed cells of every coordinate before the median
+    *bytes = lattice_applies(p, d) ? sizeof(float) * static_cast<size_t>(p->r) * static_cast<size_t>(d) : 0;
     return CS_OK;
 }
 
 extern "C" int cs_sketch_estimate(const cs_params* p, const float* S, int64_t d, int64_t i0,
                                   float* est, void* rows_ws, size_t ws_bytes, void* stream) {
-    (void)rows_ws;
-    (void)ws_bytes;
     if (!params_ok(p) || d < 0 || i0 < 0 || i0 > (int64_t)kP61 - d) return CS_EINVAL;
     if (d == 0) return CS_OK;
     if (!S || !est) return CS_EINVAL;
+    if (lattice_applies(p, d)) {
+        const size_t need = sizeof(float) * static_cast<size_t>(p->r) * static_cast<size_t>(d);
+        if (!rows_ws || reinterpret_cast<uintptr_t>(rows_ws) % 4 != 0) return CS_EINVAL;
+        if (ws_bytes < need) return CS_EWORKSPACE;
+        return launch_estimate_lattice(p, S, d, i0, est, static_cast<float*>(rows_ws), as_stream(stream));
+    }
     const unsigned grid = grid_for(d, kBlock * 8, 256 * 8);
 #define CALL(R_, P2_) \
     k_estimate<R_, P2_><<<grid, kBlock, 0, as_stream(stream)>>>(*p, S, d, i0, est)

@@ -42,6 +42,10 @@ def run(config, steps, check_workers=(0,), sample_only_after_first=False, log=pr
     st = orc.SketchSpaceState(sk, c.rho) if c.stateful else None
     dense = orc.DenseState(c.d, st.rho) if (c.stateful and c.d <= (1 << 22)) else None
     swapped_total = 0
+    # largest magnitude every state cell has held so far: the scale of fp32 error after the
+    # feedback cancels a heavy value out of its cell
+    mag_u = np.zeros((c.r, c.c))
+    mag_v = np.zeros((c.r, c.c))
     for t in range(steps):
         log(f"[cfg{c.cfg}] step {t}: d={c.d} W={c.W} r={c.r} c={c.c} k={c.k}", flush=True)
         g_w = [work.gradient(t, w) for w in range(c.W)]
@@ -59,8 +63,10 @@ def run(config, steps, check_workers=(0,), sample_only_after_first=False, log=pr
         if st is not None:
             hp.momentum()
             st.momentum(S_t)
-            assert_cells_close(hp.S_u.cpu().numpy(), st.S_u, what=f"step {t} S_u")
-            assert_cells_close(hp.S_v.cpu().numpy(), st.S_v, what=f"step {t} S_v")
+            mag_u = np.maximum(mag_u * st.rho, np.abs(st.S_u))
+            mag_v = np.maximum(mag_v, np.abs(st.S_v))
+            assert_cells_close(hp.S_u.cpu().numpy(), st.S_u, what=f"step {t} S_u", operand_mag=mag_u)
+            assert_cells_close(hp.S_v.cpu().numpy(), st.S_v, what=f"step {t} S_v", operand_mag=mag_v)
             if dense is not None:
                 dense.momentum(gsum / c.W)
         query = st.S_v if st is not None else S_t
@@ -102,13 +108,17 @@ def run(config, steps, check_workers=(0,), sample_only_after_first=False, log=pr
             delta, uhat = st.feedback(idx)
             assert_values_close(hp.delta.cpu().numpy(), delta, sigma, what=f"step {t} delta")
             assert_values_close(hp.uhat.cpu().numpy(), uhat, rms(st.S_u) + 1e-30, what=f"step {t} uhat")
-            assert_cells_close(hp.S_u.cpu().numpy(), st.S_u, what=f"step {t} S_u after feedback")
-            assert_cells_close(hp.S_v.cpu().numpy(), st.S_v, what=f"step {t} S_v after feedback")
+            assert_cells_close(hp.S_u.cpu().numpy(), st.S_u, what=f"step {t} S_u after feedback",
+                               operand_mag=mag_u)
+            assert_cells_close(hp.S_v.cpu().numpy(), st.S_v, what=f"step {t} S_v after feedback",
+                               operand_mag=mag_v)
             if dense is not None:
                 dense.feedback(idx, delta, uhat)
                 # the device tables are the sketch of a well-defined dense state (linearity)
-                assert_cells_close(hp.S_v.cpu().numpy(), sk.sketch(dense.v), what=f"step {t} S(v)")
-                assert_cells_close(hp.S_u.cpu().numpy(), sk.sketch(dense.u), what=f"step {t} S(u)")
+                assert_cells_close(hp.S_v.cpu().numpy(), sk.sketch(dense.v), what=f"step {t} S(v)",
+                                   operand_mag=mag_v)
+                assert_cells_close(hp.S_u.cpu().numpy(), sk.sketch(dense.u), what=f"step {t} S(u)",
+                                   operand_mag=mag_u)
         del g_w
     return swapped_total, work, hp
 
