@@ -1,0 +1,185 @@
+"""Benchmark of the Sketched-SGD hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of W synthetic worker gradients that are
+already resident in HBM: W Count-Sketch updates, merge, sketch-space momentum / error
+accumulation, estimate of every coordinate, top-k, exact second-round gather, sketch-space
+feedback.  Prints ONE JSON line (see the keys below).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+METRIC = "sketch+estimate+top-k throughput, Gcoords/s and % HBM peak at d=100M, r=5"
+# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
+# WRITE_SIZE, each scaled by the same counter on a plain copy kernel); None until measured.
+# Source: profiles/accumulate_cfg4_pmc.txt
+MEASURED_TRAFFIC_BYTES = None
+
+
+def cpu_baseline(cfg, work, sample_acc=8_000_000, sample_est=4_000_000):
+    """The CPU reference as it stands, single-threaded, on a bounded sample of the same
+    workload; scaled to the cost of one full step."""
+    import numpy as np
+    from oracle import cs_oracle as orc
+
+    sk = orc.SketchOracle(cfg.r, cfg.c, cfg.hash_seed)
+    n_acc = min(sample_acc, cfg.d)
+    n_est = min(sample_est, cfg.d)
+    g = work.gradient(0, 0)[:n_acc].cpu().numpy()
+    t0 = time.perf_counter()
+    T = sk.sketch(g)
+    t_acc = (time.perf_counter() - t0) / n_acc            # per coordinate of one worker
+    t0 = time.perf_counter()
+    est = sk.estimate(T, n_est)
+    t_est = (time.perf_counter() - t0) / n_est
+    k_s = max(1, int(cfg.k * n_est / cfg.d))
+    t0 = time.perf_counter()
+    orc.topk_threshold(est, k_s)
+    t_top = (time.perf_counter() - t0) / n_est
+    tabs = [T, T]
+    t0 = time.perf_counter()
+    orc.merge(tabs)
+    t_merge = (time.perf_counter() - t0) / 2 * (cfg.W + (5 if cfg.stateful else 0))
+    step_s = cfg.W * cfg.d * t_acc + cfg.d * (t_est + t_top) + t_merge
+    return {
+        "value": cfg.W * cfg.d / step_s / 1e9,
+        "unit": "Gcoords/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": (f"update of {n_acc} coords of one worker, estimate+top-k of {n_est} coords, "
+                   f"one table merge; scaled to W={cfg.W}, d={cfg.d} (est. {step_s:.1f} s/step)"),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=4)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import workloads as wl
+    from paper_1903_04488_amd import binding as B
+    from paper_1903_04488_amd.pipeline import HotPath
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    cfg = wl.CONFIGS[args.config]
+    work = wl.Workload(cfg, dev)
+    hp = HotPath(cfg.d, cfg.W, cfg.r, cfg.c, cfg.k, cfg.hash_seed, rho=cfg.rho, device=dev)
+
+    # inputs resident in HBM before the timed region: a few distinct steps' worth, cycled
+    bytes_per_set = 4 * cfg.d * cfg.W
+    n_sets = max(1, min(args.steps + args.warmup, int(60e9 // bytes_per_set), 4))
+    sets = [[work.gradient(t, w) for w in range(cfg.W)] for t in range(n_sets)]
+    torch.cuda.synchronize()
+
+    stages = ["accumulate", "merge", "momentum", "estimate", "topk", "gather", "feedback"]
+
+    def one_step(g_w, ev=None):
+        def mark(i):
+            if ev is not None:
+                ev[i].record()
+        # zeroing the worker tables belongs to the update stage; the batched update itself is
+        # bracketed by its own pair of events (ev[8], ev[9]) for the roofline figure
+        mark(0)
+        for S in hp.S_w:
+            B.cs_sketch_zero(hp.params, S)
+        mark(8)
+        B.cs_sketch_accumulate_batch(hp.params, hp.S_w, g_w)
+        mark(9)
+        mark(1)
+        hp.merge(); mark(2)
+        hp.momentum(); mark(3)
+        hp.estimate(); mark(4)
+        hp.topk(); mark(5)
+        hp.gather(g_w); mark(6)
+        hp.feedback(); mark(7)
+
+    for t in range(args.warmup):
+        one_step(sets[t % n_sets])
+    torch.cuda.synchronize()
+
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(10)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(args.steps):
+        one_step(sets[(args.warmup + t) % n_sets], events[t])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms_per_step = elapsed / args.steps * 1e3
+    stage_ms = {}
+    for i, name in enumerate(stages):
+        stage_ms[name] = sum(ev[i].elapsed_time(ev[i + 1]) for ev in events) / args.steps
+    n_launch = (cfg.W + 31) // 32
+    acc_kernel_ms = sum(ev[8].elapsed_time(ev[9]) for ev in events) / args.steps / n_launch
+    value = cfg.W * cfg.d / (ms_per_step * 1e-3) / 1e9
+
+    w_per_launch = min(cfg.W, 32)
+    alg_bytes = 4.0 * w_per_launch * cfg.d + 4.0 * cfg.r * cfg.c * w_per_launch
+    achieved = alg_bytes / (acc_kernel_ms * 1e-3) / 1e9
+    step_alg_bytes = (4.0 * cfg.W * cfg.d + 4.0 * cfg.r * cfg.c * cfg.W          # update
+                      + 4.0 * cfg.r * cfg.c * (cfg.W + 1)                        # merge
+                      + (4.0 * cfg.r * cfg.c * 5 if cfg.stateful else 0.0)       # momentum
+                      + 4.0 * cfg.r * cfg.c + 4.0 * cfg.d                        # estimate
+                      + 4.0 * cfg.d                                              # top-k
+                      + 4.0 * cfg.k * cfg.W)                                     # gather
+    out = {
+        "metric": METRIC,
+        "value": value,
+        "unit": "Gcoords/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"cfg{cfg.cfg} {cfg.name}", "d": cfg.d, "W": cfg.W, "r": cfg.r,
+                   "c": cfg.c, "k": cfg.k, "rho": cfg.rho,
+                   "input_sets_resident": n_sets},
+        "pct_hbm_peak_whole_step": 100.0 * step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "stage_ms": stage_ms,
+        "roofline": {
+            "kernel": "k_accumulate_lattice (cs_sketch_accumulate_batch)",
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC_BYTES,
+            "avg_launch_ms": acc_kernel_ms,
+            "algorithmic_bytes_per_launch": alg_bytes,
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, work)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

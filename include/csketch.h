@@ -66,7 +66,9 @@ typedef struct cs_row_plan {
     uint64_t AD;          /* (a_j  * D) mod p */
     uint64_t ADs;         /* (a'_j * D) mod p */
     int32_t  step;        /* bucket advance per lane: (AD mod c) folded into (-c/2, c/2] */
-    int32_t  reserved;
+    int32_t  scan_steps;  /* 0..4: doubling steps of the in-register pre-aggregation that are
+                             enough to add up the longest run of neighbouring lanes that can
+                             fall into one bucket with this stride */
 } cs_row_plan;
 
 typedef struct cs_params {

@@ -23,7 +23,7 @@ class CsError(RuntimeError):
 
 class CsRowPlan(ctypes.Structure):
     _fields_ = [("D", ctypes.c_uint64), ("AD", ctypes.c_uint64), ("ADs", ctypes.c_uint64),
-                ("step", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("step", ctypes.c_int32), ("scan_steps", ctypes.c_int32)]
 
 
 class CsParams(ctypes.Structure):

@@ -70,6 +70,44 @@ __device__ __forceinline__ void atomic_add_noret(float* addr, float v) {
     __hip_atomic_fetch_add(addr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Lane l receives the value of lane l - N of its row of 16 lanes (DPP row_shr); lanes whose
+// source would lie outside the row receive `fill`.
+template <int N>
+__device__ __forceinline__ uint32_t row_shr(uint32_t v, uint32_t fill) {
+    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(
+        static_cast<int>(fill), static_cast<int>(v), 0x110 + N, 0xf, 0xf, false));
+}
+// Lane l receives the value of lane l + 1 of its row of 16 lanes (DPP row_shl:1), else `fill`.
+__device__ __forceinline__ uint32_t row_shl1(uint32_t v, uint32_t fill) {
+    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(
+        static_cast<int>(fill), static_cast<int>(v), 0x101, 0xf, 0xf, false));
+}
+
+// Wavefront-level pre-aggregation of an atomic add.  Within each row of 16 lanes, every
+// maximal run of consecutive lanes holding the same key is summed (segmented inclusive scan
+// with head flags, offsets 1, 2, 4, 8); returns true in the last lane of each run, whose `v`
+// then holds the run's total.  Only adjacent lanes are ever merged, so the result is right
+// for any key pattern provided no run is longer than 2^nsteps lanes (nsteps = 4 covers a
+// whole row and is always safe; the caller passes the bound that holds for its stride).
+__device__ __forceinline__ bool segment_sum16(uint32_t key, float& v, int nsteps) {
+    const uint32_t kNone = 0xffffffffu;                      // never a valid key
+    const uint32_t head = row_shr<1>(key, kNone) != key ? 1u : 0u;   // first lane of its run
+    uint32_t f = head;
+#define CS_SEG_STEP(N)                                                          \
+    {                                                                           \
+        const float v2 = __uint_as_float(row_shr<N>(__float_as_uint(v), 0u));   \
+        const uint32_t f2 = row_shr<N>(f, 1u);                                  \
+        v += f ? 0.0f : v2;                                                     \
+        f |= f2;                                                                \
+    }
+    if (nsteps > 0) CS_SEG_STEP(1)
+    if (nsteps > 1) CS_SEG_STEP(2)
+    if (nsteps > 2) CS_SEG_STEP(4)
+    if (nsteps > 3) CS_SEG_STEP(8)
+#undef CS_SEG_STEP
+    return row_shl1(head, 1u) != 0u;                         // next lane starts a new run
+}
+
 // median of an odd number R of floats held in registers (compile-time R): odd-even
 // transposition sort, fully unrolled, then the middle element.
 template <int R>

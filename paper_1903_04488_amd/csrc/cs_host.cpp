@@ -28,19 +28,21 @@ uint64_t mulmod(uint64_t a, uint64_t b) { return (uint64_t)(((u128)a * b) % kP61
 // number in (-c/2, c/2].  64 lanes taking coordinates D apart touch a stretch of about
 // 64 |sigma| cells, i.e. about 4 |sigma| + 1 requests of 64 bytes.  A super-tile is 64 D
 // coordinates, so lanes idle when 64 D does not divide into the vector length d.  The plan
-// minimises (requests per wavefront) x (idle-lane overhead) over all D by brute force: one
-// 64-bit add per candidate, once per sketch.
+// minimises (requests per wavefront) x (idle-lane overhead) over the multiples of 4 (so that
+// every lane's run starts on a 16-byte boundary) by brute force: one 64-bit add per
+// candidate, once per sketch.
 void plan_row(cs_row_plan* rp, uint64_t a, uint64_t as, uint32_t c, bool pow2, uint64_t d_hint) {
     uint64_t best_D = 1;
     if (pow2 && c >= 64) {
         const uint64_t d_eff = d_hint ? d_hint : 64ull * c;
         uint64_t d_max = d_eff / 8;                     // at least 8 of 64 lanes busy
-        if (d_max > 4ull * c) d_max = 4ull * c;
+        if (d_max > 16ull * c) d_max = 16ull * c;
         double best_cost = 1e300, best_adv = 1e300;
+        const uint64_t a4 = mulmod(a, 4);
         uint64_t x = 0;                                 // (a * D) mod p
         const double inv_p = 1.0 / (double)kP61;
-        for (uint64_t D = 1; D <= d_max; ++D) {
-            x += a;
+        for (uint64_t D = 4; D <= d_max; D += 4) {
+            x += a4;
             if (x >= kP61) x -= kP61;
             double adv = (double)(x & (c - 1)) + (double)x * inv_p;   // [0, c + 1)
             if (adv > 0.5 * c) adv -= (double)c;
@@ -61,7 +63,23 @@ void plan_row(cs_row_plan* rp, uint64_t a, uint64_t as, uint32_t c, bool pow2, u
     int64_t step = (int64_t)(rp->AD % c);
     if (step > (int64_t)(c / 2)) step -= (int64_t)c;
     rp->step = (int32_t)step;
-    rp->reserved = 0;
+    // Longest run of neighbouring lanes in one bucket.  Rotating a hash value left by
+    // lg(2^61 / c) bits (a multiplication by 2^61 / c mod p) moves the bucket bits to the top, so
+    // the bucket is the position on a circle of circumference p cut into arcs of 2^61 / c, and a
+    // lane step moves that position by exactly Au = (AD * 2^61 / c) mod p.  At most
+    // floor((arc - 1) / min(Au, p - Au)) + 1 consecutive positions fit into one arc.
+    rp->scan_steps = 4;
+    if (pow2) {
+        const uint64_t arc = (1ull << 61) / c;
+        const uint64_t Au = mulmod(rp->AD, arc % kP61);
+        const uint64_t A1 = Au < kP61 - Au ? Au : kP61 - Au;
+        if (A1 > 0) {
+            const uint64_t longest = (arc - 1) / A1 + 1;
+            int steps = 0;
+            while (steps < 4 && (1ull << steps) < longest) ++steps;
+            rp->scan_steps = steps;
+        }
+    }
 }
 
 }  // namespace

@@ -28,7 +28,7 @@
 
 namespace cs {
 
-constexpr int kRun = 32;              // consecutive coordinates per lane and tile
+constexpr int kRun = 16;              // consecutive coordinates per lane and tile
 constexpr int kLdsStride = kRun + 1;  // padded: transposed access without bank conflicts
 
 struct TileGeom {
@@ -71,8 +71,41 @@ __device__ __forceinline__ void tile_hashes(const cs_params& p, int j, const Til
 }
 
 // ---------------------------------------------------------------------------------------
-// Alg. 4 update, lattice order.  grid = (tiles, rows); one wavefront per workgroup.
+// Alg. 4 update, lattice order.  grid = (tiles, rows); one wavefront per workgroup, so LDS
+// traffic of a wavefront is ordered by itself and no barrier is needed.
 // ---------------------------------------------------------------------------------------
+constexpr int kLanesPerRun = kRun / 4;              // lanes that fetch one run as float4 pieces
+constexpr int kRunsPerLoad = 64 / kLanesPerRun;     // runs covered by one wavefront-wide load
+constexpr int kLoads = 64 / kRunsPerLoad;           // float4 loads per lane and tile
+
+// Brings the 64 x kRun tile of one worker's vector into registers: lane L takes floats
+// 4 (L % kLanesPerRun) .. +3 of runs L / kLanesPerRun, + kRunsPerLoad, ...  Strides are
+// multiples of 4 and the vector is 16-byte aligned on the VEC path, so each piece is one
+// aligned 16-byte load.
+template <bool VEC>
+__device__ __forceinline__ void load_tile(const float* __restrict__ gw, int64_t base, int64_t D,
+                                          int mlen, int64_t d, float4 (&pre)[kLoads]) {
+    const int lane = threadIdx.x;
+    const int m4 = (lane % kLanesPerRun) * 4, r0 = lane / kLanesPerRun;
+#pragma unroll
+    for (int q = 0; q < kLoads; ++q) {
+        const int64_t rel = base + static_cast<int64_t>(q * kRunsPerLoad + r0) * D + m4;
+        float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (m4 < mlen) {
+            if (VEC && rel + 4 <= d) {
+                v = *reinterpret_cast<const float4*>(gw + rel);
+            } else {
+                if (rel + 0 < d && m4 + 0 < mlen) v.x = gw[rel + 0];
+                if (rel + 1 < d && m4 + 1 < mlen) v.y = gw[rel + 1];
+                if (rel + 2 < d && m4 + 2 < mlen) v.z = gw[rel + 2];
+                if (rel + 3 < d && m4 + 3 < mlen) v.w = gw[rel + 3];
+            }
+        }
+        pre[q] = v;
+    }
+}
+
+template <bool VEC>
 __global__ void __launch_bounds__(64)
 k_accumulate_lattice(cs_params p, LatticePtrs ptrs, int nw, int64_t d, int64_t i0, float scale) {
     __shared__ float tile_lds[64 * kLdsStride];
@@ -80,34 +113,44 @@ k_accumulate_lattice(cs_params p, LatticePtrs ptrs, int nw, int64_t d, int64_t i
     const int lane = threadIdx.x;
     const TileGeom g = tile_geom(p, j, d);
     const size_t row_off = static_cast<size_t>(j) * p.c;
+    const int nsteps = p.plan[j].scan_steps;
+    const int m4 = (lane % kLanesPerRun) * 4, r0 = lane / kLanesPerRun;
     for (int64_t tile = blockIdx.x; tile < g.ntiles; tile += gridDim.x) {
         uint32_t packed[kRun];
         int64_t base;
         int mlen;
         tile_hashes(p, j, g, tile, i0, packed, &base, &mlen);
         const int64_t my_first = base + static_cast<int64_t>(lane) * g.D;
+        float4 pre[kLoads];
+        load_tile<VEC>(ptrs.g[0], base, g.D, mlen, d, pre);
         for (int w = 0; w < nw; ++w) {
-            const float* __restrict__ gw = ptrs.g[w];
             float* __restrict__ Sw = ptrs.S[w] + row_off;
-            // coalesced load: each pass brings in two runs of kRun floats
-            const int m_ld = lane & (kRun - 1), r_ld = lane >> 5;
-#pragma unroll 8
-            for (int rr = 0; rr < 64; rr += 2) {
-                const int run = rr + r_ld;
-                const int64_t rel = base + static_cast<int64_t>(run) * g.D + m_ld;
-                float v = 0.0f;
-                if (m_ld < mlen && rel < d) v = gw[rel];
-                tile_lds[run * kLdsStride + m_ld] = v;
+#pragma unroll
+            for (int q = 0; q < kLoads; ++q) {
+                float* dst = tile_lds + (q * kRunsPerLoad + r0) * kLdsStride + m4;
+                dst[0] = pre[q].x;
+                dst[1] = pre[q].y;
+                dst[2] = pre[q].z;
+                dst[3] = pre[q].w;
             }
-            __syncthreads();
+            __builtin_amdgcn_wave_barrier();
+            // next worker's tile is fetched while this one is applied
+            if (w + 1 < nw) load_tile<VEC>(ptrs.g[w + 1], base, g.D, mlen, d, pre);
 #pragma unroll
             for (int m = 0; m < kRun; ++m) {
-                if (m < mlen && my_first + m < d) {
-                    const float v = scale * tile_lds[lane * kLdsStride + m];
-                    atomic_add_noret(Sw + (packed[m] & 0x7fffffffu), apply_sign(v, packed[m] & 0x80000000u));
-                }
+                // neighbouring lanes often fall into the same cell (the bucket advances by a
+                // fraction of a cell per lane): add them up in registers first, so that one
+                // lane per distinct cell issues the atomic
+                const bool valid = m < mlen && my_first + m < d;
+                const uint32_t cell = packed[m] & 0x7fffffffu;
+                const uint32_t key = valid ? cell : (0xfffffff0u - static_cast<uint32_t>(lane));
+                float v = valid ? apply_sign(scale * tile_lds[lane * kLdsStride + m],
+                                             packed[m] & 0x80000000u)
+                                : 0.0f;
+                const bool issue = segment_sum16(key, v, nsteps);
+                if (issue && valid) atomic_add_noret(Sw + cell, v);
             }
-            __syncthreads();
+            __builtin_amdgcn_wave_barrier();
         }
     }
 }
@@ -139,9 +182,9 @@ k_row_values_lattice(cs_params p, const float* __restrict__ S, int64_t d, int64_
             tile_lds[lane * kLdsStride + m] = v;
         }
         __syncthreads();
-        const int m_st = lane & (kRun - 1), r_st = lane >> 5;
+        const int m_st = lane % kRun, r_st = lane / kRun;
 #pragma unroll 8
-        for (int rr = 0; rr < 64; rr += 2) {
+        for (int rr = 0; rr < 64; rr += 64 / kRun) {
             const int run = rr + r_st;
             const int64_t rel = base + static_cast<int64_t>(run) * g.D + m_st;
             if (m_st < mlen && rel < d) out[rel] = tile_lds[run * kLdsStride + m_st];
@@ -210,7 +253,13 @@ bool lattice_applies(const cs_params* p, int64_t d) {
 int launch_accumulate_lattice(const cs_params* p, const LatticePtrs& ptrs, int nw, int64_t d,
                               int64_t i0, float scale, hipStream_t stream) {
     const dim3 grid(lattice_grid_x(p, d), p->r);
-    k_accumulate_lattice<<<grid, 64, 0, stream>>>(*p, ptrs, nw, d, i0, scale);
+    bool vec = true;                      // 16-byte loads need aligned vectors and strides
+    for (int w = 0; w < nw; ++w) vec = vec && reinterpret_cast<uintptr_t>(ptrs.g[w]) % 16 == 0;
+    for (uint32_t j = 0; j < p->r; ++j) vec = vec && p->plan[j].D % 4 == 0;
+    if (vec)
+        k_accumulate_lattice<true><<<grid, 64, 0, stream>>>(*p, ptrs, nw, d, i0, scale);
+    else
+        k_accumulate_lattice<false><<<grid, 64, 0, stream>>>(*p, ptrs, nw, d, i0, scale);
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
 
