@@ -27,33 +27,31 @@ uint64_t mulmod(uint64_t a, uint64_t b) { return (uint64_t)(((u128)a * b) % kP61
 // value wraps past p: on average by  sigma(D) = (AD mod c) + AD / p  buckets, read as a signed
 // number in (-c/2, c/2].  64 lanes taking coordinates D apart touch a stretch of about
 // 64 |sigma| cells, i.e. about 4 |sigma| + 1 requests of 64 bytes.  A super-tile is 64 D
-// coordinates, so lanes idle when 64 D does not divide into the vector length d.  The plan
-// minimises (requests per wavefront) x (idle-lane overhead) over the multiples of 4 (so that
-// every lane's run starts on a 16-byte boundary) by brute force: one 64-bit add per
-// candidate, once per sketch.
+// coordinates, so lanes idle when 64 D does not divide into the vector length d.  A
+// wavefront step costs about as much instruction issue as one request costs the atomic unit
+// (measured), so the plan minimises (1 + requests per wavefront) x (idle-lane overhead) over
+// all D by brute force: one 64-bit add per candidate, once per sketch.
 void plan_row(cs_row_plan* rp, uint64_t a, uint64_t as, uint32_t c, bool pow2, uint64_t d_hint) {
     uint64_t best_D = 1;
     if (pow2 && c >= 64) {
         const uint64_t d_eff = d_hint ? d_hint : 64ull * c;
         uint64_t d_max = d_eff / 8;                     // at least 8 of 64 lanes busy
         if (d_max > 16ull * c) d_max = 16ull * c;
-        double best_cost = 1e300, best_adv = 1e300;
-        const uint64_t a4 = mulmod(a, 4);
+        double best_cost = 1e300;
         uint64_t x = 0;                                 // (a * D) mod p
         const double inv_p = 1.0 / (double)kP61;
-        for (uint64_t D = 4; D <= d_max; D += 4) {
-            x += a4;
+        for (uint64_t D = 1; D <= d_max; ++D) {
+            x += a;
             if (x >= kP61) x -= kP61;
             double adv = (double)(x & (c - 1)) + (double)x * inv_p;   // [0, c + 1)
             if (adv > 0.5 * c) adv -= (double)c;
             if (adv < 0) adv = -adv;
-            if (adv >= best_adv) continue;              // only record-breaking advances matter
-            best_adv = adv;
+            if (adv > 8.0) continue;                    // more than ~33 requests: never chosen
             double req = 4.0 * adv + 1.0;
             if (req > 64.0) req = 64.0;
             const uint64_t span = 64 * D;
             const double waste = (double)(((d_eff + span - 1) / span) * span) / (double)d_eff;
-            const double cost = req * waste;
+            const double cost = (1.0 + req) * waste;
             if (cost < best_cost) { best_cost = cost; best_D = D; }
         }
     }

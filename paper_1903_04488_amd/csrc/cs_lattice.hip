@@ -78,11 +78,15 @@ constexpr int kLanesPerRun = kRun / 4;              // lanes that fetch one run 
 constexpr int kRunsPerLoad = 64 / kLanesPerRun;     // runs covered by one wavefront-wide load
 constexpr int kLoads = 64 / kRunsPerLoad;           // float4 loads per lane and tile
 
+// four floats that are only 4-byte aligned: global memory takes a 16-byte load at any dword
+// address, and a lane's run starts wherever its stride puts it
+struct __attribute__((packed, aligned(4))) float4u {
+    float x, y, z, w;
+};
+
 // Brings the 64 x kRun tile of one worker's vector into registers: lane L takes floats
-// 4 (L % kLanesPerRun) .. +3 of runs L / kLanesPerRun, + kRunsPerLoad, ...  Strides are
-// multiples of 4 and the vector is 16-byte aligned on the VEC path, so each piece is one
-// aligned 16-byte load.
-template <bool VEC>
+// 4 (L % kLanesPerRun) .. +3 of runs L / kLanesPerRun, + kRunsPerLoad, ..., each piece as one
+// 16-byte load.
 __device__ __forceinline__ void load_tile(const float* __restrict__ gw, int64_t base, int64_t D,
                                           int mlen, int64_t d, float4 (&pre)[kLoads]) {
     const int lane = threadIdx.x;
@@ -92,8 +96,9 @@ __device__ __forceinline__ void load_tile(const float* __restrict__ gw, int64_t 
         const int64_t rel = base + static_cast<int64_t>(q * kRunsPerLoad + r0) * D + m4;
         float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         if (m4 < mlen) {
-            if (VEC && rel + 4 <= d) {
-                v = *reinterpret_cast<const float4*>(gw + rel);
+            if (rel + 4 <= d && m4 + 4 <= mlen) {
+                const float4u u = *reinterpret_cast<const float4u*>(gw + rel);
+                v = make_float4(u.x, u.y, u.z, u.w);
             } else {
                 if (rel + 0 < d && m4 + 0 < mlen) v.x = gw[rel + 0];
                 if (rel + 1 < d && m4 + 1 < mlen) v.y = gw[rel + 1];
@@ -105,7 +110,6 @@ __device__ __forceinline__ void load_tile(const float* __restrict__ gw, int64_t 
     }
 }
 
-template <bool VEC>
 __global__ void __launch_bounds__(64)
 k_accumulate_lattice(cs_params p, LatticePtrs ptrs, int nw, int64_t d, int64_t i0, float scale) {
     __shared__ float tile_lds[64 * kLdsStride];
@@ -122,7 +126,7 @@ k_accumulate_lattice(cs_params p, LatticePtrs ptrs, int nw, int64_t d, int64_t i
         tile_hashes(p, j, g, tile, i0, packed, &base, &mlen);
         const int64_t my_first = base + static_cast<int64_t>(lane) * g.D;
         float4 pre[kLoads];
-        load_tile<VEC>(ptrs.g[0], base, g.D, mlen, d, pre);
+        load_tile(ptrs.g[0], base, g.D, mlen, d, pre);
         for (int w = 0; w < nw; ++w) {
             float* __restrict__ Sw = ptrs.S[w] + row_off;
 #pragma unroll
@@ -135,7 +139,7 @@ k_accumulate_lattice(cs_params p, LatticePtrs ptrs, int nw, int64_t d, int64_t i
             }
             __builtin_amdgcn_wave_barrier();
             // next worker's tile is fetched while this one is applied
-            if (w + 1 < nw) load_tile<VEC>(ptrs.g[w + 1], base, g.D, mlen, d, pre);
+            if (w + 1 < nw) load_tile(ptrs.g[w + 1], base, g.D, mlen, d, pre);
 #pragma unroll
             for (int m = 0; m < kRun; ++m) {
                 // neighbouring lanes often fall into the same cell (the bucket advances by a
@@ -253,13 +257,7 @@ bool lattice_applies(const cs_params* p, int64_t d) {
 int launch_accumulate_lattice(const cs_params* p, const LatticePtrs& ptrs, int nw, int64_t d,
                               int64_t i0, float scale, hipStream_t stream) {
     const dim3 grid(lattice_grid_x(p, d), p->r);
-    bool vec = true;                      // 16-byte loads need aligned vectors and strides
-    for (int w = 0; w < nw; ++w) vec = vec && reinterpret_cast<uintptr_t>(ptrs.g[w]) % 16 == 0;
-    for (uint32_t j = 0; j < p->r; ++j) vec = vec && p->plan[j].D % 4 == 0;
-    if (vec)
-        k_accumulate_lattice<true><<<grid, 64, 0, stream>>>(*p, ptrs, nw, d, i0, scale);
-    else
-        k_accumulate_lattice<false><<<grid, 64, 0, stream>>>(*p, ptrs, nw, d, i0, scale);
+    k_accumulate_lattice<<<grid, 64, 0, stream>>>(*p, ptrs, nw, d, i0, scale);
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
 
