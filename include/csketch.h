@@ -46,7 +46,6 @@ extern "C" {
 #endif
 
 #define CS_MAX_R 16          /* covers the paper's largest sketch (15 rows, Table 1) */
-#define CS_MAX_LANES 64      /* wavefront width; size of the per-row lane-offset tables */
 
 typedef enum cs_status {
     CS_OK = 0,
@@ -58,14 +57,14 @@ typedef enum cs_status {
 /* Traversal of one row (derived from a_j and c; does not change any result).  Because the
  * bucket hash is affine mod p, coordinates i, i + D, i + 2D, ... fall into buckets that
  * advance by a constant (a*D mod p) mod c, plus one for every wrap around p.  D is chosen
- * so that this advance is at most a few buckets: a group of lanes that takes coordinates D
- * apart then touches neighbouring cells of the row, and its atomic adds / gathers share
- * cache lines. */
+ * so that this advance is a fraction of a bucket to a few buckets: a group of `lanes` lanes
+ * that takes coordinates D apart then touches neighbouring cells of the row, and its atomic
+ * adds / gathers share cache lines. */
 typedef struct cs_row_plan {
     uint64_t D;           /* lane stride in coordinates, >= 1 */
     uint64_t AD;          /* (a_j  * D) mod p */
     uint64_t ADs;         /* (a'_j * D) mod p */
-    int32_t  step;        /* bucket advance per lane: (AD mod c) folded into (-c/2, c/2] */
+    int32_t  lanes;       /* lanes per group: 16, 32 or 64 (a wavefront holds 64 / lanes groups) */
     int32_t  scan_steps;  /* 0..4: doubling steps of the in-register pre-aggregation that are
                              enough to add up the longest run of neighbouring lanes that can
                              fall into one bucket with this stride */
@@ -75,7 +74,7 @@ typedef struct cs_params {
     uint32_t r;                 /* rows, odd, 1..CS_MAX_R */
     uint32_t c;                 /* columns, 1..2^31 */
     uint32_t c_pow2;            /* 1 if c is a power of two (fast bucket extraction) */
-    uint32_t lanes;             /* lanes per traversal group (16, 32 or 64) */
+    uint32_t reserved;
     uint64_t seed;
     uint64_t a[CS_MAX_R], b[CS_MAX_R];     /* bucket hashes */
     uint64_t as[CS_MAX_R], bs[CS_MAX_R];   /* sign hashes */

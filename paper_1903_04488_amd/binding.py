@@ -23,12 +23,12 @@ class CsError(RuntimeError):
 
 class CsRowPlan(ctypes.Structure):
     _fields_ = [("D", ctypes.c_uint64), ("AD", ctypes.c_uint64), ("ADs", ctypes.c_uint64),
-                ("step", ctypes.c_int32), ("scan_steps", ctypes.c_int32)]
+                ("lanes", ctypes.c_int32), ("scan_steps", ctypes.c_int32)]
 
 
 class CsParams(ctypes.Structure):
     _fields_ = [("r", ctypes.c_uint32), ("c", ctypes.c_uint32),
-                ("c_pow2", ctypes.c_uint32), ("lanes", ctypes.c_uint32),
+                ("c_pow2", ctypes.c_uint32), ("reserved", ctypes.c_uint32),
                 ("seed", ctypes.c_uint64),
                 ("a", ctypes.c_uint64 * CS_MAX_R), ("b", ctypes.c_uint64 * CS_MAX_R),
                 ("as_", ctypes.c_uint64 * CS_MAX_R), ("bs", ctypes.c_uint64 * CS_MAX_R),

@@ -25,17 +25,19 @@ uint64_t mulmod(uint64_t a, uint64_t b) { return (uint64_t)(((u128)a * b) % kP61
 // Along coordinates i, i + D, i + 2D, ... the hash value moves by AD = a*D mod p each time,
 // and the bucket (value mod c; c | 2^61 so p = -1 mod c) by (AD mod c), plus 1 whenever the
 // value wraps past p: on average by  sigma(D) = (AD mod c) + AD / p  buckets, read as a signed
-// number in (-c/2, c/2].  64 lanes taking coordinates D apart touch a stretch of about
-// 64 |sigma| cells, i.e. about 4 |sigma| + 1 requests of 64 bytes.  A super-tile is 64 D
-// coordinates, so lanes idle when 64 D does not divide into the vector length d.  A
-// wavefront step costs about as much instruction issue as one request costs the atomic unit
-// (measured), so the plan minimises (1 + requests per wavefront) x (idle-lane overhead) over
-// all D by brute force: one 64-bit add per candidate, once per sketch.
+// number in (-c/2, c/2].  A group of L lanes taking coordinates D apart touches a stretch of
+// about L |sigma| cells; a wavefront holds 64 / L groups, so it sends about
+// 4 |sigma| + 64 / L requests of 64 bytes.  A super-tile is L D coordinates, so lanes idle
+// when L D does not divide into the vector length d.  A wavefront step costs about as much
+// instruction issue as one request costs the atomic unit (measured), so the plan minimises
+// (1 + requests per wavefront) x (idle-lane overhead) over all D and L in {16, 32, 64} by
+// brute force: one 64-bit add per candidate D, once per sketch.
 void plan_row(cs_row_plan* rp, uint64_t a, uint64_t as, uint32_t c, bool pow2, uint64_t d_hint) {
     uint64_t best_D = 1;
+    int best_L = 64;
     if (pow2 && c >= 64) {
         const uint64_t d_eff = d_hint ? d_hint : 64ull * c;
-        uint64_t d_max = d_eff / 8;                     // at least 8 of 64 lanes busy
+        uint64_t d_max = d_eff / 8;                     // at least 8 lanes busy
         if (d_max > 16ull * c) d_max = 16ull * c;
         double best_cost = 1e300;
         uint64_t x = 0;                                 // (a * D) mod p
@@ -47,20 +49,19 @@ void plan_row(cs_row_plan* rp, uint64_t a, uint64_t as, uint32_t c, bool pow2, u
             if (adv > 0.5 * c) adv -= (double)c;
             if (adv < 0) adv = -adv;
             if (adv > 8.0) continue;                    // more than ~33 requests: never chosen
-            double req = 4.0 * adv + 1.0;
-            if (req > 64.0) req = 64.0;
-            const uint64_t span = 64 * D;
-            const double waste = (double)(((d_eff + span - 1) / span) * span) / (double)d_eff;
-            const double cost = (1.0 + req) * waste;
-            if (cost < best_cost) { best_cost = cost; best_D = D; }
+            for (int L = 16; L <= 64; L *= 2) {
+                const double req = 4.0 * adv + 64.0 / L;
+                const uint64_t span = (uint64_t)L * D;
+                const double waste = (double)(((d_eff + span - 1) / span) * span) / (double)d_eff;
+                const double cost = (1.0 + req) * waste;
+                if (cost < best_cost) { best_cost = cost; best_D = D; best_L = L; }
+            }
         }
     }
+    rp->lanes = best_L;
     rp->D = best_D;
     rp->AD = mulmod(a, rp->D);
     rp->ADs = mulmod(as, rp->D);
-    int64_t step = (int64_t)(rp->AD % c);
-    if (step > (int64_t)(c / 2)) step -= (int64_t)c;
-    rp->step = (int32_t)step;
     // Longest run of neighbouring lanes in one bucket.  Rotating a hash value left by
     // lg(2^61 / c) bits (a multiplication by 2^61 / c mod p) moves the bucket bits to the top, so
     // the bucket is the position on a circle of circumference p cut into arcs of 2^61 / c, and a
@@ -101,7 +102,6 @@ extern "C" int cs_params_init(cs_params* p, uint32_t r, uint32_t c, uint64_t see
         p->as[j] = 1 + splitmix64(&st) % (kP61 - 1);
         p->bs[j] = splitmix64(&st) % kP61;
     }
-    p->lanes = 64;
     for (uint32_t j = 0; j < r; ++j)
         plan_row(&p->plan[j], p->a[j], p->as[j], c, p->c_pow2 != 0, (uint64_t)d_hint);
     return CS_OK;

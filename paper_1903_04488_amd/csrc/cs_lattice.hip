@@ -4,21 +4,24 @@
 // power of two p = 2^61 - 1 = -1 (mod c).  Hence for any stride D
 //     h(i + D) = h(i) + (a D mod p) mod c  (+1 if the sum wrapped past p)      (mod c),
 // i.e. coordinates D apart advance through the row by a constant number of buckets.  The
-// host picks, per row, a stride D whose advance is a fraction of a bucket to a few buckets
-// (cs_row_plan).  One wavefront then takes 64 coordinates D apart, one per lane: its 64
-// atomic adds (Alg. 4 update) or 64 gathers (Alg. 4 estimate) fall into one short contiguous
-// stretch of the row and travel as a handful of 64-byte requests instead of 64.  The hardware
-// processes atomic requests at a fixed rate per request, not per lane, so this is worth an
-// order of magnitude.  No result changes: every lane still evaluates the hash of its own
-// coordinate exactly; only the order in which coordinates are visited differs.
+// host picks, per row, a stride D whose advance is a fraction of a bucket (cs_row_plan).  A
+// group of L lanes then takes L coordinates D apart, one per lane: its atomic adds (Alg. 4
+// update) or gathers (Alg. 4 estimate) fall into one short contiguous stretch of the row and
+// travel as one or two 64-byte requests instead of L.  The memory system processes atomic
+// requests at a fixed rate per request, not per lane (measured: ~21 G requests/s whatever
+// the table size), so this is worth more than an order of magnitude.  Lanes that fall into
+// the same cell are added up in registers first (segment_sum16).  No result changes: every
+// lane still evaluates the hash of its own coordinate exactly; only the order in which
+// coordinates are visited differs.
 //
-// Traversal.  For a row with stride D the vector [0, d) is cut into super-tiles of 64 D
-// coordinates; lane l owns the block [l D, (l+1) D) of its super-tile and walks it in
-// chunks of kRun consecutive coordinates.  A tile = (super-tile, chunk) = 64 runs of kRun
-// coordinates.  Global memory is always touched coalesced: a run is loaded (stored) by
-// consecutive lanes and the 64 x kRun tile is transposed through LDS, so that afterwards each
-// lane reads (writes) its own run.  A workgroup is one wavefront; nothing is shared between
-// wavefronts.
+// Traversal.  For a row with stride D and group width L the vector [0, d) is cut into
+// super-tiles of L D coordinates; lane l' of a group owns the block [l' D, (l'+1) D) of its
+// super-tile and walks it in chunks of kRun consecutive coordinates.  A wavefront holds
+// G = 64 / L groups working on G neighbouring chunks, so a wavefront tile is 64 runs of kRun
+// coordinates.  Global memory is always touched in whole runs: a run is loaded (stored) as
+// 16-byte pieces by neighbouring lanes and the 64 x kRun tile is transposed through LDS, so
+// that afterwards each lane reads (writes) its own run.  A workgroup is one wavefront;
+// nothing is shared between wavefronts, so LDS needs no barrier.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -28,36 +31,57 @@
 
 namespace cs {
 
-constexpr int kRun = 16;              // consecutive coordinates per lane and tile
-constexpr int kLdsStride = kRun + 1;  // padded: transposed access without bank conflicts
+constexpr int kRun = 16;                            // consecutive coordinates per lane and tile
+constexpr int kLdsStride = kRun + 1;                // padded: transposed access, no bank conflicts
+constexpr int kLanesPerRun = kRun / 4;              // lanes that move one run as 16-byte pieces
+constexpr int kRunsPerPass = 64 / kLanesPerRun;     // runs covered by one wavefront-wide access
+constexpr int kPasses = 64 / kRunsPerPass;          // accesses per lane and tile
+
+// four floats that are only 4-byte aligned: global memory takes a 16-byte access at any dword
+// address, and a lane's run starts wherever its stride puts it
+struct __attribute__((packed, aligned(4))) float4u {
+    float x, y, z, w;
+};
 
 struct TileGeom {
     int64_t D;         // lane stride
-    int64_t chunks;    // ceil(D / kRun)
-    int64_t ntiles;    // super-tiles * chunks
+    int L;             // lanes per group
+    int G;             // groups per wavefront = 64 / L
+    int64_t chunks;    // chunks per lane block = ceil(D / kRun)
+    int64_t wtiles;    // wavefront tiles per super-tile = ceil(chunks / G)
+    int64_t ntiles;    // super-tiles * wtiles
 };
 
-__device__ __forceinline__ TileGeom tile_geom(const cs_params& p, int j, int64_t d) {
+__host__ __device__ __forceinline__ TileGeom tile_geom(const cs_params& p, int j, int64_t d) {
     TileGeom g;
     g.D = static_cast<int64_t>(p.plan[j].D);
+    g.L = p.plan[j].lanes;
+    g.G = 64 / g.L;
     g.chunks = (g.D + kRun - 1) / kRun;
-    const int64_t span = g.D * 64;
-    g.ntiles = ((d + span - 1) / span) * g.chunks;
+    g.wtiles = (g.chunks + g.G - 1) / g.G;
+    const int64_t span = g.D * g.L;
+    g.ntiles = ((d + span - 1) / span) * g.wtiles;
     return g;
 }
 
-// Walks the 64 x kRun tile `tile` of row j: computes, for this lane's run, the packed
-// (bucket | sign bit 31) of each of its coordinates.  Returns the index (relative to the
-// vector) of the lane's first coordinate and the run length of this chunk.
-__device__ __forceinline__ void tile_hashes(const cs_params& p, int j, const TileGeom& g,
-                                            int64_t tile, int64_t i0, uint32_t (&packed)[kRun],
-                                            int64_t* base, int* mlen) {
-    const int lane = threadIdx.x;
-    const int64_t s = tile / g.chunks, t = tile - s * g.chunks;
-    *base = s * g.D * 64 + t * kRun;                       // lane 0's first coordinate
-    const int64_t left = g.D - t * kRun;
-    *mlen = left < kRun ? static_cast<int>(left) : kRun;
-    const uint64_t first = static_cast<uint64_t>(i0 + *base + static_cast<int64_t>(lane) * g.D);
+// Run `rho` (0..63) of wavefront tile `tile`: index of its first coordinate relative to the
+// vector, and how many of its kRun coordinates exist (inside the lane's block and below d).
+__device__ __forceinline__ int run_span(const TileGeom& g, int64_t tile, int rho, int64_t d,
+                                        int64_t* first) {
+    const int64_t s = tile / g.wtiles, tq = tile - s * g.wtiles;
+    const int h = rho / g.L, l = rho - h * g.L;
+    const int64_t t = tq * g.G + h;                        // chunk of this group
+    const int64_t rel = (s * g.L + l) * g.D + t * kRun;
+    *first = rel;
+    int64_t len = g.D - t * kRun;                          // left in the lane's block
+    if (d - rel < len) len = d - rel;                      // left in the vector
+    if (len > kRun) len = kRun;
+    return len > 0 ? static_cast<int>(len) : 0;
+}
+
+// packed (bucket | sign bit 31) of the kRun coordinates starting at global index `first`
+__device__ __forceinline__ void run_hashes(const cs_params& p, int j, uint64_t first,
+                                           uint32_t (&packed)[kRun]) {
     uint64_t yb = hash_state(p.a[j], p.b[j], first);
     uint64_t ys = hash_state(p.as[j], p.bs[j], first);
     const uint64_t Ab = p.a[j], As = p.as[j];              // step of one coordinate
@@ -70,43 +94,78 @@ __device__ __forceinline__ void tile_hashes(const cs_params& p, int j, const Til
     }
 }
 
-// ---------------------------------------------------------------------------------------
-// Alg. 4 update, lattice order.  grid = (tiles, rows); one wavefront per workgroup, so LDS
-// traffic of a wavefront is ordered by itself and no barrier is needed.
-// ---------------------------------------------------------------------------------------
-constexpr int kLanesPerRun = kRun / 4;              // lanes that fetch one run as float4 pieces
-constexpr int kRunsPerLoad = 64 / kLanesPerRun;     // runs covered by one wavefront-wide load
-constexpr int kLoads = 64 / kRunsPerLoad;           // float4 loads per lane and tile
-
-// four floats that are only 4-byte aligned: global memory takes a 16-byte load at any dword
-// address, and a lane's run starts wherever its stride puts it
-struct __attribute__((packed, aligned(4))) float4u {
-    float x, y, z, w;
-};
-
-// Brings the 64 x kRun tile of one worker's vector into registers: lane L takes floats
-// 4 (L % kLanesPerRun) .. +3 of runs L / kLanesPerRun, + kRunsPerLoad, ..., each piece as one
-// 16-byte load.
-__device__ __forceinline__ void load_tile(const float* __restrict__ gw, int64_t base, int64_t D,
-                                          int mlen, int64_t d, float4 (&pre)[kLoads]) {
+// Brings the 64 x kRun tile of one vector into registers: lane T takes floats
+// 4 (T % kLanesPerRun) .. +3 of runs T / kLanesPerRun, + kRunsPerPass, ...; positions that do
+// not exist read as 0.
+__device__ __forceinline__ void load_tile(const float* __restrict__ gw, const TileGeom& g,
+                                          int64_t tile, int64_t d, float4 (&pre)[kPasses]) {
     const int lane = threadIdx.x;
     const int m4 = (lane % kLanesPerRun) * 4, r0 = lane / kLanesPerRun;
 #pragma unroll
-    for (int q = 0; q < kLoads; ++q) {
-        const int64_t rel = base + static_cast<int64_t>(q * kRunsPerLoad + r0) * D + m4;
+    for (int q = 0; q < kPasses; ++q) {
+        int64_t first;
+        const int len = run_span(g, tile, q * kRunsPerPass + r0, d, &first);
+        const float* src = gw + first + m4;
         float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        if (m4 < mlen) {
-            if (rel + 4 <= d && m4 + 4 <= mlen) {
-                const float4u u = *reinterpret_cast<const float4u*>(gw + rel);
-                v = make_float4(u.x, u.y, u.z, u.w);
-            } else {
-                if (rel + 0 < d && m4 + 0 < mlen) v.x = gw[rel + 0];
-                if (rel + 1 < d && m4 + 1 < mlen) v.y = gw[rel + 1];
-                if (rel + 2 < d && m4 + 2 < mlen) v.z = gw[rel + 2];
-                if (rel + 3 < d && m4 + 3 < mlen) v.w = gw[rel + 3];
-            }
+        if (m4 + 4 <= len) {
+            const float4u u = *reinterpret_cast<const float4u*>(src);
+            v = make_float4(u.x, u.y, u.z, u.w);
+        } else if (m4 < len) {
+            v.x = src[0];
+            if (m4 + 1 < len) v.y = src[1];
+            if (m4 + 2 < len) v.z = src[2];
         }
         pre[q] = v;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Alg. 4 update, lattice order.  grid = (tiles, rows).
+// ---------------------------------------------------------------------------------------
+template <int NSTEPS>
+__device__ __forceinline__ void accumulate_row(const cs_params& p, const LatticePtrs& ptrs, int nw,
+                                               int64_t d, int64_t i0, float scale, int j,
+                                               float* tile_lds) {
+    const int lane = threadIdx.x;
+    const TileGeom g = tile_geom(p, j, d);
+    const size_t row_off = static_cast<size_t>(j) * p.c;
+    const int m4 = (lane % kLanesPerRun) * 4, r0 = lane / kLanesPerRun;
+    for (int64_t tile = blockIdx.x; tile < g.ntiles; tile += gridDim.x) {
+        int64_t my_first;
+        run_span(g, tile, lane, d, &my_first);
+        uint32_t packed[kRun];
+        run_hashes(p, j, static_cast<uint64_t>(i0 + my_first), packed);
+        float4 pre[kPasses];
+        load_tile(ptrs.g[0], g, tile, d, pre);
+        for (int w = 0; w < nw; ++w) {
+            float* __restrict__ Sw = ptrs.S[w] + row_off;
+#pragma unroll
+            for (int q = 0; q < kPasses; ++q) {
+                float* dst = tile_lds + (q * kRunsPerPass + r0) * kLdsStride + m4;
+                dst[0] = pre[q].x;
+                dst[1] = pre[q].y;
+                dst[2] = pre[q].z;
+                dst[3] = pre[q].w;
+            }
+            __builtin_amdgcn_wave_barrier();
+            float mine[kRun];
+#pragma unroll
+            for (int m = 0; m < kRun; ++m) mine[m] = tile_lds[lane * kLdsStride + m];
+            __builtin_amdgcn_wave_barrier();
+            // the next worker's tile is fetched while this one is applied
+            if (w + 1 < nw) load_tile(ptrs.g[w + 1], g, tile, d, pre);
+#pragma unroll
+            for (int m = 0; m < kRun; ++m) {
+                // Neighbouring lanes often fall into the same cell (the bucket advances by a
+                // fraction of a cell per lane): add them up in registers, so that one lane per
+                // distinct cell issues the atomic.  Positions that do not exist hold 0 and are
+                // harmless wherever they land; totals of exactly 0 are not sent.
+                const uint32_t cell = packed[m] & 0x7fffffffu;
+                float v = apply_sign(scale * mine[m], packed[m] & 0x80000000u);
+                const bool last = segment_sum16(cell, v, NSTEPS);
+                if (last && v != 0.0f) atomic_add_noret(Sw + cell, v);
+            }
+        }
     }
 }
 
@@ -114,48 +173,12 @@ __global__ void __launch_bounds__(64)
 k_accumulate_lattice(cs_params p, LatticePtrs ptrs, int nw, int64_t d, int64_t i0, float scale) {
     __shared__ float tile_lds[64 * kLdsStride];
     const int j = blockIdx.y;
-    const int lane = threadIdx.x;
-    const TileGeom g = tile_geom(p, j, d);
-    const size_t row_off = static_cast<size_t>(j) * p.c;
-    const int nsteps = p.plan[j].scan_steps;
-    const int m4 = (lane % kLanesPerRun) * 4, r0 = lane / kLanesPerRun;
-    for (int64_t tile = blockIdx.x; tile < g.ntiles; tile += gridDim.x) {
-        uint32_t packed[kRun];
-        int64_t base;
-        int mlen;
-        tile_hashes(p, j, g, tile, i0, packed, &base, &mlen);
-        const int64_t my_first = base + static_cast<int64_t>(lane) * g.D;
-        float4 pre[kLoads];
-        load_tile(ptrs.g[0], base, g.D, mlen, d, pre);
-        for (int w = 0; w < nw; ++w) {
-            float* __restrict__ Sw = ptrs.S[w] + row_off;
-#pragma unroll
-            for (int q = 0; q < kLoads; ++q) {
-                float* dst = tile_lds + (q * kRunsPerLoad + r0) * kLdsStride + m4;
-                dst[0] = pre[q].x;
-                dst[1] = pre[q].y;
-                dst[2] = pre[q].z;
-                dst[3] = pre[q].w;
-            }
-            __builtin_amdgcn_wave_barrier();
-            // next worker's tile is fetched while this one is applied
-            if (w + 1 < nw) load_tile(ptrs.g[w + 1], base, g.D, mlen, d, pre);
-#pragma unroll
-            for (int m = 0; m < kRun; ++m) {
-                // neighbouring lanes often fall into the same cell (the bucket advances by a
-                // fraction of a cell per lane): add them up in registers first, so that one
-                // lane per distinct cell issues the atomic
-                const bool valid = m < mlen && my_first + m < d;
-                const uint32_t cell = packed[m] & 0x7fffffffu;
-                const uint32_t key = valid ? cell : (0xfffffff0u - static_cast<uint32_t>(lane));
-                float v = valid ? apply_sign(scale * tile_lds[lane * kLdsStride + m],
-                                             packed[m] & 0x80000000u)
-                                : 0.0f;
-                const bool issue = segment_sum16(key, v, nsteps);
-                if (issue && valid) atomic_add_noret(Sw + cell, v);
-            }
-            __builtin_amdgcn_wave_barrier();
-        }
+    switch (p.plan[j].scan_steps) {       // uniform: compile-time scan depth inside
+        case 0: accumulate_row<0>(p, ptrs, nw, d, i0, scale, j, tile_lds); break;
+        case 1: accumulate_row<1>(p, ptrs, nw, d, i0, scale, j, tile_lds); break;
+        case 2: accumulate_row<2>(p, ptrs, nw, d, i0, scale, j, tile_lds); break;
+        case 3: accumulate_row<3>(p, ptrs, nw, d, i0, scale, j, tile_lds); break;
+        default: accumulate_row<4>(p, ptrs, nw, d, i0, scale, j, tile_lds); break;
     }
 }
 
@@ -172,28 +195,36 @@ k_row_values_lattice(cs_params p, const float* __restrict__ S, int64_t d, int64_
     const TileGeom g = tile_geom(p, j, d);
     const float* __restrict__ Sj = S + static_cast<size_t>(j) * p.c;
     float* __restrict__ out = rows + static_cast<size_t>(j) * d;
+    const int m4 = (lane % kLanesPerRun) * 4, r0 = lane / kLanesPerRun;
     for (int64_t tile = blockIdx.x; tile < g.ntiles; tile += gridDim.x) {
+        int64_t my_first;
+        const int my_len = run_span(g, tile, lane, d, &my_first);
         uint32_t packed[kRun];
-        int64_t base;
-        int mlen;
-        tile_hashes(p, j, g, tile, i0, packed, &base, &mlen);
-        const int64_t my_first = base + static_cast<int64_t>(lane) * g.D;
+        run_hashes(p, j, static_cast<uint64_t>(i0 + my_first), packed);
 #pragma unroll
         for (int m = 0; m < kRun; ++m) {
             float v = 0.0f;
-            if (m < mlen && my_first + m < d)
-                v = apply_sign(Sj[packed[m] & 0x7fffffffu], packed[m] & 0x80000000u);
+            if (m < my_len) v = apply_sign(Sj[packed[m] & 0x7fffffffu], packed[m] & 0x80000000u);
             tile_lds[lane * kLdsStride + m] = v;
         }
-        __syncthreads();
-        const int m_st = lane % kRun, r_st = lane / kRun;
-#pragma unroll 8
-        for (int rr = 0; rr < 64; rr += 64 / kRun) {
-            const int run = rr + r_st;
-            const int64_t rel = base + static_cast<int64_t>(run) * g.D + m_st;
-            if (m_st < mlen && rel < d) out[rel] = tile_lds[run * kLdsStride + m_st];
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int q = 0; q < kPasses; ++q) {
+            int64_t first;
+            const int len = run_span(g, tile, q * kRunsPerPass + r0, d, &first);
+            const float* src = tile_lds + (q * kRunsPerPass + r0) * kLdsStride + m4;
+            float* dst = out + first + m4;
+            if (m4 + 4 <= len) {
+                float4u u;
+                u.x = src[0]; u.y = src[1]; u.z = src[2]; u.w = src[3];
+                *reinterpret_cast<float4u*>(dst) = u;
+            } else if (m4 < len) {
+                dst[0] = src[0];
+                if (m4 + 1 < len) dst[1] = src[1];
+                if (m4 + 2 < len) dst[2] = src[2];
+            }
         }
-        __syncthreads();
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
@@ -217,14 +248,13 @@ k_hash_range_lattice(cs_params p, int64_t i0, int64_t n, uint32_t* __restrict__ 
     const int lane = threadIdx.x;
     const TileGeom g = tile_geom(p, j, n);
     for (int64_t tile = blockIdx.x; tile < g.ntiles; tile += gridDim.x) {
+        int64_t my_first;
+        const int my_len = run_span(g, tile, lane, n, &my_first);
         uint32_t packed[kRun];
-        int64_t base;
-        int mlen;
-        tile_hashes(p, j, g, tile, i0, packed, &base, &mlen);
-        const int64_t my_first = base + static_cast<int64_t>(lane) * g.D;
+        run_hashes(p, j, static_cast<uint64_t>(i0 + my_first), packed);
 #pragma unroll
         for (int m = 0; m < kRun; ++m) {
-            if (m < mlen && my_first + m < n) {
+            if (m < my_len) {
                 bucket[static_cast<size_t>(j) * n + my_first + m] = packed[m] & 0x7fffffffu;
                 sign[static_cast<size_t>(j) * n + my_first + m] = (packed[m] >> 31) ? -1 : 1;
             }
@@ -238,10 +268,8 @@ k_hash_range_lattice(cs_params p, int64_t i0, int64_t n, uint32_t* __restrict__ 
 static unsigned lattice_grid_x(const cs_params* p, int64_t d) {
     int64_t most = 1;
     for (uint32_t j = 0; j < p->r; ++j) {
-        const int64_t D = static_cast<int64_t>(p->plan[j].D);
-        const int64_t chunks = (D + kRun - 1) / kRun;
-        const int64_t nt = ((d + D * 64 - 1) / (D * 64)) * chunks;
-        if (nt > most) most = nt;
+        const TileGeom g = tile_geom(*p, static_cast<int>(j), d);
+        if (g.ntiles > most) most = g.ntiles;
     }
     const int64_t cap = 256 * 64;      // workgroups of one wavefront: plenty per CU
     return static_cast<unsigned>(most < cap ? most : cap);
@@ -249,8 +277,11 @@ static unsigned lattice_grid_x(const cs_params* p, int64_t d) {
 
 bool lattice_applies(const cs_params* p, int64_t d) {
     if (!p->c_pow2 || p->c < 64 || d < 4096) return false;
-    for (uint32_t j = 0; j < p->r; ++j)
-        if (p->plan[j].D <= 1) return false;
+    for (uint32_t j = 0; j < p->r; ++j) {
+        const int L = p->plan[j].lanes;
+        if (p->plan[j].D <= 1 || (L != 16 && L != 32 && L != 64)) return false;
+        if (p->plan[j].scan_steps < 0 || p->plan[j].scan_steps > 4) return false;
+    }
     return true;
 }
 

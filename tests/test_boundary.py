@@ -48,15 +48,20 @@ def test_traversal_plan_is_consistent(lib):
     for r, c, seed, d in [(5, 1 << 20, 190304492, 10**8), (5, 1 << 15, 190304489, 1 << 20),
                           (7, 1000, 3, 0), (5, 1 << 17, 9, 100)]:
         p = cs.cs_params_init(r, c, seed, d)
-        assert p.lanes in (16, 32, 64)
         for j in range(r):
             pl = p.plan[j]
-            assert pl.D >= 1
+            assert pl.D >= 1 and pl.lanes in (16, 32, 64) and 0 <= pl.scan_steps <= 4
             if d:
-                assert pl.D <= max(d // 8, 1)      # at least 8 of the 64 lanes have work
+                assert pl.D <= max(d // 8, 1)      # at least 8 lanes have work
             assert pl.AD == (p.a[j] * pl.D) % P
             assert pl.ADs == (p.as_[j] * pl.D) % P
-            assert (pl.step - pl.AD) % c == 0 and -c // 2 <= pl.step <= c // 2 + 1
+            if p.c_pow2:
+                # scan_steps covers the longest run of neighbouring lanes in one bucket
+                arc = (1 << 61) // c
+                Au = (pl.AD * arc) % P
+                A1 = min(Au, P - Au)
+                longest = (arc - 1) // A1 + 1 if A1 else 1 << 60
+                assert (1 << pl.scan_steps) >= min(longest, 16)
 
 
 def test_invalid_arguments_are_rejected_without_a_gpu(lib):
