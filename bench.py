@@ -104,10 +104,9 @@ def main():
         # zeroing the worker tables belongs to the update stage; the batched update itself is
         # bracketed by its own pair of events (ev[8], ev[9]) for the roofline figure
         mark(0)
-        for S in hp.S_w:
-            B.cs_sketch_zero(hp.params, S)
+        B.cs_bundle_zero(hp.params, hp.T, hp.W)
         mark(8)
-        B.cs_sketch_accumulate_batch(hp.params, hp.S_w, g_w)
+        B.cs_sketch_accumulate_bundle(hp.params, hp.T, g_w)
         mark(9)
         mark(1)
         hp.merge(); mark(2)
@@ -165,7 +164,7 @@ def main():
         "pct_hbm_peak_whole_step": 100.0 * step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "stage_ms": stage_ms,
         "roofline": {
-            "kernel": "k_accumulate_lattice (cs_sketch_accumulate_batch)",
+            "kernel": "k_accumulate_walk (cs_sketch_accumulate_bundle)",
             "bound": "hbm",
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,

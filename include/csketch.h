@@ -56,18 +56,24 @@ typedef enum cs_status {
 
 /* Traversal of one row (derived from a_j and c; does not change any result).  Because the
  * bucket hash is affine mod p, coordinates i, i + D, i + 2D, ... fall into buckets that
- * advance by a constant (a*D mod p) mod c, plus one for every wrap around p.  D is chosen
- * so that this advance is a fraction of a bucket to a few buckets: a group of `lanes` lanes
- * that takes coordinates D apart then touches neighbouring cells of the row, and its atomic
- * adds / gathers share cache lines. */
+ * advance by a constant (a*D mod p) mod c, plus one for every wrap around p.  Two strides
+ * with a small advance are kept per row:
+ *   D  for the estimate: a group of `lanes` lanes takes coordinates D apart and so gathers
+ *      from neighbouring cells of the row (shared cache lines);
+ *   Dw for the update: one lane walks i, i + Dw, i + 2 Dw, ... and keeps the running sum of
+ *      the cell it is in, issuing one atomic add per cell it leaves instead of one per
+ *      coordinate. */
 typedef struct cs_row_plan {
-    uint64_t D;           /* lane stride in coordinates, >= 1 */
+    uint64_t D;           /* lane stride of the estimate, >= 1 */
     uint64_t AD;          /* (a_j  * D) mod p */
     uint64_t ADs;         /* (a'_j * D) mod p */
+    uint64_t Dw;          /* walk stride of the update, >= 1 */
+    uint64_t ADw;         /* (a_j  * Dw) mod p */
+    uint64_t ADws;        /* (a'_j * Dw) mod p */
     int32_t  lanes;       /* lanes per group: 16, 32 or 64 (a wavefront holds 64 / lanes groups) */
     int32_t  scan_steps;  /* 0..4: doubling steps of the in-register pre-aggregation that are
                              enough to add up the longest run of neighbouring lanes that can
-                             fall into one bucket with this stride */
+                             fall into one bucket with stride D */
 } cs_row_plan;
 
 typedef struct cs_params {
@@ -113,6 +119,26 @@ int cs_sketch_accumulate(const cs_params* p, float* S, const float* g, int64_t d
  * S_w, g_w: HOST arrays of W device pointers (float[r][c] and float[d] each). W >= 1. */
 int cs_sketch_accumulate_batch(const cs_params* p, float* const* S_w, const float* const* g_w,
                                int32_t W, int64_t d, int64_t i0, float scale, void* stream);
+
+/* Worker bundle: the sketches of W workers stored cell-major, T[j][b][w] = S^w[j][b], i.e.
+ * float[r][c][W] contiguous.  Workers hash identically (same seed), so their updates to one
+ * cell land in W neighbouring floats: the layout that lets one memory request carry the
+ * updates of many workers.  Worker w's sketch is the strided slice T[:, :, w].
+ *
+ * cs_bundle_zero:        T = 0.
+ * cs_sketch_accumulate_bundle:  T[j][h_j(i0+t)][w] += scale * s_j(i0+t) * g_w[w][t] for all
+ *                        w < W, t < d, j < r (Alg. 3 "Compute sketch S^i" for every worker).
+ *                        g_w: HOST array of W device pointers to float[d].  W >= 1.
+ * cs_bundle_merge:       dst[j][b] = beta * dst[j][b] + alpha * sum_{w<W} T[j][b][w]
+ *                        (Alg. 3 "S_t = (1/W) sum_i S_t^i" with alpha = 1/W); dst: device
+ *                        float[r][c], not read when beta == 0; sum in ascending w, fp32.
+ * r * c * W must be below 2^40. */
+int cs_bundle_zero(const cs_params* p, float* T, int32_t W, void* stream);
+int cs_sketch_accumulate_bundle(const cs_params* p, float* T, int32_t W,
+                                const float* const* g_w, int64_t d, int64_t i0, float scale,
+                                void* stream);
+int cs_bundle_merge(const cs_params* p, float* dst, float beta, const float* T, int32_t W,
+                    float alpha, void* stream);
 
 /* Alg. 4 update for a list of (index, value) pairs:
  *     S[j][h_j(idx[t])] += scale * s_j(idx[t]) * val[t]

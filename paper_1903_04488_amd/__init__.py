@@ -9,6 +9,9 @@ from .binding import (  # noqa: F401
     CS_MAX_R,
     CsError,
     CsParams,
+    cs_bundle_merge,
+    cs_bundle_zero,
+    cs_sketch_accumulate_bundle,
     cs_estimate_workspace_bytes,
     cs_gather_exact,
     cs_hash_debug,

@@ -23,6 +23,7 @@ class CsError(RuntimeError):
 
 class CsRowPlan(ctypes.Structure):
     _fields_ = [("D", ctypes.c_uint64), ("AD", ctypes.c_uint64), ("ADs", ctypes.c_uint64),
+                ("Dw", ctypes.c_uint64), ("ADw", ctypes.c_uint64), ("ADws", ctypes.c_uint64),
                 ("lanes", ctypes.c_int32), ("scan_steps", ctypes.c_int32)]
 
 
@@ -53,6 +54,12 @@ _SIGNATURES = {
                                    ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32,
                                    ctypes.c_int64, ctypes.c_int64, ctypes.c_float,
                                    ctypes.c_void_p],
+    "cs_bundle_zero": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p],
+    "cs_sketch_accumulate_bundle": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_int32,
+                                    ctypes.POINTER(ctypes.c_void_p), ctypes.c_int64,
+                                    ctypes.c_int64, ctypes.c_float, ctypes.c_void_p],
+    "cs_bundle_merge": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_float,
+                        ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p],
     "cs_sketch_accumulate_sparse": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_void_p,
                                     ctypes.c_void_p, ctypes.c_int64, ctypes.c_float,
                                     ctypes.c_void_p],
@@ -181,6 +188,29 @@ def cs_sketch_accumulate_batch(p, S_w, g_w, i0: int = 0, scale: float = 1.0):
         ctypes.byref(p), _ptr_array(S_w, torch.float32, "S_w", _cells(p)),
         _ptr_array(g_w, torch.float32, "g_w", d), len(S_w), d, i0, scale, _stream(S_w[0])),
         "cs_sketch_accumulate_batch")
+
+
+def cs_bundle_zero(p, T, W: int):
+    _check(load_library().cs_bundle_zero(
+        ctypes.byref(p), _dev(T, torch.float32, "T", _cells(p) * W), W, _stream(T)),
+        "cs_bundle_zero")
+
+
+def cs_sketch_accumulate_bundle(p, T, g_w, i0: int = 0, scale: float = 1.0):
+    W = len(g_w)
+    if W == 0:
+        raise CsError("g_w must be a non-empty list")
+    d = g_w[0].numel()
+    _check(load_library().cs_sketch_accumulate_bundle(
+        ctypes.byref(p), _dev(T, torch.float32, "T", _cells(p) * W), W,
+        _ptr_array(g_w, torch.float32, "g_w", d), d, i0, scale, _stream(T)),
+        "cs_sketch_accumulate_bundle")
+
+
+def cs_bundle_merge(p, dst, T, W: int, alpha: float = 1.0, beta: float = 0.0):
+    _check(load_library().cs_bundle_merge(
+        ctypes.byref(p), _dev(dst, torch.float32, "dst", _cells(p)), beta,
+        _dev(T, torch.float32, "T", _cells(p) * W), W, alpha, _stream(dst)), "cs_bundle_merge")
 
 
 def cs_sketch_accumulate_sparse(p, S, idx, val, scale: float = 1.0):

@@ -8,7 +8,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcsketch.so")
-SOURCES = ["cs_host.cpp", "cs_kernels.hip", "cs_lattice.hip", "cs_topk.hip"]
+SOURCES = ["cs_host.cpp", "cs_kernels.hip", "cs_lattice.hip", "cs_walk.hip", "cs_topk.hip"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -81,6 +81,35 @@ void plan_row(cs_row_plan* rp, uint64_t a, uint64_t as, uint32_t c, bool pow2, u
     }
 }
 
+// Walk stride of the update for one row.
+//
+// A lane that visits i, i + Dw, i + 2 Dw, ... stays in one cell for about 1 / |sigma(Dw)|
+// visits and makes d / Dw visits in all, so it issues about  d/Dw * |sigma| + 1  atomic adds for
+// d / Dw coordinates: |sigma(Dw)| + Dw / d per coordinate.  The plan minimises that sum over all
+// Dw up to d / 2 by brute force.
+void plan_walk(cs_row_plan* rp, uint64_t a, uint64_t as, uint32_t c, bool pow2, uint64_t d_hint) {
+    uint64_t best_D = 1;
+    if (pow2 && c >= 64) {
+        const uint64_t d_eff = d_hint ? d_hint : 64ull * c;
+        const uint64_t d_max = d_eff / 2;
+        double best_cost = 1e300;
+        uint64_t x = 0;                                 // (a * D) mod p
+        const double inv_p = 1.0 / (double)kP61, inv_d = 1.0 / (double)d_eff;
+        for (uint64_t D = 1; D <= d_max; ++D) {
+            x += a;
+            if (x >= kP61) x -= kP61;
+            double adv = (double)(x & (c - 1)) + (double)x * inv_p;   // [0, c + 1)
+            if (adv > 0.5 * c) adv -= (double)c;
+            if (adv < 0) adv = -adv;
+            const double cost = adv + (double)D * inv_d;
+            if (cost < best_cost) { best_cost = cost; best_D = D; }
+        }
+    }
+    rp->Dw = best_D;
+    rp->ADw = mulmod(a, rp->Dw);
+    rp->ADws = mulmod(as, rp->Dw);
+}
+
 }  // namespace
 
 extern "C" int cs_params_init(cs_params* p, uint32_t r, uint32_t c, uint64_t seed,
@@ -103,7 +132,10 @@ extern "C" int cs_params_init(cs_params* p, uint32_t r, uint32_t c, uint64_t see
         p->bs[j] = splitmix64(&st) % kP61;
     }
     for (uint32_t j = 0; j < r; ++j)
+    {
         plan_row(&p->plan[j], p->a[j], p->as[j], c, p->c_pow2 != 0, (uint64_t)d_hint);
+        plan_walk(&p->plan[j], p->a[j], p->as[j], c, p->c_pow2 != 0, (uint64_t)d_hint);
+    }
     return CS_OK;
 }
 

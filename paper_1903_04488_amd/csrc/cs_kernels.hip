@@ -117,9 +117,11 @@ using BatchPtrs = LatticePtrs;
 
 // One thread per coordinate, grid-stride; the gradient is read coalesced, the r updates go
 // out as fp32 atomics.  With NW > 1 the same hash values serve NW workers.
+// `cell_stride` is 1 for separate tables and W for a bundle (S[w] then points at T + w).
 template <int R, bool POW2>
 __global__ void __launch_bounds__(kBlock)
-k_accumulate(cs_params p, BatchPtrs ptrs, int nw, int64_t d, int64_t i0, float scale) {
+k_accumulate(cs_params p, BatchPtrs ptrs, int nw, int64_t d, int64_t i0, float scale,
+             int64_t cell_stride) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
     int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
     if (t >= d) return;
@@ -137,7 +139,8 @@ k_accumulate(cs_params p, BatchPtrs ptrs, int nw, int64_t d, int64_t i0, float s
             const float v = scale * ptrs.g[w][t];
             float* S = ptrs.S[w];
 #pragma unroll
-            for (int j = 0; j < R; ++j) atomic_add_noret(S + cell[j], apply_sign(v, flip[j]));
+            for (int j = 0; j < R; ++j)
+                atomic_add_noret(S + static_cast<size_t>(cell[j]) * cell_stride, apply_sign(v, flip[j]));
         }
         st.advance();
     }
@@ -311,17 +314,23 @@ extern "C" int cs_sketch_zero(const cs_params* p, float* S, void* stream) {
     return launch_status();
 }
 
+static int accumulate_direct(const cs_params* p, const BatchPtrs& ptrs, int nw, int64_t d,
+                             int64_t i0, float scale, int64_t cell_stride, void* stream) {
+    // at least ~8 coordinates per thread so the per-thread hash set-up is amortised
+    const unsigned grid = grid_for(d, kBlock * 8, 256 * 8);
+#define CALL(R_, P2_)                                                                      \
+    k_accumulate<R_, P2_><<<grid, kBlock, 0, as_stream(stream)>>>(*p, ptrs, nw, d, i0, scale, \
+                                                                  cell_stride)
+    CS_DISPATCH_R(p, CALL);
+#undef CALL
+    return launch_status();
+}
+
 static int accumulate_launch(const cs_params* p, const BatchPtrs& ptrs, int nw, int64_t d,
                              int64_t i0, float scale, void* stream) {
     if (lattice_applies(p, d))
         return launch_accumulate_lattice(p, ptrs, nw, d, i0, scale, as_stream(stream));
-    // at least ~8 coordinates per thread so the per-thread hash set-up is amortised
-    const unsigned grid = grid_for(d, kBlock * 8, 256 * 8);
-#define CALL(R_, P2_) \
-    k_accumulate<R_, P2_><<<grid, kBlock, 0, as_stream(stream)>>>(*p, ptrs, nw, d, i0, scale)
-    CS_DISPATCH_R(p, CALL);
-#undef CALL
-    return launch_status();
+    return accumulate_direct(p, ptrs, nw, d, i0, scale, 1, stream);
 }
 
 extern "C" int cs_sketch_accumulate(const cs_params* p, float* S, const float* g, int64_t d,
@@ -329,10 +338,51 @@ extern "C" int cs_sketch_accumulate(const cs_params* p, float* S, const float* g
     if (!params_ok(p) || d < 0 || i0 < 0 || i0 > (int64_t)kP61 - d) return CS_EINVAL;
     if (d == 0) return CS_OK;
     if (!S || !g) return CS_EINVAL;
+    // a single table is a bundle of width 1
+    if (walk_applies(p, d)) return launch_accumulate_walk(p, S, 1, &g, d, i0, scale, as_stream(stream));
     BatchPtrs ptrs{};
     ptrs.S[0] = S;
     ptrs.g[0] = g;
     return accumulate_launch(p, ptrs, 1, d, i0, scale, stream);
+}
+
+static bool bundle_ok(const cs_params* p, int32_t W) {
+    return params_ok(p) && W >= 1 &&
+           static_cast<uint64_t>(p->r) * p->c * static_cast<uint64_t>(W) < (1ull << 40);
+}
+
+extern "C" int cs_bundle_zero(const cs_params* p, float* T, int32_t W, void* stream) {
+    if (!bundle_ok(p, W) || !T) return CS_EINVAL;
+    return launch_bundle_zero(T, static_cast<int64_t>(p->r) * p->c * W, as_stream(stream));
+}
+
+extern "C" int cs_sketch_accumulate_bundle(const cs_params* p, float* T, int32_t W,
+                                           const float* const* g_w, int64_t d, int64_t i0,
+                                           float scale, void* stream) {
+    if (!bundle_ok(p, W) || d < 0 || i0 < 0 || i0 > (int64_t)kP61 - d) return CS_EINVAL;
+    if (!T || !g_w) return CS_EINVAL;
+    for (int w = 0; w < W; ++w)
+        if (!g_w[w] && d > 0) return CS_EINVAL;
+    if (d == 0) return CS_OK;
+    if (walk_applies(p, d)) return launch_accumulate_walk(p, T, W, g_w, d, i0, scale, as_stream(stream));
+    for (int w0 = 0; w0 < W; w0 += kMaxBatch) {
+        const int nw = (W - w0 < kMaxBatch) ? (W - w0) : kMaxBatch;
+        BatchPtrs ptrs{};
+        for (int w = 0; w < nw; ++w) {
+            ptrs.S[w] = T + w0 + w;
+            ptrs.g[w] = g_w[w0 + w];
+        }
+        const int rc = accumulate_direct(p, ptrs, nw, d, i0, scale, W, stream);
+        if (rc != CS_OK) return rc;
+    }
+    return CS_OK;
+}
+
+extern "C" int cs_bundle_merge(const cs_params* p, float* dst, float beta, const float* T,
+                               int32_t W, float alpha, void* stream) {
+    if (!bundle_ok(p, W) || !dst || !T) return CS_EINVAL;
+    return launch_bundle_merge(dst, beta, T, W, alpha, static_cast<int64_t>(p->r) * p->c,
+                               as_stream(stream));
 }
 
 extern "C" int cs_sketch_accumulate_batch(const cs_params* p, float* const* S_w,

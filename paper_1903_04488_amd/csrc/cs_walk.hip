@@ -1,0 +1,288 @@
+// Alg. 4 update for a bundle of workers, "walk" order (power-of-two column counts).
+//
+// What limits the update on this machine is the number of atomic requests that reach memory
+// (a fixed ~21 G requests of 32 bytes per second, measured, whatever the table size), not
+// bytes or flops.  Two facts cut the requests per coordinate by two orders of magnitude:
+//
+//  1. The bucket hash is affine modulo p = 2^61 - 1, so the coordinates i, i + Dw, i + 2 Dw, ...
+//     move through a row by a constant sigma(Dw) buckets per step, and the host can pick a
+//     stride Dw for which that is a small fraction of a bucket (cs_row_plan).  A lane that
+//     walks such a progression stays in one cell for ~1/sigma consecutive visits: it keeps the
+//     running sum in a register and issues one atomic add when it leaves the cell.
+//  2. All workers use the same hash functions, so in the bundle layout T[j][b][w] the sums of
+//     32 workers for one cell are 128 contiguous bytes: 32 lanes (one per worker) flush them as
+//     four full 32-byte requests.
+//
+// Work decomposition for row j: the residues [0, Dw) are cut into chunks of kRun = 16
+// consecutive coordinates; a "walker" owns one chunk and visits it at n Dw for n = 0, 1, ...
+// A wavefront holds 64 / WL walkers of WL lanes each, lane wl of a walker serving worker wl.
+// Every hash value is evaluated exactly (incremental form of the definition), so results are
+// the same sums as in any other order, up to fp32 rounding order.
+//
+// Data movement per visit: the 64 x kRun tile (64 runs = walkers x workers, kRun floats each)
+// is loaded as 16-byte pieces by neighbouring lanes, transposed through LDS so that every
+// lane gets its own run, and the (bucket, sign) of the walker's kRun coordinates are computed
+// once per walker by a few lanes and shared through LDS.  A workgroup is one wavefront;
+// nothing is shared between wavefronts, so LDS needs no barrier.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cs_device.h"
+#include "cs_internal.h"
+#include "csketch.h"
+
+namespace cs {
+
+namespace {
+
+constexpr int kRun = 16;                 // consecutive coordinates per walker
+constexpr int kTileStride = kRun + 1;    // padded LDS row of the value tile
+constexpr int kPieces = kRun / 4;        // 16-byte pieces per run
+constexpr int kRunsPerPass = 64 / kPieces;
+constexpr int kPasses = 64 / kRunsPerPass;
+
+struct __attribute__((packed, aligned(4))) float4u {
+    float x, y, z, w;
+};
+
+struct WalkArgs {
+    const float* g[kMaxBatch];   // vectors of the workers of this launch
+    float* T;                    // bundle, float[r][c][W]
+    int32_t W;                   // bundle width
+    int32_t w0;                  // first worker of this launch
+    int32_t nw;                  // workers in this launch (<= WL)
+    int64_t d, i0;
+    float scale;
+};
+
+// WL = lanes per walker (workers served together): 1, 2, 4, 8, 16 or 32.
+template <int WL>
+__global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a) {
+    constexpr int WPW = 64 / WL;                       // walkers per wavefront
+    constexpr int PPL = (WL >= 16) ? 1 : 16 / WL;      // hash values each lane computes
+    __shared__ float tile_lds[64 * kTileStride];
+    __shared__ uint32_t hash_lds[WPW * kRun];
+    __shared__ const float* gptr_lds[kMaxBatch];
+
+    const int lane = threadIdx.x;
+    const int j = blockIdx.y;
+    const int h = lane / WL, wl = lane % WL;           // my walker, my worker slot
+    if (lane < kMaxBatch) gptr_lds[lane] = a.g[lane < a.nw ? lane : 0];
+    __builtin_amdgcn_wave_barrier();
+
+    const int64_t D = static_cast<int64_t>(p.plan[j].Dw);
+    const uint64_t ADb = p.plan[j].ADw, ADs = p.plan[j].ADws;
+    const int64_t chunks = (D + kRun - 1) / kRun;
+    const int64_t nwaves = (chunks + WPW - 1) / WPW;
+    const uint32_t mask = p.c - 1u;
+    const int64_t d = a.d;
+    float* __restrict__ Tcol = a.T + static_cast<size_t>(j) * p.c * a.W + a.w0 + wl;
+    const bool have_worker = wl < a.nw;
+
+    // loader role: piece m4 of runs r0, r0 + kRunsPerPass, ...; run rho = walker * WL + worker
+    const int m4 = (lane % kPieces) * 4, r0 = lane / kPieces;
+    // hash role: values m0 .. m0 + PPL - 1 of walker h (WL = 32: lanes 0..15 of each walker)
+    const int m0 = (WL >= 16) ? (wl % kRun) : wl * PPL;
+    const bool hash_duty = (WL <= 16) || (wl < kRun);
+
+    for (int64_t wv = blockIdx.x; wv < nwaves; wv += gridDim.x) {
+        const int64_t chunk0 = wv * WPW;               // first walker's chunk
+        const int64_t my_off = (chunk0 + h) * kRun;    // my walker's residue offset in [0, Dw)
+        // hash state of coordinate i0 + my_off + m0 (visit n = 0)
+        uint64_t yb = hash_state(p.a[j], p.b[j], static_cast<uint64_t>(a.i0 + my_off + m0));
+        uint64_t ys = hash_state(p.as[j], p.bs[j], static_cast<uint64_t>(a.i0 + my_off + m0));
+
+        float acc[kRun];
+        uint32_t cur[kRun];
+#pragma unroll
+        for (int m = 0; m < kRun; ++m) { acc[m] = 0.0f; cur[m] = 0xffffffffu; }
+
+        // visits: n D + residue < d; the first walker of the wavefront decides when to stop
+        float4 pre[kPasses];
+        auto load_visit = [&](int64_t nD) {
+#pragma unroll
+            for (int q = 0; q < kPasses; ++q) {
+                const int rho = q * kRunsPerPass + r0;
+                const int rh = rho / WL, rw = rho % WL;
+                const int64_t off = (chunk0 + rh) * kRun;          // residue offset of that run
+                const int64_t rel = nD + off;
+                int64_t len = D - off;
+                if (d - rel < len) len = d - rel;
+                if (rw >= a.nw) len = 0;
+                float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                if (m4 < len) {
+                    const float* src = gptr_lds[rw] + rel + m4;
+                    if (m4 + 4 <= len) {
+                        const float4u u = *reinterpret_cast<const float4u*>(src);
+                        v = make_float4(u.x, u.y, u.z, u.w);
+                    } else {
+                        v.x = src[0];
+                        if (m4 + 1 < len) v.y = src[1];
+                        if (m4 + 2 < len) v.z = src[2];
+                    }
+                }
+                pre[q] = v;
+            }
+        };
+
+        int64_t nD = 0;
+        load_visit(nD);
+        while (nD + chunk0 * kRun < d) {
+            // values: registers -> LDS (run-major) -> my own run
+#pragma unroll
+            for (int q = 0; q < kPasses; ++q) {
+                float* dst = tile_lds + (q * kRunsPerPass + r0) * kTileStride + m4;
+                dst[0] = pre[q].x;
+                dst[1] = pre[q].y;
+                dst[2] = pre[q].z;
+                dst[3] = pre[q].w;
+            }
+            // hashes of this visit: PPL consecutive coordinates from my state
+            if (hash_duty) {
+                uint64_t tb = yb, ts = ys;
+#pragma unroll
+                for (int q = 0; q < PPL; ++q) {
+                    hash_lds[h * kRun + m0 + q] =
+                        ((static_cast<uint32_t>(tb) - 1u) & mask) | sign_flip_of(ts);
+                    if (q + 1 < PPL) {
+                        tb = hash_advance(tb, p.a[j]);
+                        ts = hash_advance(ts, p.as[j]);
+                    }
+                }
+            }
+            yb = hash_advance(yb, ADb);
+            ys = hash_advance(ys, ADs);
+            __builtin_amdgcn_wave_barrier();
+            float mine[kRun];
+            uint32_t packed[kRun];
+#pragma unroll
+            for (int m = 0; m < kRun; ++m) mine[m] = tile_lds[lane * kTileStride + m];
+#pragma unroll
+            for (int m = 0; m < kRun; ++m) packed[m] = hash_lds[h * kRun + m];
+            __builtin_amdgcn_wave_barrier();
+            // next visit's values are fetched while this one is applied
+            nD += D;
+            if (nD + chunk0 * kRun < d) load_visit(nD);
+#pragma unroll
+            for (int m = 0; m < kRun; ++m) {
+                const uint32_t cell = packed[m] & 0x7fffffffu;
+                if (cell != cur[m]) {                      // left the cell: send its sum
+                    if (acc[m] != 0.0f)
+                        atomic_add_noret(Tcol + static_cast<size_t>(cur[m]) * a.W, acc[m]);
+                    cur[m] = cell;
+                    acc[m] = 0.0f;
+                }
+                acc[m] += apply_sign(a.scale * mine[m], packed[m] & 0x80000000u);
+            }
+        }
+#pragma unroll
+        for (int m = 0; m < kRun; ++m)
+            if (acc[m] != 0.0f && have_worker)
+                atomic_add_noret(Tcol + static_cast<size_t>(cur[m]) * a.W, acc[m]);
+    }
+}
+
+template <int WL>
+int launch_walk(const cs_params* p, const WalkArgs& a, hipStream_t stream) {
+    constexpr int WPW = 64 / WL;
+    int64_t most = 1;
+    for (uint32_t j = 0; j < p->r; ++j) {
+        const int64_t chunks = (static_cast<int64_t>(p->plan[j].Dw) + kRun - 1) / kRun;
+        const int64_t nwaves = (chunks + WPW - 1) / WPW;
+        if (nwaves > most) most = nwaves;
+    }
+    const int64_t cap = 256 * 64;
+    const dim3 grid(static_cast<unsigned>(most < cap ? most : cap), p->r);
+    k_accumulate_walk<WL><<<grid, 64, 0, stream>>>(*p, a);
+    return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
+}
+
+}  // namespace
+
+bool walk_applies(const cs_params* p, int64_t d) {
+    if (!p->c_pow2 || p->c < 64 || d < 4096) return false;
+    for (uint32_t j = 0; j < p->r; ++j)
+        if (p->plan[j].Dw <= 1) return false;
+    return true;
+}
+
+int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* const* g_w,
+                           int64_t d, int64_t i0, float scale, hipStream_t stream) {
+    for (int w0 = 0; w0 < W; w0 += kMaxBatch) {
+        WalkArgs a{};
+        a.nw = (W - w0 < kMaxBatch) ? (W - w0) : kMaxBatch;
+        for (int w = 0; w < a.nw; ++w) a.g[w] = g_w[w0 + w];
+        a.T = T;
+        a.W = W;
+        a.w0 = w0;
+        a.d = d;
+        a.i0 = i0;
+        a.scale = scale;
+        int rc;
+        if (a.nw > 16) rc = launch_walk<32>(p, a, stream);
+        else if (a.nw > 8) rc = launch_walk<16>(p, a, stream);
+        else if (a.nw > 4) rc = launch_walk<8>(p, a, stream);
+        else if (a.nw > 2) rc = launch_walk<4>(p, a, stream);
+        else if (a.nw > 1) rc = launch_walk<2>(p, a, stream);
+        else rc = launch_walk<1>(p, a, stream);
+        if (rc != CS_OK) return rc;
+    }
+    return CS_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// bundle-wide elementwise kernels
+// ---------------------------------------------------------------------------------------
+namespace {
+
+__global__ void __launch_bounds__(kBlock) k_bundle_zero(float4* __restrict__ T4, int64_t n4,
+                                                        float* __restrict__ T, int64_t n) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    for (int64_t t = t0; t < n4; t += stride) T4[t] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    for (int64_t t = n4 * 4 + t0; t < n; t += stride) T[t] = 0.0f;
+}
+
+// one thread per cell: sums the W neighbouring floats of its cell in ascending w
+__global__ void __launch_bounds__(kBlock)
+k_bundle_merge(float* __restrict__ dst, float beta, const float* __restrict__ T, int W,
+               float alpha, int64_t cells) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < cells; t += stride) {
+        const float* src = T + static_cast<size_t>(t) * W;
+        float s = 0.0f;
+        if ((W & 3) == 0) {
+            for (int w = 0; w < W; w += 4) {
+                const float4u u = *reinterpret_cast<const float4u*>(src + w);
+                s += u.x; s += u.y; s += u.z; s += u.w;
+            }
+        } else {
+            for (int w = 0; w < W; ++w) s += src[w];
+        }
+        const float base = (beta == 0.0f) ? 0.0f : beta * dst[t];
+        dst[t] = base + alpha * s;
+    }
+}
+
+}  // namespace
+
+int launch_bundle_zero(float* T, int64_t n, hipStream_t stream) {
+    const bool aligned = reinterpret_cast<uintptr_t>(T) % 16 == 0;
+    const int64_t n4 = aligned ? n / 4 : 0;
+    int64_t b = (n / 4 + kBlock - 1) / kBlock;
+    if (b < 1) b = 1;
+    if (b > 256 * 16) b = 256 * 16;
+    k_bundle_zero<<<static_cast<unsigned>(b), kBlock, 0, stream>>>(reinterpret_cast<float4*>(T),
+                                                                   n4, T, n);
+    return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
+}
+
+int launch_bundle_merge(float* dst, float beta, const float* T, int W, float alpha,
+                        int64_t cells, hipStream_t stream) {
+    int64_t b = (cells + kBlock - 1) / kBlock;
+    if (b > 256 * 32) b = 256 * 32;
+    k_bundle_merge<<<static_cast<unsigned>(b), kBlock, 0, stream>>>(dst, beta, T, W, alpha, cells);
+    return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
+}
+
+}  // namespace cs

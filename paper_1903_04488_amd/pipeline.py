@@ -1,8 +1,8 @@
 """One pass of the hot path on one GPU: buffers and the order of library calls, nothing else.
 
 Per step (Alg. 3 of the paper, with the W workers simulated on the one device):
-    worker sketches   S^w = S(g^w)                cs_sketch_accumulate_batch
-    aggregate         S_t = (1/W) sum_w S^w       cs_sketch_merge
+    worker sketches   S^w = S(g^w)                cs_sketch_accumulate_bundle  (T[j][b][w])
+    aggregate         S_t = (1/W) sum_w S^w       cs_bundle_merge
     momentum, error   S_u = rho S_u + S_t ; S_v += S_u      cs_sketch_momentum   (stateful only)
     query all         est = estimate(S_v or S_t)  cs_sketch_estimate
     choose largest    idx = top-k |est|           cs_heavy_hitters_topk
@@ -25,7 +25,8 @@ class HotPath:
         self.device = torch.device(device)
         self.params = B.cs_params_init(r, c, seed, d)
         f32 = dict(dtype=torch.float32, device=self.device)
-        self.S_w = [torch.zeros(r, c, **f32) for _ in range(W)]
+        # the W workers' sketches as one bundle, cell-major: T[j][b][w] = S^w[j][b]
+        self.T = torch.zeros(r, c, W, **f32)
         self.S_t = torch.zeros(r, c, **f32)
         self.S_u = torch.zeros(r, c, **f32) if rho is not None else None
         self.S_v = torch.zeros(r, c, **f32) if rho is not None else None
@@ -42,13 +43,16 @@ class HotPath:
                        if n_est else None)
 
     # individual stages (bench.py times them separately) ---------------------------------
+    def worker_table(self, w: int):
+        """Worker w's own sketch (a strided view of the bundle)."""
+        return self.T[:, :, w]
+
     def accumulate(self, g_w):
-        for S in self.S_w:
-            B.cs_sketch_zero(self.params, S)
-        B.cs_sketch_accumulate_batch(self.params, self.S_w, g_w)
+        B.cs_bundle_zero(self.params, self.T, self.W)
+        B.cs_sketch_accumulate_bundle(self.params, self.T, g_w)
 
     def merge(self):
-        B.cs_sketch_merge(self.params, self.S_t, self.S_w, alpha=1.0 / self.W, beta=0.0)
+        B.cs_bundle_merge(self.params, self.S_t, self.T, self.W, alpha=1.0 / self.W, beta=0.0)
 
     def momentum(self):
         if self.rho is not None:

@@ -53,7 +53,7 @@ def run(config, steps, check_workers=(0,), sample_only_after_first=False, log=pr
         hp.accumulate(g_w)
         for w in check_workers:
             ref_w = sk.sketch(g_w[w].cpu().numpy())
-            assert_cells_close(hp.S_w[w].cpu().numpy(), ref_w, what=f"step {t} worker {w} table")
+            assert_cells_close(hp.worker_table(w).cpu().numpy(), ref_w, what=f"step {t} worker {w} table")
         # ---- aggregate
         hp.merge()
         gsum = host_sum(g_w)

@@ -126,6 +126,34 @@ def test_accumulate_batch(W):
         assert_cells_close(S_w[w].cpu().numpy(), sk.sketch(gs[w], i0=17, scale=0.5), what=f"worker {w}")
 
 
+@pytest.mark.parametrize("W", [1, 2, 3, 5, 8, 13, 16, 32, 37])
+@pytest.mark.parametrize("r,c,seed,d,i0", [(5, 1 << 12, 11, 200_003, 17), (7, 1 << 15, 5, 1_000_003, 0),
+                                           (3, 1000, 9, 50_001, 3), (5, 1 << 10, 2, 1000, 0)])
+def test_accumulate_bundle(W, r, c, seed, d, i0):
+    if W > 8 and d > 500_000:
+        pytest.skip("covered by the smaller shapes")
+    p = cs.cs_params_init(r, c, seed, d)
+    sk = orc.SketchOracle(r, c, seed)
+    rng = np.random.default_rng(W * 1000 + r)
+    gs = [(rng.standard_normal(d) * 0.01).astype(np.float32) for _ in range(W)]
+    for g in gs:
+        g[rng.integers(0, d, size=20)] += 1.0
+    T = torch.full((r, c, W), 0.25, dtype=torch.float32, device=DEV)    # accumulates into T
+    cs.cs_sketch_accumulate_bundle(p, T, [dev(g) for g in gs], i0=i0, scale=0.5)
+    Th = T.cpu().numpy()
+    for w in range(W):
+        ref = sk.accumulate(np.full((r, c), 0.25), gs[w], i0=i0, scale=0.5)
+        assert_cells_close(Th[:, :, w], ref, what=f"worker {w}", terms_per_cell=d / c)
+    # merge of the bundle = (1/W) sum of the workers' tables
+    dst0 = rng.standard_normal((r, c)).astype(np.float32)
+    dst = dev(dst0)
+    cs.cs_bundle_merge(p, dst, T, W, alpha=1.0 / W, beta=0.5)
+    ref = orc.merge([Th[:, :, w] for w in range(W)], alpha=1.0 / W, beta=0.5, dst=dst0)
+    assert_cells_close(dst.cpu().numpy(), ref)
+    cs.cs_bundle_zero(p, T, W)
+    assert (T == 0).all()
+
+
 @pytest.mark.parametrize("r,c,seed", SHAPES[:5])
 def test_accumulate_sparse_with_repeats(r, c, seed):
     p = cs.cs_params_init(r, c, seed)
