@@ -45,6 +45,14 @@ struct __attribute__((packed, aligned(4))) float4u {
     float x, y, z, w;
 };
 
+// Vectors are addressed as global memory explicitly: the pointers pass through an LDS table,
+// and a generic ("flat") load would count against the LDS counter as well and force the
+// hardware to drain both before any data can be used.
+typedef const __attribute__((address_space(1))) float* gfloat_ptr;
+typedef float vec4f __attribute__((ext_vector_type(4)));
+typedef vec4f __attribute__((aligned(4))) vec4f_u;           // 16 bytes at any dword address
+typedef const __attribute__((address_space(1))) vec4f_u* gvec4_ptr;
+
 struct WalkArgs {
     const float* g[kMaxBatch];   // vectors of the workers of this launch
     float* T;                    // bundle, float[r][c][W]
@@ -62,12 +70,12 @@ __global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a)
     constexpr int PPL = (WL >= 16) ? 1 : 16 / WL;      // hash values each lane computes
     __shared__ float tile_lds[64 * kTileStride];
     __shared__ uint32_t hash_lds[WPW * kRun];
-    __shared__ const float* gptr_lds[kMaxBatch];
+    __shared__ gfloat_ptr gptr_lds[kMaxBatch];
 
     const int lane = threadIdx.x;
     const int j = blockIdx.y;
     const int h = lane / WL, wl = lane % WL;           // my walker, my worker slot
-    if (lane < kMaxBatch) gptr_lds[lane] = a.g[lane < a.nw ? lane : 0];
+    if (lane < kMaxBatch) gptr_lds[lane] = (gfloat_ptr)a.g[lane < a.nw ? lane : 0];
     __builtin_amdgcn_wave_barrier();
 
     const int64_t D = static_cast<int64_t>(p.plan[j].Dw);
@@ -99,7 +107,12 @@ __global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a)
 
         // visits: n D + residue < d; the first walker of the wavefront decides when to stop
         float4 pre[kPasses];
+        // All four pieces are requested back to back without a branch in between (a piece
+        // that is not wholly inside its run reads a safe address and is discarded); runs cut
+        // short by the end of the vector or of the residue range are patched up afterwards,
+        // which only the last visit or the last chunk ever needs.
         auto load_visit = [&](int64_t nD) {
+            bool any_partial = false;
 #pragma unroll
             for (int q = 0; q < kPasses; ++q) {
                 const int rho = q * kRunsPerPass + r0;
@@ -109,19 +122,31 @@ __global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a)
                 int64_t len = D - off;
                 if (d - rel < len) len = d - rel;
                 if (rw >= a.nw) len = 0;
-                float4 v = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-                if (m4 < len) {
-                    const float* src = gptr_lds[rw] + rel + m4;
-                    if (m4 + 4 <= len) {
-                        const float4u u = *reinterpret_cast<const float4u*>(src);
-                        v = make_float4(u.x, u.y, u.z, u.w);
-                    } else {
-                        v.x = src[0];
-                        if (m4 + 1 < len) v.y = src[1];
-                        if (m4 + 2 < len) v.z = src[2];
+                const bool full = m4 + 4 <= len;
+                const bool part = !full && m4 < len;
+                const gfloat_ptr base = gptr_lds[rw];
+                const gfloat_ptr src = full ? base + rel + m4 : base;
+                const vec4f u = *(gvec4_ptr)src;
+                pre[q] = full ? make_float4(u.x, u.y, u.z, u.w) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                any_partial |= part;
+            }
+            if (__builtin_amdgcn_ballot_w64(any_partial) != 0) {
+#pragma unroll
+                for (int q = 0; q < kPasses; ++q) {
+                    const int rho = q * kRunsPerPass + r0;
+                    const int rh = rho / WL, rw = rho % WL;
+                    const int64_t off = (chunk0 + rh) * kRun;
+                    const int64_t rel = nD + off;
+                    int64_t len = D - off;
+                    if (d - rel < len) len = d - rel;
+                    if (rw >= a.nw) len = 0;
+                    if (m4 + 4 > len && m4 < len) {
+                        const gfloat_ptr src = gptr_lds[rw] + rel + m4;
+                        pre[q].x = src[0];
+                        if (m4 + 1 < len) pre[q].y = src[1];
+                        if (m4 + 2 < len) pre[q].z = src[2];
                     }
                 }
-                pre[q] = v;
             }
         };
 
