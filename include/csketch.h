@@ -131,7 +131,7 @@ int cs_sketch_accumulate_batch(const cs_params* p, float* const* S_w, const floa
  *                        g_w: HOST array of W device pointers to float[d].  W >= 1.
  * cs_bundle_merge:       dst[j][b] = beta * dst[j][b] + alpha * sum_{w<W} T[j][b][w]
  *                        (Alg. 3 "S_t = (1/W) sum_i S_t^i" with alpha = 1/W); dst: device
- *                        float[r][c], not read when beta == 0; sum in ascending w, fp32.
+ *                        float[r][c], not read when beta == 0; fp32 sum in a fixed order.
  * r * c * W must be below 2^40. */
 int cs_bundle_zero(const cs_params* p, float* T, int32_t W, void* stream);
 int cs_sketch_accumulate_bundle(const cs_params* p, float* T, int32_t W,

@@ -178,27 +178,25 @@ __global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a)
             yb = hash_advance(yb, ADb);
             ys = hash_advance(ys, ADs);
             __builtin_amdgcn_wave_barrier();
-            float mine[kRun];
-            uint32_t packed[kRun];
-#pragma unroll
-            for (int m = 0; m < kRun; ++m) mine[m] = tile_lds[lane * kTileStride + m];
-#pragma unroll
-            for (int m = 0; m < kRun; ++m) packed[m] = hash_lds[h * kRun + m];
-            __builtin_amdgcn_wave_barrier();
-            // next visit's values are fetched while this one is applied
+            // next visit's values are fetched (into registers) while this one is applied
+            // straight out of LDS
             nD += D;
             if (nD + chunk0 * kRun < d) load_visit(nD);
+            const float* my_run = tile_lds + lane * kTileStride;
+            const uint32_t* my_hash = hash_lds + h * kRun;
 #pragma unroll
             for (int m = 0; m < kRun; ++m) {
-                const uint32_t cell = packed[m] & 0x7fffffffu;
+                const uint32_t pk = my_hash[m];
+                const uint32_t cell = pk & 0x7fffffffu;
                 if (cell != cur[m]) {                      // left the cell: send its sum
                     if (acc[m] != 0.0f)
                         atomic_add_noret(Tcol + static_cast<size_t>(cur[m]) * a.W, acc[m]);
                     cur[m] = cell;
                     acc[m] = 0.0f;
                 }
-                acc[m] += apply_sign(a.scale * mine[m], packed[m] & 0x80000000u);
+                acc[m] += apply_sign(a.scale * my_run[m], pk & 0x80000000u);
             }
+            __builtin_amdgcn_wave_barrier();
         }
 #pragma unroll
         for (int m = 0; m < kRun; ++m)
@@ -268,7 +266,7 @@ __global__ void __launch_bounds__(kBlock) k_bundle_zero(float4* __restrict__ T4,
     for (int64_t t = n4 * 4 + t0; t < n; t += stride) T[t] = 0.0f;
 }
 
-// one thread per cell: sums the W neighbouring floats of its cell in ascending w
+// one thread per cell: sums the W neighbouring floats of its cell in ascending w (any W)
 __global__ void __launch_bounds__(kBlock)
 k_bundle_merge(float* __restrict__ dst, float beta, const float* __restrict__ T, int W,
                float alpha, int64_t cells) {
@@ -276,16 +274,38 @@ k_bundle_merge(float* __restrict__ dst, float beta, const float* __restrict__ T,
     for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < cells; t += stride) {
         const float* src = T + static_cast<size_t>(t) * W;
         float s = 0.0f;
-        if ((W & 3) == 0) {
-            for (int w = 0; w < W; w += 4) {
-                const float4u u = *reinterpret_cast<const float4u*>(src + w);
-                s += u.x; s += u.y; s += u.z; s += u.w;
-            }
-        } else {
-            for (int w = 0; w < W; ++w) s += src[w];
-        }
+        for (int w = 0; w < W; ++w) s += src[w];
         const float base = (beta == 0.0f) ? 0.0f : beta * dst[t];
         dst[t] = base + alpha * s;
+    }
+}
+
+// W = 4 * LPC with LPC a power of two <= 64, 16-byte aligned bundle: the bundle is streamed
+// as consecutive 16-byte pieces (fully coalesced); the LPC neighbouring lanes that hold the
+// pieces of one cell add their partial sums with a butterfly, the first of them writes.
+template <int LPC>
+__global__ void __launch_bounds__(kBlock)
+k_bundle_merge_vec(float* __restrict__ dst, float beta, const float4* __restrict__ T4,
+                   float alpha, int64_t cells) {
+    const int64_t pieces = cells * LPC;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;      // multiple of 64
+    const int64_t start = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    // every lane of a wavefront runs the same number of iterations (shuffles need all lanes)
+    const int64_t wave_start = start - (threadIdx.x & 63);
+    for (int64_t base = wave_start; base < pieces; base += stride) {
+        const int64_t t = base + (threadIdx.x & 63);
+        float s = 0.0f;
+        if (t < pieces) {
+            const float4 v = T4[t];
+            s = (v.x + v.y) + (v.z + v.w);
+        }
+#pragma unroll
+        for (int off = 1; off < LPC; off <<= 1) s += __shfl_xor(s, off, 64);
+        if (t < pieces && (t & (LPC - 1)) == 0) {
+            const int64_t cell = t / LPC;
+            const float b = (beta == 0.0f) ? 0.0f : beta * dst[cell];
+            dst[cell] = b + alpha * s;
+        }
     }
 }
 
@@ -304,9 +324,28 @@ int launch_bundle_zero(float* T, int64_t n, hipStream_t stream) {
 
 int launch_bundle_merge(float* dst, float beta, const float* T, int W, float alpha,
                         int64_t cells, hipStream_t stream) {
-    int64_t b = (cells + kBlock - 1) / kBlock;
-    if (b > 256 * 32) b = 256 * 32;
-    k_bundle_merge<<<static_cast<unsigned>(b), kBlock, 0, stream>>>(dst, beta, T, W, alpha, cells);
+    const bool vec_ok = (W % 4 == 0) && ((W / 4) & (W / 4 - 1)) == 0 && W / 4 <= 64 &&
+                        reinterpret_cast<uintptr_t>(T) % 16 == 0;
+    if (vec_ok) {
+        const int lpc = W / 4;
+        int64_t b = (cells * lpc + kBlock - 1) / kBlock;
+        if (b > 256 * 32) b = 256 * 32;
+        const unsigned g = static_cast<unsigned>(b);
+        const float4* T4 = reinterpret_cast<const float4*>(T);
+        switch (lpc) {
+            case 1: k_bundle_merge_vec<1><<<g, kBlock, 0, stream>>>(dst, beta, T4, alpha, cells); break;
+            case 2: k_bundle_merge_vec<2><<<g, kBlock, 0, stream>>>(dst, beta, T4, alpha, cells); break;
+            case 4: k_bundle_merge_vec<4><<<g, kBlock, 0, stream>>>(dst, beta, T4, alpha, cells); break;
+            case 8: k_bundle_merge_vec<8><<<g, kBlock, 0, stream>>>(dst, beta, T4, alpha, cells); break;
+            case 16: k_bundle_merge_vec<16><<<g, kBlock, 0, stream>>>(dst, beta, T4, alpha, cells); break;
+            case 32: k_bundle_merge_vec<32><<<g, kBlock, 0, stream>>>(dst, beta, T4, alpha, cells); break;
+            default: k_bundle_merge_vec<64><<<g, kBlock, 0, stream>>>(dst, beta, T4, alpha, cells); break;
+        }
+    } else {
+        int64_t b = (cells + kBlock - 1) / kBlock;
+        if (b > 256 * 32) b = 256 * 32;
+        k_bundle_merge<<<static_cast<unsigned>(b), kBlock, 0, stream>>>(dst, beta, T, W, alpha, cells);
+    }
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
 
