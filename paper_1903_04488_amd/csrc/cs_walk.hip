@@ -93,7 +93,14 @@ __global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a)
     const int m0 = (WL >= 16) ? (wl % kRun) : wl * PPL;
     const bool hash_duty = (WL <= 16) || (wl < kRun);
 
-    for (int64_t wv = blockIdx.x; wv < nwaves; wv += gridDim.x) {
+    // Workgroups are dealt to the 8 XCDs round-robin; giving XCD x the x-th eighth of the
+    // walkers makes each XCD (and its L2) stream through its own contiguous part of every
+    // vector.  gridDim.x is a multiple of 8.
+    const int64_t per_xcd = (nwaves + 7) / 8;
+    const int64_t xcd_first = static_cast<int64_t>(blockIdx.x & 7) * per_xcd;
+    for (int64_t k = blockIdx.x >> 3; k < per_xcd; k += gridDim.x >> 3) {
+        const int64_t wv = xcd_first + k;
+        if (wv >= nwaves) break;
         const int64_t chunk0 = wv * WPW;               // first walker's chunk
         const int64_t my_off = (chunk0 + h) * kRun;    // my walker's residue offset in [0, Dw)
         // hash state of coordinate i0 + my_off + m0 (visit n = 0)
@@ -215,7 +222,9 @@ int launch_walk(const cs_params* p, const WalkArgs& a, hipStream_t stream) {
         if (nwaves > most) most = nwaves;
     }
     const int64_t cap = 256 * 64;
-    const dim3 grid(static_cast<unsigned>(most < cap ? most : cap), p->r);
+    int64_t gx = most < cap ? most : cap;
+    gx = (gx + 7) / 8 * 8;                   // the kernel deals workgroups to XCDs in eights
+    const dim3 grid(static_cast<unsigned>(gx), p->r);
     k_accumulate_walk<WL><<<grid, 64, 0, stream>>>(*p, a);
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
@@ -229,11 +238,17 @@ bool walk_applies(const cs_params* p, int64_t d) {
     return true;
 }
 
+// Workers are served in groups of kGroup = 8: with 8 lanes per walker a wavefront holds 8
+// walkers on neighbouring chunks, so every load instruction reads 512 contiguous bytes of
+// each worker's vector (measured: 5.7 TB/s, against 3.5 TB/s with 128-byte pieces when 32
+// workers share a wavefront), and a flush of 8 workers is still one whole 32-byte request.
+constexpr int kGroup = 8;
+
 int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* const* g_w,
                            int64_t d, int64_t i0, float scale, hipStream_t stream) {
-    for (int w0 = 0; w0 < W; w0 += kMaxBatch) {
+    for (int w0 = 0; w0 < W; w0 += kGroup) {
         WalkArgs a{};
-        a.nw = (W - w0 < kMaxBatch) ? (W - w0) : kMaxBatch;
+        a.nw = (W - w0 < kGroup) ? (W - w0) : kGroup;
         for (int w = 0; w < a.nw; ++w) a.g[w] = g_w[w0 + w];
         a.T = T;
         a.W = W;
@@ -242,9 +257,7 @@ int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* con
         a.i0 = i0;
         a.scale = scale;
         int rc;
-        if (a.nw > 16) rc = launch_walk<32>(p, a, stream);
-        else if (a.nw > 8) rc = launch_walk<16>(p, a, stream);
-        else if (a.nw > 4) rc = launch_walk<8>(p, a, stream);
+        if (a.nw > 4) rc = launch_walk<8>(p, a, stream);
         else if (a.nw > 2) rc = launch_walk<4>(p, a, stream);
         else if (a.nw > 1) rc = launch_walk<2>(p, a, stream);
         else rc = launch_walk<1>(p, a, stream);
