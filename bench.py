@@ -132,12 +132,14 @@ def main():
     stage_ms = {}
     for i, name in enumerate(stages):
         stage_ms[name] = sum(ev[i].elapsed_time(ev[i + 1]) for ev in events) / args.steps
-    n_launch = (cfg.W + 31) // 32
+    # the update runs as one launch per (group of 8 workers, sketch row); the algorithmic bytes
+    # of the whole update (every gradient read once, every worker table written once) are
+    # spread evenly over those launches
+    n_launch = ((cfg.W + 7) // 8) * cfg.r
     acc_kernel_ms = sum(ev[8].elapsed_time(ev[9]) for ev in events) / args.steps / n_launch
     value = cfg.W * cfg.d / (ms_per_step * 1e-3) / 1e9
 
-    w_per_launch = min(cfg.W, 32)
-    alg_bytes = 4.0 * w_per_launch * cfg.d + 4.0 * cfg.r * cfg.c * w_per_launch
+    alg_bytes = (4.0 * cfg.W * cfg.d + 4.0 * cfg.r * cfg.c * cfg.W) / n_launch
     achieved = alg_bytes / (acc_kernel_ms * 1e-3) / 1e9
     step_alg_bytes = (4.0 * cfg.W * cfg.d + 4.0 * cfg.r * cfg.c * cfg.W          # update
                       + 4.0 * cfg.r * cfg.c * (cfg.W + 1)                        # merge
@@ -172,6 +174,7 @@ def main():
             "frac": achieved / HBM_PEAK_GBS,
             "traffic": MEASURED_TRAFFIC_BYTES,
             "avg_launch_ms": acc_kernel_ms,
+            "launches_per_step": n_launch,
             "algorithmic_bytes_per_launch": alg_bytes,
         },
     }

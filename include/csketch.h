@@ -120,19 +120,24 @@ int cs_sketch_accumulate(const cs_params* p, float* S, const float* g, int64_t d
 int cs_sketch_accumulate_batch(const cs_params* p, float* const* S_w, const float* const* g_w,
                                int32_t W, int64_t d, int64_t i0, float scale, void* stream);
 
-/* Worker bundle: the sketches of W workers stored cell-major, T[j][b][w] = S^w[j][b], i.e.
- * float[r][c][W] contiguous.  Workers hash identically (same seed), so their updates to one
- * cell land in W neighbouring floats: the layout that lets one memory request carry the
- * updates of many workers.  Worker w's sketch is the strided slice T[:, :, w].
+/* Worker bundle: the sketches of W workers stored cell-major in groups of CS_BUNDLE_GROUP = 8
+ * workers,  T[w / 8][j][b][w % 8] = S^w[j][b],  i.e. float[ceil(W / 8)][r][c][8] contiguous
+ * (cs_bundle_floats() elements; slots of a last, partial group are padding and stay 0).
+ * Workers hash identically (same seed), so their updates to one cell land in 8 neighbouring
+ * floats: one 32-byte memory request carries the updates of 8 workers.  One group's table is
+ * small enough to stay in the memory-side cache while that group is being updated.
  *
+ * cs_bundle_floats:      number of floats in a bundle of W workers.
  * cs_bundle_zero:        T = 0.
- * cs_sketch_accumulate_bundle:  T[j][h_j(i0+t)][w] += scale * s_j(i0+t) * g_w[w][t] for all
+ * cs_sketch_accumulate_bundle:  S^w[j][h_j(i0+t)] += scale * s_j(i0+t) * g_w[w][t] for all
  *                        w < W, t < d, j < r (Alg. 3 "Compute sketch S^i" for every worker).
  *                        g_w: HOST array of W device pointers to float[d].  W >= 1.
- * cs_bundle_merge:       dst[j][b] = beta * dst[j][b] + alpha * sum_{w<W} T[j][b][w]
+ * cs_bundle_merge:       dst[j][b] = beta * dst[j][b] + alpha * sum_{w<W} S^w[j][b]
  *                        (Alg. 3 "S_t = (1/W) sum_i S_t^i" with alpha = 1/W); dst: device
  *                        float[r][c], not read when beta == 0; fp32 sum in a fixed order.
- * r * c * W must be below 2^40. */
+ * The bundle must be below 2^40 floats and 16-byte aligned. */
+#define CS_BUNDLE_GROUP 8
+int cs_bundle_floats(const cs_params* p, int32_t W, int64_t* n);
 int cs_bundle_zero(const cs_params* p, float* T, int32_t W, void* stream);
 int cs_sketch_accumulate_bundle(const cs_params* p, float* T, int32_t W,
                                 const float* const* g_w, int64_t d, int64_t i0, float scale,

@@ -9,6 +9,8 @@ from .binding import (  # noqa: F401
     CS_MAX_R,
     CsError,
     CsParams,
+    CS_BUNDLE_GROUP,
+    cs_bundle_floats,
     cs_bundle_merge,
     cs_bundle_zero,
     cs_sketch_accumulate_bundle,

@@ -54,6 +54,7 @@ _SIGNATURES = {
                                    ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32,
                                    ctypes.c_int64, ctypes.c_int64, ctypes.c_float,
                                    ctypes.c_void_p],
+    "cs_bundle_floats": [ctypes.POINTER(CsParams), ctypes.c_int32, ctypes.POINTER(ctypes.c_int64)],
     "cs_bundle_zero": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p],
     "cs_sketch_accumulate_bundle": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_int32,
                                     ctypes.POINTER(ctypes.c_void_p), ctypes.c_int64,
@@ -190,9 +191,19 @@ def cs_sketch_accumulate_batch(p, S_w, g_w, i0: int = 0, scale: float = 1.0):
         "cs_sketch_accumulate_batch")
 
 
+CS_BUNDLE_GROUP = 8
+
+
+def cs_bundle_floats(p, W: int) -> int:
+    out = ctypes.c_int64(0)
+    _check(load_library().cs_bundle_floats(ctypes.byref(p), W, ctypes.byref(out)),
+           "cs_bundle_floats")
+    return int(out.value)
+
+
 def cs_bundle_zero(p, T, W: int):
     _check(load_library().cs_bundle_zero(
-        ctypes.byref(p), _dev(T, torch.float32, "T", _cells(p) * W), W, _stream(T)),
+        ctypes.byref(p), _dev(T, torch.float32, "T", cs_bundle_floats(p, W)), W, _stream(T)),
         "cs_bundle_zero")
 
 
@@ -202,7 +213,7 @@ def cs_sketch_accumulate_bundle(p, T, g_w, i0: int = 0, scale: float = 1.0):
         raise CsError("g_w must be a non-empty list")
     d = g_w[0].numel()
     _check(load_library().cs_sketch_accumulate_bundle(
-        ctypes.byref(p), _dev(T, torch.float32, "T", _cells(p) * W), W,
+        ctypes.byref(p), _dev(T, torch.float32, "T", cs_bundle_floats(p, W)), W,
         _ptr_array(g_w, torch.float32, "g_w", d), d, i0, scale, _stream(T)),
         "cs_sketch_accumulate_bundle")
 
@@ -210,7 +221,8 @@ def cs_sketch_accumulate_bundle(p, T, g_w, i0: int = 0, scale: float = 1.0):
 def cs_bundle_merge(p, dst, T, W: int, alpha: float = 1.0, beta: float = 0.0):
     _check(load_library().cs_bundle_merge(
         ctypes.byref(p), _dev(dst, torch.float32, "dst", _cells(p)), beta,
-        _dev(T, torch.float32, "T", _cells(p) * W), W, alpha, _stream(dst)), "cs_bundle_merge")
+        _dev(T, torch.float32, "T", cs_bundle_floats(p, W)), W, alpha, _stream(dst)),
+        "cs_bundle_merge")
 
 
 def cs_sketch_accumulate_sparse(p, S, idx, val, scale: float = 1.0):

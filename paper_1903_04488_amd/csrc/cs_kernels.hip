@@ -338,22 +338,29 @@ extern "C" int cs_sketch_accumulate(const cs_params* p, float* S, const float* g
     if (!params_ok(p) || d < 0 || i0 < 0 || i0 > (int64_t)kP61 - d) return CS_EINVAL;
     if (d == 0) return CS_OK;
     if (!S || !g) return CS_EINVAL;
-    // a single table is a bundle of width 1
-    if (walk_applies(p, d)) return launch_accumulate_walk(p, S, 1, &g, d, i0, scale, as_stream(stream));
     BatchPtrs ptrs{};
     ptrs.S[0] = S;
     ptrs.g[0] = g;
     return accumulate_launch(p, ptrs, 1, d, i0, scale, stream);
 }
 
+static int64_t bundle_groups(int32_t W) { return (static_cast<int64_t>(W) + CS_BUNDLE_GROUP - 1) / CS_BUNDLE_GROUP; }
+
 static bool bundle_ok(const cs_params* p, int32_t W) {
     return params_ok(p) && W >= 1 &&
-           static_cast<uint64_t>(p->r) * p->c * static_cast<uint64_t>(W) < (1ull << 40);
+           static_cast<uint64_t>(p->r) * p->c * static_cast<uint64_t>(bundle_groups(W)) * CS_BUNDLE_GROUP < (1ull << 40);
+}
+
+extern "C" int cs_bundle_floats(const cs_params* p, int32_t W, int64_t* n) {
+    if (!bundle_ok(p, W) || !n) return CS_EINVAL;
+    *n = static_cast<int64_t>(p->r) * p->c * bundle_groups(W) * CS_BUNDLE_GROUP;
+    return CS_OK;
 }
 
 extern "C" int cs_bundle_zero(const cs_params* p, float* T, int32_t W, void* stream) {
     if (!bundle_ok(p, W) || !T) return CS_EINVAL;
-    return launch_bundle_zero(T, static_cast<int64_t>(p->r) * p->c * W, as_stream(stream));
+    return launch_bundle_zero(T, static_cast<int64_t>(p->r) * p->c * bundle_groups(W) * CS_BUNDLE_GROUP,
+                              as_stream(stream));
 }
 
 extern "C" int cs_sketch_accumulate_bundle(const cs_params* p, float* T, int32_t W,
@@ -365,14 +372,18 @@ extern "C" int cs_sketch_accumulate_bundle(const cs_params* p, float* T, int32_t
         if (!g_w[w] && d > 0) return CS_EINVAL;
     if (d == 0) return CS_OK;
     if (walk_applies(p, d)) return launch_accumulate_walk(p, T, W, g_w, d, i0, scale, as_stream(stream));
+    // any other sketch: one thread per coordinate; worker w's table is the strided slice
+    // starting at T + (w / 8) * r * c * 8 + w % 8 with 8 floats between cells
+    const size_t group_floats = static_cast<size_t>(p->r) * p->c * CS_BUNDLE_GROUP;
     for (int w0 = 0; w0 < W; w0 += kMaxBatch) {
         const int nw = (W - w0 < kMaxBatch) ? (W - w0) : kMaxBatch;
         BatchPtrs ptrs{};
         for (int w = 0; w < nw; ++w) {
-            ptrs.S[w] = T + w0 + w;
-            ptrs.g[w] = g_w[w0 + w];
+            const int ww = w0 + w;
+            ptrs.S[w] = T + (ww / CS_BUNDLE_GROUP) * group_floats + ww % CS_BUNDLE_GROUP;
+            ptrs.g[w] = g_w[ww];
         }
-        const int rc = accumulate_direct(p, ptrs, nw, d, i0, scale, W, stream);
+        const int rc = accumulate_direct(p, ptrs, nw, d, i0, scale, CS_BUNDLE_GROUP, stream);
         if (rc != CS_OK) return rc;
     }
     return CS_OK;
@@ -381,8 +392,9 @@ extern "C" int cs_sketch_accumulate_bundle(const cs_params* p, float* T, int32_t
 extern "C" int cs_bundle_merge(const cs_params* p, float* dst, float beta, const float* T,
                                int32_t W, float alpha, void* stream) {
     if (!bundle_ok(p, W) || !dst || !T) return CS_EINVAL;
-    return launch_bundle_merge(dst, beta, T, W, alpha, static_cast<int64_t>(p->r) * p->c,
-                               as_stream(stream));
+    if (reinterpret_cast<uintptr_t>(T) % 16 != 0) return CS_EINVAL;
+    return launch_bundle_merge(dst, beta, T, static_cast<int>(bundle_groups(W)), alpha,
+                               static_cast<int64_t>(p->r) * p->c, as_stream(stream));
 }
 
 extern "C" int cs_sketch_accumulate_batch(const cs_params* p, float* const* S_w,

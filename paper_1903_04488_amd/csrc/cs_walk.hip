@@ -9,9 +9,11 @@
 //     stride Dw for which that is a small fraction of a bucket (cs_row_plan).  A lane that
 //     walks such a progression stays in one cell for ~1/sigma consecutive visits: it keeps the
 //     running sum in a register and issues one atomic add when it leaves the cell.
-//  2. All workers use the same hash functions, so in the bundle layout T[j][b][w] the sums of
-//     32 workers for one cell are 128 contiguous bytes: 32 lanes (one per worker) flush them as
-//     four full 32-byte requests.
+//  2. All workers use the same hash functions, so in the bundle layout T[w/8][j][b][w%8] the
+//     sums of 8 workers for one cell are 32 contiguous bytes: 8 lanes (one per worker) flush
+//     them as one full 32-byte request.  One launch updates one row of one group, a slice of
+//     c x 32 bytes that stays in the memory-side cache, so the read-modify-writes of the
+//     atomics do not compete with the streaming reads for DRAM.
 //
 // Work decomposition for row j: the residues [0, Dw) are cut into chunks of kRun = 16
 // consecutive coordinates; a "walker" owns one chunk and visits it at n Dw for n = 0, 1, ...
@@ -40,6 +42,7 @@ constexpr int kTileStride = kRun + 1;    // padded LDS row of the value tile
 constexpr int kPieces = kRun / 4;        // 16-byte pieces per run
 constexpr int kRunsPerPass = 64 / kPieces;
 constexpr int kPasses = 64 / kRunsPerPass;
+constexpr int kGroup = CS_BUNDLE_GROUP;  // workers per bundle group
 
 struct __attribute__((packed, aligned(4))) float4u {
     float x, y, z, w;
@@ -54,11 +57,10 @@ typedef vec4f __attribute__((aligned(4))) vec4f_u;           // 16 bytes at any 
 typedef const __attribute__((address_space(1))) vec4f_u* gvec4_ptr;
 
 struct WalkArgs {
-    const float* g[kMaxBatch];   // vectors of the workers of this launch
-    float* T;                    // bundle, float[r][c][W]
-    int32_t W;                   // bundle width
-    int32_t w0;                  // first worker of this launch
-    int32_t nw;                  // workers in this launch (<= WL)
+    const float* g[kGroup];      // vectors of the workers of this group
+    float* Trow;                 // row j of the group's table, float[c][kGroup]
+    int32_t j;                   // sketch row
+    int32_t nw;                  // workers in this group (<= kGroup)
     int64_t d, i0;
     float scale;
 };
@@ -70,12 +72,12 @@ __global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a)
     constexpr int PPL = (WL >= 16) ? 1 : 16 / WL;      // hash values each lane computes
     __shared__ float tile_lds[64 * kTileStride];
     __shared__ uint32_t hash_lds[WPW * kRun];
-    __shared__ gfloat_ptr gptr_lds[kMaxBatch];
+    __shared__ gfloat_ptr gptr_lds[kGroup];
 
     const int lane = threadIdx.x;
-    const int j = blockIdx.y;
+    const int j = a.j;
     const int h = lane / WL, wl = lane % WL;           // my walker, my worker slot
-    if (lane < kMaxBatch) gptr_lds[lane] = (gfloat_ptr)a.g[lane < a.nw ? lane : 0];
+    if (lane < kGroup) gptr_lds[lane] = (gfloat_ptr)a.g[lane < a.nw ? lane : 0];
     __builtin_amdgcn_wave_barrier();
 
     const int64_t D = static_cast<int64_t>(p.plan[j].Dw);
@@ -84,7 +86,7 @@ __global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a)
     const int64_t nwaves = (chunks + WPW - 1) / WPW;
     const uint32_t mask = p.c - 1u;
     const int64_t d = a.d;
-    float* __restrict__ Tcol = a.T + static_cast<size_t>(j) * p.c * a.W + a.w0 + wl;
+    float* __restrict__ Tcol = a.Trow + wl;
     const bool have_worker = wl < a.nw;
 
     // loader role: piece m4 of runs r0, r0 + kRunsPerPass, ...; run rho = walker * WL + worker
@@ -197,7 +199,7 @@ __global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a)
                 const uint32_t cell = pk & 0x7fffffffu;
                 if (cell != cur[m]) {                      // left the cell: send its sum
                     if (acc[m] != 0.0f)
-                        atomic_add_noret(Tcol + static_cast<size_t>(cur[m]) * a.W, acc[m]);
+                        atomic_add_noret(Tcol + static_cast<size_t>(cur[m]) * kGroup, acc[m]);
                     cur[m] = cell;
                     acc[m] = 0.0f;
                 }
@@ -208,24 +210,19 @@ __global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a)
 #pragma unroll
         for (int m = 0; m < kRun; ++m)
             if (acc[m] != 0.0f && have_worker)
-                atomic_add_noret(Tcol + static_cast<size_t>(cur[m]) * a.W, acc[m]);
+                atomic_add_noret(Tcol + static_cast<size_t>(cur[m]) * kGroup, acc[m]);
     }
 }
 
 template <int WL>
 int launch_walk(const cs_params* p, const WalkArgs& a, hipStream_t stream) {
     constexpr int WPW = 64 / WL;
-    int64_t most = 1;
-    for (uint32_t j = 0; j < p->r; ++j) {
-        const int64_t chunks = (static_cast<int64_t>(p->plan[j].Dw) + kRun - 1) / kRun;
-        const int64_t nwaves = (chunks + WPW - 1) / WPW;
-        if (nwaves > most) most = nwaves;
-    }
+    const int64_t chunks = (static_cast<int64_t>(p->plan[a.j].Dw) + kRun - 1) / kRun;
+    const int64_t nwaves = (chunks + WPW - 1) / WPW;
     const int64_t cap = 256 * 64;
-    int64_t gx = most < cap ? most : cap;
+    int64_t gx = nwaves < cap ? nwaves : cap;
     gx = (gx + 7) / 8 * 8;                   // the kernel deals workgroups to XCDs in eights
-    const dim3 grid(static_cast<unsigned>(gx), p->r);
-    k_accumulate_walk<WL><<<grid, 64, 0, stream>>>(*p, a);
+    k_accumulate_walk<WL><<<static_cast<unsigned>(gx), 64, 0, stream>>>(*p, a);
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
 
@@ -238,30 +235,30 @@ bool walk_applies(const cs_params* p, int64_t d) {
     return true;
 }
 
-// Workers are served in groups of kGroup = 8: with 8 lanes per walker a wavefront holds 8
-// walkers on neighbouring chunks, so every load instruction reads 512 contiguous bytes of
-// each worker's vector (measured: 5.7 TB/s, against 3.5 TB/s with 128-byte pieces when 32
-// workers share a wavefront), and a flush of 8 workers is still one whole 32-byte request.
-constexpr int kGroup = 8;
-
+// With 8 lanes per walker a wavefront holds 8 walkers on neighbouring chunks, so every load
+// instruction reads 512 contiguous bytes of each worker's vector (measured: 5.7 TB/s, against
+// 3.5 TB/s with 128-byte pieces when 32 workers share a wavefront).  `group_stride` = floats
+// between the tables of consecutive groups (r * c * 8 for a bundle).
 int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* const* g_w,
                            int64_t d, int64_t i0, float scale, hipStream_t stream) {
+    const size_t row_floats = static_cast<size_t>(p->c) * kGroup;
     for (int w0 = 0; w0 < W; w0 += kGroup) {
         WalkArgs a{};
         a.nw = (W - w0 < kGroup) ? (W - w0) : kGroup;
         for (int w = 0; w < a.nw; ++w) a.g[w] = g_w[w0 + w];
-        a.T = T;
-        a.W = W;
-        a.w0 = w0;
         a.d = d;
         a.i0 = i0;
         a.scale = scale;
-        int rc;
-        if (a.nw > 4) rc = launch_walk<8>(p, a, stream);
-        else if (a.nw > 2) rc = launch_walk<4>(p, a, stream);
-        else if (a.nw > 1) rc = launch_walk<2>(p, a, stream);
-        else rc = launch_walk<1>(p, a, stream);
-        if (rc != CS_OK) return rc;
+        for (uint32_t j = 0; j < p->r; ++j) {
+            a.j = static_cast<int32_t>(j);
+            a.Trow = T + (static_cast<size_t>(w0 / kGroup) * p->r + j) * row_floats;
+            int rc;
+            if (a.nw > 4) rc = launch_walk<8>(p, a, stream);
+            else if (a.nw > 2) rc = launch_walk<4>(p, a, stream);
+            else if (a.nw > 1) rc = launch_walk<2>(p, a, stream);
+            else rc = launch_walk<1>(p, a, stream);
+            if (rc != CS_OK) return rc;
+        }
     }
     return CS_OK;
 }
@@ -279,46 +276,21 @@ __global__ void __launch_bounds__(kBlock) k_bundle_zero(float4* __restrict__ T4,
     for (int64_t t = n4 * 4 + t0; t < n; t += stride) T[t] = 0.0f;
 }
 
-// one thread per cell: sums the W neighbouring floats of its cell in ascending w (any W)
+// one thread per cell: adds the 8 slots of every group (32 contiguous bytes per group, and
+// neighbouring lanes read neighbouring cells, so every load instruction is coalesced)
 __global__ void __launch_bounds__(kBlock)
-k_bundle_merge(float* __restrict__ dst, float beta, const float* __restrict__ T, int W,
+k_bundle_merge(float* __restrict__ dst, float beta, const float4* __restrict__ T4, int groups,
                float alpha, int64_t cells) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
     for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < cells; t += stride) {
-        const float* src = T + static_cast<size_t>(t) * W;
         float s = 0.0f;
-        for (int w = 0; w < W; ++w) s += src[w];
+        for (int g = 0; g < groups; ++g) {
+            const float4* src = T4 + (static_cast<size_t>(g) * cells + t) * 2;
+            const float4 u = src[0], v = src[1];
+            s += ((u.x + u.y) + (u.z + u.w)) + ((v.x + v.y) + (v.z + v.w));
+        }
         const float base = (beta == 0.0f) ? 0.0f : beta * dst[t];
         dst[t] = base + alpha * s;
-    }
-}
-
-// W = 4 * LPC with LPC a power of two <= 64, 16-byte aligned bundle: the bundle is streamed
-// as consecutive 16-byte pieces (fully coalesced); the LPC neighbouring lanes that hold the
-// pieces of one cell add their partial sums with a butterfly, the first of them writes.
-template <int LPC>
-__global__ void __launch_bounds__(kBlock)
-k_bundle_merge_vec(float* __restrict__ dst, float beta, const float4* __restrict__ T4,
-                   float alpha, int64_t cells) {
-    const int64_t pieces = cells * LPC;
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;      // multiple of 64
-    const int64_t start = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
-    // every lane of a wavefront runs the same number of iterations (shuffles need all lanes)
-    const int64_t wave_start = start - (threadIdx.x & 63);
-    for (int64_t base = wave_start; base < pieces; base += stride) {
-        const int64_t t = base + (threadIdx.x & 63);
-        float s = 0.0f;
-        if (t < pieces) {
-            const float4 v = T4[t];
-            s = (v.x + v.y) + (v.z + v.w);
-        }
-#pragma unroll
-        for (int off = 1; off < LPC; off <<= 1) s += __shfl_xor(s, off, 64);
-        if (t < pieces && (t & (LPC - 1)) == 0) {
-            const int64_t cell = t / LPC;
-            const float b = (beta == 0.0f) ? 0.0f : beta * dst[cell];
-            dst[cell] = b + alpha * s;
-        }
     }
 }
 
@@ -335,30 +307,12 @@ int launch_bundle_zero(float* T, int64_t n, hipStream_t stream) {
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
 
-int launch_bundle_merge(float* dst, float beta, const float* T, int W, float alpha,
+int launch_bundle_merge(float* dst, float beta, const float* T, int groups, float alpha,
                         int64_t cells, hipStream_t stream) {
-    const bool vec_ok = (W % 4 == 0) && ((W / 4) & (W / 4 - 1)) == 0 && W / 4 <= 64 &&
-                        reinterpret_cast<uintptr_t>(T) % 16 == 0;
-    if (vec_ok) {
-        const int lpc = W / 4;
-        int64_t b = (cells * lpc + kBlock - 1) / kBlock;
-        if (b > 256 * 32) b = 256 * 32;
-        const unsigned g = static_cast<unsigned>(b);
-        const float4* T4 = reinterpret_cast<const float4*>(T);
-        switch (lpc) {
-            case 1: k_bundle_merge_vec<1><<<g, kBlock, 0, stream>>>(dst, beta, T4, alpha, cells); break;
-            case 2: k_bundle_merge_vec<2><<<g, kBlock, 0, stream>>>(dst, beta, T4, alpha, cells); break;
-            case 4: k_bundle_merge_vec<4><<<g, kBlock, 0, stream>>>(dst, beta, T4, alpha, cells); break;
-            case 8: k_bundle_merge_vec<8><<<g, kBlock, 0, stream>>>(dst, beta, T4, alpha, cells); break;
-            case 16: k_bundle_merge_vec<16><<<g, kBlock, 0, stream>>>(dst, beta, T4, alpha, cells); break;
-            case 32: k_bundle_merge_vec<32><<<g, kBlock, 0, stream>>>(dst, beta, T4, alpha, cells); break;
-            default: k_bundle_merge_vec<64><<<g, kBlock, 0, stream>>>(dst, beta, T4, alpha, cells); break;
-        }
-    } else {
-        int64_t b = (cells + kBlock - 1) / kBlock;
-        if (b > 256 * 32) b = 256 * 32;
-        k_bundle_merge<<<static_cast<unsigned>(b), kBlock, 0, stream>>>(dst, beta, T, W, alpha, cells);
-    }
+    int64_t b = (cells + kBlock - 1) / kBlock;
+    if (b > 256 * 32) b = 256 * 32;
+    k_bundle_merge<<<static_cast<unsigned>(b), kBlock, 0, stream>>>(
+        dst, beta, reinterpret_cast<const float4*>(T), groups, alpha, cells);
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
 

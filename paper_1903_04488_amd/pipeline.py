@@ -1,7 +1,7 @@
 """One pass of the hot path on one GPU: buffers and the order of library calls, nothing else.
 
 Per step (Alg. 3 of the paper, with the W workers simulated on the one device):
-    worker sketches   S^w = S(g^w)                cs_sketch_accumulate_bundle  (T[j][b][w])
+    worker sketches   S^w = S(g^w)                cs_sketch_accumulate_bundle  (T[w/8][j][b][w%8])
     aggregate         S_t = (1/W) sum_w S^w       cs_bundle_merge
     momentum, error   S_u = rho S_u + S_t ; S_v += S_u      cs_sketch_momentum   (stateful only)
     query all         est = estimate(S_v or S_t)  cs_sketch_estimate
@@ -25,8 +25,8 @@ class HotPath:
         self.device = torch.device(device)
         self.params = B.cs_params_init(r, c, seed, d)
         f32 = dict(dtype=torch.float32, device=self.device)
-        # the W workers' sketches as one bundle, cell-major: T[j][b][w] = S^w[j][b]
-        self.T = torch.zeros(r, c, W, **f32)
+        # the W workers' sketches as one bundle: T[w // 8][j][b][w % 8] = S^w[j][b]
+        self.T = torch.zeros(B.cs_bundle_floats(self.params, W), **f32)
         self.S_t = torch.zeros(r, c, **f32)
         self.S_u = torch.zeros(r, c, **f32) if rho is not None else None
         self.S_v = torch.zeros(r, c, **f32) if rho is not None else None
@@ -45,7 +45,8 @@ class HotPath:
     # individual stages (bench.py times them separately) ---------------------------------
     def worker_table(self, w: int):
         """Worker w's own sketch (a strided view of the bundle)."""
-        return self.T[:, :, w]
+        g = B.CS_BUNDLE_GROUP
+        return self.T.view(-1, self.r, self.c, g)[w // g, :, :, w % g]
 
     def accumulate(self, g_w):
         B.cs_bundle_zero(self.params, self.T, self.W)

@@ -138,17 +138,24 @@ def test_accumulate_bundle(W, r, c, seed, d, i0):
     gs = [(rng.standard_normal(d) * 0.01).astype(np.float32) for _ in range(W)]
     for g in gs:
         g[rng.integers(0, d, size=20)] += 1.0
-    T = torch.full((r, c, W), 0.25, dtype=torch.float32, device=DEV)    # accumulates into T
+    G = cs.CS_BUNDLE_GROUP
+    n = cs.cs_bundle_floats(p, W)
+    assert n == -(-W // G) * r * c * G
+    T = torch.full((n,), 0.25, dtype=torch.float32, device=DEV)    # accumulates into T
     cs.cs_sketch_accumulate_bundle(p, T, [dev(g) for g in gs], i0=i0, scale=0.5)
-    Th = T.cpu().numpy()
+    Th = T.cpu().numpy().reshape(-1, r, c, G)
+    tables = [Th[w // G, :, :, w % G] for w in range(W)]
     for w in range(W):
         ref = sk.accumulate(np.full((r, c), 0.25), gs[w], i0=i0, scale=0.5)
-        assert_cells_close(Th[:, :, w], ref, what=f"worker {w}", terms_per_cell=d / c)
+        assert_cells_close(tables[w], ref, what=f"worker {w}", terms_per_cell=d / c)
+    if W % G:                      # padding slots of the last group are never written
+        assert (Th[-1, :, :, W % G:] == 0.25).all()
+        T.view(-1, r, c, G)[-1, :, :, W % G:] = 0.0
     # merge of the bundle = (1/W) sum of the workers' tables
     dst0 = rng.standard_normal((r, c)).astype(np.float32)
     dst = dev(dst0)
     cs.cs_bundle_merge(p, dst, T, W, alpha=1.0 / W, beta=0.5)
-    ref = orc.merge([Th[:, :, w] for w in range(W)], alpha=1.0 / W, beta=0.5, dst=dst0)
+    ref = orc.merge(tables, alpha=1.0 / W, beta=0.5, dst=dst0)
     assert_cells_close(dst.cpu().numpy(), ref)
     cs.cs_bundle_zero(p, T, W)
     assert (T == 0).all()
