@@ -24,8 +24,9 @@ def assert_cells_close(gpu, ref, rel=REL, what="cells", terms_per_cell=0.0, oper
     configurations have at most ~100; the bound is widened by sqrt(terms / 256) beyond that,
     the growth of random-order fp32 summation error (only degenerate shapes such as c = 1).
     operand_mag: per-cell magnitude of the operands the cell was computed from, for cells that
-    are the result of a cancellation (error feedback subtracts a heavy value from the cell
-    that held it: fp32 error is relative to what was subtracted, not to what is left)."""
+    are the result of a cancellation (error feedback subtracts heavy values from the cell that
+    held them, and two heavy values of opposite sign can share a cell: fp32 error is relative
+    to what was added and subtracted, not to what is left)."""
     gpu = np.asarray(gpu, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     assert gpu.shape == ref.shape

@@ -106,6 +106,13 @@ def run(config, steps, check_workers=(0,), sample_only_after_first=False, log=pr
         if st is not None:
             hp.feedback()
             delta, uhat = st.feedback(idx)
+            # operands of the subtraction: several selected coordinates can share a cell and
+            # cancel there, so the scale of its fp32 error is the sum of their magnitudes
+            bkt, _ = sk.hash(idx)
+            for j in range(c.r):
+                bj = bkt[j].astype(np.int64)
+                mag_v[j] = np.maximum(mag_v[j], np.bincount(bj, weights=np.abs(delta), minlength=c.c))
+                mag_u[j] = np.maximum(mag_u[j], np.bincount(bj, weights=np.abs(uhat), minlength=c.c))
             assert_values_close(hp.delta.cpu().numpy(), delta, sigma, what=f"step {t} delta")
             assert_values_close(hp.uhat.cpu().numpy(), uhat, rms(st.S_u) + 1e-30, what=f"step {t} uhat")
             assert_cells_close(hp.S_u.cpu().numpy(), st.S_u, what=f"step {t} S_u after feedback",
