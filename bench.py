@@ -21,10 +21,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 METRIC = "sketch+estimate+top-k throughput, Gcoords/s and % HBM peak at d=100M, r=5"
-# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE and
-# WRITE_SIZE, each scaled by the same counter on a plain copy kernel); None until measured.
-# Source: profiles/accumulate_cfg4_pmc.txt
-MEASURED_TRAFFIC_BYTES = None
+# HBM bytes per launch of the dominant kernel at config 4, measured with rocprofv3 --pmc
+# (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the factors being what the same counters read for
+# a plain 1 GiB copy).  Source: profiles/accumulate_walk_cfg4_pmc.md.  None for other configs.
+MEASURED_TRAFFIC_BYTES = {4: 3.52e9}
 
 
 def cpu_baseline(cfg, work, sample_acc=8_000_000, sample_est=4_000_000):
@@ -69,6 +69,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a kernel of known HBM traffic) "
+                         "so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -115,6 +118,14 @@ def main():
         hp.topk(); mark(5)
         hp.gather(g_w); mark(6)
         hp.feedback(); mark(7)
+
+    if args.calibration_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for t in range(args.warmup):
         one_step(sets[t % n_sets])
@@ -172,7 +183,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.cfg),
             "avg_launch_ms": acc_kernel_ms,
             "launches_per_step": n_launch,
             "algorithmic_bytes_per_launch": alg_bytes,
