@@ -187,10 +187,6 @@ __global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a)
             yb = hash_advance(yb, ADb);
             ys = hash_advance(ys, ADs);
             __builtin_amdgcn_wave_barrier();
-            // next visit's values are fetched (into registers) while this one is applied
-            // straight out of LDS
-            nD += D;
-            if (nD + chunk0 * kRun < d) load_visit(nD);
             const float* my_run = tile_lds + lane * kTileStride;
             const uint32_t* my_hash = hash_lds + h * kRun;
 #pragma unroll
@@ -206,6 +202,12 @@ __global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a)
                 acc[m] += apply_sign(a.scale * my_run[m], pk & 0x80000000u);
             }
             __builtin_amdgcn_wave_barrier();
+            // The next visit's loads are issued after this visit's atomics on purpose: the
+            // memory counter retires in order, so the wait for those loads at the top of the
+            // loop also covers the (older) atomics, and the two latencies overlap instead of
+            // adding up.
+            nD += D;
+            if (nD + chunk0 * kRun < d) load_visit(nD);
         }
 #pragma unroll
         for (int m = 0; m < kRun; ++m)
@@ -253,7 +255,8 @@ int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* con
             a.j = static_cast<int32_t>(j);
             a.Trow = T + (static_cast<size_t>(w0 / kGroup) * p->r + j) * row_floats;
             int rc;
-            if (a.nw > 4) rc = launch_walk<8>(p, a, stream);
+            if (a.nw > 8) rc = launch_walk<16>(p, a, stream);
+            else if (a.nw > 4) rc = launch_walk<8>(p, a, stream);
             else if (a.nw > 2) rc = launch_walk<4>(p, a, stream);
             else if (a.nw > 1) rc = launch_walk<2>(p, a, stream);
             else rc = launch_walk<1>(p, a, stream);
@@ -285,9 +288,12 @@ k_bundle_merge(float* __restrict__ dst, float beta, const float4* __restrict__ T
     for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < cells; t += stride) {
         float s = 0.0f;
         for (int g = 0; g < groups; ++g) {
-            const float4* src = T4 + (static_cast<size_t>(g) * cells + t) * 2;
-            const float4 u = src[0], v = src[1];
-            s += ((u.x + u.y) + (u.z + u.w)) + ((v.x + v.y) + (v.z + v.w));
+            const float4* src = T4 + (static_cast<size_t>(g) * cells + t) * (kGroup / 4);
+#pragma unroll
+            for (int q = 0; q < kGroup / 4; ++q) {
+                const float4 u = src[q];
+                s += (u.x + u.y) + (u.z + u.w);
+            }
         }
         const float base = (beta == 0.0f) ? 0.0f : beta * dst[t];
         dst[t] = base + alpha * s;
