@@ -202,6 +202,17 @@ int cs_heavy_hitters_topk(const float* est, int64_t d, int64_t k,
 int cs_gather_exact(const float* const* vec, int32_t W, const int64_t* idx, int64_t k,
                     float alpha, float* out, void* stream);
 
+/* Alg. 3 as the paper trains with it (Sec. 5.1: "we query the Count Sketch, and then each of
+ * the workers, for the top Pk elements instead"): of n = Pk candidate coordinates cand[0..n)
+ * (ascending, as cs_heavy_hitters_topk returns them) with exact second-round values x[0..n)
+ * (cs_gather_exact), keep the k of largest |x| (equal magnitudes -> lower index), in ascending
+ * index order:  idx_out[t] = cand[pos_t],  val_out[t] = x[pos_t].
+ * cand: device int64[n]; x: device float[n]; idx_out: device int64[k]; val_out: device
+ * float[k] (may be NULL); workspace as for cs_heavy_hitters_topk(n, k).  1 <= k <= n. */
+int cs_select_exact_topk(const int64_t* cand, const float* x, int64_t n, int64_t k,
+                         int64_t* idx_out, float* val_out, void* workspace, size_t ws_bytes,
+                         void* stream);
+
 /* Error feedback / momentum masking in sketch space (Alg. 2 "Error accumulation",
  * Alg. 3 "u, v <- 0 for all updated coordinates", as far as a sketch can express them):
  *     val[n] = estimate(S, idx[n])   for all n, from the table as it is on entry, then

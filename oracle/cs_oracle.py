@@ -209,6 +209,15 @@ def gather_exact(vecs, idx, alpha: float = 1.0) -> np.ndarray:
     return alpha * acc
 
 
+def select_exact_topk(cand, x, k: int):
+    """Alg. 3 with P > 1 (Sec. 5.1): of the Pk candidates `cand` (ascending) with exact summed
+    values `x`, keep the k of largest |x| (ties -> lower index); returns (indices ascending,
+    their exact values)."""
+    cand = np.asarray(cand, dtype=np.int64)
+    pos = topk(np.asarray(x, dtype=np.float64), k)
+    return cand[pos], np.asarray(x, dtype=np.float64)[pos]
+
+
 def compression_factor(d: int, sketch_cells: int, P: int, k: int) -> float:
     """Sec. 5.3: 2d / (|S| + Pk + k)."""
     return 2.0 * d / (sketch_cells + P * k + k)

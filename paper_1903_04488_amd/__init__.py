@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     cs_hash_debug_range,
     cs_heavy_hitters_topk,
     cs_params_init,
+    cs_select_exact_topk,
     cs_sketch_accumulate,
     cs_sketch_accumulate_batch,
     cs_sketch_accumulate_sparse,

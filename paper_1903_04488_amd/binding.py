@@ -82,6 +82,9 @@ _SIGNATURES = {
     "cs_heavy_hitters_topk": [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                               ctypes.c_void_p],
+    "cs_select_exact_topk": [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                             ctypes.c_void_p],
     "cs_gather_exact": [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32, ctypes.c_void_p,
                         ctypes.c_int64, ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p],
     "cs_sketch_feedback": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_void_p,
@@ -292,6 +295,16 @@ def cs_heavy_hitters_topk(est, k: int, idx_out, val_out, workspace):
         _dev(val_out, torch.float32, "val_out", k) if val_out is not None else ctypes.c_void_p(0),
         _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(est)),
         "cs_heavy_hitters_topk")
+
+
+def cs_select_exact_topk(cand, x, k: int, idx_out, val_out, workspace):
+    n = cand.numel()
+    _check(load_library().cs_select_exact_topk(
+        _dev(cand, torch.int64, "cand"), _dev(x, torch.float32, "x", n), n, k,
+        _dev(idx_out, torch.int64, "idx_out", k),
+        _dev(val_out, torch.float32, "val_out", k) if val_out is not None else ctypes.c_void_p(0),
+        _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(x)),
+        "cs_select_exact_topk")
 
 
 def cs_gather_exact(vec, idx, out, alpha: float = 1.0):

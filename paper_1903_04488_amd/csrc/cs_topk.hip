@@ -256,6 +256,14 @@ k_topk_write(const float* __restrict__ est, int64_t d, int64_t chunk, const Topk
     }
 }
 
+// idx[t] = cand[idx[t]]: positions within the candidate list -> coordinates
+__global__ void __launch_bounds__(kBlock)
+k_remap_positions(int64_t* __restrict__ idx, const int64_t* __restrict__ cand, int64_t k) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < k; t += stride)
+        idx[t] = cand[idx[t]];
+}
+
 }  // namespace cs
 
 using namespace cs;
@@ -306,5 +314,20 @@ extern "C" int cs_heavy_hitters_topk(const float* est, int64_t d, int64_t k, int
         k_topk_scan<<<1, kBlock, 0, s>>>(ws, nblocks);
         k_topk_write<false><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, k, idx_out, val_out);
     }
+    return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
+}
+
+extern "C" int cs_select_exact_topk(const int64_t* cand, const float* x, int64_t n, int64_t k,
+                                    int64_t* idx_out, float* val_out, void* workspace,
+                                    size_t ws_bytes, void* stream) {
+    if (!cand) return CS_EINVAL;
+    // positions of the k largest |x| (ascending), then positions -> coordinates; cand is
+    // ascending, so the result is ascending too
+    const int rc = cs_heavy_hitters_topk(x, n, k, idx_out, val_out, workspace, ws_bytes, stream);
+    if (rc != CS_OK) return rc;
+    int64_t b = (k + kBlock - 1) / kBlock;
+    if (b > 4096) b = 4096;
+    k_remap_positions<<<static_cast<unsigned>(b), kBlock, 0, reinterpret_cast<hipStream_t>(stream)>>>(
+        idx_out, cand, k);
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }

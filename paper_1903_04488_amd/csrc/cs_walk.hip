@@ -15,17 +15,18 @@
 //     c x 32 bytes that stays in the memory-side cache, so the read-modify-writes of the
 //     atomics do not compete with the streaming reads for DRAM.
 //
-// Work decomposition for row j: the residues [0, Dw) are cut into chunks of kRun = 16
-// consecutive coordinates; a "walker" owns one chunk and visits it at n Dw for n = 0, 1, ...
-// A wavefront holds 64 / WL walkers of WL lanes each, lane wl of a walker serving worker wl.
+// Work decomposition for row j: the residues [0, Dw) are cut into chunks of RUN consecutive
+// coordinates; a "walker" owns one chunk and visits it at n Dw for n = 0, 1, ...  A wavefront
+// holds 64 / WL walkers of WL lanes each, lane wl of a walker serving worker wl of the group.
 // Every hash value is evaluated exactly (incremental form of the definition), so results are
 // the same sums as in any other order, up to fp32 rounding order.
 //
-// Data movement per visit: the 64 x kRun tile (64 runs = walkers x workers, kRun floats each)
-// is loaded as 16-byte pieces by neighbouring lanes, transposed through LDS so that every
-// lane gets its own run, and the (bucket, sign) of the walker's kRun coordinates are computed
-// once per walker by a few lanes and shared through LDS.  A workgroup is one wavefront;
-// nothing is shared between wavefronts, so LDS needs no barrier.
+// Data movement per visit: the 64 x RUN tile (64 runs = walkers x workers, RUN floats each) is
+// loaded as 16-byte pieces by neighbouring lanes, transposed through LDS so that every lane
+// gets its own run, and the (bucket, sign) of the walker's RUN coordinates are computed once
+// per walker by its lanes and shared through LDS, where the previous visit's values stay for
+// the "did I leave the cell" test.  A workgroup is one wavefront; nothing is shared between
+// wavefronts, so LDS needs no barrier.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -37,16 +38,7 @@ namespace cs {
 
 namespace {
 
-constexpr int kRun = 16;                 // consecutive coordinates per walker
-constexpr int kTileStride = kRun + 1;    // padded LDS row of the value tile
-constexpr int kPieces = kRun / 4;        // 16-byte pieces per run
-constexpr int kRunsPerPass = 64 / kPieces;
-constexpr int kPasses = 64 / kRunsPerPass;
 constexpr int kGroup = CS_BUNDLE_GROUP;  // workers per bundle group
-
-struct __attribute__((packed, aligned(4))) float4u {
-    float x, y, z, w;
-};
 
 // Vectors are addressed as global memory explicitly: the pointers pass through an LDS table,
 // and a generic ("flat") load would count against the LDS counter as well and force the
@@ -65,13 +57,23 @@ struct WalkArgs {
     float scale;
 };
 
-// WL = lanes per walker (workers served together): 1, 2, 4, 8, 16 or 32.
-template <int WL>
+// WL  = lanes per walker = workers served together (1, 2, 4, 8 or 16);
+// RUN = consecutive coordinates per walker and visit (16 or 32).
+// A wavefront holds WPW = 64 / WL walkers on neighbouring chunks of RUN residues, so one visit
+// reads WPW * RUN * 4 contiguous bytes of every worker's vector (512 bytes for WL = 8, RUN = 16
+// and for WL = 16, RUN = 32: measured to stream at 5.7 TB/s, against 4.5 TB/s with 256-byte and
+// 3.5 TB/s with 128-byte pieces).
+template <int WL, int RUN>
 __global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a) {
     constexpr int WPW = 64 / WL;                       // walkers per wavefront
-    constexpr int PPL = (WL >= 16) ? 1 : 16 / WL;      // hash values each lane computes
-    __shared__ float tile_lds[64 * kTileStride];
-    __shared__ uint32_t hash_lds[WPW * kRun];
+    constexpr int PPL = RUN / WL > 0 ? RUN / WL : 1;   // hash values each lane computes
+    constexpr int kStride = RUN + 1;                   // padded LDS row of the value tile
+    constexpr int kPieces = RUN / 4;                   // 16-byte pieces per run
+    constexpr int kRunsPerPass = 64 / kPieces;
+    constexpr int kPasses = kPieces;                   // 64 runs / kRunsPerPass
+    static_assert(WL * PPL == RUN || WL > RUN, "every coordinate of a walker gets a hash lane");
+    __shared__ float tile_lds[64 * kStride];
+    __shared__ uint32_t hash_lds[2][WPW * RUN];        // (bucket | sign) of this and the previous visit
     __shared__ gfloat_ptr gptr_lds[kGroup];
 
     const int lane = threadIdx.x;
@@ -82,18 +84,17 @@ __global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a)
 
     const int64_t D = static_cast<int64_t>(p.plan[j].Dw);
     const uint64_t ADb = p.plan[j].ADw, ADs = p.plan[j].ADws;
-    const int64_t chunks = (D + kRun - 1) / kRun;
+    const int64_t chunks = (D + RUN - 1) / RUN;
     const int64_t nwaves = (chunks + WPW - 1) / WPW;
     const uint32_t mask = p.c - 1u;
     const int64_t d = a.d;
     float* __restrict__ Tcol = a.Trow + wl;
-    const bool have_worker = wl < a.nw;
 
     // loader role: piece m4 of runs r0, r0 + kRunsPerPass, ...; run rho = walker * WL + worker
     const int m4 = (lane % kPieces) * 4, r0 = lane / kPieces;
-    // hash role: values m0 .. m0 + PPL - 1 of walker h (WL = 32: lanes 0..15 of each walker)
-    const int m0 = (WL >= 16) ? (wl % kRun) : wl * PPL;
-    const bool hash_duty = (WL <= 16) || (wl < kRun);
+    // hash role: values m0 .. m0 + PPL - 1 of my walker
+    const int m0 = (wl * PPL) % RUN;
+    const bool hash_duty = wl * PPL < RUN;
 
     // Workgroups are dealt to the 8 XCDs round-robin; giving XCD x the x-th eighth of the
     // walkers makes each XCD (and its L2) stream through its own contiguous part of every
@@ -104,36 +105,34 @@ __global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a)
         const int64_t wv = xcd_first + k;
         if (wv >= nwaves) break;
         const int64_t chunk0 = wv * WPW;               // first walker's chunk
-        const int64_t my_off = (chunk0 + h) * kRun;    // my walker's residue offset in [0, Dw)
+        const int64_t my_off = (chunk0 + h) * RUN;     // my walker's residue offset in [0, Dw)
         // hash state of coordinate i0 + my_off + m0 (visit n = 0)
         uint64_t yb = hash_state(p.a[j], p.b[j], static_cast<uint64_t>(a.i0 + my_off + m0));
         uint64_t ys = hash_state(p.as[j], p.bs[j], static_cast<uint64_t>(a.i0 + my_off + m0));
 
-        float acc[kRun];
-        uint32_t cur[kRun];
+        float acc[RUN];                                // running sum of the cell each coordinate is in
 #pragma unroll
-        for (int m = 0; m < kRun; ++m) { acc[m] = 0.0f; cur[m] = 0xffffffffu; }
+        for (int m = 0; m < RUN; ++m) acc[m] = 0.0f;
 
-        // visits: n D + residue < d; the first walker of the wavefront decides when to stop
+        // All pieces are requested back to back without a branch in between (a piece that is
+        // not wholly inside its run reads a safe address and is discarded); runs cut short by
+        // the end of the vector or of the residue range are patched up afterwards, which only
+        // the last visit or the last chunk ever needs.
         float4 pre[kPasses];
-        // All four pieces are requested back to back without a branch in between (a piece
-        // that is not wholly inside its run reads a safe address and is discarded); runs cut
-        // short by the end of the vector or of the residue range are patched up afterwards,
-        // which only the last visit or the last chunk ever needs.
         auto load_visit = [&](int64_t nD) {
             bool any_partial = false;
 #pragma unroll
             for (int q = 0; q < kPasses; ++q) {
                 const int rho = q * kRunsPerPass + r0;
                 const int rh = rho / WL, rw = rho % WL;
-                const int64_t off = (chunk0 + rh) * kRun;          // residue offset of that run
+                const int64_t off = (chunk0 + rh) * RUN;           // residue offset of that run
                 const int64_t rel = nD + off;
                 int64_t len = D - off;
                 if (d - rel < len) len = d - rel;
                 if (rw >= a.nw) len = 0;
                 const bool full = m4 + 4 <= len;
                 const bool part = !full && m4 < len;
-                const gfloat_ptr base = gptr_lds[rw];
+                const gfloat_ptr base = gptr_lds[rw < kGroup ? rw : 0];
                 const gfloat_ptr src = full ? base + rel + m4 : base;
                 const vec4f u = *(gvec4_ptr)src;
                 pre[q] = full ? make_float4(u.x, u.y, u.z, u.w) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
@@ -144,13 +143,13 @@ __global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a)
                 for (int q = 0; q < kPasses; ++q) {
                     const int rho = q * kRunsPerPass + r0;
                     const int rh = rho / WL, rw = rho % WL;
-                    const int64_t off = (chunk0 + rh) * kRun;
+                    const int64_t off = (chunk0 + rh) * RUN;
                     const int64_t rel = nD + off;
                     int64_t len = D - off;
                     if (d - rel < len) len = d - rel;
                     if (rw >= a.nw) len = 0;
                     if (m4 + 4 > len && m4 < len) {
-                        const gfloat_ptr src = gptr_lds[rw] + rel + m4;
+                        const gfloat_ptr src = gptr_lds[rw < kGroup ? rw : 0] + rel + m4;
                         pre[q].x = src[0];
                         if (m4 + 1 < len) pre[q].y = src[1];
                         if (m4 + 2 < len) pre[q].z = src[2];
@@ -160,24 +159,27 @@ __global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a)
         };
 
         int64_t nD = 0;
+        int par = 0;                                   // which hash buffer holds this visit
         load_visit(nD);
-        while (nD + chunk0 * kRun < d) {
-            // values: registers -> LDS (run-major) -> my own run
+        while (nD + chunk0 * RUN < d) {
+            // values: registers -> LDS (run-major); each lane then reads its own run
 #pragma unroll
             for (int q = 0; q < kPasses; ++q) {
-                float* dst = tile_lds + (q * kRunsPerPass + r0) * kTileStride + m4;
+                float* dst = tile_lds + (q * kRunsPerPass + r0) * kStride + m4;
                 dst[0] = pre[q].x;
                 dst[1] = pre[q].y;
                 dst[2] = pre[q].z;
                 dst[3] = pre[q].w;
             }
-            // hashes of this visit: PPL consecutive coordinates from my state
+            // hashes of this visit: PPL consecutive coordinates from my state; the first visit
+            // also fills the "previous" buffer, so that nothing looks like a left cell
             if (hash_duty) {
                 uint64_t tb = yb, ts = ys;
 #pragma unroll
                 for (int q = 0; q < PPL; ++q) {
-                    hash_lds[h * kRun + m0 + q] =
-                        ((static_cast<uint32_t>(tb) - 1u) & mask) | sign_flip_of(ts);
+                    const uint32_t pk = ((static_cast<uint32_t>(tb) - 1u) & mask) | sign_flip_of(ts);
+                    hash_lds[par][h * RUN + m0 + q] = pk;
+                    if (nD == 0) hash_lds[par ^ 1][h * RUN + m0 + q] = pk;
                     if (q + 1 < PPL) {
                         tb = hash_advance(tb, p.a[j]);
                         ts = hash_advance(ts, p.as[j]);
@@ -187,44 +189,48 @@ __global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a)
             yb = hash_advance(yb, ADb);
             ys = hash_advance(ys, ADs);
             __builtin_amdgcn_wave_barrier();
-            const float* my_run = tile_lds + lane * kTileStride;
-            const uint32_t* my_hash = hash_lds + h * kRun;
+            const float* my_run = tile_lds + lane * kStride;
+            const uint32_t* now = hash_lds[par] + h * RUN;
+            const uint32_t* before = hash_lds[par ^ 1] + h * RUN;
 #pragma unroll
-            for (int m = 0; m < kRun; ++m) {
-                const uint32_t pk = my_hash[m];
+            for (int m = 0; m < RUN; ++m) {
+                const uint32_t pk = now[m];
                 const uint32_t cell = pk & 0x7fffffffu;
-                if (cell != cur[m]) {                      // left the cell: send its sum
+                const uint32_t was = before[m] & 0x7fffffffu;
+                if (cell != was) {                         // left the cell: send its sum
                     if (acc[m] != 0.0f)
-                        atomic_add_noret(Tcol + static_cast<size_t>(cur[m]) * kGroup, acc[m]);
-                    cur[m] = cell;
+                        atomic_add_noret(Tcol + static_cast<size_t>(was) * kGroup, acc[m]);
                     acc[m] = 0.0f;
                 }
                 acc[m] += apply_sign(a.scale * my_run[m], pk & 0x80000000u);
             }
             __builtin_amdgcn_wave_barrier();
-            // The next visit's loads are issued after this visit's atomics on purpose: the
-            // memory counter retires in order, so the wait for those loads at the top of the
-            // loop also covers the (older) atomics, and the two latencies overlap instead of
-            // adding up.
+            // The next visit's loads are issued after this visit's atomics: the memory counter
+            // retires in order, so the wait for those loads at the top of the loop also covers
+            // the (older) atomics.
             nD += D;
-            if (nD + chunk0 * kRun < d) load_visit(nD);
+            par ^= 1;
+            if (nD + chunk0 * RUN < d) load_visit(nD);
         }
+        // the cells the walkers ended in (buffer of the last visit)
+        const uint32_t* last = hash_lds[par ^ 1] + h * RUN;
 #pragma unroll
-        for (int m = 0; m < kRun; ++m)
-            if (acc[m] != 0.0f && have_worker)
-                atomic_add_noret(Tcol + static_cast<size_t>(cur[m]) * kGroup, acc[m]);
+        for (int m = 0; m < RUN; ++m)
+            if (acc[m] != 0.0f)
+                atomic_add_noret(Tcol + static_cast<size_t>(last[m] & 0x7fffffffu) * kGroup, acc[m]);
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
-template <int WL>
+template <int WL, int RUN>
 int launch_walk(const cs_params* p, const WalkArgs& a, hipStream_t stream) {
     constexpr int WPW = 64 / WL;
-    const int64_t chunks = (static_cast<int64_t>(p->plan[a.j].Dw) + kRun - 1) / kRun;
+    const int64_t chunks = (static_cast<int64_t>(p->plan[a.j].Dw) + RUN - 1) / RUN;
     const int64_t nwaves = (chunks + WPW - 1) / WPW;
     const int64_t cap = 256 * 64;
     int64_t gx = nwaves < cap ? nwaves : cap;
     gx = (gx + 7) / 8 * 8;                   // the kernel deals workgroups to XCDs in eights
-    k_accumulate_walk<WL><<<static_cast<unsigned>(gx), 64, 0, stream>>>(*p, a);
+    k_accumulate_walk<WL, RUN><<<static_cast<unsigned>(gx), 64, 0, stream>>>(*p, a);
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
 
@@ -237,10 +243,6 @@ bool walk_applies(const cs_params* p, int64_t d) {
     return true;
 }
 
-// With 8 lanes per walker a wavefront holds 8 walkers on neighbouring chunks, so every load
-// instruction reads 512 contiguous bytes of each worker's vector (measured: 5.7 TB/s, against
-// 3.5 TB/s with 128-byte pieces when 32 workers share a wavefront).  `group_stride` = floats
-// between the tables of consecutive groups (r * c * 8 for a bundle).
 int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* const* g_w,
                            int64_t d, int64_t i0, float scale, hipStream_t stream) {
     const size_t row_floats = static_cast<size_t>(p->c) * kGroup;
@@ -255,11 +257,14 @@ int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* con
             a.j = static_cast<int32_t>(j);
             a.Trow = T + (static_cast<size_t>(w0 / kGroup) * p->r + j) * row_floats;
             int rc;
-            if (a.nw > 8) rc = launch_walk<16>(p, a, stream);
-            else if (a.nw > 4) rc = launch_walk<8>(p, a, stream);
-            else if (a.nw > 2) rc = launch_walk<4>(p, a, stream);
-            else if (a.nw > 1) rc = launch_walk<2>(p, a, stream);
-            else rc = launch_walk<1>(p, a, stream);
+#if CS_BUNDLE_GROUP >= 16
+            if (a.nw > 8) rc = launch_walk<16, 32>(p, a, stream);
+            else
+#endif
+            if (a.nw > 4) rc = launch_walk<8, 16>(p, a, stream);
+            else if (a.nw > 2) rc = launch_walk<4, 16>(p, a, stream);
+            else if (a.nw > 1) rc = launch_walk<2, 16>(p, a, stream);
+            else rc = launch_walk<1, 16>(p, a, stream);
             if (rc != CS_OK) return rc;
         }
     }

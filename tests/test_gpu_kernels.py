@@ -281,6 +281,24 @@ def test_topk_extreme_values_and_unaligned_input():
     assert 17 in want and 99_999 in want
 
 
+@pytest.mark.parametrize("n,k", [(1, 1), (600, 50), (3_600_000, 100_000), (5000, 5000)])
+def test_select_exact_topk(n, k):
+    rng = np.random.default_rng(n + k)
+    cand = np.sort(rng.choice(10**8, n, replace=False)).astype(np.int64)
+    x = (np.round(rng.standard_normal(n) * 50) / 50).astype(np.float32)      # ties
+    idx = torch.empty(k, dtype=torch.int64, device=DEV)
+    val = torch.empty(k, dtype=torch.float32, device=DEV)
+    ws = torch.empty(cs.cs_topk_workspace_bytes(n, k), dtype=torch.uint8, device=DEV)
+    cs.cs_select_exact_topk(dev(cand), dev(x), k, idx, val, ws)
+    if n > (1 << 18):
+        pos = orc.topk_threshold(x, k)
+        want_idx, want_val = cand[pos], x[pos]
+    else:
+        want_idx, want_val = orc.select_exact_topk(cand, x, k)
+    np.testing.assert_array_equal(idx.cpu().numpy(), want_idx)
+    np.testing.assert_array_equal(val.cpu().numpy(), np.asarray(want_val, dtype=np.float32))
+
+
 # ------------------------------------------------------------------------------ gather / feedback
 @pytest.mark.parametrize("W", [1, 4, 70])
 def test_gather_exact(W):

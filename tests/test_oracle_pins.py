@@ -336,6 +336,22 @@ def test_topk_against_lexsort_with_ties():
     np.testing.assert_array_equal(orc.topk_threshold(np.zeros(7), 3), [0, 1, 2])
 
 
+def test_select_exact_topk_against_lexsort():
+    rng = np.random.default_rng(21)
+    n, k = 600, 50
+    cand = np.sort(rng.choice(10**6, n, replace=False))
+    x = np.round(rng.standard_normal(n) * 3) / 3            # ties
+    order = np.lexsort((cand, -np.abs(x)))[:k]                # |x| desc, coordinate asc
+    want = np.sort(cand[order])
+    got_idx, got_val = orc.select_exact_topk(cand, x, k)
+    np.testing.assert_array_equal(got_idx, want)
+    np.testing.assert_array_equal(got_val, x[np.searchsorted(cand, want)])
+    # P = 1: the selection is the whole candidate list
+    i1, v1 = orc.select_exact_topk(cand, x, n)
+    np.testing.assert_array_equal(i1, cand)
+    np.testing.assert_array_equal(v1, x)
+
+
 def test_gather_exact_is_fancy_indexing():
     rng = np.random.default_rng(17)
     vecs = [rng.standard_normal(1000).astype(np.float32) for _ in range(5)]
