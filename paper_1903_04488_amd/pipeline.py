@@ -19,8 +19,12 @@ from . import binding as B
 
 class HotPath:
     def __init__(self, d: int, W: int, r: int, c: int, k: int, seed: int,
-                 rho: float | None = None, device="cuda:0"):
+                 rho: float | None = None, device="cuda:0", P: int = 1):
+        """P > 1: the sketch is queried for the top P*k coordinates, the workers for their exact
+        values, and the k largest exact sums are kept (Alg. 3 as the paper trains with it)."""
         self.d, self.W, self.r, self.c, self.k = d, W, r, c, k
+        self.P = P
+        self.kq = min(P * k, d)          # coordinates asked of the sketch
         self.rho = rho
         self.device = torch.device(device)
         self.params = B.cs_params_init(r, c, seed, d)
@@ -31,12 +35,16 @@ class HotPath:
         self.S_u = torch.zeros(r, c, **f32) if rho is not None else None
         self.S_v = torch.zeros(r, c, **f32) if rho is not None else None
         self.est = torch.empty(d, **f32)
-        self.idx = torch.empty(k, dtype=torch.int64, device=self.device)
-        self.est_at_idx = torch.empty(k, **f32)
-        self.x = torch.empty(k, **f32)
+        self.cand = torch.empty(self.kq, dtype=torch.int64, device=self.device)
+        self.est_at_cand = torch.empty(self.kq, **f32)
+        self.x_cand = torch.empty(self.kq, **f32)
+        # with P = 1 the candidates are the selection
+        self.idx = self.cand if P == 1 else torch.empty(k, dtype=torch.int64, device=self.device)
+        self.est_at_idx = self.est_at_cand
+        self.x = self.x_cand if P == 1 else torch.empty(k, **f32)
         self.delta = torch.empty(k, **f32)
         self.uhat = torch.empty(k, **f32)
-        self.topk_ws = torch.empty(B.cs_topk_workspace_bytes(d, k), dtype=torch.uint8,
+        self.topk_ws = torch.empty(B.cs_topk_workspace_bytes(d, self.kq), dtype=torch.uint8,
                                    device=self.device)
         n_est = B.cs_estimate_workspace_bytes(self.params, d)
         self.est_ws = (torch.empty(n_est, dtype=torch.uint8, device=self.device)
@@ -66,10 +74,12 @@ class HotPath:
         B.cs_sketch_estimate(self.params, self.query_table(), self.est, 0, self.est_ws)
 
     def topk(self):
-        B.cs_heavy_hitters_topk(self.est, self.k, self.idx, self.est_at_idx, self.topk_ws)
+        B.cs_heavy_hitters_topk(self.est, self.kq, self.cand, self.est_at_cand, self.topk_ws)
 
     def gather(self, g_w):
-        B.cs_gather_exact(g_w, self.idx, self.x, alpha=1.0 / self.W)
+        B.cs_gather_exact(g_w, self.cand, self.x_cand, alpha=1.0 / self.W)
+        if self.P > 1:
+            B.cs_select_exact_topk(self.cand, self.x_cand, self.k, self.idx, self.x, self.topk_ws)
 
     def feedback(self):
         if self.rho is not None:

@@ -173,3 +173,32 @@ def test_config4_full_two_steps():
 @pytest.mark.timeout(1500)
 def test_config5_full_two_steps():
     run(wl.CONFIGS[5], 2, check_workers=(255,), sample_only_after_first=True)
+
+
+# ----------------------------------------------------------------------------- P > 1
+@pytest.mark.parametrize("P", [4, 36])
+def test_top_pk_then_exact_topk(P):
+    """Alg. 3 as the paper trains with it (Sec. 5.1): the sketch is asked for the top P*k
+    coordinates, the workers for their exact values, and the k largest exact sums are kept."""
+    c = wl.scaled(1, d=(1 << 20) + 77, W=4, c=1 << 14, k=250, n_heavy=400)
+    work = wl.Workload(c, DEV)
+    hp = HotPath(c.d, c.W, c.r, c.c, c.k, c.hash_seed, rho=None, device=DEV, P=P)
+    sk = orc.SketchOracle(c.r, c.c, c.hash_seed)
+    g_w = [work.gradient(0, w) for w in range(c.W)]
+    idx, x = hp.step(g_w)
+    gsum = host_sum(g_w)
+    S_t = sk.sketch(gsum, scale=1.0 / c.W)
+    est_ref = sk.estimate(S_t, c.d)
+    cand = hp.cand.cpu().numpy()
+    assert_valid_topk(cand, est_ref, P * c.k, rms(S_t), what="top-Pk candidates")
+    x_cand_ref = gsum[cand] / c.W
+    scale = float(np.sqrt((gsum ** 2).mean())) / c.W
+    assert_values_close(hp.x_cand.cpu().numpy(), x_cand_ref, scale, what="exact values of candidates")
+    # the final k: positions within the candidate list, judged on the reference's exact values
+    pos = np.searchsorted(cand, idx.cpu().numpy())
+    assert (cand[pos] == idx.cpu().numpy()).all()
+    assert_valid_topk(pos, x_cand_ref, c.k, scale, what="k largest exact sums")
+    assert_values_close(x.cpu().numpy(), x_cand_ref[pos], scale, what="exact values of the selection")
+    # with more candidates the exact second round recovers at least as many planted coordinates
+    found = np.isin(work.heavy_idx.cpu().numpy(), idx.cpu().numpy()).sum()
+    assert found >= 0.9 * min(c.k, c.n_heavy)
