@@ -294,8 +294,13 @@ int launch_accumulate_lattice(const cs_params* p, const LatticePtrs& ptrs, int n
 
 int launch_estimate_lattice(const cs_params* p, const float* S, int64_t d, int64_t i0,
                             float* est, float* rows, hipStream_t stream) {
-    const dim3 grid(lattice_grid_x(p, d), p->r);
-    k_row_values_lattice<<<grid, 64, 0, stream>>>(*p, S, d, i0, rows);
+    if (walk_applies(p, d)) {
+        const int rc = launch_row_values_walk(p, S, d, i0, rows, stream);
+        if (rc != CS_OK) return rc;
+    } else {
+        const dim3 grid(lattice_grid_x(p, d), p->r);
+        k_row_values_lattice<<<grid, 64, 0, stream>>>(*p, S, d, i0, rows);
+    }
     int64_t b = (d + kBlock - 1) / kBlock;
     if (b > 256 * 16) b = 256 * 16;
     const unsigned mg = static_cast<unsigned>(b);

@@ -39,6 +39,9 @@ namespace cs {
 namespace {
 
 constexpr int kGroup = CS_BUNDLE_GROUP;  // workers per bundle group
+#ifndef CS_WALK_NWAVE8
+#define CS_WALK_NWAVE8 2
+#endif
 
 // Vectors are addressed as global memory explicitly: the pointers pass through an LDS table,
 // and a generic ("flat") load would count against the LDS counter as well and force the
@@ -63,8 +66,11 @@ struct WalkArgs {
 // reads WPW * RUN * 4 contiguous bytes of every worker's vector (512 bytes for WL = 8, RUN = 16
 // and for WL = 16, RUN = 32: measured to stream at 5.7 TB/s, against 4.5 TB/s with 256-byte and
 // 3.5 TB/s with 128-byte pieces).
-template <int WL, int RUN>
-__global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a) {
+// NWAVE = wavefronts per workgroup; they work on neighbouring sets of walkers at about the same
+// time (nothing is shared and nothing is synchronised between them), which widens the
+// contiguous stretch of every vector that is being read at one moment.
+template <int WL, int RUN, int NWAVE>
+__global__ void __launch_bounds__(64 * NWAVE) k_accumulate_walk(cs_params p, WalkArgs a) {
     constexpr int WPW = 64 / WL;                       // walkers per wavefront
     constexpr int PPL = RUN / WL > 0 ? RUN / WL : 1;   // hash values each lane computes
     constexpr int kStride = RUN + 1;                   // padded LDS row of the value tile
@@ -72,11 +78,14 @@ __global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a)
     constexpr int kRunsPerPass = 64 / kPieces;
     constexpr int kPasses = kPieces;                   // 64 runs / kRunsPerPass
     static_assert(WL * PPL == RUN || WL > RUN, "every coordinate of a walker gets a hash lane");
-    __shared__ float tile_lds[64 * kStride];
-    __shared__ uint32_t hash_lds[2][WPW * RUN];        // (bucket | sign) of this and the previous visit
-    __shared__ gfloat_ptr gptr_lds[kGroup];
+    __shared__ float tile_lds_all[NWAVE][64 * kStride];
+    __shared__ uint32_t hash_lds_all[NWAVE][2][WPW * RUN];   // (bucket | sign), this and previous visit
+    __shared__ gfloat_ptr gptr_lds_all[NWAVE][kGroup];
 
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, wq = threadIdx.x >> 6;
+    float* tile_lds = tile_lds_all[wq];
+    uint32_t (*hash_lds)[WPW * RUN] = hash_lds_all[wq];
+    gfloat_ptr* gptr_lds = gptr_lds_all[wq];
     const int j = a.j;
     const int h = lane / WL, wl = lane % WL;           // my walker, my worker slot
     if (lane < kGroup) gptr_lds[lane] = (gfloat_ptr)a.g[lane < a.nw ? lane : 0];
@@ -99,11 +108,12 @@ __global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a)
     // Workgroups are dealt to the 8 XCDs round-robin; giving XCD x the x-th eighth of the
     // walkers makes each XCD (and its L2) stream through its own contiguous part of every
     // vector.  gridDim.x is a multiple of 8.
-    const int64_t per_xcd = (nwaves + 7) / 8;
+    const int64_t ngroups = (nwaves + NWAVE - 1) / NWAVE;      // workgroup-sized sets of walkers
+    const int64_t per_xcd = (ngroups + 7) / 8;
     const int64_t xcd_first = static_cast<int64_t>(blockIdx.x & 7) * per_xcd;
     for (int64_t k = blockIdx.x >> 3; k < per_xcd; k += gridDim.x >> 3) {
-        const int64_t wv = xcd_first + k;
-        if (wv >= nwaves) break;
+        const int64_t wv = (xcd_first + k) * NWAVE + wq;
+        if (xcd_first + k >= ngroups || wv >= nwaves) break;
         const int64_t chunk0 = wv * WPW;               // first walker's chunk
         const int64_t my_off = (chunk0 + h) * RUN;     // my walker's residue offset in [0, Dw)
         // hash state of coordinate i0 + my_off + m0 (visit n = 0)
@@ -222,15 +232,16 @@ __global__ void __launch_bounds__(64) k_accumulate_walk(cs_params p, WalkArgs a)
     }
 }
 
-template <int WL, int RUN>
+template <int WL, int RUN, int NWAVE>
 int launch_walk(const cs_params* p, const WalkArgs& a, hipStream_t stream) {
     constexpr int WPW = 64 / WL;
     const int64_t chunks = (static_cast<int64_t>(p->plan[a.j].Dw) + RUN - 1) / RUN;
     const int64_t nwaves = (chunks + WPW - 1) / WPW;
-    const int64_t cap = 256 * 64;
-    int64_t gx = nwaves < cap ? nwaves : cap;
+    const int64_t ngroups = (nwaves + NWAVE - 1) / NWAVE;
+    const int64_t cap = 256 * 64 / NWAVE;
+    int64_t gx = ngroups < cap ? ngroups : cap;
     gx = (gx + 7) / 8 * 8;                   // the kernel deals workgroups to XCDs in eights
-    k_accumulate_walk<WL, RUN><<<static_cast<unsigned>(gx), 64, 0, stream>>>(*p, a);
+    k_accumulate_walk<WL, RUN, NWAVE><<<static_cast<unsigned>(gx), 64 * NWAVE, 0, stream>>>(*p, a);
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
 
@@ -258,17 +269,123 @@ int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* con
             a.Trow = T + (static_cast<size_t>(w0 / kGroup) * p->r + j) * row_floats;
             int rc;
 #if CS_BUNDLE_GROUP >= 16
-            if (a.nw > 8) rc = launch_walk<16, 32>(p, a, stream);
+            if (a.nw > 8) rc = launch_walk<16, 16, 2>(p, a, stream);
             else
 #endif
-            if (a.nw > 4) rc = launch_walk<8, 16>(p, a, stream);
-            else if (a.nw > 2) rc = launch_walk<4, 16>(p, a, stream);
-            else if (a.nw > 1) rc = launch_walk<2, 16>(p, a, stream);
-            else rc = launch_walk<1, 16>(p, a, stream);
+            if (a.nw > 4) rc = launch_walk<8, 16, CS_WALK_NWAVE8>(p, a, stream);
+            else if (a.nw > 2) rc = launch_walk<4, 16, 1>(p, a, stream);
+            else if (a.nw > 1) rc = launch_walk<2, 16, 1>(p, a, stream);
+            else rc = launch_walk<1, 16, 1>(p, a, stream);
             if (rc != CS_OK) return rc;
         }
     }
     return CS_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// Alg. 4 estimate, walk order: rows[j][i] = s_j(i) S[j][h_j(i)] for every coordinate.
+//
+// The same stride serves the query: a lane that walks i, i + Dw, i + 2 Dw, ... stays in one
+// cell for ~1/sigma visits, so it keeps that cell's value in a register and gathers again
+// only when it leaves the cell (one gather per ~10 coordinates instead of one per
+// coordinate).  The 64 lanes of a wavefront own 64 neighbouring chunks of 16 residues, so
+// every visit writes 4 KB of contiguous output (transposed through LDS into whole 16-byte
+// pieces).  A second kernel takes the median over rows.
+// ---------------------------------------------------------------------------------------
+namespace {
+
+constexpr int kQRun = 16;
+
+__global__ void __launch_bounds__(64)
+k_row_values_walk(cs_params p, const float* __restrict__ S, int64_t d, int64_t i0,
+                  float* __restrict__ rows) {
+    constexpr int kStride = kQRun + 1;
+    constexpr int kPieces = kQRun / 4, kRunsPerPass = 64 / kPieces, kPasses = kPieces;
+    __shared__ float tile_lds[64 * kStride];
+    const int lane = threadIdx.x;
+    const int j = blockIdx.y;
+    const int64_t D = static_cast<int64_t>(p.plan[j].Dw);
+    const uint64_t ADb = p.plan[j].ADw, ADs = p.plan[j].ADws;
+    const uint64_t Ab = p.a[j], As = p.as[j];
+    const int64_t chunks = (D + kQRun - 1) / kQRun;
+    const int64_t nwaves = (chunks + 63) / 64;
+    const uint32_t mask = p.c - 1u;
+    const float* __restrict__ Sj = S + static_cast<size_t>(j) * p.c;
+    float* __restrict__ out = rows + static_cast<size_t>(j) * d;
+    const int m4 = (lane % kPieces) * 4, r0 = lane / kPieces;
+
+    const int64_t per_xcd = (nwaves + 7) / 8;
+    const int64_t xcd_first = static_cast<int64_t>(blockIdx.x & 7) * per_xcd;
+    for (int64_t k = blockIdx.x >> 3; k < per_xcd; k += gridDim.x >> 3) {
+        const int64_t wv = xcd_first + k;
+        if (wv >= nwaves) break;
+        const int64_t chunk0 = wv * 64;
+        const int64_t my_off = (chunk0 + lane) * kQRun;          // my residue offset in [0, Dw)
+        uint64_t yb = hash_state(p.a[j], p.b[j], static_cast<uint64_t>(i0 + my_off));
+        uint64_t ys = hash_state(p.as[j], p.bs[j], static_cast<uint64_t>(i0 + my_off));
+        uint32_t cur[kQRun];
+        float val[kQRun];
+#pragma unroll
+        for (int m = 0; m < kQRun; ++m) { cur[m] = 0xffffffffu; val[m] = 0.0f; }
+
+        for (int64_t nD = 0; nD + chunk0 * kQRun < d; nD += D) {
+            int64_t my_len = D - my_off;                         // coordinates of mine that exist
+            if (d - (nD + my_off) < my_len) my_len = d - (nD + my_off);
+            uint64_t tb = yb, ts = ys;
+#pragma unroll
+            for (int m = 0; m < kQRun; ++m) {
+                const uint32_t cell = (static_cast<uint32_t>(tb) - 1u) & mask;
+                if (cell != cur[m] && m < my_len) {              // entered a new cell: fetch it
+                    cur[m] = cell;
+                    val[m] = Sj[cell];
+                }
+                tile_lds[lane * kStride + m] = apply_sign(val[m], sign_flip_of(ts));
+                tb = hash_advance(tb, Ab);
+                ts = hash_advance(ts, As);
+            }
+            yb = hash_advance(yb, ADb);
+            ys = hash_advance(ys, ADs);
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int q = 0; q < kPasses; ++q) {
+                const int rho = q * kRunsPerPass + r0;           // run = lane that owns it
+                const int64_t off = (chunk0 + rho) * kQRun;
+                const int64_t rel = nD + off;
+                int64_t len = D - off;
+                if (d - rel < len) len = d - rel;
+                const float* src = tile_lds + rho * kStride + m4;
+                float* dst = out + rel + m4;
+                if (m4 + 4 <= len) {
+                    vec4f u;
+                    u.x = src[0]; u.y = src[1]; u.z = src[2]; u.w = src[3];
+                    *reinterpret_cast<vec4f_u*>(dst) = u;
+                } else if (m4 < len) {
+                    dst[0] = src[0];
+                    if (m4 + 1 < len) dst[1] = src[1];
+                    if (m4 + 2 < len) dst[2] = src[2];
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+}
+
+}  // namespace
+
+int launch_row_values_walk(const cs_params* p, const float* S, int64_t d, int64_t i0,
+                           float* rows, hipStream_t stream) {
+    int64_t most = 1;
+    for (uint32_t j = 0; j < p->r; ++j) {
+        const int64_t chunks = (static_cast<int64_t>(p->plan[j].Dw) + kQRun - 1) / kQRun;
+        const int64_t nwaves = (chunks + 63) / 64;
+        if (nwaves > most) most = nwaves;
+    }
+    const int64_t cap = 256 * 64;
+    int64_t gx = most < cap ? most : cap;
+    gx = (gx + 7) / 8 * 8;
+    const dim3 grid(static_cast<unsigned>(gx), p->r);
+    k_row_values_walk<<<grid, 64, 0, stream>>>(*p, S, d, i0, rows);
+    return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
 
 // ---------------------------------------------------------------------------------------
