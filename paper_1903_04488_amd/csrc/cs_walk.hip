@@ -99,7 +99,8 @@ __global__ void __launch_bounds__(64 * NWAVE) k_accumulate_walk(cs_params p, Wal
     const int64_t d = a.d;
     float* __restrict__ Tcol = a.Trow + wl;
 
-    // loader role: piece m4 of runs r0, r0 + kRunsPerPass, ...; run rho = walker * WL + worker
+    // loader role: piece m4 of runs r0, r0 + kRunsPerPass, ...; run rho = worker * WPW + walker,
+    // so that one load instruction covers neighbouring walkers (contiguous bytes) of few workers
     const int m4 = (lane % kPieces) * 4, r0 = lane / kPieces;
     // hash role: values m0 .. m0 + PPL - 1 of my walker
     const int m0 = (wl * PPL) % RUN;
@@ -134,7 +135,7 @@ __global__ void __launch_bounds__(64 * NWAVE) k_accumulate_walk(cs_params p, Wal
 #pragma unroll
             for (int q = 0; q < kPasses; ++q) {
                 const int rho = q * kRunsPerPass + r0;
-                const int rh = rho / WL, rw = rho % WL;
+                const int rw = rho / WPW, rh = rho % WPW;     // worker-major: neighbouring lanes, neighbouring walkers
                 const int64_t off = (chunk0 + rh) * RUN;           // residue offset of that run
                 const int64_t rel = nD + off;
                 int64_t len = D - off;
@@ -152,7 +153,7 @@ __global__ void __launch_bounds__(64 * NWAVE) k_accumulate_walk(cs_params p, Wal
 #pragma unroll
                 for (int q = 0; q < kPasses; ++q) {
                     const int rho = q * kRunsPerPass + r0;
-                    const int rh = rho / WL, rw = rho % WL;
+                    const int rw = rho / WPW, rh = rho % WPW;     // worker-major: neighbouring lanes, neighbouring walkers
                     const int64_t off = (chunk0 + rh) * RUN;
                     const int64_t rel = nD + off;
                     int64_t len = D - off;
@@ -175,7 +176,8 @@ __global__ void __launch_bounds__(64 * NWAVE) k_accumulate_walk(cs_params p, Wal
             // values: registers -> LDS (run-major); each lane then reads its own run
 #pragma unroll
             for (int q = 0; q < kPasses; ++q) {
-                float* dst = tile_lds + (q * kRunsPerPass + r0) * kStride + m4;
+                const int rho = q * kRunsPerPass + r0;
+                float* dst = tile_lds + ((rho % WPW) * WL + rho / WPW) * kStride + m4;
                 dst[0] = pre[q].x;
                 dst[1] = pre[q].y;
                 dst[2] = pre[q].z;
