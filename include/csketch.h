@@ -76,15 +76,41 @@ typedef struct cs_row_plan {
                              fall into one bucket with stride D */
 } cs_row_plan;
 
+/* Visit list of one row for the update of a worker bundle (derived from a_j, c and d_hint;
+ * does not change any result).  With c a power of two, h_j(i) is the top log2(c) bits of
+ * u(i) = (2^(61 - log2 c) * (a_j i + b_j)) mod p, and u(i + s) = (u(i) + U(s)) mod p with
+ * U(s) = (2^(61 - log2 c) * a_j * s) mod p.  The list holds, in increasing order, s_0 = 0 and
+ * every offset s < d_hint with U(s) below a chosen bound of at most (ncell - 1) cells, so
+ * that  h_j(i + s_k) - h_j(i)  (mod c)  lies in  [0, ncell)  for every i and k.  A lane that
+ * visits i + s_0, i + s_1, ... therefore needs only ncell running sums and sends each to
+ * memory once, after its last visit.  Visit k covers the coordinates [s_k, s_k + gap_k),
+ * gap_k = s_{k+1} - s_k (s_K = d_hint); return times of a rotation to an interval take at most
+ * three values, so gaps are stored as 2-bit codes into gap[] (code 3 = the last, cut gap). */
+#define CS_MAX_VISITS 512
+typedef struct cs_visit_plan {
+    uint32_t K;                 /* number of visits; 0 = no list (the stride walk is used) */
+    uint32_t ncell;             /* running sums per lane and coordinate: 2, 3 or 4 */
+    uint64_t cover;             /* the list covers vectors of length <= cover (= d_hint) */
+    uint64_t gmax;              /* largest gap = number of residues that lanes own */
+    uint64_t cost;              /* estimated atomic requests per worker group, this list */
+    uint64_t cost_walk;         /* the same for the stride walk with cs_row_plan.Dw */
+    uint64_t gap[4];            /* gap value per code */
+    uint64_t A[4], As[4];       /* (a_j * gap) mod p, (a'_j * gap) mod p per code */
+    uint32_t code[CS_MAX_VISITS / 16];   /* 2 bits per visit, visit k in word k / 16 */
+} cs_visit_plan;
+
+#define CS_FLAG_NO_VISIT_LIST 1u   /* cs_params.flags: always use the stride walk (testing) */
+
 typedef struct cs_params {
     uint32_t r;                 /* rows, odd, 1..CS_MAX_R */
     uint32_t c;                 /* columns, 1..2^31 */
     uint32_t c_pow2;            /* 1 if c is a power of two (fast bucket extraction) */
-    uint32_t reserved;
+    uint32_t flags;             /* 0, or CS_FLAG_* set by the caller after cs_params_init */
     uint64_t seed;
     uint64_t a[CS_MAX_R], b[CS_MAX_R];     /* bucket hashes */
     uint64_t as[CS_MAX_R], bs[CS_MAX_R];   /* sign hashes */
     cs_row_plan plan[CS_MAX_R];
+    cs_visit_plan visit[CS_MAX_R];
 } cs_params;
 
 /* Alg. 4 init: fills *p for an r x c sketch from `seed` (host, no GPU needed).

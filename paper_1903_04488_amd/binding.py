@@ -27,13 +27,31 @@ class CsRowPlan(ctypes.Structure):
                 ("lanes", ctypes.c_int32), ("scan_steps", ctypes.c_int32)]
 
 
+CS_MAX_VISITS = 512
+CS_FLAG_NO_VISIT_LIST = 1
+
+
+class CsVisitPlan(ctypes.Structure):
+    _fields_ = [("K", ctypes.c_uint32), ("ncell", ctypes.c_uint32),
+                ("cover", ctypes.c_uint64), ("gmax", ctypes.c_uint64),
+                ("cost", ctypes.c_uint64), ("cost_walk", ctypes.c_uint64),
+                ("gap", ctypes.c_uint64 * 4),
+                ("A", ctypes.c_uint64 * 4), ("As", ctypes.c_uint64 * 4),
+                ("code", ctypes.c_uint32 * (CS_MAX_VISITS // 16))]
+
+    def gaps(self):
+        """Gap of every visit, in order (decoded from the 2-bit codes)."""
+        return [int(self.gap[(self.code[k // 16] >> (2 * (k % 16))) & 3]) for k in range(self.K)]
+
+
 class CsParams(ctypes.Structure):
     _fields_ = [("r", ctypes.c_uint32), ("c", ctypes.c_uint32),
-                ("c_pow2", ctypes.c_uint32), ("reserved", ctypes.c_uint32),
+                ("c_pow2", ctypes.c_uint32), ("flags", ctypes.c_uint32),
                 ("seed", ctypes.c_uint64),
                 ("a", ctypes.c_uint64 * CS_MAX_R), ("b", ctypes.c_uint64 * CS_MAX_R),
                 ("as_", ctypes.c_uint64 * CS_MAX_R), ("bs", ctypes.c_uint64 * CS_MAX_R),
-                ("plan", CsRowPlan * CS_MAX_R)]
+                ("plan", CsRowPlan * CS_MAX_R),
+                ("visit", CsVisitPlan * CS_MAX_R)]
 
 
 def library_path() -> str:

@@ -3,6 +3,8 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <vector>
+
 #include "csketch.h"
 
 namespace {
@@ -110,6 +112,106 @@ void plan_walk(cs_row_plan* rp, uint64_t a, uint64_t as, uint32_t c, bool pow2, 
     rp->ADws = mulmod(as, rp->Dw);
 }
 
+// Visit list of the bundle update for one row (cs_visit_plan).
+//
+// Rotating a hash value left by sh = 61 - log2(c) bits is a multiplication by 2^sh mod p, so
+// u(i) = rot(a i + b) is again affine in i, its top bits are the bucket, and moving s
+// coordinates on adds exactly U(s) = (s * U(1)) mod p.  For a bound omega (in cells) the list
+// is { s < d : U(s) < omega * 2^sh } together with s = 0: every visit of a lane then lands
+// in one of ncell = ceil(omega) + 1 neighbouring cells, whose sums it keeps in registers.
+// Lanes own the residues [0, gmax), gmax the largest gap between neighbouring list entries,
+// so a worker group sends about ncell * gmax requests for the whole vector; the bound is
+// chosen to make that product smallest (one scan of s = 1 .. d - 1 collects the candidates
+// for the widest bound, narrower ones are subsets).
+void plan_visits(cs_visit_plan* vp, const cs_row_plan* rp, uint64_t a, uint64_t as, uint32_t c,
+                 bool pow2, uint64_t d_hint) {
+    memset(vp, 0, sizeof(*vp));
+    if (!pow2 || c < 64 || d_hint < 4096 || d_hint >= (1ull << 40)) return;
+    int lc = 0;
+    while ((1u << lc) < c) ++lc;
+    const int sh = 61 - lc;
+    const uint64_t cell = 1ull << sh;
+    const uint64_t u1 = mulmod(a, cell % kP61);            // U(1)
+    // the stride walk's requests, for comparison: d (|sigma(Dw)| + Dw / d)
+    {
+        const uint64_t Uw = mulmod(u1, rp->Dw % kP61);
+        const uint64_t mag = Uw < kP61 - Uw ? Uw : kP61 - Uw;
+        vp->cost_walk = (uint64_t)((double)d_hint * ((double)mag / (double)cell)) + rp->Dw;
+    }
+    const double per_cell = (double)d_hint / (double)c;    // list entries per cell of bound
+    double omega_max = (CS_MAX_VISITS - 16) / per_cell;
+    if (omega_max > 3.0) omega_max = 3.0;
+    if (omega_max * per_cell < 8.0) return;                // too few visits to pay off
+    const uint64_t U_max = (uint64_t)(omega_max * (double)cell);
+    std::vector<uint64_t> cs_, cu_;                        // candidate offsets and their U
+    {
+        uint64_t u = 0;
+        for (uint64_t s = 1; s < d_hint; ++s) {
+            u += u1;
+            if (u >= kP61) u -= kP61;
+            if (u < U_max) {
+                cs_.push_back(s);
+                cu_.push_back(u);
+                if (cs_.size() > 16 * CS_MAX_VISITS) return;   // not a rotation-like row: give up
+            }
+        }
+    }
+    uint64_t best_cost = ~0ull, best_bound = 0;
+    constexpr int kGrid = 96;
+    for (int t = 1; t <= kGrid; ++t) {
+        const uint64_t bound = (uint64_t)((double)U_max * t / kGrid);
+        if (bound == 0) continue;
+        uint64_t prev = 0, gmax = 0, K = 1;
+        for (size_t q = 0; q < cs_.size(); ++q)
+            if (cu_[q] < bound) {
+                if (cs_[q] - prev > gmax) gmax = cs_[q] - prev;
+                prev = cs_[q];
+                ++K;
+            }
+        if (d_hint - prev > gmax) gmax = d_hint - prev;
+        if (K < 4 || K > CS_MAX_VISITS) continue;
+        const uint64_t ncell = ((bound + cell - 1) >> sh) + 1;
+        const uint64_t cost = ncell * gmax;
+        if (cost < best_cost) { best_cost = cost; best_bound = bound; }
+    }
+    if (best_bound == 0) return;
+    // build the list for the chosen bound
+    uint64_t gaps[3], prev = 0;
+    int ngap = 0;
+    uint32_t K = 0;
+    auto add_visit = [&](uint64_t gap, bool last) -> bool {
+        int code = 3;
+        if (!last) {
+            for (code = 0; code < ngap; ++code)
+                if (gaps[code] == gap) break;
+            if (code == ngap) {
+                if (ngap == 3) return false;               // more than three return times
+                gaps[ngap++] = gap;
+            }
+        }
+        vp->code[K / 16] |= (uint32_t)code << (2 * (K % 16));
+        ++K;
+        return true;
+    };
+    for (size_t q = 0; q < cs_.size(); ++q)
+        if (cu_[q] < best_bound) {
+            if (!add_visit(cs_[q] - prev, false)) { memset(vp->code, 0, sizeof(vp->code)); return; }
+            prev = cs_[q];
+        }
+    add_visit(d_hint - prev, true);
+    for (int q = 0; q < 4; ++q) {
+        const uint64_t gap = q < ngap ? gaps[q] : (q == 3 ? d_hint - prev : 0);
+        vp->gap[q] = gap;
+        vp->A[q] = mulmod(a, gap % kP61);
+        vp->As[q] = mulmod(as, gap % kP61);
+        if (gap > vp->gmax) vp->gmax = gap;
+    }
+    vp->ncell = (uint32_t)(((best_bound + cell - 1) >> sh) + 1);
+    vp->cover = d_hint;
+    vp->cost = best_cost;
+    vp->K = K;
+}
+
 }  // namespace
 
 extern "C" int cs_params_init(cs_params* p, uint32_t r, uint32_t c, uint64_t seed,
@@ -135,6 +237,8 @@ extern "C" int cs_params_init(cs_params* p, uint32_t r, uint32_t c, uint64_t see
     {
         plan_row(&p->plan[j], p->a[j], p->as[j], c, p->c_pow2 != 0, (uint64_t)d_hint);
         plan_walk(&p->plan[j], p->a[j], p->as[j], c, p->c_pow2 != 0, (uint64_t)d_hint);
+        plan_visits(&p->visit[j], &p->plan[j], p->a[j], p->as[j], c, p->c_pow2 != 0,
+                    (uint64_t)d_hint);
     }
     return CS_OK;
 }

@@ -2,11 +2,24 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 #include "csketch.h"
 
 namespace cs {
+
+// What kernels receive by value: cs_params without the visit lists (kernel arguments are
+// limited to 4 KB); a list travels separately to the one kernel that reads it.
+struct KParams {
+    uint32_t r, c, c_pow2, flags;
+    uint64_t seed;
+    uint64_t a[CS_MAX_R], b[CS_MAX_R];
+    uint64_t as[CS_MAX_R], bs[CS_MAX_R];
+    cs_row_plan plan[CS_MAX_R];
+};
+static_assert(offsetof(cs_params, visit) == sizeof(KParams), "KParams is the head of cs_params");
+inline const KParams& kparams(const cs_params* p) { return *reinterpret_cast<const KParams*>(p); }
 
 constexpr int kMaxBatch = 32;   // workers per launch of the batched update kernels
 

@@ -52,7 +52,7 @@ inline unsigned grid_for(int64_t n, int per_block = kBlock, int max_blocks = 256
 // ---------------------------------------------------------------------------------------
 template <bool POW2>
 __global__ void __launch_bounds__(kBlock)
-k_hash_list(cs_params p, const int64_t* __restrict__ idx, int64_t n,
+k_hash_list(KParams p, const int64_t* __restrict__ idx, int64_t n,
             uint32_t* __restrict__ bucket, int8_t* __restrict__ sign) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
     for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < n; t += stride) {
@@ -73,7 +73,7 @@ struct RowStates {
     uint64_t yb[R], ys[R];    // y-form states of the bucket and sign hashes
     uint64_t Ab[R], As[R];    // (a_j * stride) mod p, (a'_j * stride) mod p
 
-    __device__ __forceinline__ void init(const cs_params& p, uint64_t first, uint64_t stride) {
+    __device__ __forceinline__ void init(const KParams& p, uint64_t first, uint64_t stride) {
 #pragma unroll
         for (int j = 0; j < R; ++j) {
             yb[j] = hash_state(p.a[j], p.b[j], first);
@@ -93,7 +93,7 @@ struct RowStates {
 
 template <int R, bool POW2>
 __global__ void __launch_bounds__(kBlock)
-k_hash_range(cs_params p, int64_t i0, int64_t n, uint32_t* __restrict__ bucket,
+k_hash_range(KParams p, int64_t i0, int64_t n, uint32_t* __restrict__ bucket,
              int8_t* __restrict__ sign) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
     int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
@@ -120,7 +120,7 @@ using BatchPtrs = LatticePtrs;
 // `cell_stride` is 1 for separate tables and W for a bundle (S[w] then points at T + w).
 template <int R, bool POW2>
 __global__ void __launch_bounds__(kBlock)
-k_accumulate(cs_params p, BatchPtrs ptrs, int nw, int64_t d, int64_t i0, float scale,
+k_accumulate(KParams p, BatchPtrs ptrs, int nw, int64_t d, int64_t i0, float scale,
              int64_t cell_stride) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
     int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
@@ -148,7 +148,7 @@ k_accumulate(cs_params p, BatchPtrs ptrs, int nw, int64_t d, int64_t i0, float s
 
 template <bool POW2>
 __global__ void __launch_bounds__(kBlock)
-k_accumulate_sparse(cs_params p, float* __restrict__ S, const int64_t* __restrict__ idx,
+k_accumulate_sparse(KParams p, float* __restrict__ S, const int64_t* __restrict__ idx,
                     const float* __restrict__ val, int64_t n, float scale) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
     for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < n; t += stride) {
@@ -215,7 +215,7 @@ k_momentum(float* __restrict__ Su, float* __restrict__ Sv, const float* __restri
 // ---------------------------------------------------------------------------------------
 template <int R, bool POW2>
 __global__ void __launch_bounds__(kBlock)
-k_estimate(cs_params p, const float* __restrict__ S, int64_t d, int64_t i0,
+k_estimate(KParams p, const float* __restrict__ S, int64_t d, int64_t i0,
            float* __restrict__ est) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
     int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
@@ -237,7 +237,7 @@ k_estimate(cs_params p, const float* __restrict__ S, int64_t d, int64_t i0,
 
 template <int R, bool POW2>
 __global__ void __launch_bounds__(kBlock)
-k_estimate_sparse(cs_params p, const float* __restrict__ S, const int64_t* __restrict__ idx,
+k_estimate_sparse(KParams p, const float* __restrict__ S, const int64_t* __restrict__ idx,
                   int64_t n, float* __restrict__ out) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
     for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < n; t += stride) {
@@ -286,9 +286,9 @@ extern "C" int cs_hash_debug(const cs_params* p, const int64_t* idx, int64_t n,
     if (n == 0) return CS_OK;
     if (!idx || !bucket || !sign) return CS_EINVAL;
     if (p->c_pow2)
-        k_hash_list<true><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(*p, idx, n, bucket, sign);
+        k_hash_list<true><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(kparams(p), idx, n, bucket, sign);
     else
-        k_hash_list<false><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(*p, idx, n, bucket, sign);
+        k_hash_list<false><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(kparams(p), idx, n, bucket, sign);
     return launch_status();
 }
 
@@ -301,7 +301,7 @@ extern "C" int cs_hash_debug_range(const cs_params* p, int64_t i0, int64_t n,
     // a small grid on purpose: every thread takes several strided steps
     const unsigned grid = grid_for(n, kBlock * 8, 64);
 #define CALL(R_, P2_) \
-    k_hash_range<R_, P2_><<<grid, kBlock, 0, as_stream(stream)>>>(*p, i0, n, bucket, sign)
+    k_hash_range<R_, P2_><<<grid, kBlock, 0, as_stream(stream)>>>(kparams(p), i0, n, bucket, sign)
     CS_DISPATCH_R(p, CALL);
 #undef CALL
     return launch_status();
@@ -319,7 +319,7 @@ static int accumulate_direct(const cs_params* p, const BatchPtrs& ptrs, int nw, 
     // at least ~8 coordinates per thread so the per-thread hash set-up is amortised
     const unsigned grid = grid_for(d, kBlock * 8, 256 * 8);
 #define CALL(R_, P2_)                                                                      \
-    k_accumulate<R_, P2_><<<grid, kBlock, 0, as_stream(stream)>>>(*p, ptrs, nw, d, i0, scale, \
+    k_accumulate<R_, P2_><<<grid, kBlock, 0, as_stream(stream)>>>(kparams(p), ptrs, nw, d, i0, scale, \
                                                                   cell_stride)
     CS_DISPATCH_R(p, CALL);
 #undef CALL
@@ -425,9 +425,9 @@ extern "C" int cs_sketch_accumulate_sparse(const cs_params* p, float* S, const i
     if (n == 0) return CS_OK;
     if (!S || !idx || !val) return CS_EINVAL;
     if (p->c_pow2)
-        k_accumulate_sparse<true><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(*p, S, idx, val, n, scale);
+        k_accumulate_sparse<true><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(kparams(p), S, idx, val, n, scale);
     else
-        k_accumulate_sparse<false><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(*p, S, idx, val, n, scale);
+        k_accumulate_sparse<false><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(kparams(p), S, idx, val, n, scale);
     return launch_status();
 }
 
@@ -485,7 +485,7 @@ extern "C" int cs_sketch_estimate(const cs_params* p, const float* S, int64_t d,
     }
     const unsigned grid = grid_for(d, kBlock * 8, 256 * 8);
 #define CALL(R_, P2_) \
-    k_estimate<R_, P2_><<<grid, kBlock, 0, as_stream(stream)>>>(*p, S, d, i0, est)
+    k_estimate<R_, P2_><<<grid, kBlock, 0, as_stream(stream)>>>(kparams(p), S, d, i0, est)
     CS_DISPATCH_R(p, CALL);
 #undef CALL
     return launch_status();
@@ -497,7 +497,7 @@ extern "C" int cs_sketch_estimate_sparse(const cs_params* p, const float* S, con
     if (n == 0) return CS_OK;
     if (!S || !idx || !out) return CS_EINVAL;
 #define CALL(R_, P2_) \
-    k_estimate_sparse<R_, P2_><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(*p, S, idx, n, out)
+    k_estimate_sparse<R_, P2_><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(kparams(p), S, idx, n, out)
     CS_DISPATCH_R(p, CALL);
 #undef CALL
     return launch_status();

@@ -52,7 +52,7 @@ struct TileGeom {
     int64_t ntiles;    // super-tiles * wtiles
 };
 
-__host__ __device__ __forceinline__ TileGeom tile_geom(const cs_params& p, int j, int64_t d) {
+__host__ __device__ __forceinline__ TileGeom tile_geom(const KParams& p, int j, int64_t d) {
     TileGeom g;
     g.D = static_cast<int64_t>(p.plan[j].D);
     g.L = p.plan[j].lanes;
@@ -80,7 +80,7 @@ __device__ __forceinline__ int run_span(const TileGeom& g, int64_t tile, int rho
 }
 
 // packed (bucket | sign bit 31) of the kRun coordinates starting at global index `first`
-__device__ __forceinline__ void run_hashes(const cs_params& p, int j, uint64_t first,
+__device__ __forceinline__ void run_hashes(const KParams& p, int j, uint64_t first,
                                            uint32_t (&packed)[kRun]) {
     uint64_t yb = hash_state(p.a[j], p.b[j], first);
     uint64_t ys = hash_state(p.as[j], p.bs[j], first);
@@ -123,7 +123,7 @@ __device__ __forceinline__ void load_tile(const float* __restrict__ gw, const Ti
 // Alg. 4 update, lattice order.  grid = (tiles, rows).
 // ---------------------------------------------------------------------------------------
 template <int NSTEPS>
-__device__ __forceinline__ void accumulate_row(const cs_params& p, const LatticePtrs& ptrs, int nw,
+__device__ __forceinline__ void accumulate_row(const KParams& p, const LatticePtrs& ptrs, int nw,
                                                int64_t d, int64_t i0, float scale, int j,
                                                float* tile_lds) {
     const int lane = threadIdx.x;
@@ -170,7 +170,7 @@ __device__ __forceinline__ void accumulate_row(const cs_params& p, const Lattice
 }
 
 __global__ void __launch_bounds__(64)
-k_accumulate_lattice(cs_params p, LatticePtrs ptrs, int nw, int64_t d, int64_t i0, float scale) {
+k_accumulate_lattice(KParams p, LatticePtrs ptrs, int nw, int64_t d, int64_t i0, float scale) {
     __shared__ float tile_lds[64 * kLdsStride];
     const int j = blockIdx.y;
     switch (p.plan[j].scan_steps) {       // uniform: compile-time scan depth inside
@@ -187,7 +187,7 @@ k_accumulate_lattice(cs_params p, LatticePtrs ptrs, int nw, int64_t d, int64_t i
 // coordinate goes to rows[j][i]; a second kernel takes the median over rows.
 // ---------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(64)
-k_row_values_lattice(cs_params p, const float* __restrict__ S, int64_t d, int64_t i0,
+k_row_values_lattice(KParams p, const float* __restrict__ S, int64_t d, int64_t i0,
                      float* __restrict__ rows) {
     __shared__ float tile_lds[64 * kLdsStride];
     const int j = blockIdx.y;
@@ -242,7 +242,7 @@ k_median_rows(const float* __restrict__ rows, int64_t d, float* __restrict__ est
 
 // parity hook: buckets and signs of a contiguous range, visited in lattice order
 __global__ void __launch_bounds__(64)
-k_hash_range_lattice(cs_params p, int64_t i0, int64_t n, uint32_t* __restrict__ bucket,
+k_hash_range_lattice(KParams p, int64_t i0, int64_t n, uint32_t* __restrict__ bucket,
                      int8_t* __restrict__ sign) {
     const int j = blockIdx.y;
     const int lane = threadIdx.x;
@@ -268,7 +268,7 @@ k_hash_range_lattice(cs_params p, int64_t i0, int64_t n, uint32_t* __restrict__ 
 static unsigned lattice_grid_x(const cs_params* p, int64_t d) {
     int64_t most = 1;
     for (uint32_t j = 0; j < p->r; ++j) {
-        const TileGeom g = tile_geom(*p, static_cast<int>(j), d);
+        const TileGeom g = tile_geom(kparams(p), static_cast<int>(j), d);
         if (g.ntiles > most) most = g.ntiles;
     }
     const int64_t cap = 256 * 64;      // workgroups of one wavefront: plenty per CU
@@ -288,7 +288,7 @@ bool lattice_applies(const cs_params* p, int64_t d) {
 int launch_accumulate_lattice(const cs_params* p, const LatticePtrs& ptrs, int nw, int64_t d,
                               int64_t i0, float scale, hipStream_t stream) {
     const dim3 grid(lattice_grid_x(p, d), p->r);
-    k_accumulate_lattice<<<grid, 64, 0, stream>>>(*p, ptrs, nw, d, i0, scale);
+    k_accumulate_lattice<<<grid, 64, 0, stream>>>(kparams(p), ptrs, nw, d, i0, scale);
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
 
@@ -299,7 +299,7 @@ int launch_estimate_lattice(const cs_params* p, const float* S, int64_t d, int64
         if (rc != CS_OK) return rc;
     } else {
         const dim3 grid(lattice_grid_x(p, d), p->r);
-        k_row_values_lattice<<<grid, 64, 0, stream>>>(*p, S, d, i0, rows);
+        k_row_values_lattice<<<grid, 64, 0, stream>>>(kparams(p), S, d, i0, rows);
     }
     int64_t b = (d + kBlock - 1) / kBlock;
     if (b > 256 * 16) b = 256 * 16;
@@ -321,7 +321,7 @@ int launch_estimate_lattice(const cs_params* p, const float* S, int64_t d, int64
 int launch_hash_range_lattice(const cs_params* p, int64_t i0, int64_t n, uint32_t* bucket,
                               int8_t* sign, hipStream_t stream) {
     const dim3 grid(lattice_grid_x(p, n), p->r);
-    k_hash_range_lattice<<<grid, 64, 0, stream>>>(*p, i0, n, bucket, sign);
+    k_hash_range_lattice<<<grid, 64, 0, stream>>>(kparams(p), i0, n, bucket, sign);
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
 

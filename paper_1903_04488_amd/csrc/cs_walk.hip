@@ -70,7 +70,7 @@ struct WalkArgs {
 // time (nothing is shared and nothing is synchronised between them), which widens the
 // contiguous stretch of every vector that is being read at one moment.
 template <int WL, int RUN, int NWAVE>
-__global__ void __launch_bounds__(64 * NWAVE) k_accumulate_walk(cs_params p, WalkArgs a) {
+__global__ void __launch_bounds__(64 * NWAVE) k_accumulate_walk(KParams p, WalkArgs a) {
     constexpr int WPW = 64 / WL;                       // walkers per wavefront
     constexpr int PPL = RUN / WL > 0 ? RUN / WL : 1;   // hash values each lane computes
     constexpr int kStride = RUN + 1;                   // padded LDS row of the value tile
@@ -82,7 +82,8 @@ __global__ void __launch_bounds__(64 * NWAVE) k_accumulate_walk(cs_params p, Wal
     __shared__ uint32_t hash_lds_all[NWAVE][2][WPW * RUN];   // (bucket | sign), this and previous visit
     __shared__ gfloat_ptr gptr_lds_all[NWAVE][kGroup];
 
-    const int lane = threadIdx.x & 63, wq = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wq = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wavefront-uniform
     float* tile_lds = tile_lds_all[wq];
     uint32_t (*hash_lds)[WPW * RUN] = hash_lds_all[wq];
     gfloat_ptr* gptr_lds = gptr_lds_all[wq];
@@ -243,8 +244,329 @@ int launch_walk(const cs_params* p, const WalkArgs& a, hipStream_t stream) {
     const int64_t cap = 256 * 64 / NWAVE;
     int64_t gx = ngroups < cap ? ngroups : cap;
     gx = (gx + 7) / 8 * 8;                   // the kernel deals workgroups to XCDs in eights
-    k_accumulate_walk<WL, RUN, NWAVE><<<static_cast<unsigned>(gx), 64 * NWAVE, 0, stream>>>(*p, a);
+    k_accumulate_walk<WL, RUN, NWAVE><<<static_cast<unsigned>(gx), 64 * NWAVE, 0, stream>>>(kparams(p), a);
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
+}
+
+// ---------------------------------------------------------------------------------------
+// The same update along a visit list (cs_visit_plan) instead of a single stride.
+//
+// The list s_0 = 0 < s_1 < ... holds every offset whose bucket advance is below a bound of
+// ncell - 1 cells, so whatever a lane meets at i + s_k lies in one of the NC = ncell cells
+// that start at the cell of i.  A lane therefore keeps NC running sums per coordinate of its
+// run for the whole kernel and sends each to memory exactly once at the end: NC atomic
+// requests per RUN-residue and worker group for the entire vector, and none inside the loop.
+// Visit k covers [s_k, s_k + gap_k); the walker that owns residues [off, off + RUN) takes part
+// in it when off < gap_k, so lanes own the residues below the largest gap.  Loads, the LDS
+// transpose and the roles of lanes are those of the stride walk above.
+// ---------------------------------------------------------------------------------------
+struct VisitArgs {
+    uint32_t K, pad;
+    uint64_t gmax;
+    uint64_t gap[4], A[4], As[4];
+    uint32_t code[CS_MAX_VISITS / 16];
+};
+
+
+typedef float vec2f __attribute__((ext_vector_type(2)));
+typedef vec2f __attribute__((aligned(4))) vec2f_u;            // 8 bytes at any dword address
+typedef const __attribute__((address_space(1))) vec2f_u* gvec2_ptr;
+
+// N consecutive floats from global memory at any dword address, as the widest requests
+template <int N>
+__device__ __forceinline__ void load_floats(gfloat_ptr src, float (&out)[N]) {
+    static_assert(N == 2 || N % 4 == 0, "pieces of 2, 4, 8 or 16 floats");
+    if constexpr (N == 2) {
+        const vec2f u = *(gvec2_ptr)src;
+        out[0] = u.x;
+        out[1] = u.y;
+    } else {
+#pragma unroll
+        for (int t = 0; t < N; t += 4) {
+            const vec4f u = *(gvec4_ptr)(src + t);
+            out[t] = u.x;
+            out[t + 1] = u.y;
+            out[t + 2] = u.z;
+            out[t + 3] = u.w;
+        }
+    }
+}
+
+template <int WL, int RUN, int NWAVE, int NC>
+__global__ void __launch_bounds__(64 * NWAVE)
+k_accumulate_visits(KParams p, VisitArgs v, WalkArgs a) {
+    constexpr int WPW = 64 / WL;                       // walkers per wavefront
+    constexpr int PPL = RUN / WL;                      // hash values each lane computes
+    constexpr int FPL = RUN / WL;                      // floats each lane requests per worker
+    constexpr int SPAN = WPW * RUN;                    // residues a wavefront owns
+    constexpr int kStride = RUN + 1;
+    constexpr int kSetBlock = 4;                       // neighbouring walker sets per XCD turn
+    constexpr int kRec = NC == 2 ? 2 : 4;              // words of a coordinate's record
+    static_assert(WL <= 8 && WL * PPL == RUN, "every coordinate of a walker gets a hash lane");
+    static_assert(NC >= 2 && NC <= 4, "two to four running sums");
+    // Per wavefront: the value tile (one padded row per lane), one record per coordinate of
+    // every walker (sign word, then one all-ones / all-zeros word per cell but the last,
+    // telling which running sum the coordinate belongs to in this visit), the walkers' first
+    // cells, and the (bucket | sign) words of the stride walk, for the fallback.
+    __shared__ float tile_lds_all[NWAVE][64 * kStride];
+    __shared__ __attribute__((aligned(16))) uint32_t rec_lds_all[NWAVE][SPAN * kRec];
+    __shared__ uint32_t first_lds_all[NWAVE][SPAN];
+    __shared__ uint32_t raw_lds_all[NWAVE][SPAN];
+
+    const int lane = threadIdx.x & 63;
+    const int wq = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wavefront-uniform
+    float* tile_lds = tile_lds_all[wq];
+    uint32_t* rec_lds = rec_lds_all[wq];
+    uint32_t* first_lds = first_lds_all[wq];
+    uint32_t* raw_lds = raw_lds_all[wq];
+    const int j = a.j;
+    const int h = lane / WL, wl = lane % WL;
+    const int nw = a.nw;
+    const bool live = wl < nw;                          // my worker exists
+
+    const int64_t chunks = (static_cast<int64_t>(v.gmax) + RUN - 1) / RUN;
+    const int64_t nwaves = (chunks + WPW - 1) / WPW;
+    const uint32_t mask = p.c - 1u;
+    const int64_t d = a.d;
+    float* __restrict__ Tcol = a.Trow + wl;
+    const int m0 = wl * PPL;                           // hash role: coordinates m0 .. m0 + PPL - 1
+    float* my_row = tile_lds + lane * kStride;         // consumer role: my walker's run of my worker
+    const uint32_t* my_rec = rec_lds + h * RUN * kRec;
+    uint32_t* rec_dst = rec_lds + (h * RUN + m0) * kRec;
+    const uint64_t Aj = p.a[j], Asj = p.as[j];
+    // loader role: floats lspan .. lspan + FPL - 1 of the wavefront's span, of every worker;
+    // they belong to walker lspan / RUN and go to that walker's row of each worker
+    const int lspan = lane * FPL;
+    float* tile_dst = tile_lds + (lspan / RUN) * WL * kStride + lspan % RUN;
+    // the list's three gaps and the cut last one, with their hash advances, in scalar registers
+    const uint64_t g0 = v.gap[0], g1 = v.gap[1], g2 = v.gap[2], g3 = v.gap[3];
+    const uint64_t A0 = v.A[0], A1 = v.A[1], A2 = v.A[2], A3 = v.A[3];
+    const uint64_t B0 = v.As[0], B1 = v.As[1], B2 = v.As[2], B3 = v.As[3];
+    auto code_of = [&](uint32_t k) { return (v.code[k >> 4] >> ((k & 15u) * 2u)) & 3u; };
+    auto pick = [](uint32_t code, uint64_t x0, uint64_t x1, uint64_t x2, uint64_t x3) {
+        return code == 0u ? x0 : code == 1u ? x1 : code == 2u ? x2 : x3;
+    };
+
+    // Walkers with small residues take part in every visit, those with large ones only in
+    // the visits with the largest gap, so the sets of walkers are dealt to the XCDs in short
+    // blocks rather than as eight long ranges: every XCD gets the same mix.
+    const int64_t ngroups = (nwaves + NWAVE - 1) / NWAVE;
+    for (int64_t vi = blockIdx.x; ; vi += gridDim.x) {
+        const int64_t slot = vi >> 3;
+        const int64_t set = ((slot / kSetBlock) * 8 + (vi & 7)) * kSetBlock + slot % kSetBlock;
+        if ((slot / kSetBlock) * 8 * kSetBlock >= ngroups) break;
+        const int64_t wv = set * NWAVE + wq;
+        if (set >= ngroups || wv >= nwaves) continue;
+        const int64_t first_res = wv * SPAN;           // first residue of this wavefront's walkers
+        uint64_t yb = hash_state(p.a[j], p.b[j], static_cast<uint64_t>(a.i0 + first_res + h * RUN + m0));
+        uint64_t ys = hash_state(p.as[j], p.bs[j], static_cast<uint64_t>(a.i0 + first_res + h * RUN + m0));
+
+        // the cells my coordinates start in (visit 0, whether or not I take part in it)
+        uint32_t first_cell[PPL];
+        {
+            uint64_t tb = yb;
+#pragma unroll
+            for (int q = 0; q < PPL; ++q) {
+                first_cell[q] = (static_cast<uint32_t>(tb) - 1u) & mask;
+                first_lds[h * RUN + m0 + q] = first_cell[q];
+                if (q + 1 < PPL) tb = hash_advance(tb, Aj);
+            }
+        }
+
+        float acc[NC][RUN];
+#pragma unroll
+        for (int q = 0; q < NC; ++q)
+#pragma unroll
+            for (int m = 0; m < RUN; ++m) acc[q][m] = 0.0f;
+
+        // Requests of the visit at offset s.  `room` = residues from first_res on that belong
+        // to the visit and exist; when the whole span does, every piece is whole and needs no
+        // check (one wavefront-uniform base per worker plus a fixed lane offset).  Otherwise
+        // pieces are cut where the visit or the vector ends, and missing values count as 0.
+        float pre[WL][FPL];
+        auto load_visit = [&](int64_t s, int64_t room) {
+            if (room >= SPAN) {
+#pragma unroll
+                for (int w = 0; w < WL; ++w) {
+                    const gfloat_ptr base =
+                        (gfloat_ptr)a.g[w < nw ? w : 0] + (first_res + s);
+                    load_floats<FPL>(base + lspan, pre[w]);
+                }
+            } else {
+                const int len = static_cast<int>(room) - lspan;    // of my piece: >= FPL whole, <= 0 none
+#pragma unroll
+                for (int w = 0; w < WL; ++w) {
+                    const gfloat_ptr src =
+                        (gfloat_ptr)a.g[w < nw ? w : 0] + (first_res + s) + lspan;
+#pragma unroll
+                    for (int t = 0; t < FPL; ++t) pre[w][t] = 0.0f;
+                    if (len >= FPL) {
+                        load_floats<FPL>(src, pre[w]);
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < FPL; ++t)
+                            if (t < len) pre[w][t] = src[t];
+                    }
+                }
+            }
+        };
+        // room of the visit with gap `gap` at offset s; > 0 means this wavefront takes part
+        auto room_of = [&](int64_t s, int64_t gap) {
+            const int64_t in_gap = gap - first_res, in_vec = d - s - first_res;
+            return in_gap < in_vec ? in_gap : in_vec;
+        };
+
+        int64_t s = 0;                                 // offset of visit k
+        uint32_t code = code_of(0);
+        bool active = room_of(0, static_cast<int64_t>(pick(code, g0, g1, g2, g3))) > 0;
+        if (active) load_visit(0, room_of(0, static_cast<int64_t>(pick(code, g0, g1, g2, g3))));
+        for (uint32_t k = 0; k < v.K; ++k) {
+            // visit k: its values are on their way (requested one turn earlier)
+            bool bad = false;
+            if (active) {
+#pragma unroll
+                for (int w = 0; w < WL; ++w)
+#pragma unroll
+                    for (int t = 0; t < FPL; ++t) tile_dst[w * kStride + t] = pre[w][t];
+                uint64_t tb = yb, ts = ys;
+#pragma unroll
+                for (int q = 0; q < PPL; ++q) {
+                    const uint32_t cell = (static_cast<uint32_t>(tb) - 1u) & mask;
+                    const uint32_t rel = (cell - first_cell[q]) & mask;
+                    const uint32_t flip = sign_flip_of(ts);
+                    bad |= rel >= static_cast<uint32_t>(NC);
+                    if (NC == 2) {
+                        *reinterpret_cast<uint2*>(rec_dst + q * kRec) =
+                            make_uint2(flip, rel == 0u ? ~0u : 0u);
+                    } else {
+                        *reinterpret_cast<uint4*>(rec_dst + q * kRec) = make_uint4(
+                            flip, rel == 0u ? ~0u : 0u, rel == 1u ? ~0u : 0u, rel == 2u ? ~0u : 0u);
+                    }
+                    if (q + 1 < PPL) {
+                        tb = hash_advance(tb, Aj);
+                        ts = hash_advance(ts, Asj);
+                    }
+                }
+            }
+            // A coordinate outside the NC cells cannot happen with a list built by
+            // cs_params_init; the check is kept so that a wrong list costs time, never
+            // correctness: such a visit's values go to memory one by one, and the tile is
+            // cleared so that the sums below take nothing from it.
+            const bool stray = active && __builtin_amdgcn_ballot_w64(bad) != 0;
+            if (stray) {
+                uint64_t tb = yb, ts = ys;
+#pragma unroll
+                for (int q = 0; q < PPL; ++q) {
+                    raw_lds[h * RUN + m0 + q] = ((static_cast<uint32_t>(tb) - 1u) & mask) | sign_flip_of(ts);
+                    if (q + 1 < PPL) {
+                        tb = hash_advance(tb, Aj);
+                        ts = hash_advance(ts, Asj);
+                    }
+                }
+            }
+            const int64_t gap = static_cast<int64_t>(pick(code, g0, g1, g2, g3));
+            yb = hash_advance(yb, pick(code, A0, A1, A2, A3));
+            ys = hash_advance(ys, pick(code, B0, B1, B2, B3));
+            // request visit k + 1, to fly while visit k is added up
+            const bool was_active = active;
+            s += gap;
+            active = false;
+            if (k + 1 < v.K) {
+                code = code_of(k + 1);
+                const int64_t room = room_of(s, static_cast<int64_t>(pick(code, g0, g1, g2, g3)));
+                active = room > 0;
+                if (active) load_visit(s, room);
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (stray) {
+                const uint32_t* raw = raw_lds + h * RUN;
+#pragma unroll
+                for (int m = 0; m < RUN; ++m) {
+                    const uint32_t pk = raw[m];
+                    const float val = apply_sign(a.scale * my_row[m], pk & 0x80000000u);
+                    if (live && val != 0.0f)
+                        atomic_add_noret(Tcol + static_cast<size_t>(pk & 0x7fffffffu) * kGroup, val);
+                    my_row[m] = 0.0f;
+                }
+            }
+            if (was_active) {
+#pragma unroll
+                for (int m = 0; m < RUN; ++m) {
+                    if (NC == 2) {
+                        const uint2 rec = *reinterpret_cast<const uint2*>(my_rec + m * kRec);
+                        const uint32_t bits = __float_as_uint(my_row[m]) ^ rec.x;
+                        const uint32_t t0 = bits & rec.y;
+                        acc[0][m] += __uint_as_float(t0);
+                        acc[1][m] += __uint_as_float(bits ^ t0);
+                    } else {
+                        const uint4 rec = *reinterpret_cast<const uint4*>(my_rec + m * kRec);
+                        const uint32_t bits = __float_as_uint(my_row[m]) ^ rec.x;
+                        const uint32_t t0 = bits & rec.y, t1 = bits & rec.z;
+                        acc[0][m] += __uint_as_float(t0);
+                        acc[1][m] += __uint_as_float(t1);
+                        if (NC == 3) {
+                            acc[2][m] += __uint_as_float(bits ^ t0 ^ t1);
+                        } else {
+                            const uint32_t t2 = bits & rec.w;
+                            acc[2][m] += __uint_as_float(t2);
+                            acc[NC - 1][m] += __uint_as_float(bits ^ t0 ^ t1 ^ t2);
+                        }
+                    }
+                    // keeps the LDS reads of later coordinates from being hoisted over the sums
+                    // of earlier ones, which would cost a register per read in flight
+                    if (m % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        // every running sum goes to memory once
+        const uint32_t* first = first_lds + h * RUN;
+#pragma unroll
+        for (int m = 0; m < RUN; ++m) {
+            const uint32_t c0 = first[m];
+#pragma unroll
+            for (int q = 0; q < NC; ++q)
+                if (live && acc[q][m] != 0.0f)
+                    atomic_add_noret(Tcol + static_cast<size_t>((c0 + q) & mask) * kGroup,
+                                     a.scale * acc[q][m]);
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+template <int WL, int RUN, int NWAVE>
+int launch_visits(const cs_params* p, const WalkArgs& a, hipStream_t stream) {
+    constexpr int WPW = 64 / WL;
+    const cs_visit_plan& vp = p->visit[a.j];
+    VisitArgs v{};
+    v.K = vp.K;
+    v.gmax = vp.gmax;
+    for (int q = 0; q < 4; ++q) { v.gap[q] = vp.gap[q]; v.A[q] = vp.A[q]; v.As[q] = vp.As[q]; }
+    for (int q = 0; q < CS_MAX_VISITS / 16; ++q) v.code[q] = vp.code[q];
+    const int64_t chunks = (static_cast<int64_t>(vp.gmax) + RUN - 1) / RUN;
+    const int64_t nwaves = (chunks + WPW - 1) / WPW;
+    const int64_t ngroups = (nwaves + NWAVE - 1) / NWAVE;
+    const int64_t cap = 256 * 64 / NWAVE;
+    int64_t gx = ngroups < cap ? ngroups : cap;
+    gx = (gx + 7) / 8 * 8;                   // the kernel deals workgroups to XCDs in eights
+    const unsigned grid = static_cast<unsigned>(gx), block = 64 * NWAVE;
+    const KParams& kp = kparams(p);
+    switch (vp.ncell) {
+        case 2: k_accumulate_visits<WL, RUN, NWAVE, 2><<<grid, block, 0, stream>>>(kp, v, a); break;
+        case 3: k_accumulate_visits<WL, RUN, NWAVE, 3><<<grid, block, 0, stream>>>(kp, v, a); break;
+        case 4: k_accumulate_visits<WL, RUN, NWAVE, 4><<<grid, block, 0, stream>>>(kp, v, a); break;
+        default: return CS_EINVAL;
+    }
+    return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
+}
+
+// the visit list of row j serves vectors of length d, and is expected to send fewer requests
+bool visits_apply(const cs_params* p, uint32_t j, int64_t d) {
+    const cs_visit_plan& vp = p->visit[j];
+    if ((p->flags & CS_FLAG_NO_VISIT_LIST) != 0 || vp.K == 0) return false;
+    if (vp.ncell < 2 || vp.ncell > 4 || vp.K > CS_MAX_VISITS) return false;
+    if (static_cast<uint64_t>(d) > vp.cover) return false;
+    return vp.cost < vp.cost_walk;
 }
 
 }  // namespace
@@ -270,14 +592,21 @@ int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* con
             a.j = static_cast<int32_t>(j);
             a.Trow = T + (static_cast<size_t>(w0 / kGroup) * p->r + j) * row_floats;
             int rc;
+            if (visits_apply(p, j, d)) {
+                if (a.nw > 4) rc = launch_visits<8, 16, CS_WALK_NWAVE8>(p, a, stream);
+                else if (a.nw > 2) rc = launch_visits<4, 16, 1>(p, a, stream);
+                else if (a.nw > 1) rc = launch_visits<2, 16, 1>(p, a, stream);
+                else rc = launch_visits<1, 16, 1>(p, a, stream);
+            } else {
 #if CS_BUNDLE_GROUP >= 16
-            if (a.nw > 8) rc = launch_walk<16, 16, 2>(p, a, stream);
-            else
+                if (a.nw > 8) rc = launch_walk<16, 16, 2>(p, a, stream);
+                else
 #endif
-            if (a.nw > 4) rc = launch_walk<8, 16, CS_WALK_NWAVE8>(p, a, stream);
-            else if (a.nw > 2) rc = launch_walk<4, 16, 1>(p, a, stream);
-            else if (a.nw > 1) rc = launch_walk<2, 16, 1>(p, a, stream);
-            else rc = launch_walk<1, 16, 1>(p, a, stream);
+                if (a.nw > 4) rc = launch_walk<8, 16, CS_WALK_NWAVE8>(p, a, stream);
+                else if (a.nw > 2) rc = launch_walk<4, 16, 1>(p, a, stream);
+                else if (a.nw > 1) rc = launch_walk<2, 16, 1>(p, a, stream);
+                else rc = launch_walk<1, 16, 1>(p, a, stream);
+            }
             if (rc != CS_OK) return rc;
         }
     }
@@ -299,7 +628,7 @@ namespace {
 constexpr int kQRun = 16;
 
 __global__ void __launch_bounds__(64)
-k_row_values_walk(cs_params p, const float* __restrict__ S, int64_t d, int64_t i0,
+k_row_values_walk(KParams p, const float* __restrict__ S, int64_t d, int64_t i0,
                   float* __restrict__ rows) {
     constexpr int kStride = kQRun + 1;
     constexpr int kPieces = kQRun / 4, kRunsPerPass = 64 / kPieces, kPasses = kPieces;
@@ -386,7 +715,7 @@ int launch_row_values_walk(const cs_params* p, const float* S, int64_t d, int64_
     int64_t gx = most < cap ? most : cap;
     gx = (gx + 7) / 8 * 8;
     const dim3 grid(static_cast<unsigned>(gx), p->r);
-    k_row_values_walk<<<grid, 64, 0, stream>>>(*p, S, d, i0, rows);
+    k_row_values_walk<<<grid, 64, 0, stream>>>(kparams(p), S, d, i0, rows);
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
 

@@ -5,6 +5,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 import paper_1903_04488_amd as cs
@@ -62,6 +63,54 @@ def test_traversal_plan_is_consistent(lib):
                 A1 = min(Au, P - Au)
                 longest = (arc - 1) // A1 + 1 if A1 else 1 << 60
                 assert (1 << pl.scan_steps) >= min(longest, 16)
+
+
+@pytest.mark.parametrize("r,c,seed,d", [(5, 1 << 15, 190304489, 1 << 20), (7, 1 << 19, 190304493, 25_000_000),
+                                        (5, 1 << 12, 11, 200_003), (3, 64, 3, 5_000_000),
+                                        (5, 1000, 9, 50_001), (5, 1 << 15, 2, 1000), (5, 1 << 15, 2, 0)])
+def test_visit_list_is_consistent(lib, r, c, seed, d):
+    """The visit list of the bundle update: starts at offset 0, gaps tile [0, d_hint) exactly,
+    the hash advances belong to the gaps, and -- the property the kernel's running sums rest
+    on -- moving any coordinate by any listed offset advances its bucket by fewer than ncell
+    cells (checked with Python integers on random coordinates and on coordinates chosen to sit
+    at the edges of a cell)."""
+    p = cs.cs_params_init(r, c, seed, d)
+    rng = np.random.default_rng(seed)
+    pow2 = c & (c - 1) == 0
+    for j in range(r):
+        v = p.visit[j]
+        if not pow2 or d < 4096:
+            assert v.K == 0
+            continue
+        if v.K == 0:
+            continue
+        assert 4 <= v.K <= binding.CS_MAX_VISITS and 2 <= v.ncell <= 4
+        assert v.cover == d
+        gaps = v.gaps()
+        assert all(g > 0 for g in gaps) and sum(gaps) == d
+        assert v.gmax == max(gaps)
+        assert len(set(gaps[:-1])) <= 3            # return times of a rotation to an interval
+        for q in range(4):
+            assert v.A[q] == (p.a[j] * v.gap[q]) % P and v.As[q] == (p.as_[j] * v.gap[q]) % P
+        a, b = int(p.a[j]), int(p.b[j])
+        offsets = np.cumsum([0] + gaps[:-1]).tolist()
+        # coordinates whose hash value is the first / last of a cell's arc, and random ones
+        sh = 61 - (c.bit_length() - 1)
+        inv_a = pow(a, P - 2, P)
+        edge = []
+        for cell in (0, 1, c // 2, c - 1):
+            for u in ((cell << sh), ((cell + 1) << sh) - 1):          # rotated value
+                x = ((u & ((1 << sh) - 1)) << (61 - sh)) | (u >> sh)  # rotate back by sh bits
+                if x < P:
+                    edge.append(((x - b) * inv_a) % P)
+        coords = edge + rng.integers(0, 1 << 40, size=40).tolist()
+        for i in coords:
+            h0 = ((a * i + b) % P) % c
+            for s in offsets:
+                rel = ((((a * (i + s) + b) % P) % c) - h0) % c
+                assert rel < v.ncell, (j, i, s, rel)
+        # the list must beat the stride walk by its own estimate to be used at all
+        assert v.cost > 0 and v.cost_walk > 0
 
 
 def test_invalid_arguments_are_rejected_without_a_gpu(lib):

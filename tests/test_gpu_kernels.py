@@ -161,6 +161,63 @@ def test_accumulate_bundle(W, r, c, seed, d, i0):
     assert (T == 0).all()
 
 
+def _bundle_tables(p, gs, r, c, i0=0, scale=1.0):
+    W, G = len(gs), cs.CS_BUNDLE_GROUP
+    T = torch.zeros(cs.cs_bundle_floats(p, W), dtype=torch.float32, device=DEV)
+    cs.cs_sketch_accumulate_bundle(p, T, [dev(g) for g in gs], i0=i0, scale=scale)
+    Th = T.cpu().numpy().reshape(-1, r, c, G)
+    return [Th[w // G, :, :, w % G] for w in range(W)]
+
+
+@pytest.mark.parametrize("W", [1, 2, 3, 8, 13])
+def test_accumulate_bundle_every_traversal(W):
+    """The same vectors through the visit-list update (the default when a list exists), the
+    stride walk (list switched off by flag), a forged list whose offsets do not keep a lane
+    within its cells (every such visit takes the kernel's one-by-one fallback), and vectors
+    shorter and longer than the length the list was built for: all against the reference."""
+    import ctypes
+    from paper_1903_04488_amd import binding
+    r, c, seed, d = 5, 1 << 12, 11, 200_003
+    P = (1 << 61) - 1
+    p = cs.cs_params_init(r, c, seed, d)
+    assert all(p.visit[j].K > 0 for j in range(r))
+    sk = orc.SketchOracle(r, c, seed)
+    rng = np.random.default_rng(W)
+    gs = [(rng.standard_normal(d) * 0.01).astype(np.float32) for _ in range(W)]
+    for g in gs:
+        g[rng.integers(0, d, size=20)] -= 1.0
+    refs = [sk.sketch(g, i0=5, scale=2.0) for g in gs]
+
+    def check(params, what):
+        for w, tab in enumerate(_bundle_tables(params, gs, r, c, i0=5, scale=2.0)):
+            assert_cells_close(tab, refs[w], what=f"{what}, worker {w}", terms_per_cell=d / c)
+
+    check(p, "visit list")
+    walk = binding.CsParams.from_buffer_copy(p)
+    walk.flags = binding.CS_FLAG_NO_VISIT_LIST
+    check(walk, "stride walk")
+    forged = binding.CsParams.from_buffer_copy(p)
+    g0 = 30_011
+    for j in range(r):
+        v = forged.visit[j]
+        ctypes.memset(ctypes.byref(v), 0, ctypes.sizeof(v))
+        v.K, v.ncell, v.cover, v.gmax, v.cost, v.cost_walk = 3, 2, d, d - 2 * g0, 1, 2
+        v.gap[0], v.gap[3] = g0, d - 2 * g0
+        v.A[0], v.As[0] = (p.a[j] * g0) % P, (p.as_[j] * g0) % P
+        v.code[0] = 0b110000                      # visits 0, 1: code 0; visit 2: code 3
+    check(forged, "forged list")
+    # shorter than planned: the list still applies; longer: the stride walk takes over
+    for d2 in (d - 12_345, 4_100):
+        short = [g[:d2] for g in gs]
+        for w, tab in enumerate(_bundle_tables(p, short, r, c)):
+            assert_cells_close(tab, sk.sketch(short[w]), what=f"d = {d2}, worker {w}",
+                               terms_per_cell=d2 / c)
+    pl = cs.cs_params_init(r, c, seed, d - 50_000)
+    assert pl.visit[0].cover < d
+    for w, tab in enumerate(_bundle_tables(pl, gs, r, c, i0=5, scale=2.0)):
+        assert_cells_close(tab, refs[w], what=f"longer than planned, worker {w}", terms_per_cell=d / c)
+
+
 @pytest.mark.parametrize("r,c,seed", SHAPES[:5])
 def test_accumulate_sparse_with_repeats(r, c, seed):
     p = cs.cs_params_init(r, c, seed)
