@@ -9,6 +9,7 @@ hot path of Sketched-SGD computes, step by step, in the paper's order and notati
                       exact values; momentum u <- m u + g and error accumulation v <- v + u,
                       here held as their sketches (linear images), see SketchSpaceState
     Sec. 5.2          "query every coordinate, then choose the largest"
+    Alg. 1 (Sec. 4)   HEAVYMIX: l2 estimate from the sketch, threshold split, random fill
 
 Only tests, the smoke check and the benchmark's cpu_baseline leg may import this module.
 It imports nothing from the HIP package and the HIP package imports nothing from here.
@@ -18,7 +19,8 @@ routine (sort, sum, fancy indexing) is written with numpy.
 Every function here is pinned by tests/test_oracle_pins.py to something other than
 itself (dense-matrix product on tiny inputs, linearity, closed-form row variance, AMS
 special case, planted-sparse recovery, numpy's stable argsort, a dense-state twin of the
-sketch-space state).  Nothing in this file is "parity unpinned"; the one free choice
+sketch-space state; for HEAVYMIX: the exact norm of sparse vectors, the paper's (1 +- 0.5)
+band, a brute-force split, the uniformity of the fill and the k/d contraction of Lemma 1).  Nothing in this file is "parity unpinned"; the one free choice
 (the value fed back in sketch space, SketchSpaceState.feedback) is a documented reading,
 pinned internally by the dense-state twin.
 """
@@ -216,6 +218,57 @@ def select_exact_topk(cand, x, k: int):
     cand = np.asarray(cand, dtype=np.int64)
     pos = topk(np.asarray(x, dtype=np.float64), k)
     return cand[pos], np.asarray(x, dtype=np.float64)[pos]
+
+
+# ---------------------------------------------------------------------------
+# HEAVYMIX (Alg. 1): threshold split and random fill
+# ---------------------------------------------------------------------------
+def l2sq_estimate(T):
+    """Alg. 1 step 1 ("query l2^2 from the sketch"), by the AMS argument of App. C: a row's
+    counters are signed sums over disjoint sets of coordinates, so the sum of their squares
+    has expectation ||g||^2; the median over the r rows controls the failure probability.
+    Returns (median over rows, the r row sums)."""
+    rows = (np.asarray(T, dtype=np.float64) ** 2).sum(axis=1)
+    return float(np.sort(rows)[rows.size // 2]), rows
+
+
+def heavymix_fill_keys(rng_seed: int, d: int) -> np.ndarray:
+    """The random order behind rand_l(NH) (Alg. 1 step 4): coordinate i gets the 30 top bits
+    of the (i+1)-th output of the SplitMix64 generator started at rng_seed; the l non-heavy
+    coordinates with the largest keys are drawn (equal keys: lower index first).  Keys of
+    distinct coordinates are independent uniform draws, so this is a uniform sample without
+    replacement up to the (2^-30) chance of equal keys.  SplitMix64 is written out here with
+    numpy's wrapping uint64 arithmetic."""
+    with np.errstate(over="ignore"):
+        z = np.uint64(rng_seed) + np.arange(1, d + 1, dtype=np.uint64) * np.uint64(0x9E3779B97F4A7C15)
+        z = (z ^ (z >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+        z = (z ^ (z >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+        z = z ^ (z >> np.uint64(31))
+    return (z >> np.uint64(34)).astype(np.uint32)
+
+
+def heavymix_select(est, k: int, l2sq: float, rng_seed: int):
+    """Alg. 1 steps 3-4.  H = { i : est_i^2 >= l2sq / k } (the listing's comparison of est_i
+    itself with l2sq / k is read as the squared form that Sec. 4's proof and Def. 2 of App. C
+    use); the selection is H plus l = k - |H| coordinates drawn uniformly at random from the
+    others.  The estimates are taken in binary32 (what the sketch query returns), their
+    squares and the threshold in binary64.  The proof's "|H| <= k" holds for exact values
+    only; if more than k estimates pass, the k largest of them are kept, ordered by the top
+    30 bits of the binary32 magnitude, equal ones by lower index.
+    Returns (k indices ascending, number of heavy coordinates among them)."""
+    est32 = np.ascontiguousarray(est, dtype=np.float32)
+    d = est32.size
+    theta = np.float64(l2sq) / np.float64(k)
+    heavy = est32.astype(np.float64) ** 2 >= theta
+    H = np.flatnonzero(heavy)
+    if H.size >= k:
+        key = ((est32.view(np.uint32)[H] & np.uint32(0x7FFFFFFF)) >> np.uint32(1)).astype(np.int64)
+        keep = H[np.argsort(-key, kind="stable")[:k]]
+        return np.sort(keep).astype(np.int64), k
+    NH = np.flatnonzero(~heavy)
+    key = heavymix_fill_keys(rng_seed, d)[NH].astype(np.int64)
+    fill = NH[np.argsort(-key, kind="stable")[: k - H.size]]
+    return np.sort(np.concatenate([H, fill])).astype(np.int64), int(H.size)
 
 
 def compression_factor(d: int, sketch_cells: int, P: int, k: int) -> float:

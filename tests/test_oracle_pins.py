@@ -12,6 +12,9 @@ paper or the mathematics fixes, not against itself.
   top-k, gather  numpy lexsort / fancy indexing
   state          sketch-space momentum / error feedback equals the sketch of its dense twin
   accounting     compression factors printed in Table 1 and App. E
+  HEAVYMIX       l2 estimate exact on sparse vectors and inside the (1 +- 0.5) band of Alg. 1;
+                 threshold split against a plain loop; fill keys against the published
+                 generator; uniformity of the fill; the k/d contraction of Lemma 1
 """
 import os
 
@@ -434,6 +437,105 @@ def test_momentum_recursion_closed_form():
 
 
 # ----------------------------------------------------------------------------- accounting
+# ----------------------------------------------------------------------------- HEAVYMIX
+def test_l2sq_exact_on_sparse_and_in_band_on_dense():
+    sk = orc.SketchOracle(5, 1 << 12, 21)
+    d = 1 << 16
+    g = np.zeros(d)
+    g[777] = -3.0
+    l2, rows = orc.l2sq_estimate(sk.sketch(g))
+    assert l2 == 9.0 and (rows == 9.0).all()                 # 1-sparse: every row holds g_i once
+    g = np.zeros(d)
+    idx = np.array([5, 1000, 40000, 65535])
+    g[idx] = [1.0, -2.0, 0.5, 4.0]
+    b, _ = sk.hash(idx)
+    assert all(len(set(row)) == idx.size for row in b)       # no two share a bucket in any row
+    l2, rows = orc.l2sq_estimate(sk.sketch(g))
+    assert l2 == pytest.approx(21.25, rel=1e-15) and np.allclose(rows, 21.25, rtol=1e-15)
+    rng = np.random.default_rng(3)
+    g = rng.standard_normal(d)
+    true = float(g @ g)
+    l2, rows = orc.l2sq_estimate(sk.sketch(g))
+    assert 0.5 * true <= l2 <= 1.5 * true                    # Alg. 1 step 1
+    # AMS: a row's estimate has relative standard deviation about sqrt(2 / c) = 2.2 %
+    assert np.abs(rows / true - 1).max() < 0.12 and abs(l2 / true - 1) < 0.06
+    assert l2 == np.median(rows)
+
+
+def test_heavymix_fill_keys_are_the_published_generator():
+    for seed in (0, 1234567, (1 << 64) - 3):
+        want = orc.splitmix64(seed, 1000) >> np.uint64(34)     # C version, pinned to the published vector
+        np.testing.assert_array_equal(orc.heavymix_fill_keys(seed, 1000), want.astype(np.uint32))
+
+
+def test_heavymix_split_and_fill_against_plain_loops():
+    rng = np.random.default_rng(8)
+    d, k = 60, 12
+    est = rng.standard_normal(d).astype(np.float32)
+    est[[3, 17, 41]] = [5.0, -6.0, 4.5]
+    est[20] = np.nan                                          # never heavy, may be drawn
+    l2sq = 100.0                                              # threshold 100 / 12: |est| >= 2.887
+    got, n_heavy = orc.heavymix_select(est, k, l2sq, rng_seed=99)
+    H = [i for i in range(d) if float(est[i]) * float(est[i]) >= l2sq / k]
+    assert H == [3, 17, 41] and n_heavy == 3
+    keys = [int(x) >> 34 for x in orc.splitmix64(99, d)]
+    NH = sorted((i for i in range(d) if i not in H), key=lambda i: (-keys[i], i))
+    assert got.tolist() == sorted(H + NH[: k - len(H)])
+    assert len(set(got.tolist())) == k
+    # a different seed draws a different fill but the same heavy part
+    other, _ = orc.heavymix_select(est, k, l2sq, rng_seed=100)
+    assert set(H) <= set(other.tolist()) and other.tolist() != got.tolist()
+    # more than k pass a tiny threshold: the k largest magnitudes, ties to the lower index
+    est2 = est.copy()
+    est2[20] = 0.0
+    est2[50] = est2[3]
+    sel, n_heavy = orc.heavymix_select(est2, 4, 1e-6, rng_seed=1)
+    assert n_heavy == 4 and sel.tolist() == [3, 17, 41, 50]
+    sel, _ = orc.heavymix_select(est2, 3, 1e-6, rng_seed=1)
+    assert sel.tolist() == [3, 17, 50]                        # 5.0 twice (3, 50) and -6.0; 4.5 is out
+
+
+def test_heavymix_fill_is_uniform_without_replacement():
+    d, k, trials = 120, 12, 4000
+    est = np.zeros(d, dtype=np.float32)
+    counts = np.zeros(d)
+    for seed in range(trials):
+        sel, n_heavy = orc.heavymix_select(est, k, 1.0, rng_seed=seed * 7919 + 1)
+        assert n_heavy == 0 and sel.size == k and np.unique(sel).size == k
+        counts[sel] += 1
+    expect = trials * k / d
+    chi2 = float(((counts - expect) ** 2 / (expect * (1 - k / d))).sum())
+    assert 70 < chi2 < 175, chi2                              # d - 1 = 119 degrees of freedom
+
+
+def test_heavymix_is_a_k_over_d_contraction():
+    """Lemma 1: E ||g - HEAVYMIX(g)||^2 <= (1 - k/d) ||g||^2, with equality when nothing is
+    heavy (a uniform draw of k of d coordinates keeps k/d of the energy in expectation)."""
+    rng = np.random.default_rng(12)
+    d, k, trials = 3000, 60, 400
+    sk = orc.SketchOracle(5, 1 << 10, 4)
+    for n_planted in (0, 6):
+        g = rng.standard_normal(d)
+        planted = rng.choice(d, n_planted, replace=False)
+        g[planted] = 40.0 * np.sign(g[planted])
+        T = sk.sketch(g)
+        est = sk.estimate(T, d)
+        l2sq, _ = orc.l2sq_estimate(T)
+        total = float(g @ g)
+        err = []
+        for seed in range(trials):
+            sel, n_heavy = orc.heavymix_select(est, k, l2sq, rng_seed=seed)
+            assert n_heavy == n_planted and set(planted.tolist()) <= set(sel.tolist())
+            rest = g.copy()
+            rest[sel] = 0.0                                    # second round: exact values
+            err.append(float(rest @ rest))
+        ratio = np.mean(err) / total
+        if n_planted == 0:
+            assert ratio == pytest.approx(1 - k / d, rel=0.01)
+        else:
+            assert ratio < (1 - k / d) * (1 - 0.5)             # the planted part alone is > half
+
+
 def test_compression_numbers_printed_in_paper(golden_dir):
     rows = [l.split() for l in open(os.path.join(golden_dir, "compression_table.txt"))
             if l.strip() and not l.startswith("#")]
