@@ -239,6 +239,31 @@ int cs_select_exact_topk(const int64_t* cand, const float* x, int64_t n, int64_t
                          int64_t* idx_out, float* val_out, void* workspace, size_t ws_bytes,
                          void* stream);
 
+/* HEAVYMIX (Sec. 4, Alg. 1), the recovery the convergence proof is stated for.
+ *
+ * cs_sketch_l2sq -- Alg. 1 step 1, "query l2^2 from the sketch": by the AMS argument of
+ * App. C a row's sum of squared counters estimates ||g||^2; the median over the r rows is
+ * taken.  out: device double[1 + r], 8-byte aligned: out[0] = the median, out[1 + j] =
+ * sum_b S[j][b]^2 (binary64 sums in a fixed order).  S: device float[r][c].
+ *
+ * cs_heavymix_select -- Alg. 1 steps 3-4.  H = { i : est[i]^2 >= l2sq[0] / k } (the listing's
+ * comparison is read in the squared form that Sec. 4's proof and App. C's definition of an
+ * l2^2-heavy hitter use; est in binary32, square and threshold in binary64), and the selection
+ * is H plus  l = k - |H|  of the remaining coordinates drawn uniformly at random without
+ * replacement: coordinate i is given the top 30 bits of the (i+1)-th output of SplitMix64
+ * started at rng_seed, and the l largest of these win (equal ones: lower index first).  If
+ * k or more estimates pass the threshold, the k largest of them by the top 30 bits of their
+ * binary32 magnitude are returned (equal ones: lower index first).
+ * est: device float[d]; l2sq: device double (the out[0] above, read on the device, no host
+ * synchronisation); idx_out: device int64[k], ascending; val_out: device float[k] or NULL,
+ * val_out[t] = est[idx_out[t]]; n_heavy: device int64 or NULL, receives min(|H|, k);
+ * workspace as for cs_heavy_hitters_topk.  1 <= k <= d.  The exact values of the selection
+ * (Alg. 1 step 5) are what cs_gather_exact returns. */
+int cs_sketch_l2sq(const cs_params* p, const float* S, double* out, void* stream);
+int cs_heavymix_select(const float* est, int64_t d, int64_t k, const double* l2sq,
+                       uint64_t rng_seed, int64_t* idx_out, float* val_out, int64_t* n_heavy,
+                       void* workspace, size_t ws_bytes, void* stream);
+
 /* Error feedback / momentum masking in sketch space (Alg. 2 "Error accumulation",
  * Alg. 3 "u, v <- 0 for all updated coordinates", as far as a sketch can express them):
  *     val[n] = estimate(S, idx[n])   for all n, from the table as it is on entry, then

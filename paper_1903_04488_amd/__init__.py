@@ -21,6 +21,8 @@ from .binding import (  # noqa: F401
     cs_heavy_hitters_topk,
     cs_params_init,
     cs_select_exact_topk,
+    cs_sketch_l2sq,
+    cs_heavymix_select,
     cs_sketch_accumulate,
     cs_sketch_accumulate_batch,
     cs_sketch_accumulate_sparse,

@@ -103,6 +103,10 @@ _SIGNATURES = {
     "cs_select_exact_topk": [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                              ctypes.c_void_p],
+    "cs_sketch_l2sq": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p],
+    "cs_heavymix_select": [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
+                           ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                           ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p],
     "cs_gather_exact": [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32, ctypes.c_void_p,
                         ctypes.c_int64, ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p],
     "cs_sketch_feedback": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_void_p,
@@ -323,6 +327,24 @@ def cs_select_exact_topk(cand, x, k: int, idx_out, val_out, workspace):
         _dev(val_out, torch.float32, "val_out", k) if val_out is not None else ctypes.c_void_p(0),
         _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(x)),
         "cs_select_exact_topk")
+
+
+def cs_sketch_l2sq(p, S, out):
+    _check(load_library().cs_sketch_l2sq(
+        ctypes.byref(p), _dev(S, torch.float32, "S", _cells(p)),
+        _dev(out, torch.float64, "out", 1 + p.r), _stream(S)), "cs_sketch_l2sq")
+
+
+def cs_heavymix_select(est, k: int, l2sq, rng_seed: int, idx_out, val_out, n_heavy, workspace):
+    d = est.numel()
+    null = ctypes.c_void_p(0)
+    _check(load_library().cs_heavymix_select(
+        _dev(est, torch.float32, "est"), d, k, _dev(l2sq, torch.float64, "l2sq"),
+        rng_seed & 0xFFFFFFFFFFFFFFFF, _dev(idx_out, torch.int64, "idx_out", k),
+        _dev(val_out, torch.float32, "val_out", k) if val_out is not None else null,
+        _dev(n_heavy, torch.int64, "n_heavy", 1) if n_heavy is not None else null,
+        _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(est)),
+        "cs_heavymix_select")
 
 
 def cs_gather_exact(vec, idx, out, alpha: float = 1.0):

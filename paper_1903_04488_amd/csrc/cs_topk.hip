@@ -34,7 +34,39 @@ struct TopkWs {
     uint64_t eq[kMaxSelBlocks];     // per block: entries with key == theta -> exclusive scan
 };
 
-__device__ __forceinline__ uint32_t key_of(float v) { return __float_as_uint(v) & 0x7fffffffu; }
+// Selection keys (31 bits, larger = selected first; equal keys: lower index first).
+// KeyMagnitude: the magnitude bits of the estimate (top-k by |est|).
+struct KeyMagnitude {
+    __device__ __forceinline__ void init() {}
+    __device__ __forceinline__ uint32_t operator()(float v, int64_t) const {
+        return __float_as_uint(v) & 0x7fffffffu;
+    }
+};
+// KeyHeavymix (Alg. 1 steps 3-4): a coordinate is heavy when est^2 >= l2sq / k (binary32
+// estimate, squared and compared in binary64: the product of two binary32 values is exact
+// there).  Heavy coordinates get bit 30 plus the top 30 magnitude bits, so they come before
+// every other coordinate and, should more than k be heavy, in order of magnitude; the others
+// get the top 30 bits of a counter-based random word -- the (i+1)-th output of SplitMix64
+// started at `seed` -- so the k - |H| of them with the largest words are a uniform draw
+// without replacement.
+struct KeyHeavymix {
+    const double* l2sq;       // device: the norm estimate of cs_sketch_l2sq
+    double k;
+    uint64_t seed;
+    double theta;
+    __device__ __forceinline__ void init() { theta = *l2sq / k; }
+    __device__ __forceinline__ bool heavy(float v) const {
+        return static_cast<double>(v) * static_cast<double>(v) >= theta;
+    }
+    __device__ __forceinline__ uint32_t operator()(float v, int64_t i) const {
+        if (heavy(v)) return 0x40000000u | ((__float_as_uint(v) & 0x7fffffffu) >> 1);
+        uint64_t z = seed + (static_cast<uint64_t>(i) + 1u) * 0x9E3779B97F4A7C15ull;
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        z ^= z >> 31;
+        return static_cast<uint32_t>(z >> 34);
+    }
+};
 
 __global__ void __launch_bounds__(kBlock) k_topk_clear(TopkWs* ws, uint64_t k) {
     for (int t = threadIdx.x; t < 3 * kBins; t += kBlock) (&ws->hist[0][0])[t] = 0;
@@ -47,9 +79,10 @@ __global__ void __launch_bounds__(kBlock) k_topk_clear(TopkWs* ws, uint64_t k) {
 
 // PASS 0: bin = key >> 20 (2048 bins); PASS 1: entries with key >> 20 == prefix, bin = bits
 // 19..10; PASS 2: entries with key >> 10 == prefix, bin = bits 9..0.
-template <int PASS>
+template <int PASS, typename KEY>
 __global__ void __launch_bounds__(kBlock)
-k_topk_hist(const float* __restrict__ est, int64_t d, TopkWs* ws) {
+k_topk_hist(const float* __restrict__ est, int64_t d, TopkWs* ws, KEY kf) {
+    kf.init();
     __shared__ uint32_t lh[kBins];
     constexpr int nb = (PASS == 0) ? 2048 : 1024;
     for (int t = threadIdx.x; t < nb; t += kBlock) lh[t] = 0;
@@ -57,7 +90,7 @@ k_topk_hist(const float* __restrict__ est, int64_t d, TopkWs* ws) {
     const uint32_t prefix = ws->sel.prefix;
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
     for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < d; t += stride) {
-        const uint32_t key = key_of(est[t]);
+        const uint32_t key = kf(est[t], t);
         if (PASS == 0) {
             atomicAdd(&lh[key >> 20], 1u);
         } else if (PASS == 1) {
@@ -155,9 +188,10 @@ __device__ __forceinline__ void load_items(const float* __restrict__ est, int64_
 }
 
 // per block: how many entries of its chunk are above / equal to theta
-template <bool VEC>
+template <bool VEC, typename KEY>
 __global__ void __launch_bounds__(kBlock)
-k_topk_count(const float* __restrict__ est, int64_t d, int64_t chunk, TopkWs* ws) {
+k_topk_count(const float* __restrict__ est, int64_t d, int64_t chunk, TopkWs* ws, KEY kf) {
+    kf.init();
     __shared__ uint32_t lds[kBlock / 64];
     const uint32_t theta = ws->sel.prefix;
     const int64_t lo = static_cast<int64_t>(blockIdx.x) * chunk;
@@ -166,11 +200,12 @@ k_topk_count(const float* __restrict__ est, int64_t d, int64_t chunk, TopkWs* ws
     for (int64_t tile = lo; tile < hi; tile += kTile) {
         float v[kItems];
         int nvalid;
-        load_items<VEC>(est, tile + static_cast<int64_t>(threadIdx.x) * kItems, hi, v, nvalid);
+        const int64_t base = tile + static_cast<int64_t>(threadIdx.x) * kItems;
+        load_items<VEC>(est, base, hi, v, nvalid);
         uint32_t c = 0;
 #pragma unroll
         for (int q = 0; q < kItems; ++q)
-            if (q < nvalid) c += classify(key_of(v[q]), theta);
+            if (q < nvalid) c += classify(kf(v[q], base + q), theta);
         uint32_t total;
         block_inclusive_scan(c, lds, &total);
         n_gt += total & 0xffffu;
@@ -210,10 +245,11 @@ __global__ void __launch_bounds__(kBlock) k_topk_scan(TopkWs* ws, int nblocks) {
 // ordered compaction: index t is selected when key > theta, or key == theta and fewer than
 // need_eq equal entries precede it; its output slot is (#greater before t) + min(#equal
 // before t, need_eq), which is its rank among the selected in ascending index order.
-template <bool VEC>
+template <bool VEC, typename KEY>
 __global__ void __launch_bounds__(kBlock)
 k_topk_write(const float* __restrict__ est, int64_t d, int64_t chunk, const TopkWs* ws,
-             int64_t k, int64_t* __restrict__ idx_out, float* __restrict__ val_out) {
+             int64_t k, int64_t* __restrict__ idx_out, float* __restrict__ val_out, KEY kf) {
+    kf.init();
     __shared__ uint32_t lds[kBlock / 64];
     const uint32_t theta = ws->sel.prefix;
     const uint64_t need_eq = ws->sel.k_rem;
@@ -229,7 +265,7 @@ k_topk_write(const float* __restrict__ est, int64_t d, int64_t chunk, const Topk
         uint32_t c = 0;
 #pragma unroll
         for (int q = 0; q < kItems; ++q)
-            if (q < nvalid) c += classify(key_of(v[q]), theta);
+            if (q < nvalid) c += classify(kf(v[q], base + q), theta);
         uint32_t total;
         const uint32_t incl = block_inclusive_scan(c, lds, &total);
         if (c) {
@@ -238,7 +274,7 @@ k_topk_write(const float* __restrict__ est, int64_t d, int64_t chunk, const Topk
 #pragma unroll
             for (int q = 0; q < kItems; ++q) {
                 if (q >= nvalid) break;
-                const uint32_t key = key_of(v[q]);
+                const uint32_t key = kf(v[q], base + q);
                 const bool is_gt = key > theta, is_eq = key == theta;
                 if (is_gt || (is_eq && e < need_eq)) {
                     const uint64_t slot = g + (e < need_eq ? e : need_eq);
@@ -264,6 +300,53 @@ k_remap_positions(int64_t* __restrict__ idx, const int64_t* __restrict__ cand, i
         idx[t] = cand[idx[t]];
 }
 
+// Alg. 1 step 1: out[1 + j] = sum_b S[j][b]^2, one workgroup per row, binary64 sums in a
+// fixed order (each thread a strided share, then a tree over the workgroup).
+__global__ void __launch_bounds__(kBlock)
+k_row_sumsq(const float* __restrict__ S, uint32_t c, double* __restrict__ out) {
+    __shared__ double part[kBlock];
+    const float* row = S + static_cast<size_t>(blockIdx.x) * c;
+    double acc = 0.0;
+    for (uint32_t b = threadIdx.x; b < c; b += kBlock) {
+        const double v = static_cast<double>(row[b]);
+        acc += v * v;
+    }
+    part[threadIdx.x] = acc;
+    __syncthreads();
+    for (int off = kBlock / 2; off > 0; off >>= 1) {
+        if (static_cast<int>(threadIdx.x) < off) part[threadIdx.x] += part[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[1 + blockIdx.x] = part[0];
+}
+
+// out[0] = median of out[1 .. r] (r odd, <= CS_MAX_R): insertion sort by one thread
+__global__ void k_median_of_rows(double* out, int r) {
+    double v[CS_MAX_R];
+    for (int j = 0; j < r; ++j) {
+        double x = out[1 + j];
+        int q = j;
+        while (q > 0 && v[q - 1] > x) { v[q] = v[q - 1]; --q; }
+        v[q] = x;
+    }
+    out[0] = v[r / 2];
+}
+
+// how many of the selected coordinates passed the threshold
+__global__ void __launch_bounds__(kBlock)
+k_count_heavy(const float* __restrict__ est, const int64_t* __restrict__ idx, int64_t k,
+              KeyHeavymix kf, unsigned long long* __restrict__ n_heavy) {
+    kf.init();
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    unsigned long long mine = 0;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < k; t += stride)
+        mine += kf.heavy(est[idx[t]]) ? 1u : 0u;
+    for (int off = 32; off > 0; off >>= 1) mine += __shfl_down(mine, off, 64);
+    if ((threadIdx.x & 63) == 0 && mine) atomicAdd(n_heavy, mine);
+}
+
+__global__ void k_clear_u64(unsigned long long* x) { *x = 0; }
+
 }  // namespace cs
 
 using namespace cs;
@@ -284,36 +367,71 @@ extern "C" int cs_topk_workspace_bytes(int64_t d, int64_t k, size_t* bytes) {
     return CS_OK;
 }
 
-extern "C" int cs_heavy_hitters_topk(const float* est, int64_t d, int64_t k, int64_t* idx_out,
-                                     float* val_out, void* workspace, size_t ws_bytes,
-                                     void* stream) {
+// the k entries with the largest keys, ascending by index (see the header of this file)
+template <typename KEY>
+static int select_largest(const float* est, int64_t d, int64_t k, int64_t* idx_out, float* val_out,
+                          void* workspace, size_t ws_bytes, hipStream_t s, KEY kf) {
     if (d < 1 || k < 1 || k > d || !est || !idx_out || !workspace) return CS_EINVAL;
     if (reinterpret_cast<uintptr_t>(workspace) % 8 != 0) return CS_EINVAL;
     if (ws_bytes < sizeof(TopkWs)) return CS_EWORKSPACE;
-    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     TopkWs* ws = static_cast<TopkWs*>(workspace);
     const unsigned hgrid = static_cast<unsigned>(
         (d + kBlock * 16 - 1) / (kBlock * 16) < 2048 ? (d + kBlock * 16 - 1) / (kBlock * 16) : 2048);
     k_topk_clear<<<1, kBlock, 0, s>>>(ws, static_cast<uint64_t>(k));
-    k_topk_hist<0><<<hgrid, kBlock, 0, s>>>(est, d, ws);
+    k_topk_hist<0, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf);
     k_topk_find<0><<<1, kBlock, 0, s>>>(ws);
-    k_topk_hist<1><<<hgrid, kBlock, 0, s>>>(est, d, ws);
+    k_topk_hist<1, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf);
     k_topk_find<1><<<1, kBlock, 0, s>>>(ws);
-    k_topk_hist<2><<<hgrid, kBlock, 0, s>>>(est, d, ws);
+    k_topk_hist<2, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf);
     k_topk_find<2><<<1, kBlock, 0, s>>>(ws);
     int nblocks;
     int64_t chunk;
     topk_geometry(d, &nblocks, &chunk);
     const bool vec = reinterpret_cast<uintptr_t>(est) % 16 == 0;
     if (vec) {
-        k_topk_count<true><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws);
+        k_topk_count<true, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, kf);
         k_topk_scan<<<1, kBlock, 0, s>>>(ws, nblocks);
-        k_topk_write<true><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, k, idx_out, val_out);
+        k_topk_write<true, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, k, idx_out, val_out, kf);
     } else {
-        k_topk_count<false><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws);
+        k_topk_count<false, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, kf);
         k_topk_scan<<<1, kBlock, 0, s>>>(ws, nblocks);
-        k_topk_write<false><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, k, idx_out, val_out);
+        k_topk_write<false, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, k, idx_out, val_out, kf);
     }
+    return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
+}
+
+extern "C" int cs_heavy_hitters_topk(const float* est, int64_t d, int64_t k, int64_t* idx_out,
+                                     float* val_out, void* workspace, size_t ws_bytes,
+                                     void* stream) {
+    return select_largest(est, d, k, idx_out, val_out, workspace, ws_bytes,
+                          reinterpret_cast<hipStream_t>(stream), KeyMagnitude{});
+}
+
+extern "C" int cs_sketch_l2sq(const cs_params* p, const float* S, double* out, void* stream) {
+    if (!p || !S || !out) return CS_EINVAL;
+    if (p->r == 0 || p->r > CS_MAX_R || (p->r & 1u) == 0 || p->c == 0) return CS_EINVAL;
+    if (reinterpret_cast<uintptr_t>(out) % 8 != 0) return CS_EINVAL;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    k_row_sumsq<<<p->r, kBlock, 0, s>>>(S, p->c, out);
+    k_median_of_rows<<<1, 1, 0, s>>>(out, static_cast<int>(p->r));
+    return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
+}
+
+extern "C" int cs_heavymix_select(const float* est, int64_t d, int64_t k, const double* l2sq,
+                                  uint64_t rng_seed, int64_t* idx_out, float* val_out,
+                                  int64_t* n_heavy, void* workspace, size_t ws_bytes,
+                                  void* stream) {
+    if (!l2sq || reinterpret_cast<uintptr_t>(l2sq) % 8 != 0) return CS_EINVAL;
+    if (n_heavy && reinterpret_cast<uintptr_t>(n_heavy) % 8 != 0) return CS_EINVAL;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    KeyHeavymix kf{l2sq, static_cast<double>(k), rng_seed, 0.0};
+    const int rc = select_largest(est, d, k, idx_out, val_out, workspace, ws_bytes, s, kf);
+    if (rc != CS_OK || !n_heavy) return rc;
+    unsigned long long* cnt = reinterpret_cast<unsigned long long*>(n_heavy);
+    k_clear_u64<<<1, 1, 0, s>>>(cnt);
+    int64_t b = (k + kBlock - 1) / kBlock;
+    if (b > 1024) b = 1024;
+    k_count_heavy<<<static_cast<unsigned>(b), kBlock, 0, s>>>(est, idx_out, k, kf, cnt);
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
 

@@ -138,6 +138,11 @@ def test_invalid_arguments_are_rejected_without_a_gpu(lib):
     bad = binding.CsParams()
     bad.r, bad.c = 4, 16
     assert lib.cs_sketch_zero(ctypes.byref(bad), fake, null) == -1
+    assert lib.cs_sketch_l2sq(ctypes.byref(p), fake, null, null) == -1
+    assert lib.cs_sketch_l2sq(ctypes.byref(p), fake, ctypes.c_void_p(260), null) == -1    # misaligned
+    assert lib.cs_heavymix_select(fake, 10, 5, null, 1, fake, null, null, fake, 1 << 20, null) == -1
+    assert lib.cs_heavymix_select(fake, 10, 11, fake, 1, fake, null, null, fake, 1 << 20, null) == -1
+    assert lib.cs_heavymix_select(fake, 10, 5, fake, 1, fake, null, null, fake, 8, null) == -2
 
 
 def test_status_strings(lib):

@@ -385,3 +385,64 @@ def test_feedback_removes_estimated_values():
     np.testing.assert_array_equal(val.cpu().numpy(), ref_val.astype(np.float32))
     sk.accumulate_sparse(T, idx, ref_val, scale=-1.0)
     assert_cells_close(S.cpu().numpy(), T)
+
+
+# ------------------------------------------------------------------------------ HEAVYMIX
+@pytest.mark.parametrize("r,c,seed,d,k,planted", [
+    (5, 1 << 12, 31, 200_003, 100, 12),
+    (7, 1 << 15, 32, 3_000_001, 1000, 40),
+    (5, 1 << 15, 190304489, 10_000_000, 2000, 0),
+    (3, 64, 33, 5_000, 5_000, 3),            # k = d: everything is selected
+    (1, 1 << 10, 34, 70_000, 1, 1),
+])
+def test_heavymix_l2_estimate_and_selection(r, c, seed, d, k, planted):
+    """Alg. 1 on the device against the reference: the norm estimate from the same fp32 table
+    (binary64 sums: equal to rounding order), then the threshold split and the seeded fill on
+    the same binary32 estimates and the same threshold, which must agree index by index."""
+    p = cs.cs_params_init(r, c, seed, d)
+    sk = orc.SketchOracle(r, c, seed)
+    rng = np.random.default_rng(seed)
+    g = (rng.standard_normal(d) * 0.01).astype(np.float32)
+    where = rng.choice(d, planted, replace=False)
+    g[where] = (rng.uniform(0.5, 1.0, planted) * rng.choice([-1.0, 1.0], planted)).astype(np.float32)
+    S = torch.zeros(r, c, dtype=torch.float32, device=DEV)
+    cs.cs_sketch_accumulate(p, S, dev(g))
+    out = torch.empty(1 + r, dtype=torch.float64, device=DEV)
+    cs.cs_sketch_l2sq(p, S, out)
+    ref_l2, ref_rows = orc.l2sq_estimate(ref_table_from_device(S))
+    got = out.cpu().numpy()
+    np.testing.assert_allclose(got[1:], ref_rows, rtol=1e-12)
+    np.testing.assert_allclose(got[0], ref_l2, rtol=1e-12)
+    true = float(g.astype(np.float64) @ g.astype(np.float64))
+    if c >= 1 << 12:
+        assert 0.5 * true <= got[0] <= 1.5 * true                      # Alg. 1 step 1
+
+    est = torch.empty(d, dtype=torch.float32, device=DEV)
+    ws_e = torch.empty(cs.cs_estimate_workspace_bytes(p, d), dtype=torch.uint8, device=DEV)
+    cs.cs_sketch_estimate(p, S, est, workspace=ws_e if ws_e.numel() else None)
+    est_h = est.cpu().numpy()
+    ws = torch.empty(cs.cs_topk_workspace_bytes(d, k), dtype=torch.uint8, device=DEV)
+    idx = torch.empty(k, dtype=torch.int64, device=DEV)
+    val = torch.empty(k, dtype=torch.float32, device=DEV)
+    n_heavy = torch.full((1,), -1, dtype=torch.int64, device=DEV)
+    # the sketch's own threshold, one so small that more than k pass, one so large that none does
+    for l2sq in (float(got[0]), 1e-12, 1e12):
+        l2 = torch.tensor([l2sq], dtype=torch.float64, device=DEV)
+        for rng_seed in (7, (1 << 64) - 1):
+            cs.cs_heavymix_select(est, k, l2 if l2sq != float(got[0]) else out, rng_seed, idx, val,
+                                  n_heavy, ws)
+            ref_idx, ref_heavy = orc.heavymix_select(est_h, k, l2sq, rng_seed)
+            np.testing.assert_array_equal(idx.cpu().numpy(), ref_idx)
+            np.testing.assert_array_equal(val.cpu().numpy(), est_h[ref_idx])
+            assert int(n_heavy.item()) == ref_heavy
+        if l2sq == float(got[0]) and planted and c >= 1 << 12 and k < d:
+            # the heavy ones are planted coordinates: those whose square reaches l2sq / k
+            heavy = ref_idx[est_h[ref_idx].astype(np.float64) ** 2 >= l2sq / k]
+            assert 0 < ref_heavy == heavy.size and set(heavy.tolist()) <= set(where.tolist())
+            clear = where[g[where].astype(np.float64) ** 2 >= 1.5 * l2sq / k]
+            assert set(clear.tolist()) <= set(heavy.tolist())
+        if l2sq == 1e12:
+            assert ref_heavy == 0
+    # without the optional outputs
+    cs.cs_heavymix_select(est, k, out, 7, idx, None, None, ws)
+    np.testing.assert_array_equal(idx.cpu().numpy(), orc.heavymix_select(est_h, k, float(got[0]), 7)[0])
