@@ -264,6 +264,21 @@ int cs_heavymix_select(const float* est, int64_t d, int64_t k, const double* l2s
                        uint64_t rng_seed, int64_t* idx_out, float* val_out, int64_t* n_heavy,
                        void* workspace, size_t ws_bytes, void* stream);
 
+/* Alg. 3 as printed, with dense state on every worker (the sketch-space form above keeps only
+ * r x c numbers per state vector; this form keeps 2 d floats per worker and is exact).
+ * cs_dense_momentum -- "Momentum" and "Error accumulation" for W workers:
+ *     u_w[t] = rho * u_w[t] + g_w[t]  (one fused multiply-add),   v_w[t] = v_w[t] + u_w[t].
+ *   The sketch of v_w is then taken with cs_sketch_accumulate_bundle(v_w), and the second
+ *   round reads v_w through cs_gather_exact.
+ * cs_dense_mask -- "u, v <- 0 for all coordinates of the update":
+ *     u_w[idx[n]] = v_w[idx[n]] = 0   for every worker w and n < k.
+ * u_w, v_w, g_w: HOST arrays of W device pointers to float[d]; u_w, v_w updated in place.
+ * idx: device int64[k], each in [0, d).  W >= 1, d >= 0, k >= 0. */
+int cs_dense_momentum(float* const* u_w, float* const* v_w, const float* const* g_w,
+                      int32_t W, int64_t d, float rho, void* stream);
+int cs_dense_mask(float* const* u_w, float* const* v_w, int32_t W, const int64_t* idx,
+                  int64_t k, void* stream);
+
 /* Error feedback / momentum masking in sketch space (Alg. 2 "Error accumulation",
  * Alg. 3 "u, v <- 0 for all updated coordinates", as far as a sketch can express them):
  *     val[n] = estimate(S, idx[n])   for all n, from the table as it is on entry, then

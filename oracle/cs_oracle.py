@@ -300,6 +300,39 @@ class DenseState:
         self.u[idx] -= delta_u
 
 
+class DenseWorkerState:
+    """Alg. 3 as printed: every worker i keeps its own dense u^i, v^i.
+        u^i <- m u^i + g^i ;  v^i <- v^i + u^i ;  the sketch of v^i goes to the server ;
+        the server asks for exact values of v^i at the chosen coordinates and sums them ;
+        u^i, v^i <- 0 at the coordinates of the update.
+    m is the fp32 value of the momentum constant, as the device receives it."""
+
+    def __init__(self, W: int, d: int, rho: float):
+        self.u = [np.zeros(d, dtype=np.float64) for _ in range(W)]
+        self.v = [np.zeros(d, dtype=np.float64) for _ in range(W)]
+        self.rho = float(np.float32(rho))
+
+    def momentum(self, g_w):
+        for i, g in enumerate(g_w):
+            self.u[i] = self.rho * self.u[i] + np.asarray(g, dtype=np.float64)
+            self.v[i] = self.v[i] + self.u[i]
+
+    def mean_v(self):
+        acc = np.zeros_like(self.v[0])
+        for v in self.v:
+            acc = acc + v
+        return acc / len(self.v)
+
+    def exact(self, idx):
+        """second round: (1/W) sum_i v^i[idx]"""
+        return gather_exact(self.v, idx, alpha=1.0 / len(self.v))
+
+    def mask(self, idx):
+        for i in range(len(self.v)):
+            self.u[i][idx] = 0.0
+            self.v[i][idx] = 0.0
+
+
 class SketchSpaceState:
     """Momentum and error accumulation of Alg. 3 kept as sketches S_u = S(u), S_v = S(v).
 

@@ -22,6 +22,8 @@ from .binding import (  # noqa: F401
     cs_params_init,
     cs_select_exact_topk,
     cs_sketch_l2sq,
+    cs_dense_momentum,
+    cs_dense_mask,
     cs_heavymix_select,
     cs_sketch_accumulate,
     cs_sketch_accumulate_batch,

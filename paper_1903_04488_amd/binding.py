@@ -109,6 +109,11 @@ _SIGNATURES = {
                            ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p],
     "cs_gather_exact": [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32, ctypes.c_void_p,
                         ctypes.c_int64, ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p],
+    "cs_dense_momentum": [ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p),
+                          ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32, ctypes.c_int64,
+                          ctypes.c_float, ctypes.c_void_p],
+    "cs_dense_mask": [ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p),
+                      ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p],
     "cs_sketch_feedback": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_void_p,
                            ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p],
 }
@@ -353,6 +358,25 @@ def cs_gather_exact(vec, idx, out, alpha: float = 1.0):
     _check(load_library().cs_gather_exact(
         _ptr_array(vec, torch.float32, "vec", d), len(vec), _dev(idx, torch.int64, "idx"), k,
         alpha, _dev(out, torch.float32, "out", k), _stream(out)), "cs_gather_exact")
+
+
+def cs_dense_momentum(u_w, v_w, g_w, rho: float):
+    W, d = len(g_w), g_w[0].numel()
+    if len(u_w) != W or len(v_w) != W:
+        raise CsError("u_w, v_w and g_w must have one tensor per worker")
+    _check(load_library().cs_dense_momentum(
+        _ptr_array(u_w, torch.float32, "u_w", d), _ptr_array(v_w, torch.float32, "v_w", d),
+        _ptr_array(g_w, torch.float32, "g_w", d), W, d, rho, _stream(g_w[0])), "cs_dense_momentum")
+
+
+def cs_dense_mask(u_w, v_w, idx):
+    W = len(u_w)
+    if len(v_w) != W:
+        raise CsError("u_w and v_w must have one tensor per worker")
+    d = u_w[0].numel()
+    _check(load_library().cs_dense_mask(
+        _ptr_array(u_w, torch.float32, "u_w", d), _ptr_array(v_w, torch.float32, "v_w", d), W,
+        _dev(idx, torch.int64, "idx"), idx.numel(), _stream(idx)), "cs_dense_mask")
 
 
 def cs_sketch_feedback(p, S, idx, val):

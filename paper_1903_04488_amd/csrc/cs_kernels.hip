@@ -273,6 +273,57 @@ k_gather(GatherPtrs ptrs, int nw, const int64_t* __restrict__ idx, int64_t k, fl
     }
 }
 
+// Alg. 3 "Momentum" and "Error accumulation" with dense per-worker state:
+// u = rho u + g (one fused multiply-add), v = v + u.  blockIdx.y = worker; 20 bytes of
+// traffic per coordinate, 16-byte accesses when the three vectors are 16-byte aligned.
+struct DensePtrs {
+    float* u[kMaxBatch];
+    float* v[kMaxBatch];
+    const float* g[kMaxBatch];
+};
+
+template <bool VEC>
+__global__ void __launch_bounds__(kBlock)
+k_dense_momentum(DensePtrs ptrs, int64_t d, float rho) {
+    float* __restrict__ u = ptrs.u[blockIdx.y];
+    float* __restrict__ v = ptrs.v[blockIdx.y];
+    const float* __restrict__ g = ptrs.g[blockIdx.y];
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    int64_t done = 0;
+    if (VEC) {
+        const int64_t n4 = d / 4;
+        for (int64_t t = t0; t < n4; t += stride) {
+            float4 uu = reinterpret_cast<float4*>(u)[t], vv = reinterpret_cast<float4*>(v)[t];
+            const float4 gg = reinterpret_cast<const float4*>(g)[t];
+            uu.x = __fmaf_rn(rho, uu.x, gg.x); uu.y = __fmaf_rn(rho, uu.y, gg.y);
+            uu.z = __fmaf_rn(rho, uu.z, gg.z); uu.w = __fmaf_rn(rho, uu.w, gg.w);
+            vv.x += uu.x; vv.y += uu.y; vv.z += uu.z; vv.w += uu.w;
+            reinterpret_cast<float4*>(u)[t] = uu;
+            reinterpret_cast<float4*>(v)[t] = vv;
+        }
+        done = n4 * 4;
+    }
+    for (int64_t t = done + t0; t < d; t += stride) {
+        const float un = __fmaf_rn(rho, u[t], g[t]);
+        u[t] = un;
+        v[t] += un;
+    }
+}
+
+// Alg. 3 last step: u, v <- 0 on the coordinates of the update, for every worker
+__global__ void __launch_bounds__(kBlock)
+k_dense_mask(DensePtrs ptrs, const int64_t* __restrict__ idx, int64_t k) {
+    float* __restrict__ u = ptrs.u[blockIdx.y];
+    float* __restrict__ v = ptrs.v[blockIdx.y];
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    for (int64_t n = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; n < k; n += stride) {
+        const int64_t i = idx[n];
+        u[i] = 0.0f;
+        v[i] = 0.0f;
+    }
+}
+
 }  // namespace cs
 
 using namespace cs;
@@ -516,6 +567,53 @@ extern "C" int cs_gather_exact(const float* const* vec, int32_t W, const int64_t
         for (int w = 0; w < nw; ++w) ptrs.vec[w] = vec[w0 + w];
         k_gather<<<grid_for(k), kBlock, 0, as_stream(stream)>>>(ptrs, nw, idx, k, alpha, out,
                                                                 w0 == 0, w0 + nw == W);
+        if (launch_status() != CS_OK) return CS_EHIP;
+    }
+    return CS_OK;
+}
+
+extern "C" int cs_dense_momentum(float* const* u_w, float* const* v_w, const float* const* g_w,
+                                 int32_t W, int64_t d, float rho, void* stream) {
+    if (!u_w || !v_w || !g_w || W < 1 || d < 0) return CS_EINVAL;
+    bool vec = true;
+    for (int w = 0; w < W; ++w) {
+        if (!u_w[w] || !v_w[w] || !g_w[w]) return CS_EINVAL;
+        vec = vec && (reinterpret_cast<uintptr_t>(u_w[w]) | reinterpret_cast<uintptr_t>(v_w[w]) |
+                      reinterpret_cast<uintptr_t>(g_w[w])) % 16 == 0;
+    }
+    if (d == 0) return CS_OK;
+    for (int w0 = 0; w0 < W; w0 += kMaxBatch) {
+        const int nw = (W - w0 < kMaxBatch) ? (W - w0) : kMaxBatch;
+        DensePtrs ptrs{};
+        for (int w = 0; w < nw; ++w) {
+            ptrs.u[w] = u_w[w0 + w];
+            ptrs.v[w] = v_w[w0 + w];
+            ptrs.g[w] = g_w[w0 + w];
+        }
+        const dim3 grid(grid_for(vec ? (d + 3) / 4 : d, kBlock, 2048), static_cast<unsigned>(nw));
+        if (vec) k_dense_momentum<true><<<grid, kBlock, 0, as_stream(stream)>>>(ptrs, d, rho);
+        else k_dense_momentum<false><<<grid, kBlock, 0, as_stream(stream)>>>(ptrs, d, rho);
+        if (launch_status() != CS_OK) return CS_EHIP;
+    }
+    return CS_OK;
+}
+
+extern "C" int cs_dense_mask(float* const* u_w, float* const* v_w, int32_t W, const int64_t* idx,
+                             int64_t k, void* stream) {
+    if (!u_w || !v_w || W < 1 || k < 0) return CS_EINVAL;
+    for (int w = 0; w < W; ++w)
+        if (!u_w[w] || !v_w[w]) return CS_EINVAL;
+    if (k == 0) return CS_OK;
+    if (!idx) return CS_EINVAL;
+    for (int w0 = 0; w0 < W; w0 += kMaxBatch) {
+        const int nw = (W - w0 < kMaxBatch) ? (W - w0) : kMaxBatch;
+        DensePtrs ptrs{};
+        for (int w = 0; w < nw; ++w) {
+            ptrs.u[w] = u_w[w0 + w];
+            ptrs.v[w] = v_w[w0 + w];
+        }
+        const dim3 grid(grid_for(k), static_cast<unsigned>(nw));
+        k_dense_mask<<<grid, kBlock, 0, as_stream(stream)>>>(ptrs, idx, k);
         if (launch_status() != CS_OK) return CS_EHIP;
     }
     return CS_OK;

@@ -97,3 +97,40 @@ class HotPath:
         self.gather(g_w)
         self.feedback()
         return self.idx, self.x
+
+
+class DenseStatePath(HotPath):
+    """Alg. 3 as printed: momentum u^w and error accumulation v^w are dense vectors on every
+    worker (2 W d floats), the sketch is taken of v^w, the second round returns exact sums of
+    v^w, and u^w, v^w are zeroed on the coordinates of the update.  Costs one more streaming
+    pass over the state (20 bytes per coordinate and worker) than the sketch-space form.
+
+        momentum, error   u^w = rho u^w + g^w ; v^w += u^w          cs_dense_momentum
+        worker sketches   S^w = S(v^w)                              cs_sketch_accumulate_bundle
+        aggregate, query, choose                                    as in HotPath (stateless)
+        second round      x = (1/W) sum_w v^w[idx]                  cs_gather_exact
+        masking           u^w[idx] = v^w[idx] = 0                   cs_dense_mask
+    """
+
+    def __init__(self, d, W, r, c, k, seed, rho, device="cuda:0", P: int = 1):
+        super().__init__(d, W, r, c, k, seed, rho=None, device=device, P=P)
+        self.m = rho
+        f32 = dict(dtype=torch.float32, device=self.device)
+        self.u_w = [torch.zeros(d, **f32) for _ in range(W)]
+        self.v_w = [torch.zeros(d, **f32) for _ in range(W)]
+
+    def dense_momentum(self, g_w):
+        B.cs_dense_momentum(self.u_w, self.v_w, g_w, self.m)
+
+    def mask(self):
+        B.cs_dense_mask(self.u_w, self.v_w, self.idx)
+
+    def step(self, g_w):
+        self.dense_momentum(g_w)
+        self.accumulate(self.v_w)
+        self.merge()
+        self.estimate()
+        self.topk()
+        self.gather(self.v_w)
+        self.mask()
+        return self.idx, self.x

@@ -16,7 +16,7 @@ import torch
 
 import workloads as wl
 from oracle import cs_oracle as orc
-from paper_1903_04488_amd.pipeline import HotPath
+from paper_1903_04488_amd.pipeline import DenseStatePath, HotPath
 from parity_util import assert_cells_close, assert_valid_topk, assert_values_close
 
 pytestmark = pytest.mark.gpu
@@ -202,3 +202,87 @@ def test_top_pk_then_exact_topk(P):
     # with more candidates the exact second round recovers at least as many planted coordinates
     found = np.isin(work.heavy_idx.cpu().numpy(), idx.cpu().numpy()).sum()
     assert found >= 0.9 * min(c.k, c.n_heavy)
+
+
+# ----------------------------------------------------------------------------- dense state
+@pytest.mark.parametrize("P", [1, 4])
+def test_dense_worker_state_all_steps(P):
+    """Alg. 3 as printed (per-worker dense u, v; sketch of v; exact second round on v; u, v
+    zeroed on the update), four steps against the reference, teacher-forced on the selection."""
+    c = wl.scaled(4, d=(1 << 20) + 4_321, W=5, c=1 << 14, k=1500, steps=4)
+    work = wl.Workload(c, DEV)
+    hp = DenseStatePath(c.d, c.W, c.r, c.c, c.k, c.hash_seed, rho=c.rho, device=DEV, P=P)
+    sk = orc.SketchOracle(c.r, c.c, c.hash_seed)
+    st = orc.DenseWorkerState(c.W, c.d, c.rho)
+    for t in range(c.steps):
+        g_w = [work.gradient(t, w) for w in range(c.W)]
+        hp.dense_momentum(g_w)
+        st.momentum([g.cpu().numpy() for g in g_w])
+        for w in range(c.W):
+            # t + 1 fused multiply-adds and additions per element so far
+            assert_values_close(hp.u_w[w].cpu().numpy(), st.u[w], rms(st.u[w]), rel=1e-6 * (t + 1),
+                                what=f"step {t} u of worker {w}")
+            assert_values_close(hp.v_w[w].cpu().numpy(), st.v[w], rms(st.v[w]), rel=1e-6 * (t + 1),
+                                what=f"step {t} v of worker {w}")
+        # from here on the reference continues from the device's state, so that the sketch,
+        # the estimates and the selection are compared at the stated 1e-5 on equal inputs
+        for w in range(c.W):
+            st.u[w] = hp.u_w[w].cpu().numpy().astype(np.float64)
+            st.v[w] = hp.v_w[w].cpu().numpy().astype(np.float64)
+        hp.accumulate(hp.v_w)
+        hp.merge()
+        S_t = sk.sketch(st.mean_v())
+        assert_cells_close(hp.worker_table(c.W - 1).cpu().numpy(), sk.sketch(st.v[c.W - 1]),
+                           what=f"step {t} table of the last worker")
+        assert_cells_close(hp.S_t.cpu().numpy(), S_t, what=f"step {t} merged table")
+        hp.estimate()
+        hp.topk()
+        est_ref = sk.estimate(S_t, c.d)
+        assert_values_close(hp.est.cpu().numpy(), est_ref, rms(S_t), what=f"step {t} estimates")
+        cand = hp.cand.cpu().numpy()
+        assert_valid_topk(cand, est_ref, P * c.k, rms(S_t), what=f"step {t} top-Pk")
+        hp.gather(hp.v_w)
+        scale = rms(st.mean_v())
+        x_cand_ref = st.exact(cand)
+        assert_values_close(hp.x_cand.cpu().numpy(), x_cand_ref, scale, what=f"step {t} exact sums")
+        idx = hp.idx.cpu().numpy()
+        if P > 1:
+            pos = np.searchsorted(cand, idx)
+            assert (cand[pos] == idx).all()
+            assert_valid_topk(pos, x_cand_ref, c.k, scale, what=f"step {t} k largest exact sums")
+        hp.mask()
+        st.mask(idx)
+        for w in range(c.W):
+            np.testing.assert_array_equal(hp.u_w[w].cpu().numpy(), st.u[w].astype(np.float32))
+            np.testing.assert_array_equal(hp.v_w[w].cpu().numpy(), st.v[w].astype(np.float32))
+            assert (hp.v_w[w][hp.idx] == 0).all() and (hp.u_w[w][hp.idx] == 0).all()
+    # error accumulation at work: what was not sent stays in v (Alg. 3), so v is not zero
+    assert float(hp.v_w[0].abs().max()) > 0
+
+
+def test_dense_momentum_unaligned_and_tail():
+    """vectors that start 4 bytes past a 16-byte boundary and a length that is not a multiple
+    of four: the scalar form of the kernel, and the scalar tail of the vector form"""
+    import paper_1903_04488_amd as cs
+    d, W, rho = 10_003, 3, 0.9
+    rng = np.random.default_rng(0)
+    for shift in (1, 0):
+        u, v, g = [], [], []
+        ref = orc.DenseWorkerState(W, d, rho)
+        for w in range(W):
+            for q, dst in enumerate((u, v, g)):
+                buf = torch.zeros(d + 8, dtype=torch.float32, device=DEV)
+                view = buf[shift: shift + d]
+                view.copy_(torch.from_numpy(rng.standard_normal(d).astype(np.float32)))
+                assert (view.data_ptr() % 16 != 0) == bool(shift)
+                dst.append(view)
+            ref.u[w] = u[w].cpu().numpy().astype(np.float64)
+            ref.v[w] = v[w].cpu().numpy().astype(np.float64)
+        cs.cs_dense_momentum(u, v, g, rho)
+        ref.momentum([x.cpu().numpy() for x in g])
+        for w in range(W):
+            assert_values_close(u[w].cpu().numpy(), ref.u[w], 1.0, rel=1e-6, what="u")
+            assert_values_close(v[w].cpu().numpy(), ref.v[w], 1.0, rel=1e-6, what="v")
+        idx = torch.tensor([0, 5, d - 1], dtype=torch.int64, device=DEV)
+        cs.cs_dense_mask(u, v, idx)
+        assert all((x[idx] == 0).all() for x in u + v) and all(float(x.abs().sum()) > 0 for x in u + v)

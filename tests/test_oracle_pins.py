@@ -421,6 +421,42 @@ def test_sketch_space_state_equals_sketch_of_dense_state():
     assert np.abs(dense.v[heavy]).max() < 2.0
 
 
+def test_dense_worker_state_worked_example_and_mean_recursion():
+    """Alg. 3 with per-worker u, v: a two-step example computed by hand, and the fact that the
+    workers' mean follows the single-vector recursion (DenseState) when the fed-back values
+    are the exact means -- zeroing u^i, v^i at idx subtracts exactly their means there."""
+    st = orc.DenseWorkerState(2, 3, 0.5)
+    st.momentum([np.array([1.0, 2.0, 0.0]), np.array([3.0, 0.0, -1.0])])
+    assert st.u[0].tolist() == [1.0, 2.0, 0.0] and st.v[1].tolist() == [3.0, 0.0, -1.0]
+    assert st.exact(np.array([0])).tolist() == [2.0]                    # (1 + 3) / 2
+    st.mask(np.array([0]))
+    assert st.u[0].tolist() == [0.0, 2.0, 0.0] and st.v[1].tolist() == [0.0, 0.0, -1.0]
+    st.momentum([np.array([1.0, 1.0, 1.0]), np.array([0.0, 0.0, 2.0])])
+    # worker 0: u = 0.5 * [0, 2, 0] + [1, 1, 1] = [1, 2, 1];  v = [0, 2, 0] + u = [1, 4, 1]
+    # worker 1: u = 0.5 * [0, 0, -1] + [0, 0, 2] = [0, 0, 1.5];  v = [0, 0, -1] + u = [0, 0, 0.5]
+    assert st.u[0].tolist() == [1.0, 2.0, 1.0] and st.v[0].tolist() == [1.0, 4.0, 1.0]
+    assert st.u[1].tolist() == [0.0, 0.0, 1.5] and st.v[1].tolist() == [0.0, 0.0, 0.5]
+    assert st.mean_v().tolist() == [0.5, 2.0, 0.75]
+
+    rng = np.random.default_rng(2)
+    W, d, rho = 3, 500, 0.9
+    workers = orc.DenseWorkerState(W, d, rho)
+    mean = orc.DenseState(d, workers.rho)
+    for t in range(5):
+        g_w = [rng.standard_normal(d) for _ in range(W)]
+        workers.momentum(g_w)
+        mean.momentum(sum(g_w) / W)
+        np.testing.assert_allclose(workers.mean_v(), mean.v, rtol=0, atol=1e-12)
+        idx = np.sort(rng.choice(d, 40, replace=False))
+        x = workers.exact(idx)
+        np.testing.assert_allclose(x, mean.v[idx], rtol=0, atol=1e-12)
+        mean_u = sum(workers.u) / W
+        mean.feedback(idx, mean.v[idx].copy(), mean_u[idx].copy())
+        workers.mask(idx)
+        assert all((u[idx] == 0).all() and (v[idx] == 0).all() for u, v in zip(workers.u, workers.v))
+        np.testing.assert_allclose(workers.mean_v(), mean.v, rtol=0, atol=1e-12)
+
+
 def test_momentum_recursion_closed_form():
     # constant sketch input: S_u after n steps = (1 - rho^n)/(1 - rho) S, S_v = sum of those
     sk = orc.SketchOracle(3, 16, 59)
