@@ -50,10 +50,26 @@ __device__ __forceinline__ uint64_t hash_advance(uint64_t y, uint64_t A) {
     return (t & kP61) + (t >> 61);
 }
 
+// Column count with what the reduction of a hash value modulo c needs.  For a power of two
+// that is a mask.  Otherwise (the paper's 180 000-column sketches, Table 1) the remainder
+// of a 61-bit value by a 32-bit one is taken with one high multiplication: with
+// M = floor((2^64 - 1) / c), q = floor(x M / 2^64) is floor(x / c) or one less for every
+// x < 2^61 (the error x (2^64 - M c) / (c 2^64) is below x / 2^64 < 1/8), so x - q c lies in
+// [0, 2c) and one conditional subtraction finishes it.  M costs one division per thread.
+struct Columns {
+    uint32_t c;
+    uint64_t M;
+};
 template <bool POW2>
-__device__ __forceinline__ uint32_t bucket_of(uint64_t y, uint32_t c) {
-    if (POW2) return (static_cast<uint32_t>(y) - 1u) & (c - 1u);
-    return static_cast<uint32_t>((y - 1) % c);
+__device__ __forceinline__ Columns columns_of(uint32_t c) {
+    return Columns{c, POW2 ? 0ull : ~0ull / c};
+}
+template <bool POW2>
+__device__ __forceinline__ uint32_t bucket_of(uint64_t y, const Columns& col) {
+    if (POW2) return (static_cast<uint32_t>(y) - 1u) & (col.c - 1u);
+    const uint64_t x = y - 1;
+    const uint64_t rem = x - mulhi64(x, col.M) * col.c;      // < 2c
+    return static_cast<uint32_t>(rem >= col.c ? rem - col.c : rem);
 }
 
 // 0x80000000 when s = -1 (x odd, i.e. y even), 0 when s = +1: XOR it into a float's bits.

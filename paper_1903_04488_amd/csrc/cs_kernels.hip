@@ -55,12 +55,13 @@ __global__ void __launch_bounds__(kBlock)
 k_hash_list(KParams p, const int64_t* __restrict__ idx, int64_t n,
             uint32_t* __restrict__ bucket, int8_t* __restrict__ sign) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    const Columns col = columns_of<POW2>(p.c);
     for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < n; t += stride) {
         const uint64_t i = static_cast<uint64_t>(idx[t]);
         for (uint32_t j = 0; j < p.r; ++j) {
             const uint64_t yb = hash_state(p.a[j], p.b[j], i);
             const uint64_t ys = hash_state(p.as[j], p.bs[j], i);
-            bucket[static_cast<size_t>(j) * n + t] = bucket_of<POW2>(yb, p.c);
+            bucket[static_cast<size_t>(j) * n + t] = bucket_of<POW2>(yb, col);
             sign[static_cast<size_t>(j) * n + t] = sign_flip_of(ys) ? -1 : 1;
         }
     }
@@ -96,6 +97,7 @@ __global__ void __launch_bounds__(kBlock)
 k_hash_range(KParams p, int64_t i0, int64_t n, uint32_t* __restrict__ bucket,
              int8_t* __restrict__ sign) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    const Columns col = columns_of<POW2>(p.c);
     int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
     if (t >= n) return;
     RowStates<R> st;
@@ -103,7 +105,7 @@ k_hash_range(KParams p, int64_t i0, int64_t n, uint32_t* __restrict__ bucket,
     for (; t < n; t += stride) {
 #pragma unroll
         for (int j = 0; j < R; ++j) {
-            bucket[static_cast<size_t>(j) * n + t] = bucket_of<POW2>(st.yb[j], p.c);
+            bucket[static_cast<size_t>(j) * n + t] = bucket_of<POW2>(st.yb[j], col);
             sign[static_cast<size_t>(j) * n + t] = sign_flip_of(st.ys[j]) ? -1 : 1;
         }
         st.advance();
@@ -123,6 +125,7 @@ __global__ void __launch_bounds__(kBlock)
 k_accumulate(KParams p, BatchPtrs ptrs, int nw, int64_t d, int64_t i0, float scale,
              int64_t cell_stride) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    const Columns col = columns_of<POW2>(p.c);
     int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
     if (t >= d) return;
     RowStates<R> st;
@@ -132,7 +135,7 @@ k_accumulate(KParams p, BatchPtrs ptrs, int nw, int64_t d, int64_t i0, float sca
         uint32_t cell[R], flip[R];
 #pragma unroll
         for (int j = 0; j < R; ++j) {
-            cell[j] = static_cast<uint32_t>(j) * c + bucket_of<POW2>(st.yb[j], c);
+            cell[j] = static_cast<uint32_t>(j) * c + bucket_of<POW2>(st.yb[j], col);
             flip[j] = sign_flip_of(st.ys[j]);
         }
         for (int w = 0; w < nw; ++w) {
@@ -151,13 +154,14 @@ __global__ void __launch_bounds__(kBlock)
 k_accumulate_sparse(KParams p, float* __restrict__ S, const int64_t* __restrict__ idx,
                     const float* __restrict__ val, int64_t n, float scale) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    const Columns col = columns_of<POW2>(p.c);
     for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < n; t += stride) {
         const uint64_t i = static_cast<uint64_t>(idx[t]);
         const float v = scale * val[t];
         for (uint32_t j = 0; j < p.r; ++j) {
             const uint64_t yb = hash_state(p.a[j], p.b[j], i);
             const uint64_t ys = hash_state(p.as[j], p.bs[j], i);
-            atomic_add_noret(S + static_cast<size_t>(j) * p.c + bucket_of<POW2>(yb, p.c),
+            atomic_add_noret(S + static_cast<size_t>(j) * p.c + bucket_of<POW2>(yb, col),
                              apply_sign(v, sign_flip_of(ys)));
         }
     }
@@ -218,6 +222,7 @@ __global__ void __launch_bounds__(kBlock)
 k_estimate(KParams p, const float* __restrict__ S, int64_t d, int64_t i0,
            float* __restrict__ est) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    const Columns col = columns_of<POW2>(p.c);
     int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
     if (t >= d) return;
     RowStates<R> st;
@@ -227,7 +232,7 @@ k_estimate(KParams p, const float* __restrict__ S, int64_t d, int64_t i0,
         float v[R];
 #pragma unroll
         for (int j = 0; j < R; ++j) {
-            const float cellv = S[static_cast<size_t>(j) * c + bucket_of<POW2>(st.yb[j], c)];
+            const float cellv = S[static_cast<size_t>(j) * c + bucket_of<POW2>(st.yb[j], col)];
             v[j] = apply_sign(cellv, sign_flip_of(st.ys[j]));
         }
         est[t] = median_odd<R>(v);
@@ -240,6 +245,7 @@ __global__ void __launch_bounds__(kBlock)
 k_estimate_sparse(KParams p, const float* __restrict__ S, const int64_t* __restrict__ idx,
                   int64_t n, float* __restrict__ out) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    const Columns col = columns_of<POW2>(p.c);
     for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < n; t += stride) {
         const uint64_t i = static_cast<uint64_t>(idx[t]);
         float v[R];
@@ -247,7 +253,7 @@ k_estimate_sparse(KParams p, const float* __restrict__ S, const int64_t* __restr
         for (int j = 0; j < R; ++j) {
             const uint64_t yb = hash_state(p.a[j], p.b[j], i);
             const uint64_t ys = hash_state(p.as[j], p.bs[j], i);
-            v[j] = apply_sign(S[static_cast<size_t>(j) * p.c + bucket_of<POW2>(yb, p.c)],
+            v[j] = apply_sign(S[static_cast<size_t>(j) * p.c + bucket_of<POW2>(yb, col)],
                               sign_flip_of(ys));
         }
         out[t] = median_odd<R>(v);
