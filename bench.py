@@ -177,7 +177,7 @@ def main():
         "pct_hbm_peak_whole_step": 100.0 * step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "stage_ms": stage_ms,
         "roofline": {
-            "kernel": "k_accumulate_walk (cs_sketch_accumulate_bundle)",
+            "kernel": "k_accumulate_visits (cs_sketch_accumulate_bundle)",
             "bound": "hbm",
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,
