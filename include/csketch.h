@@ -239,6 +239,22 @@ int cs_select_exact_topk(const int64_t* cand, const float* x, int64_t n, int64_t
                          int64_t* idx_out, float* val_out, void* workspace, size_t ws_bytes,
                          void* stream);
 
+/* Sketches in 16 bits per cell (Sec. 6: "quantizing sketches to 16 bits ... leads to no drop in
+ * accuracy"): what a worker would put on the wire.  Round to nearest, ties to even; NaN stays
+ * NaN, overflow gives infinity.  fmt: CS_FMT_BF16 (upper half of the binary32 pattern: 8
+ * exponent, 7 fraction bits -- keeps the range of sums of gradient elements) or CS_FMT_F16
+ * (IEEE binary16).
+ * cs_quantize16 / cs_dequantize16: elementwise over n values (a table float[r][c] or a whole
+ *   worker bundle -- the layout is kept).  x, out, q: device.
+ * cs_bundle_merge16: cs_bundle_merge reading a quantised bundle (uint16[ceil(W/8)][r][c][8],
+ *   16-byte aligned): dst = beta * dst + alpha * sum_w value(S16^w); fp32 sum, fixed order. */
+#define CS_FMT_BF16 0
+#define CS_FMT_F16 1
+int cs_quantize16(const float* x, int64_t n, uint16_t* out, int32_t fmt, void* stream);
+int cs_dequantize16(const uint16_t* q, int64_t n, float* out, int32_t fmt, void* stream);
+int cs_bundle_merge16(const cs_params* p, float* dst, float beta, const uint16_t* T16, int32_t W,
+                      float alpha, int32_t fmt, void* stream);
+
 /* HEAVYMIX (Sec. 4, Alg. 1), the recovery the convergence proof is stated for.
  *
  * cs_sketch_l2sq -- Alg. 1 step 1, "query l2^2 from the sketch": by the AMS argument of

@@ -271,6 +271,38 @@ def heavymix_select(est, k: int, l2sq: float, rng_seed: int):
     return np.sort(np.concatenate([H, fill])).astype(np.int64), int(H.size)
 
 
+# ---------------------------------------------------------------------------
+# 16-bit sketches (Sec. 6: "quantizing sketches to 16 bits")
+# ---------------------------------------------------------------------------
+def quantize16(x, fmt: str) -> np.ndarray:
+    """binary32 -> 16-bit storage, round to nearest, ties to even; returns the uint16 patterns.
+    fmt "bf16": the upper half of the binary32 pattern (8 exponent bits, 7 fraction bits);
+    fmt "f16": IEEE binary16 (numpy's conversion).  NaN stays NaN (quiet), overflow gives inf."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if fmt == "f16":
+        with np.errstate(over="ignore"):
+            return x.astype(np.float16).view(np.uint16)
+    if fmt != "bf16":
+        raise ValueError(fmt)
+    bits = x.view(np.uint32).astype(np.uint64)
+    lower, keep = bits & np.uint64(0xFFFF), bits >> np.uint64(16)
+    up = (lower > np.uint64(0x8000)) | ((lower == np.uint64(0x8000)) & ((keep & np.uint64(1)) == 1))
+    out = (keep + up.astype(np.uint64)).astype(np.uint16)
+    nan = np.isnan(x)
+    out[nan] = ((bits[nan] >> np.uint64(16)) | np.uint64(0x0040)).astype(np.uint16)
+    return out
+
+
+def dequantize16(q, fmt: str) -> np.ndarray:
+    """the binary64 value of every 16-bit pattern (exact)"""
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    if fmt == "f16":
+        return q.view(np.float16).astype(np.float64)
+    if fmt != "bf16":
+        raise ValueError(fmt)
+    return (q.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
 def compression_factor(d: int, sketch_cells: int, P: int, k: int) -> float:
     """Sec. 5.3: 2d / (|S| + Pk + k)."""
     return 2.0 * d / (sketch_cells + P * k + k)

@@ -22,6 +22,11 @@ from .binding import (  # noqa: F401
     cs_params_init,
     cs_select_exact_topk,
     cs_sketch_l2sq,
+    cs_quantize16,
+    cs_dequantize16,
+    cs_bundle_merge16,
+    CS_FMT_BF16,
+    CS_FMT_F16,
     cs_dense_momentum,
     cs_dense_mask,
     cs_heavymix_select,

@@ -103,6 +103,10 @@ _SIGNATURES = {
     "cs_select_exact_topk": [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                              ctypes.c_void_p],
+    "cs_quantize16": [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p],
+    "cs_dequantize16": [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p],
+    "cs_bundle_merge16": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p,
+                          ctypes.c_int32, ctypes.c_float, ctypes.c_int32, ctypes.c_void_p],
     "cs_sketch_l2sq": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p],
     "cs_heavymix_select": [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
                            ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
@@ -332,6 +336,31 @@ def cs_select_exact_topk(cand, x, k: int, idx_out, val_out, workspace):
         _dev(val_out, torch.float32, "val_out", k) if val_out is not None else ctypes.c_void_p(0),
         _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(x)),
         "cs_select_exact_topk")
+
+
+CS_FMT_BF16, CS_FMT_F16 = 0, 1
+
+
+def cs_quantize16(x, out, fmt: int):
+    """out: int16 tensor (torch has no uint16 arithmetic; the bit patterns are what matters)"""
+    n = x.numel()
+    _check(load_library().cs_quantize16(_dev(x, torch.float32, "x"), n,
+                                        _dev(out, torch.int16, "out", n), fmt, _stream(x)),
+           "cs_quantize16")
+
+
+def cs_dequantize16(q, out, fmt: int):
+    n = q.numel()
+    _check(load_library().cs_dequantize16(_dev(q, torch.int16, "q"), n,
+                                          _dev(out, torch.float32, "out", n), fmt, _stream(q)),
+           "cs_dequantize16")
+
+
+def cs_bundle_merge16(p, dst, T16, W: int, fmt: int, alpha: float = 1.0, beta: float = 0.0):
+    _check(load_library().cs_bundle_merge16(
+        ctypes.byref(p), _dev(dst, torch.float32, "dst", _cells(p)), beta,
+        _dev(T16, torch.int16, "T16", cs_bundle_floats(p, W)), W, alpha, fmt, _stream(dst)),
+        "cs_bundle_merge16")
 
 
 def cs_sketch_l2sq(p, S, out):

@@ -13,6 +13,7 @@
 // results are bit-identical to the definition because the identity holds over the integers.
 #pragma once
 
+#include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -79,6 +80,22 @@ __device__ __forceinline__ uint32_t sign_flip_of(uint64_t y) {
 
 __device__ __forceinline__ float apply_sign(float v, uint32_t flip) {
     return __uint_as_float(__float_as_uint(v) ^ flip);
+}
+
+// 16-bit storage of sketch cells (Sec. 6 of the paper: "quantizing sketches to 16 bits"):
+// round to nearest, ties to even.  FMT 0 = bfloat16 (upper half of the binary32 pattern),
+// FMT 1 = IEEE binary16 (the hardware conversion, whose default rounding is the same).
+template <int FMT>
+__device__ __forceinline__ uint16_t to_16(float v) {
+    if (FMT == 1) return __half_as_ushort(__float2half_rn(v));
+    const uint32_t bits = __float_as_uint(v);
+    if ((bits & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((bits >> 16) | 0x0040u);  // NaN
+    return static_cast<uint16_t>((bits + 0x7fffu + ((bits >> 16) & 1u)) >> 16);
+}
+template <int FMT>
+__device__ __forceinline__ float from_16(uint16_t q) {
+    if (FMT == 1) return __half2float(__ushort_as_half(q));
+    return __uint_as_float(static_cast<uint32_t>(q) << 16);
 }
 
 // fp32 add into global memory, result not needed: one hardware global_atomic_add_f32.

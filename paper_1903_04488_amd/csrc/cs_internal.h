@@ -49,5 +49,7 @@ int launch_row_values_walk(const cs_params* p, const float* S, int64_t d, int64_
 int launch_bundle_zero(float* T, int64_t n, hipStream_t stream);
 int launch_bundle_merge(float* dst, float beta, const float* T, int groups, float alpha,
                         int64_t cells, hipStream_t stream);
+int launch_bundle_merge16(float* dst, float beta, const uint16_t* T16, int groups, float alpha,
+                          int64_t cells, int fmt, hipStream_t stream);
 
 }  // namespace cs

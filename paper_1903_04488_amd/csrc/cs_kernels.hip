@@ -279,6 +279,22 @@ k_gather(GatherPtrs ptrs, int nw, const int64_t* __restrict__ idx, int64_t k, fl
     }
 }
 
+template <int FMT>
+__global__ void __launch_bounds__(kBlock)
+k_quantize16(const float* __restrict__ x, int64_t n, uint16_t* __restrict__ out) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < n; t += stride)
+        out[t] = to_16<FMT>(x[t]);
+}
+
+template <int FMT>
+__global__ void __launch_bounds__(kBlock)
+k_dequantize16(const uint16_t* __restrict__ q, int64_t n, float* __restrict__ out) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < n; t += stride)
+        out[t] = from_16<FMT>(q[t]);
+}
+
 // Alg. 3 "Momentum" and "Error accumulation" with dense per-worker state:
 // u = rho u + g (one fused multiply-add), v = v + u.  blockIdx.y = worker; 20 bytes of
 // traffic per coordinate, 16-byte accesses when the three vectors are 16-byte aligned.
@@ -452,6 +468,33 @@ extern "C" int cs_bundle_merge(const cs_params* p, float* dst, float beta, const
     if (reinterpret_cast<uintptr_t>(T) % 16 != 0) return CS_EINVAL;
     return launch_bundle_merge(dst, beta, T, static_cast<int>(bundle_groups(W)), alpha,
                                static_cast<int64_t>(p->r) * p->c, as_stream(stream));
+}
+
+extern "C" int cs_quantize16(const float* x, int64_t n, uint16_t* out, int32_t fmt, void* stream) {
+    if (n < 0 || (fmt != CS_FMT_BF16 && fmt != CS_FMT_F16)) return CS_EINVAL;
+    if (n == 0) return CS_OK;
+    if (!x || !out) return CS_EINVAL;
+    if (fmt == CS_FMT_BF16) k_quantize16<0><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(x, n, out);
+    else k_quantize16<1><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(x, n, out);
+    return launch_status();
+}
+
+extern "C" int cs_dequantize16(const uint16_t* q, int64_t n, float* out, int32_t fmt, void* stream) {
+    if (n < 0 || (fmt != CS_FMT_BF16 && fmt != CS_FMT_F16)) return CS_EINVAL;
+    if (n == 0) return CS_OK;
+    if (!q || !out) return CS_EINVAL;
+    if (fmt == CS_FMT_BF16) k_dequantize16<0><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(q, n, out);
+    else k_dequantize16<1><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(q, n, out);
+    return launch_status();
+}
+
+extern "C" int cs_bundle_merge16(const cs_params* p, float* dst, float beta, const uint16_t* T16,
+                                 int32_t W, float alpha, int32_t fmt, void* stream) {
+    if (!bundle_ok(p, W) || !dst || !T16) return CS_EINVAL;
+    if (fmt != CS_FMT_BF16 && fmt != CS_FMT_F16) return CS_EINVAL;
+    if (reinterpret_cast<uintptr_t>(T16) % 16 != 0) return CS_EINVAL;
+    return launch_bundle_merge16(dst, beta, T16, static_cast<int>(bundle_groups(W)), alpha,
+                                 static_cast<int64_t>(p->r) * p->c, fmt, as_stream(stream));
 }
 
 extern "C" int cs_sketch_accumulate_batch(const cs_params* p, float* const* S_w,

@@ -753,7 +753,41 @@ k_bundle_merge(float* __restrict__ dst, float beta, const float4* __restrict__ T
     }
 }
 
+// the same merge from a bundle stored in 16 bits per cell: one 16-byte load per group and cell
+template <int FMT>
+__global__ void __launch_bounds__(kBlock)
+k_bundle_merge16(float* __restrict__ dst, float beta, const uint4* __restrict__ T16, int groups,
+                 float alpha, int64_t cells) {
+    static_assert(kGroup == 8, "8 cells of 16 bits are one 16-byte load");
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < cells; t += stride) {
+        float s = 0.0f;
+        for (int g = 0; g < groups; ++g) {
+            const uint4 q = T16[static_cast<size_t>(g) * cells + t];
+            const uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+            for (int h = 0; h < 4; h += 2)
+                s += (from_16<FMT>(static_cast<uint16_t>(w[h])) + from_16<FMT>(static_cast<uint16_t>(w[h] >> 16))) +
+                     (from_16<FMT>(static_cast<uint16_t>(w[h + 1])) + from_16<FMT>(static_cast<uint16_t>(w[h + 1] >> 16)));
+        }
+        const float base = (beta == 0.0f) ? 0.0f : beta * dst[t];
+        dst[t] = base + alpha * s;
+    }
+}
+
 }  // namespace
+
+int launch_bundle_merge16(float* dst, float beta, const uint16_t* T16, int groups, float alpha,
+                          int64_t cells, int fmt, hipStream_t stream) {
+    int64_t b = (cells + kBlock - 1) / kBlock;
+    if (b > 256 * 16) b = 256 * 16;
+    const uint4* src = reinterpret_cast<const uint4*>(T16);
+    if (fmt == CS_FMT_BF16)
+        k_bundle_merge16<0><<<static_cast<unsigned>(b), kBlock, 0, stream>>>(dst, beta, src, groups, alpha, cells);
+    else
+        k_bundle_merge16<1><<<static_cast<unsigned>(b), kBlock, 0, stream>>>(dst, beta, src, groups, alpha, cells);
+    return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
+}
 
 int launch_bundle_zero(float* T, int64_t n, hipStream_t stream) {
     const bool aligned = reinterpret_cast<uintptr_t>(T) % 16 == 0;

@@ -138,6 +138,13 @@ def test_invalid_arguments_are_rejected_without_a_gpu(lib):
     bad = binding.CsParams()
     bad.r, bad.c = 4, 16
     assert lib.cs_sketch_zero(ctypes.byref(bad), fake, null) == -1
+    assert lib.cs_quantize16(fake, 10, fake, 2, null) == -1
+    assert lib.cs_quantize16(null, 10, fake, 0, null) == -1
+    assert lib.cs_quantize16(fake, 0, fake, 0, null) == 0
+    assert lib.cs_dequantize16(fake, -1, fake, 0, null) == -1
+    assert lib.cs_bundle_merge16(ctypes.byref(p), fake, 0.0, ctypes.c_void_p(264), 8, 1.0, 0, null) == -1
+    assert lib.cs_dense_momentum(None, None, None, 1, 10, 0.9, null) == -1
+    assert lib.cs_dense_mask(None, None, 1, fake, 10, null) == -1
     assert lib.cs_sketch_l2sq(ctypes.byref(p), fake, null, null) == -1
     assert lib.cs_sketch_l2sq(ctypes.byref(p), fake, ctypes.c_void_p(260), null) == -1    # misaligned
     assert lib.cs_heavymix_select(fake, 10, 5, null, 1, fake, null, null, fake, 1 << 20, null) == -1

@@ -446,3 +446,50 @@ def test_heavymix_l2_estimate_and_selection(r, c, seed, d, k, planted):
     # without the optional outputs
     cs.cs_heavymix_select(est, k, out, 7, idx, None, None, ws)
     np.testing.assert_array_equal(idx.cpu().numpy(), orc.heavymix_select(est_h, k, float(got[0]), 7)[0])
+
+
+# ------------------------------------------------------------------------------ 16-bit sketches
+@pytest.mark.parametrize("fmt,name", [(0, "bf16"), (1, "f16")])
+def test_quantize16_bit_exact_and_merge(fmt, name):
+    """binary32 -> 16 bits on the device equals the reference pattern for pattern (random
+    values over the whole exponent range, every special value, ties), dequantisation is exact,
+    and the merge of a quantised bundle equals the reference merge of the dequantised tables."""
+    rng = np.random.default_rng(fmt)
+    special = np.array([0.0, -0.0, 1.0, -2.5, np.inf, -np.inf, 1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8,
+                        1 + 2.0 ** -11, 1 + 3 * 2.0 ** -11, 65504.0, 65520.0, 3.4e38, 2.0 ** -24,
+                        2.0 ** -25, 1e-40, -1e-40, 6e-8], dtype=np.float32)
+    x = np.concatenate([
+        special,
+        (rng.standard_normal(300_000) * 10.0 ** rng.uniform(-12, 12, 300_000)).astype(np.float32),
+        rng.integers(0, 1 << 32, 300_000, dtype=np.uint64).astype(np.uint32).view(np.float32)])
+    q = torch.empty(x.size, dtype=torch.int16, device=DEV)
+    cs.cs_quantize16(dev(x), q, fmt)
+    got = q.cpu().numpy().view(np.uint16)
+    want = orc.quantize16(x, name)
+    ok = ~np.isnan(x)
+    np.testing.assert_array_equal(got[ok], want[ok])
+    assert np.isnan(orc.dequantize16(got[~ok], name)).all()              # NaN stays NaN
+    back = torch.empty(x.size, dtype=torch.float32, device=DEV)
+    cs.cs_dequantize16(q, back, fmt)
+    np.testing.assert_array_equal(back.cpu().numpy()[ok].astype(np.float64), orc.dequantize16(want[ok], name))
+
+    r, c, seed, d, W = 5, 1 << 12, 11, 100_003, 13
+    p = cs.cs_params_init(r, c, seed, d)
+    gs = [(rng.standard_normal(d) * 0.01).astype(np.float32) for _ in range(W)]
+    T = torch.zeros(cs.cs_bundle_floats(p, W), dtype=torch.float32, device=DEV)
+    cs.cs_sketch_accumulate_bundle(p, T, [dev(g) for g in gs])
+    T16 = torch.empty(T.numel(), dtype=torch.int16, device=DEV)
+    cs.cs_quantize16(T, T16, fmt)
+    G = cs.CS_BUNDLE_GROUP
+    Th = T.cpu().numpy().reshape(-1, r, c, G)
+    tables16 = [orc.dequantize16(orc.quantize16(Th[w // G, :, :, w % G], name), name).reshape(r, c)
+                for w in range(W)]
+    dst0 = rng.standard_normal((r, c)).astype(np.float32)
+    dst = dev(dst0)
+    cs.cs_bundle_merge16(p, dst, T16, W, fmt, alpha=1.0 / W, beta=0.25)
+    assert_cells_close(dst.cpu().numpy(), orc.merge(tables16, alpha=1.0 / W, beta=0.25, dst=dst0))
+    # what 16 bits cost: a value moves by at most half a unit in the last place, 2^-9 (bf16) or 2^-12 (f16) of itself
+    exact = orc.merge([Th[w // G, :, :, w % G] for w in range(W)], alpha=1.0 / W)
+    cs.cs_bundle_merge16(p, dst, T16, W, fmt, alpha=1.0 / W, beta=0.0)
+    err = np.abs(dst.cpu().numpy() - exact).max() / np.abs(exact).max()
+    assert err < (2.0 ** -8 if fmt == 0 else 2.0 ** -11)

@@ -12,6 +12,8 @@ paper or the mathematics fixes, not against itself.
   top-k, gather  numpy lexsort / fancy indexing
   state          sketch-space momentum / error feedback equals the sketch of its dense twin
   accounting     compression factors printed in Table 1 and App. E
+  16-bit cells   hand-computed bit patterns (ties to even, overflow, subnormals) and PyTorch's
+                 CPU conversions
   HEAVYMIX       l2 estimate exact on sparse vectors and inside the (1 +- 0.5) band of Alg. 1;
                  threshold split against a plain loop; fill keys against the published
                  generator; uniformity of the fill; the k/d contraction of Lemma 1
@@ -570,6 +572,43 @@ def test_heavymix_is_a_k_over_d_contraction():
             assert ratio == pytest.approx(1 - k / d, rel=0.01)
         else:
             assert ratio < (1 - k / d) * (1 - 0.5)             # the planted part alone is > half
+
+
+# ----------------------------------------------------------------------------- 16-bit sketches
+def test_quantize16_known_patterns_and_library_conversions():
+    import torch
+    f = np.float32
+    cases = [                                   # value, bf16 pattern, f16 pattern
+        (0.0, 0x0000, 0x0000), (-0.0, 0x8000, 0x8000), (1.0, 0x3F80, 0x3C00),
+        (-2.5, 0xC020, 0xC100), (np.inf, 0x7F80, 0x7C00), (-np.inf, 0xFF80, 0xFC00),
+        (1.0 + 2.0 ** -8, 0x3F80, 0x3C04),      # bf16: exactly half way, even neighbour below
+        (1.0 + 3 * 2.0 ** -8, 0x3F82, 0x3C0C),  # bf16: half way, even neighbour above
+        (1.0 + 2.0 ** -8 + 2.0 ** -20, 0x3F81, 0x3C04),   # just above half way
+        (1.0 + 2.0 ** -11, 0x3F80, 0x3C00),     # f16: half way between 1 and 1 + 2^-10, even below
+        (1.0 + 3 * 2.0 ** -11, 0x3F80, 0x3C02),
+        (65504.0, 0x4780, 0x7BFF), (65520.0, 0x4780, 0x7C00),   # f16: largest finite; overflow
+        (3.4e38, 0x7F80, None),                 # bf16: rounds up past the largest finite value
+        (2.0 ** -24, 0x3380, 0x0001), (2.0 ** -25, 0x3300, 0x0000),   # f16 subnormals
+    ]
+    for x, bf, hf in cases:
+        assert int(orc.quantize16([f(x)], "bf16")[0]) == bf, (x, hex(bf))
+        if hf is not None:
+            assert int(orc.quantize16([f(x)], "f16")[0]) == hf, (x, hex(hf))
+    assert np.isnan(orc.dequantize16(orc.quantize16([np.nan], "bf16"), "bf16")[0])
+    rng = np.random.default_rng(5)
+    x = np.concatenate([rng.standard_normal(200_000) * 10.0 ** rng.uniform(-12, 12, 200_000),
+                        rng.integers(0, 1 << 32, 200_000, dtype=np.uint64).astype(np.uint32).view(np.float32)])
+    x = x.astype(np.float32)
+    ok = ~np.isnan(x)
+    t = torch.from_numpy(x)
+    np.testing.assert_array_equal(orc.quantize16(x, "bf16")[ok],
+                                  t.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)[ok])
+    np.testing.assert_array_equal(orc.quantize16(x, "f16")[ok],
+                                  t.to(torch.float16).view(torch.int16).numpy().view(np.uint16)[ok])
+    for fmt, ulp in (("bf16", 2.0 ** -8), ("f16", 2.0 ** -11)):
+        back = orc.dequantize16(orc.quantize16(x, fmt), fmt)
+        fin = ok & np.isfinite(back) & (np.abs(x) > 1e-4) & (np.abs(x) < 6e4)
+        assert (np.abs(back[fin] - x[fin].astype(np.float64)) <= ulp * np.abs(x[fin])).all()
 
 
 def test_compression_numbers_printed_in_paper(golden_dir):
