@@ -68,6 +68,13 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=4)
+    ap.add_argument("--variant", default="sketch-state",
+                    choices=["sketch-state", "dense-state", "heavymix", "top-pk"],
+                    help="sketch-state: the headline path (momentum / error feedback as sketches; "
+                         "stateless for configs 1-3).  dense-state: Alg. 3 as printed, dense u, v "
+                         "per worker.  heavymix: Alg. 1 selection (norm estimate, threshold, random "
+                         "fill) on the merged sketch, no state.  top-pk: P = 16 candidates per "
+                         "selected coordinate, exact second round, k largest exact sums")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known HBM traffic) "
@@ -82,7 +89,7 @@ def main():
 
     import workloads as wl
     from paper_1903_04488_amd import binding as B
-    from paper_1903_04488_amd.pipeline import HotPath
+    from paper_1903_04488_amd.pipeline import DenseStatePath, HotPath
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -90,7 +97,18 @@ def main():
     dev = "cuda:0"
     cfg = wl.CONFIGS[args.config]
     work = wl.Workload(cfg, dev)
-    hp = HotPath(cfg.d, cfg.W, cfg.r, cfg.c, cfg.k, cfg.hash_seed, rho=cfg.rho, device=dev)
+    variant = args.variant
+    if variant == "dense-state":
+        hp = DenseStatePath(cfg.d, cfg.W, cfg.r, cfg.c, cfg.k, cfg.hash_seed,
+                            rho=cfg.rho if cfg.rho is not None else 0.9, device=dev)
+    elif variant == "top-pk":
+        hp = HotPath(cfg.d, cfg.W, cfg.r, cfg.c, cfg.k, cfg.hash_seed, rho=cfg.rho, device=dev, P=16)
+    elif variant == "heavymix":
+        hp = HotPath(cfg.d, cfg.W, cfg.r, cfg.c, cfg.k, cfg.hash_seed, rho=None, device=dev)
+        l2sq = torch.empty(1 + cfg.r, dtype=torch.float64, device=dev)
+        n_heavy = torch.empty(1, dtype=torch.int64, device=dev)
+    else:
+        hp = HotPath(cfg.d, cfg.W, cfg.r, cfg.c, cfg.k, cfg.hash_seed, rho=cfg.rho, device=dev)
 
     # inputs resident in HBM before the timed region: a few distinct steps' worth, cycled
     bytes_per_set = 4 * cfg.d * cfg.W
@@ -98,26 +116,51 @@ def main():
     sets = [[work.gradient(t, w) for w in range(cfg.W)] for t in range(n_sets)]
     torch.cuda.synchronize()
 
-    stages = ["accumulate", "merge", "momentum", "estimate", "topk", "gather", "feedback"]
+    # stage names per variant; stage i runs between events i and i + 1.  Stage 0 is always the
+    # update (zeroing the worker tables belongs to it); the batched update itself is bracketed
+    # by its own pair of events (ev[8], ev[9]) for the roofline figure.
+    stages = {"sketch-state": ["accumulate", "merge", "momentum", "estimate", "topk", "gather", "feedback"],
+              "top-pk": ["accumulate", "merge", "momentum", "estimate", "topk", "gather+select", "feedback"],
+              "dense-state": ["dense_momentum", "accumulate", "merge", "estimate", "topk", "gather", "mask"],
+              "heavymix": ["accumulate", "merge", "l2sq", "estimate", "heavymix_select", "gather", "-"]}[variant]
 
     def one_step(g_w, ev=None):
         def mark(i):
             if ev is not None:
                 ev[i].record()
-        # zeroing the worker tables belongs to the update stage; the batched update itself is
-        # bracketed by its own pair of events (ev[8], ev[9]) for the roofline figure
+
+        def update(vecs):
+            B.cs_bundle_zero(hp.params, hp.T, hp.W)
+            mark(8)
+            B.cs_sketch_accumulate_bundle(hp.params, hp.T, vecs)
+            mark(9)
+
         mark(0)
-        B.cs_bundle_zero(hp.params, hp.T, hp.W)
-        mark(8)
-        B.cs_sketch_accumulate_bundle(hp.params, hp.T, g_w)
-        mark(9)
-        mark(1)
-        hp.merge(); mark(2)
-        hp.momentum(); mark(3)
-        hp.estimate(); mark(4)
-        hp.topk(); mark(5)
-        hp.gather(g_w); mark(6)
-        hp.feedback(); mark(7)
+        if variant == "dense-state":
+            hp.dense_momentum(g_w); mark(1)
+            update(hp.v_w); mark(2)
+            hp.merge(); mark(3)
+            hp.estimate(); mark(4)
+            hp.topk(); mark(5)
+            hp.gather(hp.v_w); mark(6)
+            hp.mask(); mark(7)
+        elif variant == "heavymix":
+            update(g_w); mark(1)
+            hp.merge(); mark(2)
+            B.cs_sketch_l2sq(hp.params, hp.S_t, l2sq); mark(3)
+            hp.estimate(); mark(4)
+            B.cs_heavymix_select(hp.est, cfg.k, l2sq, 12345, hp.cand, hp.est_at_cand, n_heavy,
+                                 hp.topk_ws); mark(5)
+            hp.gather(g_w); mark(6)
+            mark(7)
+        else:
+            update(g_w); mark(1)
+            hp.merge(); mark(2)
+            hp.momentum(); mark(3)
+            hp.estimate(); mark(4)
+            hp.topk(); mark(5)
+            hp.gather(g_w); mark(6)
+            hp.feedback(); mark(7)
 
     if args.calibration_copy:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
@@ -171,8 +214,8 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"cfg{cfg.cfg} {cfg.name}", "d": cfg.d, "W": cfg.W, "r": cfg.r,
-                   "c": cfg.c, "k": cfg.k, "rho": cfg.rho,
+        "config": {"workload": f"cfg{cfg.cfg} {cfg.name}", "variant": variant, "d": cfg.d,
+                   "W": cfg.W, "r": cfg.r, "c": cfg.c, "k": cfg.k, "rho": cfg.rho,
                    "input_sets_resident": n_sets},
         "pct_hbm_peak_whole_step": 100.0 * step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "stage_ms": stage_ms,
