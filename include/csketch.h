@@ -92,7 +92,7 @@ typedef struct cs_visit_plan {
     uint32_t ncell;             /* running sums per lane and coordinate: 2, 3 or 4 */
     uint64_t cover;             /* the list covers vectors of length <= cover (= d_hint) */
     uint64_t gmax;              /* largest gap = number of residues that lanes own */
-    uint64_t cost;              /* estimated atomic requests per worker group, this list */
+    uint64_t cost;              /* estimated time of one launch with this list, nanoseconds */
     uint64_t cost_walk;         /* the same for the stride walk with cs_row_plan.Dw */
     uint64_t gap[4];            /* gap value per code */
     uint64_t A[4], As[4];       /* (a_j * gap) mod p, (a'_j * gap) mod p per code */

@@ -112,6 +112,22 @@ void plan_walk(cs_row_plan* rp, uint64_t a, uint64_t as, uint32_t c, bool pow2, 
     rp->ADws = mulmod(as, rp->Dw);
 }
 
+// Estimated time, in nanoseconds, of one launch of the bundle update for a group of 8 workers:
+// `visits` turns of the busiest wavefront in a row (each costs about kVisitNs of latency that
+// nothing hides when few wavefronts are resident), stretched when there are more wavefronts
+// than the chip holds at once; never less than reading the 8 vectors at the rate this access
+// pattern reaches; plus the atomic requests at the rate of the memory-side atomic unit.  The
+// constants are measurements on MI355X (bundle update at d = 10^6 .. 10^8).
+double update_time_ns(double visits, double residues, double requests, double d) {
+    const double kVisitNs = 900.0, kResidentWaves = 4096.0;
+    const double kBytesPerNs = 4600.0, kRequestsPerNs = 24.0;
+    const double waves = residues / 128.0;
+    double serial = visits * kVisitNs;
+    if (waves > kResidentWaves) serial *= waves / kResidentWaves;
+    const double stream = d * 32.0 / kBytesPerNs;
+    return (serial > stream ? serial : stream) + requests / kRequestsPerNs;
+}
+
 // Visit list of the bundle update for one row (cs_visit_plan).
 //
 // Rotating a hash value left by sh = 61 - log2(c) bits is a multiplication by 2^sh mod p, so
@@ -120,9 +136,10 @@ void plan_walk(cs_row_plan* rp, uint64_t a, uint64_t as, uint32_t c, bool pow2, 
 // is { s < d : U(s) < omega * 2^sh } together with s = 0: every visit of a lane then lands
 // in one of ncell = ceil(omega) + 1 neighbouring cells, whose sums it keeps in registers.
 // Lanes own the residues [0, gmax), gmax the largest gap between neighbouring list entries,
-// so a worker group sends about ncell * gmax requests for the whole vector; the bound is
-// chosen to make that product smallest (one scan of s = 1 .. d - 1 collects the candidates
-// for the widest bound, narrower ones are subsets).
+// so a worker group sends about ncell * gmax requests for the whole vector, in K visits.  A
+// wide bound means many visits and few requests, a narrow one the opposite; the bound is
+// chosen by the time model above (one scan of s = 1 .. d - 1 collects the candidates for the
+// widest bound, narrower ones are subsets).
 void plan_visits(cs_visit_plan* vp, const cs_row_plan* rp, uint64_t a, uint64_t as, uint32_t c,
                  bool pow2, uint64_t d_hint) {
     memset(vp, 0, sizeof(*vp));
@@ -136,7 +153,9 @@ void plan_visits(cs_visit_plan* vp, const cs_row_plan* rp, uint64_t a, uint64_t 
     {
         const uint64_t Uw = mulmod(u1, rp->Dw % kP61);
         const uint64_t mag = Uw < kP61 - Uw ? Uw : kP61 - Uw;
-        vp->cost_walk = (uint64_t)((double)d_hint * ((double)mag / (double)cell)) + rp->Dw;
+        const double requests = (double)d_hint * ((double)mag / (double)cell) + (double)rp->Dw;
+        vp->cost_walk = (uint64_t)update_time_ns((double)d_hint / (double)rp->Dw, (double)rp->Dw,
+                                                 requests, (double)d_hint);
     }
     const double per_cell = (double)d_hint / (double)c;    // list entries per cell of bound
     double omega_max = (CS_MAX_VISITS - 16) / per_cell;
@@ -171,7 +190,8 @@ void plan_visits(cs_visit_plan* vp, const cs_row_plan* rp, uint64_t a, uint64_t 
         if (d_hint - prev > gmax) gmax = d_hint - prev;
         if (K < 4 || K > CS_MAX_VISITS) continue;
         const uint64_t ncell = ((bound + cell - 1) >> sh) + 1;
-        const uint64_t cost = ncell * gmax;
+        const uint64_t cost = (uint64_t)update_time_ns((double)K, (double)gmax,
+                                                       (double)(ncell * gmax), (double)d_hint);
         if (cost < best_cost) { best_cost = cost; best_bound = bound; }
     }
     if (best_bound == 0) return;

@@ -261,10 +261,26 @@ int launch_walk(const cs_params* p, const WalkArgs& a, hipStream_t stream) {
 // transpose and the roles of lanes are those of the stride walk above.
 // ---------------------------------------------------------------------------------------
 struct VisitArgs {
-    uint32_t K, pad;
+    uint32_t K;                  // visits
+    int32_t j;                   // sketch row
     uint64_t gmax;
+    uint64_t a, b, as, bs;       // hash constants of row j
     uint64_t gap[4], A[4], As[4];
     uint32_t code[CS_MAX_VISITS / 16];
+};
+// Rows that share the number of running sums are updated by one launch (blockIdx.y = row of
+// the set): their serial chains of visits overlap, and there are fewer launch tails.
+constexpr int kRowsPerLaunch = 8;
+struct VisitRows {
+    VisitArgs row[kRowsPerLaunch];
+};
+struct VisitWorkers {
+    const float* g[kGroup];      // vectors of the workers of this group
+    float* T;                    // the group's table, float[r][c][kGroup]
+    int64_t d, i0;
+    uint32_t c;
+    int32_t nw;                  // workers in this group (<= kGroup)
+    float scale;
 };
 
 
@@ -294,7 +310,8 @@ __device__ __forceinline__ void load_floats(gfloat_ptr src, float (&out)[N]) {
 
 template <int WL, int RUN, int NWAVE, int NC>
 __global__ void __launch_bounds__(64 * NWAVE)
-k_accumulate_visits(KParams p, VisitArgs v, WalkArgs a) {
+k_accumulate_visits(VisitRows rows, VisitWorkers a) {
+    const VisitArgs& v = rows.row[blockIdx.y];
     constexpr int WPW = 64 / WL;                       // walkers per wavefront
     constexpr int PPL = RUN / WL;                      // hash values each lane computes
     constexpr int FPL = RUN / WL;                      // floats each lane requests per worker
@@ -319,21 +336,20 @@ k_accumulate_visits(KParams p, VisitArgs v, WalkArgs a) {
     uint32_t* rec_lds = rec_lds_all[wq];
     uint32_t* first_lds = first_lds_all[wq];
     uint32_t* raw_lds = raw_lds_all[wq];
-    const int j = a.j;
     const int h = lane / WL, wl = lane % WL;
     const int nw = a.nw;
     const bool live = wl < nw;                          // my worker exists
 
     const int64_t chunks = (static_cast<int64_t>(v.gmax) + RUN - 1) / RUN;
     const int64_t nwaves = (chunks + WPW - 1) / WPW;
-    const uint32_t mask = p.c - 1u;
+    const uint32_t mask = a.c - 1u;
     const int64_t d = a.d;
-    float* __restrict__ Tcol = a.Trow + wl;
+    float* __restrict__ Tcol = a.T + static_cast<size_t>(v.j) * a.c * kGroup + wl;
     const int m0 = wl * PPL;                           // hash role: coordinates m0 .. m0 + PPL - 1
     float* my_row = tile_lds + lane * kStride;         // consumer role: my walker's run of my worker
     const uint32_t* my_rec = rec_lds + h * RUN * kRec;
     uint32_t* rec_dst = rec_lds + (h * RUN + m0) * kRec;
-    const uint64_t Aj = p.a[j], Asj = p.as[j];
+    const uint64_t Aj = v.a, Asj = v.as;
     // loader role: floats lspan .. lspan + FPL - 1 of the wavefront's span, of every worker;
     // they belong to walker lspan / RUN and go to that walker's row of each worker
     const int lspan = lane * FPL;
@@ -358,8 +374,8 @@ k_accumulate_visits(KParams p, VisitArgs v, WalkArgs a) {
         const int64_t wv = set * NWAVE + wq;
         if (set >= ngroups || wv >= nwaves) continue;
         const int64_t first_res = wv * SPAN;           // first residue of this wavefront's walkers
-        uint64_t yb = hash_state(p.a[j], p.b[j], static_cast<uint64_t>(a.i0 + first_res + h * RUN + m0));
-        uint64_t ys = hash_state(p.as[j], p.bs[j], static_cast<uint64_t>(a.i0 + first_res + h * RUN + m0));
+        uint64_t yb = hash_state(v.a, v.b, static_cast<uint64_t>(a.i0 + first_res + h * RUN + m0));
+        uint64_t ys = hash_state(v.as, v.bs, static_cast<uint64_t>(a.i0 + first_res + h * RUN + m0));
 
         // the cells my coordinates start in (visit 0, whether or not I take part in it)
         uint32_t first_cell[PPL];
@@ -534,27 +550,36 @@ k_accumulate_visits(KParams p, VisitArgs v, WalkArgs a) {
     }
 }
 
+// one launch: the rows `js` (all with ncell running sums) of one group of workers
 template <int WL, int RUN, int NWAVE>
-int launch_visits(const cs_params* p, const WalkArgs& a, hipStream_t stream) {
+int launch_visits(const cs_params* p, const VisitWorkers& a, const uint32_t* js, int nrows,
+                  uint32_t ncell, hipStream_t stream) {
     constexpr int WPW = 64 / WL;
-    const cs_visit_plan& vp = p->visit[a.j];
-    VisitArgs v{};
-    v.K = vp.K;
-    v.gmax = vp.gmax;
-    for (int q = 0; q < 4; ++q) { v.gap[q] = vp.gap[q]; v.A[q] = vp.A[q]; v.As[q] = vp.As[q]; }
-    for (int q = 0; q < CS_MAX_VISITS / 16; ++q) v.code[q] = vp.code[q];
-    const int64_t chunks = (static_cast<int64_t>(vp.gmax) + RUN - 1) / RUN;
-    const int64_t nwaves = (chunks + WPW - 1) / WPW;
-    const int64_t ngroups = (nwaves + NWAVE - 1) / NWAVE;
+    VisitRows rows{};
+    int64_t most = 1;
+    for (int q = 0; q < nrows; ++q) {
+        const uint32_t j = js[q];
+        const cs_visit_plan& vp = p->visit[j];
+        VisitArgs& v = rows.row[q];
+        v.K = vp.K;
+        v.j = static_cast<int32_t>(j);
+        v.gmax = vp.gmax;
+        v.a = p->a[j]; v.b = p->b[j]; v.as = p->as[j]; v.bs = p->bs[j];
+        for (int t = 0; t < 4; ++t) { v.gap[t] = vp.gap[t]; v.A[t] = vp.A[t]; v.As[t] = vp.As[t]; }
+        for (int t = 0; t < CS_MAX_VISITS / 16; ++t) v.code[t] = vp.code[t];
+        const int64_t chunks = (static_cast<int64_t>(vp.gmax) + RUN - 1) / RUN;
+        const int64_t nwaves = (chunks + WPW - 1) / WPW;
+        const int64_t ngroups = (nwaves + NWAVE - 1) / NWAVE;
+        if (ngroups > most) most = ngroups;
+    }
     const int64_t cap = 256 * 64 / NWAVE;
-    int64_t gx = ngroups < cap ? ngroups : cap;
+    int64_t gx = most < cap ? most : cap;
     gx = (gx + 7) / 8 * 8;                   // the kernel deals workgroups to XCDs in eights
-    const unsigned grid = static_cast<unsigned>(gx), block = 64 * NWAVE;
-    const KParams& kp = kparams(p);
-    switch (vp.ncell) {
-        case 2: k_accumulate_visits<WL, RUN, NWAVE, 2><<<grid, block, 0, stream>>>(kp, v, a); break;
-        case 3: k_accumulate_visits<WL, RUN, NWAVE, 3><<<grid, block, 0, stream>>>(kp, v, a); break;
-        case 4: k_accumulate_visits<WL, RUN, NWAVE, 4><<<grid, block, 0, stream>>>(kp, v, a); break;
+    const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(nrows)), block(64 * NWAVE);
+    switch (ncell) {
+        case 2: k_accumulate_visits<WL, RUN, NWAVE, 2><<<grid, block, 0, stream>>>(rows, a); break;
+        case 3: k_accumulate_visits<WL, RUN, NWAVE, 3><<<grid, block, 0, stream>>>(rows, a); break;
+        case 4: k_accumulate_visits<WL, RUN, NWAVE, 4><<<grid, block, 0, stream>>>(rows, a); break;
         default: return CS_EINVAL;
     }
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
@@ -582,31 +607,53 @@ int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* con
                            int64_t d, int64_t i0, float scale, hipStream_t stream) {
     const size_t row_floats = static_cast<size_t>(p->c) * kGroup;
     for (int w0 = 0; w0 < W; w0 += kGroup) {
+        const int nw = (W - w0 < kGroup) ? (W - w0) : kGroup;
+        float* Tg = T + static_cast<size_t>(w0 / kGroup) * p->r * row_floats;
+        // rows with a visit list: one launch per number of running sums (and per 8 rows)
+        VisitWorkers vw{};
+        for (int w = 0; w < nw; ++w) vw.g[w] = g_w[w0 + w];
+        vw.T = Tg;
+        vw.d = d;
+        vw.i0 = i0;
+        vw.c = p->c;
+        vw.nw = nw;
+        vw.scale = scale;
+        for (uint32_t ncell = 2; ncell <= 4; ++ncell) {
+            uint32_t js[kRowsPerLaunch];
+            int nrows = 0;
+            for (uint32_t j = 0; j <= p->r; ++j) {
+                if (j < p->r && visits_apply(p, j, d) && p->visit[j].ncell == ncell) js[nrows++] = j;
+                if (nrows == kRowsPerLaunch || (j == p->r && nrows > 0)) {
+                    int rc;
+                    if (nw > 4) rc = launch_visits<8, 16, CS_WALK_NWAVE8>(p, vw, js, nrows, ncell, stream);
+                    else if (nw > 2) rc = launch_visits<4, 16, 1>(p, vw, js, nrows, ncell, stream);
+                    else if (nw > 1) rc = launch_visits<2, 16, 1>(p, vw, js, nrows, ncell, stream);
+                    else rc = launch_visits<1, 16, 1>(p, vw, js, nrows, ncell, stream);
+                    if (rc != CS_OK) return rc;
+                    nrows = 0;
+                }
+            }
+        }
+        // the other rows: stride walk, one launch per row
         WalkArgs a{};
-        a.nw = (W - w0 < kGroup) ? (W - w0) : kGroup;
-        for (int w = 0; w < a.nw; ++w) a.g[w] = g_w[w0 + w];
+        a.nw = nw;
+        for (int w = 0; w < nw; ++w) a.g[w] = g_w[w0 + w];
         a.d = d;
         a.i0 = i0;
         a.scale = scale;
         for (uint32_t j = 0; j < p->r; ++j) {
+            if (visits_apply(p, j, d)) continue;
             a.j = static_cast<int32_t>(j);
-            a.Trow = T + (static_cast<size_t>(w0 / kGroup) * p->r + j) * row_floats;
+            a.Trow = Tg + j * row_floats;
             int rc;
-            if (visits_apply(p, j, d)) {
-                if (a.nw > 4) rc = launch_visits<8, 16, CS_WALK_NWAVE8>(p, a, stream);
-                else if (a.nw > 2) rc = launch_visits<4, 16, 1>(p, a, stream);
-                else if (a.nw > 1) rc = launch_visits<2, 16, 1>(p, a, stream);
-                else rc = launch_visits<1, 16, 1>(p, a, stream);
-            } else {
 #if CS_BUNDLE_GROUP >= 16
-                if (a.nw > 8) rc = launch_walk<16, 16, 2>(p, a, stream);
-                else
+            if (nw > 8) rc = launch_walk<16, 16, 2>(p, a, stream);
+            else
 #endif
-                if (a.nw > 4) rc = launch_walk<8, 16, CS_WALK_NWAVE8>(p, a, stream);
-                else if (a.nw > 2) rc = launch_walk<4, 16, 1>(p, a, stream);
-                else if (a.nw > 1) rc = launch_walk<2, 16, 1>(p, a, stream);
-                else rc = launch_walk<1, 16, 1>(p, a, stream);
-            }
+            if (nw > 4) rc = launch_walk<8, 16, CS_WALK_NWAVE8>(p, a, stream);
+            else if (nw > 2) rc = launch_walk<4, 16, 1>(p, a, stream);
+            else if (nw > 1) rc = launch_walk<2, 16, 1>(p, a, stream);
+            else rc = launch_walk<1, 16, 1>(p, a, stream);
             if (rc != CS_OK) return rc;
         }
     }
