@@ -21,15 +21,16 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 METRIC = "sketch+estimate+top-k throughput, Gcoords/s and % HBM peak at d=100M, r=5"
-# HBM bytes per launch of the dominant kernel at config 4, measured with rocprofv3 --pmc
-# (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the factors being what the same counters read for
-# a plain 1 GiB copy).  Source: profiles/accumulate_walk_cfg4_pmc.md.  None for other configs.
-MEASURED_TRAFFIC_BYTES = {4: 3.52e9}
+# HBM bytes per launch of the dominant kernel at config 4 (average over the 12 launches of a
+# step), measured with rocprofv3 --pmc: FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the factors
+# being what the same counters read for a plain 1 GiB copy.
+# Source: profiles/accumulate_visits_cfg4_pmc.md.  None for other configs.
+MEASURED_TRAFFIC_BYTES = {4: 5.99e9}
 
 
-def cpu_baseline(cfg, work, sample_acc=8_000_000, sample_est=4_000_000):
+def cpu_baseline(cfg, work, sample_acc=64_000_000, sample_est=32_000_000):
     """The CPU reference as it stands, single-threaded, on a bounded sample of the same
-    workload; scaled to the cost of one full step."""
+    workload (sized for 10-30 s of CPU work at config 4); scaled to the cost of one full step."""
     import numpy as np
     from oracle import cs_oracle as orc
 
@@ -186,10 +187,10 @@ def main():
     stage_ms = {}
     for i, name in enumerate(stages):
         stage_ms[name] = sum(ev[i].elapsed_time(ev[i + 1]) for ev in events) / args.steps
-    # the update runs as one launch per (group of 8 workers, sketch row); the algorithmic bytes
-    # of the whole update (every gradient read once, every worker table written once) are
-    # spread evenly over those launches
-    n_launch = ((cfg.W + 7) // 8) * cfg.r
+    # the update runs as a few launches per group of 8 workers (rows that share a traversal
+    # share a launch); the algorithmic bytes of the whole update (every gradient read once,
+    # every worker table written once) are spread evenly over those launches
+    n_launch = B.cs_bundle_update_launches(hp.params, cfg.W, cfg.d)
     acc_kernel_ms = sum(ev[8].elapsed_time(ev[9]) for ev in events) / args.steps / n_launch
     value = cfg.W * cfg.d / (ms_per_step * 1e-3) / 1e9
 
@@ -220,7 +221,7 @@ def main():
         "pct_hbm_peak_whole_step": 100.0 * step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "stage_ms": stage_ms,
         "roofline": {
-            "kernel": "k_accumulate_visits (cs_sketch_accumulate_bundle)",
+            "kernel": "k_accumulate_visits (all launches of cs_sketch_accumulate_bundle)",
             "bound": "hbm",
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,

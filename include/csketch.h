@@ -164,6 +164,10 @@ int cs_sketch_accumulate_batch(const cs_params* p, float* const* S_w, const floa
  * The bundle must be below 2^40 floats and 16-byte aligned. */
 #define CS_BUNDLE_GROUP 8
 int cs_bundle_floats(const cs_params* p, int32_t W, int64_t* n);
+/* *n = number of kernel launches one cs_sketch_accumulate_bundle(p, T, W, g_w, d, ...) call
+ * makes (rows that share a traversal share a launch); for reading profiles and for dividing
+ * a timed call into per-launch figures.  Host only. */
+int cs_bundle_update_launches(const cs_params* p, int32_t W, int64_t d, int32_t* n);
 int cs_bundle_zero(const cs_params* p, float* T, int32_t W, void* stream);
 int cs_sketch_accumulate_bundle(const cs_params* p, float* T, int32_t W,
                                 const float* const* g_w, int64_t d, int64_t i0, float scale,

@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     cs_params_init,
     cs_select_exact_topk,
     cs_sketch_l2sq,
+    cs_bundle_update_launches,
     cs_quantize16,
     cs_dequantize16,
     cs_bundle_merge16,

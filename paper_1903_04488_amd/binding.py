@@ -103,6 +103,8 @@ _SIGNATURES = {
     "cs_select_exact_topk": [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                              ctypes.c_void_p],
+    "cs_bundle_update_launches": [ctypes.POINTER(CsParams), ctypes.c_int32, ctypes.c_int64,
+                                  ctypes.POINTER(ctypes.c_int32)],
     "cs_quantize16": [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p],
     "cs_dequantize16": [ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p],
     "cs_bundle_merge16": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p,
@@ -250,6 +252,13 @@ def cs_sketch_accumulate_bundle(p, T, g_w, i0: int = 0, scale: float = 1.0):
         ctypes.byref(p), _dev(T, torch.float32, "T", cs_bundle_floats(p, W)), W,
         _ptr_array(g_w, torch.float32, "g_w", d), d, i0, scale, _stream(T)),
         "cs_sketch_accumulate_bundle")
+
+
+def cs_bundle_update_launches(p, W: int, d: int) -> int:
+    n = ctypes.c_int32(0)
+    _check(load_library().cs_bundle_update_launches(ctypes.byref(p), W, d, ctypes.byref(n)),
+           "cs_bundle_update_launches")
+    return int(n.value)
 
 
 def cs_bundle_merge(p, dst, T, W: int, alpha: float = 1.0, beta: float = 0.0):

@@ -462,6 +462,14 @@ extern "C" int cs_sketch_accumulate_bundle(const cs_params* p, float* T, int32_t
     return CS_OK;
 }
 
+extern "C" int cs_bundle_update_launches(const cs_params* p, int32_t W, int64_t d, int32_t* n) {
+    if (!bundle_ok(p, W) || d < 0 || !n) return CS_EINVAL;
+    if (d == 0) { *n = 0; return CS_OK; }
+    if (walk_applies(p, d)) { *n = count_accumulate_walk_launches(p, W, d); return CS_OK; }
+    *n = (W + kMaxBatch - 1) / kMaxBatch;
+    return CS_OK;
+}
+
 extern "C" int cs_bundle_merge(const cs_params* p, float* dst, float beta, const float* T,
                                int32_t W, float alpha, void* stream) {
     if (!bundle_ok(p, W) || !dst || !T) return CS_EINVAL;

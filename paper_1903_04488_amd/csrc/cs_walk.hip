@@ -603,6 +603,20 @@ bool walk_applies(const cs_params* p, int64_t d) {
     return true;
 }
 
+// kernel launches one call of launch_accumulate_walk makes (same grouping as below)
+int count_accumulate_walk_launches(const cs_params* p, int W, int64_t d) {
+    int per_group = 0;
+    for (uint32_t ncell = 2; ncell <= 4; ++ncell) {
+        int nrows = 0;
+        for (uint32_t j = 0; j < p->r; ++j)
+            if (visits_apply(p, j, d) && p->visit[j].ncell == ncell) ++nrows;
+        per_group += (nrows + kRowsPerLaunch - 1) / kRowsPerLaunch;
+    }
+    for (uint32_t j = 0; j < p->r; ++j)
+        if (!visits_apply(p, j, d)) ++per_group;
+    return per_group * ((W + kGroup - 1) / kGroup);
+}
+
 int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* const* g_w,
                            int64_t d, int64_t i0, float scale, hipStream_t stream) {
     const size_t row_floats = static_cast<size_t>(p->c) * kGroup;
