@@ -145,8 +145,11 @@ __device__ __forceinline__ bool segment_sum16(uint32_t key, float& v, int nsteps
 // transposition sort, fully unrolled, then the middle element.
 template <int R>
 __device__ __forceinline__ float median_odd(float (&v)[R]) {
-    if (R == 1) return v[0];
-    if (R == 3) return fmaxf(fminf(v[0], v[1]), fminf(fmaxf(v[0], v[1]), v[2]));
+    if constexpr (R == 1) {
+        return v[0];
+    } else if constexpr (R == 3) {
+        return fmaxf(fminf(v[0], v[1]), fminf(fmaxf(v[0], v[1]), v[2]));
+    } else {
 #pragma unroll
     for (int pass = 0; pass < R; ++pass) {
 #pragma unroll
@@ -158,6 +161,7 @@ __device__ __forceinline__ float median_odd(float (&v)[R]) {
         }
     }
     return v[R / 2];
+    }
 }
 
 }  // namespace cs

@@ -228,11 +228,30 @@ k_row_values_lattice(KParams p, const float* __restrict__ S, int64_t d, int64_t 
     }
 }
 
-template <int R>
+// est[t] = median over rows of rows[j][t]; VEC: four coordinates per thread with 16-byte
+// accesses (d a multiple of 4, both arrays 16-byte aligned, so every row is aligned too)
+template <int R, bool VEC>
 __global__ void __launch_bounds__(kBlock)
 k_median_rows(const float* __restrict__ rows, int64_t d, float* __restrict__ est) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
-    for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < d; t += stride) {
+    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (VEC) {
+        const int64_t n4 = d / 4;
+        for (int64_t t = t0; t < n4; t += stride) {
+            typedef float f4 __attribute__((ext_vector_type(4)));
+            float vx[R], vy[R], vz[R], vw[R];
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+                const f4 q = __builtin_nontemporal_load(
+                    reinterpret_cast<const f4*>(rows + static_cast<size_t>(j) * d) + t);
+                vx[j] = q.x; vy[j] = q.y; vz[j] = q.z; vw[j] = q.w;
+            }
+            reinterpret_cast<float4*>(est)[t] =
+                make_float4(median_odd<R>(vx), median_odd<R>(vy), median_odd<R>(vz), median_odd<R>(vw));
+        }
+        return;
+    }
+    for (int64_t t = t0; t < d; t += stride) {
         float v[R];
 #pragma unroll
         for (int j = 0; j < R; ++j) v[j] = rows[static_cast<size_t>(j) * d + t];
@@ -304,17 +323,17 @@ int launch_estimate_lattice(const cs_params* p, const float* S, int64_t d, int64
     int64_t b = (d + kBlock - 1) / kBlock;
     if (b > 256 * 16) b = 256 * 16;
     const unsigned mg = static_cast<unsigned>(b);
+    const bool vec = d % 4 == 0 && (reinterpret_cast<uintptr_t>(rows) | reinterpret_cast<uintptr_t>(est)) % 16 == 0;
+#define CS_MEDIAN(R_)                                                                   \
+    case R_:                                                                            \
+        if (vec) k_median_rows<R_, true><<<mg, kBlock, 0, stream>>>(rows, d, est);       \
+        else k_median_rows<R_, false><<<mg, kBlock, 0, stream>>>(rows, d, est);          \
+        break;
     switch (p->r) {
-        case 1: k_median_rows<1><<<mg, kBlock, 0, stream>>>(rows, d, est); break;
-        case 3: k_median_rows<3><<<mg, kBlock, 0, stream>>>(rows, d, est); break;
-        case 5: k_median_rows<5><<<mg, kBlock, 0, stream>>>(rows, d, est); break;
-        case 7: k_median_rows<7><<<mg, kBlock, 0, stream>>>(rows, d, est); break;
-        case 9: k_median_rows<9><<<mg, kBlock, 0, stream>>>(rows, d, est); break;
-        case 11: k_median_rows<11><<<mg, kBlock, 0, stream>>>(rows, d, est); break;
-        case 13: k_median_rows<13><<<mg, kBlock, 0, stream>>>(rows, d, est); break;
-        case 15: k_median_rows<15><<<mg, kBlock, 0, stream>>>(rows, d, est); break;
+        CS_MEDIAN(1) CS_MEDIAN(3) CS_MEDIAN(5) CS_MEDIAN(7) CS_MEDIAN(9) CS_MEDIAN(11) CS_MEDIAN(13) CS_MEDIAN(15)
         default: return CS_EINVAL;
     }
+#undef CS_MEDIAN
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
 

@@ -750,7 +750,9 @@ k_row_values_walk(KParams p, const float* __restrict__ S, int64_t d, int64_t i0,
                 if (m4 + 4 <= len) {
                     vec4f u;
                     u.x = src[0]; u.y = src[1]; u.z = src[2]; u.w = src[3];
-                    *reinterpret_cast<vec4f_u*>(dst) = u;
+                    // streamed out, read once by the median kernel: kept out of the way of
+                    // the table row that the gathers want to find in L2
+                    __builtin_nontemporal_store(u, reinterpret_cast<vec4f_u*>(dst));
                 } else if (m4 < len) {
                     dst[0] = src[0];
                     if (m4 + 1 < len) dst[1] = src[1];
