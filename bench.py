@@ -76,6 +76,9 @@ def main():
                          "per worker.  heavymix: Alg. 1 selection (norm estimate, threshold, random "
                          "fill) on the merged sketch, no state.  top-pk: P = 16 candidates per "
                          "selected coordinate, exact second round, k largest exact sums")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the same step replayed from a HIP graph (one submission per "
+                         "step instead of one per kernel); reported as graph_ms_per_step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known HBM traffic) "
@@ -233,6 +236,17 @@ def main():
             "algorithmic_bytes_per_launch": alg_bytes,
         },
     }
+    if args.graph:
+        from paper_1903_04488_amd.pipeline import GraphedStep
+        graphed = GraphedStep(hp, sets[0])
+        for _ in range(args.warmup):
+            graphed.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graphed.replay()
+        torch.cuda.synchronize()
+        out["graph_ms_per_step"] = (time.perf_counter() - t0) / args.steps * 1e3
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, work)
     print(json.dumps(out))

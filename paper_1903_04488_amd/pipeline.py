@@ -134,3 +134,42 @@ class DenseStatePath(HotPath):
         self.gather(self.v_w)
         self.mask()
         return self.idx, self.x
+
+
+class GraphedStep:
+    """One step of a HotPath (or DenseStatePath) captured once as a HIP graph and replayed.
+
+    Every stage of a step is a fixed sequence of kernel launches on the caller's stream with
+    fixed device pointers -- no allocation, no host synchronisation, no memset node -- so the
+    whole step can be recorded and replayed with one submission.  That matters when a step is
+    dozens of launches of a few microseconds each (small vectors); for d = 10^8 the kernels
+    dominate and the graph changes nothing.  The gradients live in static buffers `g_w` that the
+    caller overwrites before each replay; results appear in the HotPath's own tensors."""
+
+    def __init__(self, path: HotPath, g_w):
+        self.path = path
+        self.g_w = g_w
+        # one warm-up step outside the capture, on a side stream (a captured launch does not
+        # execute, the warm-up does: the state it advanced is put back afterwards)
+        saved = [t.clone() for t in self._state()]
+        side = torch.cuda.Stream(device=path.device)
+        side.wait_stream(torch.cuda.current_stream(path.device))
+        with torch.cuda.stream(side):
+            path.step(g_w)
+        torch.cuda.current_stream(path.device).wait_stream(side)
+        torch.cuda.synchronize(path.device)
+        for t, s in zip(self._state(), saved):
+            t.copy_(s)
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            path.step(g_w)
+
+    def _state(self):
+        p = self.path
+        out = [t for t in (p.S_u, p.S_v) if t is not None]
+        out += list(getattr(p, "u_w", [])) + list(getattr(p, "v_w", []))
+        return out
+
+    def replay(self):
+        self.graph.replay()
+        return self.path.idx, self.path.x

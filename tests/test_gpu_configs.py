@@ -16,7 +16,7 @@ import torch
 
 import workloads as wl
 from oracle import cs_oracle as orc
-from paper_1903_04488_amd.pipeline import DenseStatePath, HotPath
+from paper_1903_04488_amd.pipeline import DenseStatePath, GraphedStep, HotPath
 from parity_util import assert_cells_close, assert_valid_topk, assert_values_close
 
 pytestmark = pytest.mark.gpu
@@ -286,3 +286,44 @@ def test_dense_momentum_unaligned_and_tail():
         idx = torch.tensor([0, 5, d - 1], dtype=torch.int64, device=DEV)
         cs.cs_dense_mask(u, v, idx)
         assert all((x[idx] == 0).all() for x in u + v) and all(float(x.abs().sum()) > 0 for x in u + v)
+
+
+# ----------------------------------------------------------------------------- HIP graph
+@pytest.mark.parametrize("stateful", [False, True])
+def test_step_replayed_from_a_hip_graph_matches_eager(stateful):
+    """A step recorded once as a HIP graph and replayed: three replays, with the program's own
+    eager work (input generation, device-to-host copies, synchronisation) between them, each
+    checked against the same step run eagerly on a second instance.  Sums in the tables may
+    differ in rounding order between any two runs (atomic adds); everything else must agree
+    exactly because the planted coordinates stand far above the rest."""
+    c = wl.scaled(4 if stateful else 1, d=(1 << 19) + 321, W=5, c=1 << 13, k=300, steps=3,
+                  n_heavy=300 if not stateful else 0)
+    work = wl.Workload(c, DEV)
+    eager = HotPath(c.d, c.W, c.r, c.c, c.k, c.hash_seed, rho=c.rho, device=DEV)
+    graphed = HotPath(c.d, c.W, c.r, c.c, c.k, c.hash_seed, rho=c.rho, device=DEV)
+    static = [torch.zeros(c.d, dtype=torch.float32, device=DEV) for _ in range(c.W)]
+    for w in range(c.W):
+        static[w].copy_(work.gradient(0, w))
+    step = GraphedStep(graphed, static)
+    if stateful:
+        assert float(graphed.S_v.abs().max()) == 0.0          # recording left the state untouched
+    for t in range(3):
+        g_w = [work.gradient(t, w) for w in range(c.W)]
+        for w in range(c.W):
+            static[w].copy_(g_w[w])
+        idx_e, x_e = eager.step(g_w)
+        idx_g, x_g = step.replay()
+        torch.cuda.synchronize()
+        assert_cells_close(graphed.S_t.cpu().numpy(), eager.S_t.cpu().numpy().astype(np.float64),
+                           what=f"replay {t} merged table")
+        sigma = rms(eager.S_t.cpu().numpy())
+        assert_values_close(graphed.est.cpu().numpy(), eager.est.cpu().numpy(), sigma, what=f"replay {t} est")
+        assert_valid_topk(idx_g.cpu().numpy(), eager.est.cpu().numpy(), c.k, sigma, what=f"replay {t} top-k")
+        same = np.intersect1d(idx_g.cpu().numpy(), idx_e.cpu().numpy()).size
+        assert same >= 0.98 * c.k
+        if stateful:
+            assert_cells_close(graphed.S_v.cpu().numpy(), eager.S_v.cpu().numpy().astype(np.float64),
+                               rel=1e-4, what=f"replay {t} S_v")
+        else:
+            np.testing.assert_array_equal(idx_g.cpu().numpy(), idx_e.cpu().numpy())
+            np.testing.assert_array_equal(x_g.cpu().numpy(), x_e.cpu().numpy())
