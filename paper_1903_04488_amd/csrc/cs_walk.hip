@@ -319,6 +319,10 @@ k_accumulate_visits(VisitRows rows, VisitWorkers a) {
     constexpr int kStride = RUN + 1;
     constexpr int kSetBlock = 4;                       // neighbouring walker sets per XCD turn
     constexpr int kRec = NC == 2 ? 2 : 4;              // words of a coordinate's record
+    // records of one walker, padded by one record: the 8 lanes of a walker read the same record
+    // (a broadcast), the walkers of a wavefront different ones, which without the pad would
+    // all start in the same LDS bank
+    constexpr int kRecWalker = (RUN + 1) * kRec;
     static_assert(WL <= 8 && WL * PPL == RUN, "every coordinate of a walker gets a hash lane");
     static_assert(NC >= 2 && NC <= 4, "two to four running sums");
     // Per wavefront: the value tile (one padded row per lane), one record per coordinate of
@@ -326,7 +330,7 @@ k_accumulate_visits(VisitRows rows, VisitWorkers a) {
     // telling which running sum the coordinate belongs to in this visit), the walkers' first
     // cells, and the (bucket | sign) words of the stride walk, for the fallback.
     __shared__ float tile_lds_all[NWAVE][64 * kStride];
-    __shared__ __attribute__((aligned(16))) uint32_t rec_lds_all[NWAVE][SPAN * kRec];
+    __shared__ __attribute__((aligned(16))) uint32_t rec_lds_all[NWAVE][WPW * kRecWalker];
     __shared__ uint32_t first_lds_all[NWAVE][SPAN];
     __shared__ uint32_t raw_lds_all[NWAVE][SPAN];
 
@@ -347,8 +351,8 @@ k_accumulate_visits(VisitRows rows, VisitWorkers a) {
     float* __restrict__ Tcol = a.T + static_cast<size_t>(v.j) * a.c * kGroup + wl;
     const int m0 = wl * PPL;                           // hash role: coordinates m0 .. m0 + PPL - 1
     float* my_row = tile_lds + lane * kStride;         // consumer role: my walker's run of my worker
-    const uint32_t* my_rec = rec_lds + h * RUN * kRec;
-    uint32_t* rec_dst = rec_lds + (h * RUN + m0) * kRec;
+    const uint32_t* my_rec = rec_lds + h * kRecWalker;
+    uint32_t* rec_dst = rec_lds + h * kRecWalker + m0 * kRec;
     const uint64_t Aj = v.a, Asj = v.as;
     // loader role: floats lspan .. lspan + FPL - 1 of the wavefront's span, of every worker;
     // they belong to walker lspan / RUN and go to that walker's row of each worker
