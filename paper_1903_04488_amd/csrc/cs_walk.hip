@@ -268,8 +268,8 @@ struct VisitArgs {
     uint64_t gap[4], A[4], As[4];
     uint32_t code[CS_MAX_VISITS / 16];
 };
-// Rows that share the number of running sums are updated by one launch (blockIdx.y = row of
-// the set): their serial chains of visits overlap, and there are fewer launch tails.
+// The rows of a sketch are updated by one launch (blockIdx.y = row of the set): their serial
+// chains of visits overlap, and there are fewer launch tails.
 constexpr int kRowsPerLaunch = 8;
 struct VisitRows {
     VisitArgs row[kRowsPerLaunch];
@@ -609,15 +609,12 @@ bool walk_applies(const cs_params* p, int64_t d) {
 
 // kernel launches one call of launch_accumulate_walk makes (same grouping as below)
 int count_accumulate_walk_launches(const cs_params* p, int W, int64_t d) {
-    int per_group = 0;
-    for (uint32_t ncell = 2; ncell <= 4; ++ncell) {
-        int nrows = 0;
-        for (uint32_t j = 0; j < p->r; ++j)
-            if (visits_apply(p, j, d) && p->visit[j].ncell == ncell) ++nrows;
-        per_group += (nrows + kRowsPerLaunch - 1) / kRowsPerLaunch;
+    int listed = 0, per_group = 0;
+    for (uint32_t j = 0; j < p->r; ++j) {
+        if (visits_apply(p, j, d)) ++listed;
+        else ++per_group;
     }
-    for (uint32_t j = 0; j < p->r; ++j)
-        if (!visits_apply(p, j, d)) ++per_group;
+    per_group += (listed + kRowsPerLaunch - 1) / kRowsPerLaunch;
     return per_group * ((W + kGroup - 1) / kGroup);
 }
 
@@ -627,7 +624,6 @@ int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* con
     for (int w0 = 0; w0 < W; w0 += kGroup) {
         const int nw = (W - w0 < kGroup) ? (W - w0) : kGroup;
         float* Tg = T + static_cast<size_t>(w0 / kGroup) * p->r * row_floats;
-        // rows with a visit list: one launch per number of running sums (and per 8 rows)
         VisitWorkers vw{};
         for (int w = 0; w < nw; ++w) vw.g[w] = g_w[w0 + w];
         vw.T = Tg;
@@ -636,11 +632,17 @@ int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* con
         vw.c = p->c;
         vw.nw = nw;
         vw.scale = scale;
-        for (uint32_t ncell = 2; ncell <= 4; ++ncell) {
+        // All rows with a visit list go into one launch (per 8 rows), compiled for the largest
+        // number of running sums among them: a row that needs fewer simply never touches the
+        // extra ones.  One launch overlaps the rows' serial chains of visits and has one tail.
+        uint32_t ncell = 2;
+        for (uint32_t j = 0; j < p->r; ++j)
+            if (visits_apply(p, j, d) && p->visit[j].ncell > ncell) ncell = p->visit[j].ncell;
+        {
             uint32_t js[kRowsPerLaunch];
             int nrows = 0;
             for (uint32_t j = 0; j <= p->r; ++j) {
-                if (j < p->r && visits_apply(p, j, d) && p->visit[j].ncell == ncell) js[nrows++] = j;
+                if (j < p->r && visits_apply(p, j, d)) js[nrows++] = j;
                 if (nrows == kRowsPerLaunch || (j == p->r && nrows > 0)) {
                     int rc;
                     if (nw > 4) rc = launch_visits<8, 16, CS_WALK_NWAVE8>(p, vw, js, nrows, ncell, stream);
