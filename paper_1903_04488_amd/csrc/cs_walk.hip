@@ -1,32 +1,37 @@
-// Alg. 4 update for a bundle of workers, "walk" order (power-of-two column counts).
+// Alg. 4 update for a bundle of workers (power-of-two column counts), and the bundle-wide
+// elementwise kernels.
 //
-// What limits the update on this machine is the number of atomic requests that reach memory
-// (a fixed ~21 G requests of 32 bytes per second, measured, whatever the table size), not
-// bytes or flops.  Two facts cut the requests per coordinate by two orders of magnitude:
+// Done naively the update is one atomic add per coordinate, row and worker, and this machine
+// executes fp32 atomics at the memory side at a fixed ~21-24 G requests of 32 bytes per second
+// (measured, whatever the table size).  Three facts cut the requests by a factor of ~300, after
+// which the kernel is bound by reading the vectors:
 //
-//  1. The bucket hash is affine modulo p = 2^61 - 1, so the coordinates i, i + Dw, i + 2 Dw, ...
-//     move through a row by a constant sigma(Dw) buckets per step, and the host can pick a
-//     stride Dw for which that is a small fraction of a bucket (cs_row_plan).  A lane that
-//     walks such a progression stays in one cell for ~1/sigma consecutive visits: it keeps the
-//     running sum in a register and issues one atomic add when it leaves the cell.
+//  1. The bucket hash is affine modulo p = 2^61 - 1, so moving s coordinates on moves a
+//     coordinate through a row by an amount that depends on s only.  The host lists offsets for
+//     which that amount is a fraction of a cell (cs_row_plan: one stride and its multiples;
+//     cs_visit_plan: every such offset below the vector length), and a lane visits its
+//     coordinates in that order, keeping running sums in registers: one per coordinate,
+//     flushed when the cell changes, in the stride walk (k_accumulate_walk); two to four per
+//     coordinate, flushed once at the very end, with a visit list (k_accumulate_visits, the
+//     kernel that normally runs).
 //  2. All workers use the same hash functions, so in the bundle layout T[w/8][j][b][w%8] the
 //     sums of 8 workers for one cell are 32 contiguous bytes: 8 lanes (one per worker) flush
-//     them as one full 32-byte request.  One launch updates one row of one group, a slice of
-//     c x 32 bytes that stays in the memory-side cache, so the read-modify-writes of the
-//     atomics do not compete with the streaming reads for DRAM.
+//     them as one full 32-byte request.
+//  3. Every row needs its own visiting order, so a group's vectors are read once per row; the
+//     rows of a group run in one launch.
 //
-// Work decomposition for row j: the residues [0, Dw) are cut into chunks of RUN consecutive
-// coordinates; a "walker" owns one chunk and visits it at n Dw for n = 0, 1, ...  A wavefront
-// holds 64 / WL walkers of WL lanes each, lane wl of a walker serving worker wl of the group.
-// Every hash value is evaluated exactly (incremental form of the definition), so results are
-// the same sums as in any other order, up to fp32 rounding order.
+// Work decomposition for row j: the residues below the stride (or below the largest gap of the
+// list) are cut into chunks of RUN consecutive coordinates; a "walker" owns one chunk and
+// visits it at every listed offset.  A wavefront holds 64 / WL walkers of WL lanes each, lane
+// wl of a walker serving worker wl of the group.  Every hash value is evaluated exactly
+// (incremental form of the definition), so results are the same sums as in any other order,
+// up to fp32 rounding order.
 //
 // Data movement per visit: the 64 x RUN tile (64 runs = walkers x workers, RUN floats each) is
-// loaded as 16-byte pieces by neighbouring lanes, transposed through LDS so that every lane
-// gets its own run, and the (bucket, sign) of the walker's RUN coordinates are computed once
-// per walker by its lanes and shared through LDS, where the previous visit's values stay for
-// the "did I leave the cell" test.  A workgroup is one wavefront; nothing is shared between
-// wavefronts, so LDS needs no barrier.
+// requested as contiguous pieces by neighbouring lanes, transposed through LDS so that every
+// lane gets its own run, and the (bucket, sign) of a walker's RUN coordinates are computed once
+// per walker by its lanes and shared through LDS.  Nothing is shared between the wavefronts of
+// a workgroup, so LDS needs no barrier.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 

@@ -596,9 +596,8 @@ def test_quantize16_known_patterns_and_library_conversions():
             assert int(orc.quantize16([f(x)], "f16")[0]) == hf, (x, hex(hf))
     assert np.isnan(orc.dequantize16(orc.quantize16([np.nan], "bf16"), "bf16")[0])
     rng = np.random.default_rng(5)
-    x = np.concatenate([rng.standard_normal(200_000) * 10.0 ** rng.uniform(-12, 12, 200_000),
+    x = np.concatenate([(rng.standard_normal(200_000) * 10.0 ** rng.uniform(-12, 12, 200_000)).astype(np.float32),
                         rng.integers(0, 1 << 32, 200_000, dtype=np.uint64).astype(np.uint32).view(np.float32)])
-    x = x.astype(np.float32)
     ok = ~np.isnan(x)
     t = torch.from_numpy(x)
     np.testing.assert_array_equal(orc.quantize16(x, "bf16")[ok],
