@@ -21,11 +21,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 METRIC = "sketch+estimate+top-k throughput, Gcoords/s and % HBM peak at d=100M, r=5"
-# HBM bytes per launch of the dominant kernel at config 4 (average over the 12 launches of a
-# step), measured with rocprofv3 --pmc: FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the factors
-# being what the same counters read for a plain 1 GiB copy.
+# HBM bytes per launch of the dominant kernel at config 4 (4 launches per step, one per group
+# of 8 workers), measured with rocprofv3 --pmc: FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
+# factors being what the same counters read for a plain 1 GiB copy.
 # Source: profiles/accumulate_visits_cfg4_pmc.md.  None for other configs.
-MEASURED_TRAFFIC_BYTES = {4: 5.91e9}
+MEASURED_TRAFFIC_BYTES = {4: 1.737e10}
 
 
 def cpu_baseline(cfg, work, sample_acc=64_000_000, sample_est=32_000_000):
