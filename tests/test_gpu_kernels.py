@@ -219,6 +219,30 @@ def test_accumulate_bundle_every_traversal(W):
         assert_cells_close(tab, refs[w], what=f"longer than planned, worker {w}", terms_per_cell=d / c)
 
 
+def test_accumulate_bundle_nan_and_inf_stay_in_their_cells():
+    """Device data are not validated: a NaN or an infinity in a vector must end up in exactly the
+    r cells of its coordinate (as in the reference), not in neighbouring running sums."""
+    r, c, seed, d, W = 5, 1 << 12, 11, 200_003, 8
+    p = cs.cs_params_init(r, c, seed, d)
+    assert all(p.visit[j].K > 0 for j in range(r))
+    sk = orc.SketchOracle(r, c, seed)
+    rng = np.random.default_rng(4)
+    gs = [(rng.standard_normal(d) * 0.01).astype(np.float32) for _ in range(W)]
+    gs[2][[7, 100_000]] = [np.nan, np.inf]
+    gs[5][[150_000, 150_001, 199_999]] = [-np.inf, np.inf, np.nan]
+    for w, tab in enumerate(_bundle_tables(p, gs, r, c)):
+        with np.errstate(invalid="ignore"):
+            ref = sk.sketch(gs[w])
+        assert (np.isnan(tab) == np.isnan(ref)).all(), f"worker {w}: NaN cells differ"
+        assert (np.isinf(tab) == np.isinf(ref)).all() and (np.sign(tab[np.isinf(ref)]) == np.sign(ref[np.isinf(ref)])).all()
+        fin = np.isfinite(ref)
+        assert fin.sum() >= r * c - 3 * r
+        good_rows = np.where(fin, ref, 0.0)
+        err = np.abs(np.where(fin, tab, 0.0) - good_rows)
+        sigma = np.sqrt((good_rows ** 2).mean(axis=1, keepdims=True))
+        assert (err <= 1e-5 * np.maximum(np.abs(good_rows), sigma)).all()
+
+
 @pytest.mark.parametrize("r,c,seed", SHAPES[:5])
 def test_accumulate_sparse_with_repeats(r, c, seed):
     p = cs.cs_params_init(r, c, seed)
