@@ -79,7 +79,7 @@ __global__ void __launch_bounds__(kBlock) k_topk_clear(TopkWs* ws, uint64_t k) {
 
 // PASS 0: bin = key >> 20 (2048 bins); PASS 1: entries with key >> 20 == prefix, bin = bits
 // 19..10; PASS 2: entries with key >> 10 == prefix, bin = bits 9..0.
-template <int PASS, typename KEY>
+template <int PASS, bool VEC, typename KEY>
 __global__ void __launch_bounds__(kBlock)
 k_topk_hist(const float* __restrict__ est, int64_t d, TopkWs* ws, KEY kf) {
     kf.init();
@@ -88,9 +88,7 @@ k_topk_hist(const float* __restrict__ est, int64_t d, TopkWs* ws, KEY kf) {
     for (int t = threadIdx.x; t < nb; t += kBlock) lh[t] = 0;
     __syncthreads();
     const uint32_t prefix = ws->sel.prefix;
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
-    for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < d; t += stride) {
-        const uint32_t key = kf(est[t], t);
+    auto tally = [&](uint32_t key) {
         if (PASS == 0) {
             atomicAdd(&lh[key >> 20], 1u);
         } else if (PASS == 1) {
@@ -98,7 +96,27 @@ k_topk_hist(const float* __restrict__ est, int64_t d, TopkWs* ws, KEY kf) {
         } else {
             if ((key >> 10) == prefix) atomicAdd(&lh[key & 1023u], 1u);
         }
+    };
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    int64_t done = 0;
+    if (VEC) {                                   // est is 16-byte aligned: four elements per load
+        const int64_t n4 = d / 4;
+        const float4* est4 = reinterpret_cast<const float4*>(est);
+        int64_t t = t0;
+        for (; t + stride < n4; t += 2 * stride) {   // two loads in flight
+            const float4 u = est4[t], w = est4[t + stride];
+            tally(kf(u.x, 4 * t)); tally(kf(u.y, 4 * t + 1)); tally(kf(u.z, 4 * t + 2)); tally(kf(u.w, 4 * t + 3));
+            const int64_t t2 = t + stride;
+            tally(kf(w.x, 4 * t2)); tally(kf(w.y, 4 * t2 + 1)); tally(kf(w.z, 4 * t2 + 2)); tally(kf(w.w, 4 * t2 + 3));
+        }
+        if (t < n4) {
+            const float4 u = est4[t];
+            tally(kf(u.x, 4 * t)); tally(kf(u.y, 4 * t + 1)); tally(kf(u.z, 4 * t + 2)); tally(kf(u.w, 4 * t + 3));
+        }
+        done = n4 * 4;
     }
+    for (int64_t t = done + t0; t < d; t += stride) tally(kf(est[t], t));
     __syncthreads();
     for (int t = threadIdx.x; t < nb; t += kBlock) {
         const uint32_t v = lh[t];
@@ -392,17 +410,26 @@ static int select_largest(const float* est, int64_t d, int64_t k, int64_t* idx_o
     TopkWs* ws = static_cast<TopkWs*>(workspace);
     const unsigned hgrid = static_cast<unsigned>(
         (d + kBlock * 16 - 1) / (kBlock * 16) < 2048 ? (d + kBlock * 16 - 1) / (kBlock * 16) : 2048);
+    const bool vec = reinterpret_cast<uintptr_t>(est) % 16 == 0;
     k_topk_clear<<<1, kBlock, 0, s>>>(ws, static_cast<uint64_t>(k));
-    k_topk_hist<0, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf);
-    k_topk_find<0><<<1, kBlock, 0, s>>>(ws);
-    k_topk_hist<1, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf);
-    k_topk_find<1><<<1, kBlock, 0, s>>>(ws);
-    k_topk_hist<2, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf);
-    k_topk_find<2><<<1, kBlock, 0, s>>>(ws);
+    if (vec) {
+        k_topk_hist<0, true, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf);
+        k_topk_find<0><<<1, kBlock, 0, s>>>(ws);
+        k_topk_hist<1, true, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf);
+        k_topk_find<1><<<1, kBlock, 0, s>>>(ws);
+        k_topk_hist<2, true, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf);
+        k_topk_find<2><<<1, kBlock, 0, s>>>(ws);
+    } else {
+        k_topk_hist<0, false, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf);
+        k_topk_find<0><<<1, kBlock, 0, s>>>(ws);
+        k_topk_hist<1, false, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf);
+        k_topk_find<1><<<1, kBlock, 0, s>>>(ws);
+        k_topk_hist<2, false, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf);
+        k_topk_find<2><<<1, kBlock, 0, s>>>(ws);
+    }
     int nblocks;
     int64_t chunk;
     topk_geometry(d, &nblocks, &chunk);
-    const bool vec = reinterpret_cast<uintptr_t>(est) % 16 == 0;
     if (vec) {
         k_topk_count<true, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, kf);
         k_topk_scan<<<1, kBlock, 0, s>>>(ws, nblocks);
