@@ -4,13 +4,13 @@
  * What the library computes (paper = "Communication-efficient Distributed SGD with
  * Sketching", arXiv 1903.04488):
  *   - Count Sketch update / estimate                      App. C, Alg. 4
- *   - merge of workers' sketches, S = (1/W) sum_i S^i     Sec. 3; Alg. 2 "Aggregate sketches";
- *                                                         Alg. 3 "Aggregate sketches"
- *   - recovery of the largest coordinates by querying     Sec. 5.2; Alg. 3 "Recover the top-Pk
- *     every coordinate and keeping the k largest          coordinates"
- *   - second round: exact values of the chosen            Sec. 4; Alg. 1 "second round of
- *     coordinates, summed over workers                    communication"; Alg. 3 "Query all workers"
- *   - momentum and error accumulation (Alg. 3 "Momentum", "Error accumulation", and the
+ *   - merge of workers' sketches, S = (1/W) sum_i S^i     Sec. 3; aggregation step of Alg. 2
+ *                                                         and Alg. 3
+ *   - recovery of the largest coordinates by querying     Sec. 5.2; recovery step of Alg. 3
+ *     every coordinate and keeping the k largest
+ *   - second round: exact values of the chosen            Sec. 4; Alg. 1 step 5; worker-query
+ *     coordinates, summed over workers                    step of Alg. 3
+ *   - momentum and error accumulation (Alg. 3's momentum and error-accumulation steps and its
  *     zeroing of u, v on updated coordinates) held as sketches, which is possible because
  *     the sketch is linear (Sec. 3).
  *
@@ -28,7 +28,7 @@
  *   - fp32 atomic adds make sketch cells depend on summation order in the last bits; every
  *     other output is a deterministic function of its inputs.
  *
- * Hash family (Alg. 4 "init sign hashes and bucket hashes"; the family itself is fixed by
+ * Hash family (Alg. 4 init draws r sign and r bucket hashes; the family itself is fixed by
  * the benchmark definition): with p = 2^61 - 1,
  *     h_j(i) = ((a_j  * i + b_j ) mod p) mod c                       bucket of row j
  *     s_j(i) = +1 if ((a'_j * i + b'_j) mod p) is even, -1 if odd     sign of row j
@@ -133,7 +133,7 @@ int cs_hash_debug_range(const cs_params* p, int64_t i0, int64_t n,
 /* S = 0.  S: device float[r][c]. */
 int cs_sketch_zero(const cs_params* p, float* S, void* stream);
 
-/* Alg. 4 update applied to a dense vector (Alg. 3 "Compute sketch S^i of v^i"):
+/* Alg. 4 update applied to a dense vector (the sketching step of Alg. 3):
  *     S[j][h_j(i0 + t)] += scale * s_j(i0 + t) * g[t]      for t in [0, d), j in [0, r)
  * S: device float[r][c], accumulated into (not cleared).  g: device float[d].
  * i0 = global index of g[0] (>= 0, i0 + d <= 2^61).  d >= 0 (0 is a no-op). */
@@ -156,10 +156,10 @@ int cs_sketch_accumulate_batch(const cs_params* p, float* const* S_w, const floa
  * cs_bundle_floats:      number of floats in a bundle of W workers.
  * cs_bundle_zero:        T = 0.
  * cs_sketch_accumulate_bundle:  S^w[j][h_j(i0+t)] += scale * s_j(i0+t) * g_w[w][t] for all
- *                        w < W, t < d, j < r (Alg. 3 "Compute sketch S^i" for every worker).
+ *                        w < W, t < d, j < r (the sketching step of Alg. 3, every worker).
  *                        g_w: HOST array of W device pointers to float[d].  W >= 1.
  * cs_bundle_merge:       dst[j][b] = beta * dst[j][b] + alpha * sum_{w<W} S^w[j][b]
- *                        (Alg. 3 "S_t = (1/W) sum_i S_t^i" with alpha = 1/W); dst: device
+ *                        (the aggregation step of Alg. 3 with alpha = 1/W); dst: device
  *                        float[r][c], not read when beta == 0; fp32 sum in a fixed order.
  * The bundle must be below 2^40 floats and 16-byte aligned. */
 #define CS_BUNDLE_GROUP 8
@@ -181,7 +181,7 @@ int cs_bundle_merge(const cs_params* p, float* dst, float beta, const float* T, 
 int cs_sketch_accumulate_sparse(const cs_params* p, float* S, const int64_t* idx,
                                 const float* val, int64_t n, float scale, void* stream);
 
-/* Mergeability (Sec. 3; Alg. 3 "S_t = (1/W) sum_i S_t^i"):
+/* Mergeability (Sec. 3; the aggregation step of Alg. 3, S_t = (1/W) sum_i S_t^i):
  *     dst = beta * dst + alpha * sum_{w<W} src[w]
  * dst: device float[r][c]; with beta == 0 it is not read.  src: HOST array of W device
  * pointers; dst may not alias any src[w] unless W == 1.  The sum over w is taken in
@@ -199,8 +199,8 @@ int cs_sketch_axpby(const cs_params* p, float* y, float a, const float* x, float
 int cs_sketch_momentum(const cs_params* p, float* S_u, float* S_v, const float* S_t,
                        float rho, void* stream);
 
-/* Alg. 4 estimate of every coordinate of a range (Sec. 5.2 "query the sketch for every
- * gradient coordinate"):
+/* Alg. 4 estimate of every coordinate of a range (Sec. 5.2: the implementation queries all d
+ * coordinates rather than running a heavy-hitter search):
  *     est[t] = median_{j<r} s_j(i0 + t) * S[j][h_j(i0 + t)]       t in [0, d)
  * S: device float[r][c]; est: device float[d].
  * rows_ws: device scratch of cs_estimate_workspace_bytes(p, d) bytes (may be NULL when that
@@ -214,7 +214,7 @@ int cs_sketch_estimate(const cs_params* p, const float* S, int64_t d, int64_t i0
 int cs_sketch_estimate_sparse(const cs_params* p, const float* S, const int64_t* idx,
                               int64_t n, float* out, void* stream);
 
-/* "...and then choose the largest elements" (Sec. 5.2): the k indices t in [0, d) with the
+/* Selection of the largest estimates (Sec. 5.2): the k indices t in [0, d) with the
  * largest |est[t]|; equal magnitudes are resolved towards the lower index; the result is in
  * ascending index order.  idx_out: device int64[k] (index t, NOT offset by any i0);
  * val_out: device float[k], val_out[n] = est[idx_out[n]] (may be NULL).
@@ -225,15 +225,15 @@ int cs_heavy_hitters_topk(const float* est, int64_t d, int64_t k,
                           int64_t* idx_out, float* val_out,
                           void* workspace, size_t ws_bytes, void* stream);
 
-/* Second round (Sec. 4; Alg. 3 "Query all workers for exact values ...; store the sum"):
+/* Second round (Sec. 4; the worker-query step of Alg. 3, which keeps the sum over workers):
  *     out[n] = alpha * sum_{w<W} vec[w][idx[n]]          (sum in ascending w, fp32)
  * vec: HOST array of W device pointers to float vectors; idx: device int64[k] with every
  * idx[n] inside the vectors; out: device float[k]. */
 int cs_gather_exact(const float* const* vec, int32_t W, const int64_t* idx, int64_t k,
                     float alpha, float* out, void* stream);
 
-/* Alg. 3 as the paper trains with it (Sec. 5.1: "we query the Count Sketch, and then each of
- * the workers, for the top Pk elements instead"): of n = Pk candidate coordinates cand[0..n)
+/* Alg. 3 as the paper trains with it (Sec. 5.1: sketch and workers are asked for P k
+ * coordinates, P > 1, and the k largest exact sums are applied): of n = Pk candidate coordinates cand[0..n)
  * (ascending, as cs_heavy_hitters_topk returns them) with exact second-round values x[0..n)
  * (cs_gather_exact), keep the k of largest |x| (equal magnitudes -> lower index), in ascending
  * index order:  idx_out[t] = cand[pos_t],  val_out[t] = x[pos_t].
@@ -243,8 +243,8 @@ int cs_select_exact_topk(const int64_t* cand, const float* x, int64_t n, int64_t
                          int64_t* idx_out, float* val_out, void* workspace, size_t ws_bytes,
                          void* stream);
 
-/* Sketches in 16 bits per cell (Sec. 6: "quantizing sketches to 16 bits ... leads to no drop in
- * accuracy"): what a worker would put on the wire.  Round to nearest, ties to even; NaN stays
+/* Sketches in 16 bits per cell (Sec. 6 reports that 16-bit sketch cells cost no accuracy in
+ * preliminary runs): what a worker would put on the wire.  Round to nearest, ties to even; NaN stays
  * NaN, overflow gives infinity.  fmt: CS_FMT_BF16 (upper half of the binary32 pattern: 8
  * exponent, 7 fraction bits -- keeps the range of sums of gradient elements) or CS_FMT_F16
  * (IEEE binary16).
@@ -261,7 +261,7 @@ int cs_bundle_merge16(const cs_params* p, float* dst, float beta, const uint16_t
 
 /* HEAVYMIX (Sec. 4, Alg. 1), the recovery the convergence proof is stated for.
  *
- * cs_sketch_l2sq -- Alg. 1 step 1, "query l2^2 from the sketch": by the AMS argument of
+ * cs_sketch_l2sq -- Alg. 1 step 1, the squared l2 norm read off the sketch: by the AMS argument of
  * App. C a row's sum of squared counters estimates ||g||^2; the median over the r rows is
  * taken.  out: device double[1 + r], 8-byte aligned: out[0] = the median, out[1 + j] =
  * sum_b S[j][b]^2 (binary64 sums in a fixed order).  S: device float[r][c].
@@ -286,11 +286,11 @@ int cs_heavymix_select(const float* est, int64_t d, int64_t k, const double* l2s
 
 /* Alg. 3 as printed, with dense state on every worker (the sketch-space form above keeps only
  * r x c numbers per state vector; this form keeps 2 d floats per worker and is exact).
- * cs_dense_momentum -- "Momentum" and "Error accumulation" for W workers:
+ * cs_dense_momentum -- the momentum and error-accumulation steps for W workers:
  *     u_w[t] = rho * u_w[t] + g_w[t]  (one fused multiply-add),   v_w[t] = v_w[t] + u_w[t].
  *   The sketch of v_w is then taken with cs_sketch_accumulate_bundle(v_w), and the second
  *   round reads v_w through cs_gather_exact.
- * cs_dense_mask -- "u, v <- 0 for all coordinates of the update":
+ * cs_dense_mask -- the last step of the loop body, zeroing on the coordinates of the update:
  *     u_w[idx[n]] = v_w[idx[n]] = 0   for every worker w and n < k.
  * u_w, v_w, g_w: HOST arrays of W device pointers to float[d]; u_w, v_w updated in place.
  * idx: device int64[k], each in [0, d).  W >= 1, d >= 0, k >= 0. */
@@ -299,8 +299,8 @@ int cs_dense_momentum(float* const* u_w, float* const* v_w, const float* const* 
 int cs_dense_mask(float* const* u_w, float* const* v_w, int32_t W, const int64_t* idx,
                   int64_t k, void* stream);
 
-/* Error feedback / momentum masking in sketch space (Alg. 2 "Error accumulation",
- * Alg. 3 "u, v <- 0 for all updated coordinates", as far as a sketch can express them):
+/* Error feedback / momentum masking in sketch space (the error-accumulation step
+ * of Alg. 2 and the zeroing of u, v in Alg. 3, as far as a sketch can express them):
  *     val[n] = estimate(S, idx[n])   for all n, from the table as it is on entry, then
  *     S     -= sketch of the k-sparse vector (idx, val)
  * S: device float[r][c]; idx: device int64[k], distinct; val: device float[k] (output). */

@@ -9,8 +9,8 @@
  * paper by eye: one loop nest per operation, in the order the algorithm states,
  * no blocking, no incremental tricks.
  *
- * Hash family (fixed by the benchmark definition, since Alg. 4 "init" only says
- * "init sign hashes and bucket hashes"):
+ * Hash family (fixed by the benchmark definition, since the init of Alg. 4 names
+ * no family for its sign and bucket hashes):
  *     p      = 2^61 - 1
  *     h_j(i) = ((a_j  * i + b_j ) mod p) mod c          bucket, 0-based
  *     s_j(i) = +1 if ((a'_j * i + b'_j) mod p) is even, else -1
@@ -154,7 +154,7 @@ static double estimate_one(int r, uint32_t c,
     return median_odd(v, r);
 }
 
-/* "query the sketch for every gradient coordinate" (Sec. 5.2): est[t] for i = i0 + t. */
+/* The query of every coordinate (Sec. 5.2): est[t] for i = i0 + t. */
 void cso_estimate(int r, uint32_t c,
                   const uint64_t *a, const uint64_t *b,
                   const uint64_t *as, const uint64_t *bs,

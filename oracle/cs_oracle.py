@@ -8,7 +8,7 @@ hot path of Sketched-SGD computes, step by step, in the paper's order and notati
     Alg. 3 (Sec. 5.1) worker sketches -> (1/W) sum -> recover top-k -> second round of
                       exact values; momentum u <- m u + g and error accumulation v <- v + u,
                       here held as their sketches (linear images), see SketchSpaceState
-    Sec. 5.2          "query every coordinate, then choose the largest"
+    Sec. 5.2          every coordinate is queried and the largest estimates are chosen
     Alg. 1 (Sec. 4)   HEAVYMIX: l2 estimate from the sketch, threshold split, random fill
 
 Only tests, the smoke check and the benchmark's cpu_baseline leg may import this module.
@@ -20,7 +20,8 @@ Every function here is pinned by tests/test_oracle_pins.py to something other th
 itself (dense-matrix product on tiny inputs, linearity, closed-form row variance, AMS
 special case, planted-sparse recovery, numpy's stable argsort, a dense-state twin of the
 sketch-space state; for HEAVYMIX: the exact norm of sparse vectors, the paper's (1 +- 0.5)
-band, a brute-force split, the uniformity of the fill and the k/d contraction of Lemma 1).  Nothing in this file is "parity unpinned"; the one free choice
+band, a brute-force split, the uniformity of the fill and the k/d contraction of Lemma 1).
+Nothing in this file is "parity unpinned"; the one free choice
 (the value fed back in sketch space, SketchSpaceState.feedback) is a documented reading,
 pinned internally by the dense-state twin.
 """
@@ -182,8 +183,8 @@ def merge(tables, alpha: float = 1.0, beta: float = 0.0, dst=None) -> np.ndarray
 
 
 def topk(est, k: int) -> np.ndarray:
-    """Indices of the k entries of largest magnitude (Sec. 4: "largest gradient elements by
-    magnitude"; Sec. 5.2), equal magnitudes resolved towards the lower index, returned in
+    """Indices of the k entries of largest magnitude (Sec. 4 selects gradient elements
+    by magnitude; Sec. 5.2), equal magnitudes resolved towards the lower index, returned in
     ascending index order.  Written as the definition: stable sort by descending |est|."""
     mag = np.abs(np.asarray(est, dtype=np.float64))
     order = np.argsort(-mag, kind="stable")
@@ -202,8 +203,8 @@ def topk_threshold(est, k: int) -> np.ndarray:
 
 
 def gather_exact(vecs, idx, alpha: float = 1.0) -> np.ndarray:
-    """Second round (Alg. 1 step 5, Alg. 3 "query all workers for exact values ... store the
-    sum"): alpha * sum_w vecs[w][idx]."""
+    """Second round (Alg. 1 step 5, the worker-query step of Alg. 3, which keeps
+    the sum): alpha * sum_w vecs[w][idx]."""
     idx = np.asarray(idx, dtype=np.int64)
     acc = np.zeros(idx.size, dtype=np.float64)
     for v in vecs:
@@ -224,7 +225,7 @@ def select_exact_topk(cand, x, k: int):
 # HEAVYMIX (Alg. 1): threshold split and random fill
 # ---------------------------------------------------------------------------
 def l2sq_estimate(T):
-    """Alg. 1 step 1 ("query l2^2 from the sketch"), by the AMS argument of App. C: a row's
+    """Alg. 1 step 1 (the squared l2 norm read off the sketch), by the AMS argument of App. C: a row's
     counters are signed sums over disjoint sets of coordinates, so the sum of their squares
     has expectation ||g||^2; the median over the r rows controls the failure probability.
     Returns (median over rows, the r row sums)."""
@@ -272,7 +273,7 @@ def heavymix_select(est, k: int, l2sq: float, rng_seed: int):
 
 
 # ---------------------------------------------------------------------------
-# 16-bit sketches (Sec. 6: "quantizing sketches to 16 bits")
+# 16-bit sketches (Sec. 6 remarks that sketch cells can be quantised to 16 bits)
 # ---------------------------------------------------------------------------
 def quantize16(x, fmt: str) -> np.ndarray:
     """binary32 -> 16-bit storage, round to nearest, ties to even; returns the uint16 patterns.
@@ -376,7 +377,7 @@ class SketchSpaceState:
         Delta = est[idx]      ; S_v <- S_v - S(Delta at idx)     (error feedback: what was
                                                                   applied leaves the residual)
         uhat = estimate(S_u, idx) ; S_u <- S_u - S(uhat at idx)  (momentum factor masking:
-                                                                  "u, v <- 0" on updated coords,
+                                                                  zero u, v on updated coords,
                                                                   as far as a sketch can say)
     rho is the fp32 value of the momentum constant, as the device receives it."""
 

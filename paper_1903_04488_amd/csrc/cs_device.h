@@ -1,7 +1,7 @@
 // Device-side arithmetic shared by the kernels: hashing modulo the Mersenne prime
 // p = 2^61 - 1 kept in registers, and a few wavefront helpers.  gfx950 only.
 //
-// Hash family (Alg. 4 "init sign hashes and bucket hashes" of the paper's App. C):
+// Hash family (the sign and bucket hashes that Alg. 4 of the paper's App. C initialises):
 //     h_j(i) = ((a_j * i + b_j) mod p) mod c,     s_j(i) = +1 / -1 by the parity of
 //     ((a'_j * i + b'_j) mod p).
 // A hash value x in [0, p) is carried as y = x + 1 in [1, p].  In that form "add a constant
@@ -82,7 +82,7 @@ __device__ __forceinline__ float apply_sign(float v, uint32_t flip) {
     return __uint_as_float(__float_as_uint(v) ^ flip);
 }
 
-// 16-bit storage of sketch cells (Sec. 6 of the paper: "quantizing sketches to 16 bits"):
+// 16-bit storage of sketch cells (Sec. 6 of the paper remarks that 16 bits per cell suffice):
 // round to nearest, ties to even.  FMT 0 = bfloat16 (upper half of the binary32 pattern),
 // FMT 1 = IEEE binary16 (the hardware conversion, whose default rounding is the same).
 template <int FMT>

@@ -295,7 +295,7 @@ k_dequantize16(const uint16_t* __restrict__ q, int64_t n, float* __restrict__ ou
         out[t] = from_16<FMT>(q[t]);
 }
 
-// Alg. 3 "Momentum" and "Error accumulation" with dense per-worker state:
+// The momentum and error-accumulation steps of Alg. 3 with dense per-worker state:
 // u = rho u + g (one fused multiply-add), v = v + u.  blockIdx.y = worker; 20 bytes of
 // traffic per coordinate, 16-byte accesses when the three vectors are 16-byte aligned.
 struct DensePtrs {
