@@ -100,6 +100,8 @@ typedef struct cs_visit_plan {
 } cs_visit_plan;
 
 #define CS_FLAG_NO_VISIT_LIST 1u   /* cs_params.flags: always use the stride walk (testing) */
+#define CS_FLAG_NO_LDS_TABLE 2u    /* cs_params.flags: tiny tables are updated in memory, not in a
+                                      workgroup-private LDS copy (testing) */
 
 typedef struct cs_params {
     uint32_t r;                 /* rows, odd, 1..CS_MAX_R */

@@ -29,6 +29,7 @@ class CsRowPlan(ctypes.Structure):
 
 CS_MAX_VISITS = 512
 CS_FLAG_NO_VISIT_LIST = 1
+CS_FLAG_NO_LDS_TABLE = 2
 
 
 class CsVisitPlan(ctypes.Structure):

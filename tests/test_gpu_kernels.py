@@ -7,6 +7,7 @@ import pytest
 import torch
 
 import paper_1903_04488_amd as cs
+from paper_1903_04488_amd import binding
 from oracle import cs_oracle as orc
 from parity_util import assert_cells_close, assert_values_close
 
@@ -129,11 +130,20 @@ def test_accumulate_batch(W):
 @pytest.mark.parametrize("W", [1, 2, 3, 5, 8, 13, 16, 32, 37])
 @pytest.mark.parametrize("r,c,seed,d,i0", [(5, 1 << 12, 11, 200_003, 17), (7, 1 << 15, 5, 1_000_003, 0),
                                            (3, 1000, 9, 50_001, 3), (5, 1 << 10, 2, 1000, 0),
-                                           (3, 64, 3, 2_000_003, 5)])      # d / c = 31 250: thinned lists
-def test_accumulate_bundle(W, r, c, seed, d, i0):
+                                           (3, 64, 3, 2_000_003, 5),       # d / c = 31 250: thinned lists
+                                           (15, 180_000, 4, 400_003, 1 << 40),    # a sketch shape of Table 1
+                                           (7, 40, 6, 100_003, 0), (7, 40, 6, 784, 0),   # App. E's sketch
+                                           (5, 100, 8, 300_001, 7), (1, 100, 8, 300_001, 7),
+                                           (3, 32, 5, 70_001, 0)])         # table in LDS
+@pytest.mark.parametrize("lds_table", [True, False])
+def test_accumulate_bundle(W, r, c, seed, d, i0, lds_table):
     if W > 8 and d > 500_000:
         pytest.skip("covered by the smaller shapes")
     p = cs.cs_params_init(r, c, seed, d)
+    if not lds_table:
+        if c > 128 or r * c > 2048:
+            pytest.skip("not a table that would get a workgroup-private copy anyway")
+        p.flags = binding.CS_FLAG_NO_LDS_TABLE
     sk = orc.SketchOracle(r, c, seed)
     rng = np.random.default_rng(W * 1000 + r)
     gs = [(rng.standard_normal(d) * 0.01).astype(np.float32) for _ in range(W)]
@@ -177,7 +187,6 @@ def test_accumulate_bundle_every_traversal(W):
     within its cells (every such visit takes the kernel's one-by-one fallback), and vectors
     shorter and longer than the length the list was built for: all against the reference."""
     import ctypes
-    from paper_1903_04488_amd import binding
     r, c, seed, d = 5, 1 << 12, 11, 200_003
     P = (1 << 61) - 1
     p = cs.cs_params_init(r, c, seed, d)
