@@ -699,15 +699,27 @@ namespace {
 
 constexpr int kQRun = 16;
 
+// A short vector leaves a row with few chunks (Dw / 1024 wavefronts) and a long serial chain
+// of visits each; the chain is then cut into segments that separate wavefronts walk
+// (blockIdx.z), at the price of one more gather per lane and segment.
+struct RowSegments {
+    int n[CS_MAX_R];
+};
+
 __global__ void __launch_bounds__(64)
-k_row_values_walk(KParams p, const float* __restrict__ S, int64_t d, int64_t i0,
+k_row_values_walk(KParams p, RowSegments segs, const float* __restrict__ S, int64_t d, int64_t i0,
                   float* __restrict__ rows) {
     constexpr int kStride = kQRun + 1;
     constexpr int kPieces = kQRun / 4, kRunsPerPass = 64 / kPieces, kPasses = kPieces;
     __shared__ float tile_lds[64 * kStride];
     const int lane = threadIdx.x;
     const int j = blockIdx.y;
+    const int nseg = segs.n[j];
+    if (static_cast<int>(blockIdx.z) >= nseg) return;
     const int64_t D = static_cast<int64_t>(p.plan[j].Dw);
+    const int64_t visits = (d + D - 1) / D;
+    const int64_t nD0 = visits * blockIdx.z / nseg * D;          // my segment of the chain
+    const int64_t nD1 = visits * (blockIdx.z + 1) / nseg * D;
     const uint64_t ADb = p.plan[j].ADw, ADs = p.plan[j].ADws;
     const uint64_t Ab = p.a[j], As = p.as[j];
     const int64_t chunks = (D + kQRun - 1) / kQRun;
@@ -724,14 +736,14 @@ k_row_values_walk(KParams p, const float* __restrict__ S, int64_t d, int64_t i0,
         if (wv >= nwaves) break;
         const int64_t chunk0 = wv * 64;
         const int64_t my_off = (chunk0 + lane) * kQRun;          // my residue offset in [0, Dw)
-        uint64_t yb = hash_state(p.a[j], p.b[j], static_cast<uint64_t>(i0 + my_off));
-        uint64_t ys = hash_state(p.as[j], p.bs[j], static_cast<uint64_t>(i0 + my_off));
+        uint64_t yb = hash_state(p.a[j], p.b[j], static_cast<uint64_t>(i0 + nD0 + my_off));
+        uint64_t ys = hash_state(p.as[j], p.bs[j], static_cast<uint64_t>(i0 + nD0 + my_off));
         uint32_t cur[kQRun];
         float val[kQRun];
 #pragma unroll
         for (int m = 0; m < kQRun; ++m) { cur[m] = 0xffffffffu; val[m] = 0.0f; }
 
-        for (int64_t nD = 0; nD + chunk0 * kQRun < d; nD += D) {
+        for (int64_t nD = nD0; nD < nD1 && nD + chunk0 * kQRun < d; nD += D) {
             int64_t my_len = D - my_off;                         // coordinates of mine that exist
             if (d - (nD + my_off) < my_len) my_len = d - (nD + my_off);
             uint64_t tb = yb, ts = ys;
@@ -788,8 +800,22 @@ int launch_row_values_walk(const cs_params* p, const float* S, int64_t d, int64_
     const int64_t cap = 256 * 64;
     int64_t gx = most < cap ? most : cap;
     gx = (gx + 7) / 8 * 8;
-    const dim3 grid(static_cast<unsigned>(gx), p->r);
-    k_row_values_walk<<<grid, 64, 0, stream>>>(kparams(p), S, d, i0, rows);
+    // about 2048 wavefronts per row, at least 4 visits per segment
+    RowSegments segs{};
+    int most_segs = 1;
+    for (uint32_t j = 0; j < p->r; ++j) {
+        const int64_t Dw = static_cast<int64_t>(p->plan[j].Dw);
+        const int64_t nwaves = ((Dw + kQRun - 1) / kQRun + 63) / 64;
+        const int64_t visits = (d + Dw - 1) / Dw;
+        int64_t n = 2048 / nwaves;
+        if (n > visits / 4) n = visits / 4;
+        if (n < 1) n = 1;
+        if (n > 1024) n = 1024;
+        segs.n[j] = static_cast<int>(n);
+        if (segs.n[j] > most_segs) most_segs = segs.n[j];
+    }
+    const dim3 grid(static_cast<unsigned>(gx), p->r, static_cast<unsigned>(most_segs));
+    k_row_values_walk<<<grid, 64, 0, stream>>>(kparams(p), segs, S, d, i0, rows);
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
 
