@@ -25,7 +25,7 @@ METRIC = "sketch+estimate+top-k throughput, Gcoords/s and % HBM peak at d=100M, 
 # of 8 workers), measured with rocprofv3 --pmc: FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
 # factors being what the same counters read for a plain 1 GiB copy.
 # Source: profiles/accumulate_visits_cfg4_pmc.md.  None for other configs.
-MEASURED_TRAFFIC_BYTES = {4: 1.737e10}
+MEASURED_TRAFFIC_BYTES = {4: 1.741e10}
 
 
 def cpu_baseline(cfg, work, sample_acc=64_000_000, sample_est=32_000_000):
@@ -205,6 +205,25 @@ def main():
                       + 4.0 * cfg.r * cfg.c + 4.0 * cfg.d                        # estimate
                       + 4.0 * cfg.d                                              # top-k
                       + 4.0 * cfg.k * cfg.W)                                     # gather
+    # the streaming-read ceiling of this machine, measured live with the library's plain read kernel:
+    # one worker vector read repeatedly, and one whole input set (what a row's pass of the
+    # update reads).  Outside the timed steps.
+    probe_out = torch.zeros(1, dtype=torch.float32, device=dev)
+
+    def read_rate(vecs, reps):
+        B.cs_probe_stream_read(vecs, probe_out)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            B.cs_probe_stream_read(vecs, probe_out)
+        e1.record()
+        torch.cuda.synchronize()
+        return 4.0 * cfg.d * len(vecs) * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    stream_one = read_rate(sets[0][:1], 8)
+    stream_set = read_rate(sets[0], 3)
+    traffic = MEASURED_TRAFFIC_BYTES.get(cfg.cfg)
+
     out = {
         "metric": METRIC,
         "value": value,
@@ -222,6 +241,9 @@ def main():
                    "W": cfg.W, "r": cfg.r, "c": cfg.c, "k": cfg.k, "rho": cfg.rho,
                    "input_sets_resident": n_sets},
         "pct_hbm_peak_whole_step": 100.0 * step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "pct_stream_read_whole_step": 100.0 * step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / stream_set,
+        "stream_read": {"one_vector_GBs": stream_one, "one_input_set_GBs": stream_set,
+                        "kernel": "cs_probe_stream_read (plain 16-byte loads)"},
         "stage_ms": stage_ms,
         "roofline": {
             "kernel": "k_accumulate_visits (all launches of cs_sketch_accumulate_bundle)",
@@ -230,7 +252,8 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.cfg),
+            "traffic": traffic,
+            "traffic_GBs": traffic / (acc_kernel_ms * 1e-3) / 1e9 if traffic else None,
             "avg_launch_ms": acc_kernel_ms,
             "launches_per_step": n_launch,
             "algorithmic_bytes_per_launch": alg_bytes,

@@ -30,6 +30,7 @@ from .binding import (  # noqa: F401
     CS_FMT_F16,
     cs_dense_momentum,
     cs_dense_mask,
+    cs_probe_stream_read,
     cs_heavymix_select,
     cs_sketch_accumulate,
     cs_sketch_accumulate_batch,

@@ -119,6 +119,8 @@ _SIGNATURES = {
     "cs_dense_momentum": [ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p),
                           ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32, ctypes.c_int64,
                           ctypes.c_float, ctypes.c_void_p],
+    "cs_probe_stream_read": [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32, ctypes.c_int64,
+                             ctypes.c_void_p, ctypes.c_void_p],
     "cs_dense_mask": [ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p),
                       ctypes.c_int32, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p],
     "cs_sketch_feedback": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_void_p,
@@ -416,6 +418,13 @@ def cs_dense_mask(u_w, v_w, idx):
     _check(load_library().cs_dense_mask(
         _ptr_array(u_w, torch.float32, "u_w", d), _ptr_array(v_w, torch.float32, "v_w", d), W,
         _dev(idx, torch.int64, "idx"), idx.numel(), _stream(idx)), "cs_dense_mask")
+
+
+def cs_probe_stream_read(x_w, out):
+    d = x_w[0].numel()
+    _check(load_library().cs_probe_stream_read(
+        _ptr_array(x_w, torch.float32, "x_w", d), len(x_w), d, _dev(out, torch.float32, "out", 1),
+        _stream(out)), "cs_probe_stream_read")
 
 
 def cs_sketch_feedback(p, S, idx, val):

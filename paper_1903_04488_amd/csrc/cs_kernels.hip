@@ -428,6 +428,51 @@ k_dense_momentum(DensePtrs ptrs, int64_t d, float rho) {
     }
 }
 
+// Measurement aid: a plain streaming read of the workers' vectors, the access that every
+// HBM-bound kernel here is compared with.  blockIdx.y = worker; 16-byte loads, two in flight
+// per thread, when the vectors are 16-byte aligned; the sum of everything read is added to
+// out[0] (one atomic per workgroup, a few thousand per launch) so that the loads cannot be
+// dropped.
+struct ProbePtrs {
+    const float* x[kMaxBatch];
+};
+
+template <bool VEC>
+__global__ void __launch_bounds__(kBlock)
+k_probe_stream_read(ProbePtrs ptrs, int64_t d, float* __restrict__ out) {
+    const float* __restrict__ x = ptrs.x[blockIdx.y];
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    float acc = 0.0f;
+    int64_t done = 0;
+    if (VEC) {
+        const float4* __restrict__ x4 = reinterpret_cast<const float4*>(x);
+        const int64_t n4 = d / 4;
+        int64_t t = t0;
+        for (; t + stride < n4; t += 2 * stride) {
+            const float4 p = x4[t], q = x4[t + stride];
+            acc += ((p.x + p.y) + (p.z + p.w)) + ((q.x + q.y) + (q.z + q.w));
+        }
+        if (t < n4) {
+            const float4 p = x4[t];
+            acc += (p.x + p.y) + (p.z + p.w);
+        }
+        done = n4 * 4;
+    }
+    for (int64_t t = done + t0; t < d; t += stride) acc += x[t];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+    __shared__ float part[kBlock / 64];
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float s = 0.0f;
+#pragma unroll
+        for (int q = 0; q < kBlock / 64; ++q) s += part[q];
+        atomic_add_noret(out, s);                       // one per workgroup
+    }
+}
+
 // Alg. 3 last step: u, v <- 0 on the coordinates of the update, for every worker
 __global__ void __launch_bounds__(kBlock)
 k_dense_mask(DensePtrs ptrs, const int64_t* __restrict__ idx, int64_t k) {
@@ -758,6 +803,29 @@ extern "C" int cs_dense_momentum(float* const* u_w, float* const* v_w, const flo
         const dim3 grid(grid_for(vec ? (d + 3) / 4 : d, kBlock, 2048), static_cast<unsigned>(nw));
         if (vec) k_dense_momentum<true><<<grid, kBlock, 0, as_stream(stream)>>>(ptrs, d, rho);
         else k_dense_momentum<false><<<grid, kBlock, 0, as_stream(stream)>>>(ptrs, d, rho);
+        if (launch_status() != CS_OK) return CS_EHIP;
+    }
+    return CS_OK;
+}
+
+extern "C" int cs_probe_stream_read(const float* const* x_w, int32_t W, int64_t d, float* out,
+                                    void* stream) {
+    if (!x_w || W < 1 || d < 0 || !out) return CS_EINVAL;
+    bool vec = true;
+    for (int w = 0; w < W; ++w) {
+        if (!x_w[w]) return CS_EINVAL;
+        vec = vec && reinterpret_cast<uintptr_t>(x_w[w]) % 16 == 0;
+    }
+    if (d == 0) return CS_OK;
+    for (int w0 = 0; w0 < W; w0 += kMaxBatch) {
+        const int nw = (W - w0 < kMaxBatch) ? (W - w0) : kMaxBatch;
+        ProbePtrs ptrs{};
+        for (int w = 0; w < nw; ++w) ptrs.x[w] = x_w[w0 + w];
+        // about 4096 workgroups per launch, shared out among the workers
+        const dim3 grid(grid_for(vec ? (d + 3) / 4 : d, kBlock * 2, (4096 + nw - 1) / nw),
+                        static_cast<unsigned>(nw));
+        if (vec) k_probe_stream_read<true><<<grid, kBlock, 0, as_stream(stream)>>>(ptrs, d, out);
+        else k_probe_stream_read<false><<<grid, kBlock, 0, as_stream(stream)>>>(ptrs, d, out);
         if (launch_status() != CS_OK) return CS_EHIP;
     }
     return CS_OK;

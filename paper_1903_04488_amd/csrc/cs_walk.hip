@@ -361,8 +361,17 @@ k_accumulate_visits(VisitRows rows, VisitWorkers a) {
     const uint64_t Aj = v.a, Asj = v.as;
     // loader role: floats lspan .. lspan + FPL - 1 of the wavefront's span, of every worker;
     // they belong to walker lspan / RUN and go to that walker's row of each worker
-    const int lspan = lane * FPL;
-    float* tile_dst = tile_lds + (lspan / RUN) * WL * kStride + lspan % RUN;
+    // With 8 workers and 8-byte pieces, two workers share a request instead: the lower 32 lanes
+    // take 16 bytes each of one worker's 512-byte span, the upper 32 lanes of the next worker's.
+    // Same bytes and the same time, but half the load instructions and half the address
+    // registers (16 VGPRs fewer).
+    constexpr bool PAIR = WL == 8 && FPL == 2;
+    constexpr int kLoads = PAIR ? WL / 2 : WL;         // load instructions per visit
+    constexpr int kPer = PAIR ? 2 * FPL : FPL;         // floats per lane and instruction
+    const int half = PAIR ? lane >> 5 : 0;
+    const int lspan = PAIR ? (lane & 31) * kPer : lane * FPL;
+    float* tile_dst = tile_lds + ((lspan / RUN) * WL + half) * kStride + lspan % RUN;
+    constexpr int kRowStep = PAIR ? 2 * kStride : kStride;   // tile rows between my loads
     // the list's three gaps and the cut last one, with their hash advances, in scalar registers
     const uint64_t g0 = v.gap[0], g1 = v.gap[1], g2 = v.gap[2], g3 = v.gap[3];
     const uint64_t A0 = v.A[0], A1 = v.A[1], A2 = v.A[2], A3 = v.A[3];
@@ -408,28 +417,34 @@ k_accumulate_visits(VisitRows rows, VisitWorkers a) {
         // to the visit and exist; when the whole span does, every piece is whole and needs no
         // check (one wavefront-uniform base per worker plus a fixed lane offset).  Otherwise
         // pieces are cut where the visit or the vector ends, and missing values count as 0.
-        float pre[WL][FPL];
+        float pre[kLoads][kPer];
+        // the vector that load instruction `w` of this lane reads
+        auto vector_of = [&](int w) -> gfloat_ptr {
+            if constexpr (PAIR) {
+                const float* lo = a.g[2 * w < nw ? 2 * w : 0];
+                const float* hi = a.g[2 * w + 1 < nw ? 2 * w + 1 : 0];
+                return (gfloat_ptr)(half ? hi : lo);
+            } else {
+                return (gfloat_ptr)a.g[w < nw ? w : 0];
+            }
+        };
         auto load_visit = [&](int64_t s, int64_t room) {
             if (room >= SPAN) {
 #pragma unroll
-                for (int w = 0; w < WL; ++w) {
-                    const gfloat_ptr base =
-                        (gfloat_ptr)a.g[w < nw ? w : 0] + (first_res + s);
-                    load_floats<FPL>(base + lspan, pre[w]);
-                }
+                for (int w = 0; w < kLoads; ++w)
+                    load_floats<kPer>(vector_of(w) + (first_res + s) + lspan, pre[w]);
             } else {
-                const int len = static_cast<int>(room) - lspan;    // of my piece: >= FPL whole, <= 0 none
+                const int len = static_cast<int>(room) - lspan;    // of my piece: >= kPer whole, <= 0 none
 #pragma unroll
-                for (int w = 0; w < WL; ++w) {
-                    const gfloat_ptr src =
-                        (gfloat_ptr)a.g[w < nw ? w : 0] + (first_res + s) + lspan;
+                for (int w = 0; w < kLoads; ++w) {
+                    const gfloat_ptr src = vector_of(w) + (first_res + s) + lspan;
 #pragma unroll
-                    for (int t = 0; t < FPL; ++t) pre[w][t] = 0.0f;
-                    if (len >= FPL) {
-                        load_floats<FPL>(src, pre[w]);
+                    for (int t = 0; t < kPer; ++t) pre[w][t] = 0.0f;
+                    if (len >= kPer) {
+                        load_floats<kPer>(src, pre[w]);
                     } else {
 #pragma unroll
-                        for (int t = 0; t < FPL; ++t)
+                        for (int t = 0; t < kPer; ++t)
                             if (t < len) pre[w][t] = src[t];
                     }
                 }
@@ -450,9 +465,9 @@ k_accumulate_visits(VisitRows rows, VisitWorkers a) {
             bool bad = false;
             if (active) {
 #pragma unroll
-                for (int w = 0; w < WL; ++w)
+                for (int w = 0; w < kLoads; ++w)
 #pragma unroll
-                    for (int t = 0; t < FPL; ++t) tile_dst[w * kStride + t] = pre[w][t];
+                    for (int t = 0; t < kPer; ++t) tile_dst[w * kRowStep + t] = pre[w][t];
                 uint64_t tb = yb, ts = ys;
 #pragma unroll
                 for (int q = 0; q < PPL; ++q) {

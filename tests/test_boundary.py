@@ -145,6 +145,7 @@ def test_invalid_arguments_are_rejected_without_a_gpu(lib):
     assert lib.cs_bundle_merge16(ctypes.byref(p), fake, 0.0, ctypes.c_void_p(264), 8, 1.0, 0, null) == -1
     assert lib.cs_dense_momentum(None, None, None, 1, 10, 0.9, null) == -1
     assert lib.cs_dense_mask(None, None, 1, fake, 10, null) == -1
+    assert lib.cs_probe_stream_read(None, 1, 10, fake, null) == -1
     assert lib.cs_sketch_l2sq(ctypes.byref(p), fake, null, null) == -1
     assert lib.cs_sketch_l2sq(ctypes.byref(p), fake, ctypes.c_void_p(260), null) == -1    # misaligned
     assert lib.cs_heavymix_select(fake, 10, 5, null, 1, fake, null, null, fake, 1 << 20, null) == -1

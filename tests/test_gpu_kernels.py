@@ -527,3 +527,14 @@ def test_quantize16_bit_exact_and_merge(fmt, name):
     cs.cs_bundle_merge16(p, dst, T16, W, fmt, alpha=1.0 / W, beta=0.0)
     err = np.abs(dst.cpu().numpy() - exact).max() / np.abs(exact).max()
     assert err < (2.0 ** -8 if fmt == 0 else 2.0 ** -11)
+
+
+@pytest.mark.parametrize("W,d,offset", [(1, 1, 0), (3, 1_000_003, 0), (2, 4096, 1), (40, 70_001, 0)])
+def test_probe_stream_read_adds_up_everything_it_reads(W, d, offset):
+    """The measurement aid reads every element exactly once: its sum equals the exact sum."""
+    rng = np.random.default_rng(d)
+    xs = [rng.integers(-8, 9, size=d + offset).astype(np.float32) for _ in range(W)]   # exact in fp32
+    vecs = [dev(x)[offset:] for x in xs]                  # offset 1: not 16-byte aligned
+    out = torch.full((1,), 3.0, dtype=torch.float32, device=DEV)
+    cs.cs_probe_stream_read(vecs, out)
+    assert out.item() == 3.0 + sum(float(x[offset:].astype(np.float64).sum()) for x in xs)
