@@ -1,7 +1,8 @@
 // Microbenchmarks of the MI355X memory system that the kernel design rests on (standalone
 // program, not part of libcsketch.so): rate of fp32 / integer global atomics by access pattern,
 // table size and number of active XCDs; random and contiguous gathers; streaming read bandwidth
-// by buffer size; lane-strided streaming; LDS atomics.  Every access is in bounds by
+// by buffer size; the reads of the bundle update without its processing; lane-strided
+// streaming; LDS atomics.  Every access is in bounds by
 // construction (indices are masked with the table size).
 //
 //   hipcc -O3 --offload-arch=gfx950 -munsafe-fp-atomics -o cs_microbench cs_microbench.hip
@@ -105,6 +106,76 @@ __global__ void __launch_bounds__(256) k_lds(int iters, float* sink) {
     if (lds[threadIdx.x] == 0x12345678u) sink[0] = 1.f;
 }
 
+// ---- reads in the order and piece size of the bundle update, without its processing ----------
+// Eight vectors; a wavefront owns 128 residues and visits base + k G for k = 0 .. K-1 (G = the
+// gap of a visit list), reading 512 bytes of every vector per visit, the next visit requested
+// before the current one is consumed.  MODE 0: 8 bytes per lane and vector (8 loads); MODE 1:
+// 16 bytes per lane, two vectors per load (4 loads).  k_plain8 is the plain read of the same
+// vectors (blockIdx.y = vector).  All addresses are below d by the `ok` test.
+typedef float vec2f __attribute__((ext_vector_type(2)));
+typedef float vec4f __attribute__((ext_vector_type(4)));
+typedef vec2f __attribute__((aligned(4))) vec2f_u;
+typedef vec4f __attribute__((aligned(4))) vec4f_u;
+struct Vectors8 { const float* g[8]; };
+
+__global__ void __launch_bounds__(256) k_plain8(Vectors8 p, int64_t d, float* sink) {
+    const float4* x4 = (const float4*)p.g[blockIdx.y];
+    const int64_t n4 = d / 4, stride = (int64_t)gridDim.x * 256;
+    float acc = 0.f;
+    int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    for (; t + stride < n4; t += 2 * stride) {
+        float4 a = x4[t], b = x4[t + stride];
+        acc += a.x + a.y + a.z + a.w + b.x + b.y + b.z + b.w;
+    }
+    if (t < n4) { float4 a = x4[t]; acc += a.x + a.y + a.z + a.w; }
+    if (acc == 12345.678f) sink[0] = acc;
+}
+
+// DEAL 1: workgroups are dealt to the XCDs (blockIdx.x mod 8) in blocks of 4 neighbours, as the
+// update does, so that most of the lines that two neighbouring pieces share are fetched by one L2.
+template <int MODE, int NWAVE, int DEAL>
+__global__ void __launch_bounds__(64 * NWAVE) k_visit_reads(Vectors8 p, int64_t d, int64_t G, int K, float* sink) {
+    const int lane = threadIdx.x & 63;
+    int64_t set = blockIdx.x;
+    if (DEAL) {
+        const int64_t slot = set >> 3;
+        set = ((slot / 4) * 8 + (set & 7)) * 4 + slot % 4;
+    }
+    const int64_t base = (set * NWAVE + (threadIdx.x >> 6)) * 128;
+    if (base >= G) return;
+    float acc = 0.f, pre[16];
+    auto load = [&](int64_t pos) {
+        if (MODE == 0) {
+#pragma unroll
+            for (int w = 0; w < 8; ++w) {
+                vec2f u = *(const vec2f_u*)(p.g[w] + pos + lane * 2);
+                pre[2 * w] = u.x; pre[2 * w + 1] = u.y;
+            }
+        } else {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float* src = (lane >> 5) ? p.g[2 * w + 1] : p.g[2 * w];
+                vec4f u = *(const vec4f_u*)(src + pos + (lane & 31) * 4);
+                pre[4 * w] = u.x; pre[4 * w + 1] = u.y; pre[4 * w + 2] = u.z; pre[4 * w + 3] = u.w;
+            }
+        }
+    };
+    int64_t pos = base;
+    bool ok = pos + 128 <= d;
+    if (ok) load(pos);
+    for (int k = 0; k < K; ++k) {
+        float cur[16];
+#pragma unroll
+        for (int t = 0; t < 16; ++t) cur[t] = ok ? pre[t] : 0.f;
+        pos += G;
+        ok = (k + 1 < K) && pos + 128 <= d;
+        if (ok) load(pos);
+#pragma unroll
+        for (int t = 0; t < 16; ++t) acc += cur[t];
+    }
+    if (acc == 12345.678f) sink[0] = acc;
+}
+
 template <typename F>
 float time_ms(F f, int reps = 3) {
     hipEvent_t a, b; CK(hipEventCreate(&a)); CK(hipEventCreate(&b));
@@ -151,6 +222,30 @@ int main() {
         printf("read %6zu MB x%d : %8.3f ms  %7.2f TB/s\n", mb, passes, ms, (double)bytes * passes / ms / 1e9);
         CK(hipFree(buf));
         fflush(stdout);
+    }
+    // reads of the bundle update without its processing: 8 vectors of 10^8 floats
+    {
+        const int64_t d = 100000000;
+        Vectors8 v8;
+        for (int w = 0; w < 8; ++w) { float* x; CK(hipMalloc(&x, d * 4)); CK(hipMemset(x, 0, d * 4)); v8.g[w] = x; }
+        const double bytes = 8.0 * d * 4;
+        float t = time_ms([&] { k_plain8<<<dim3(512, 8), 256>>>(v8, d, sink); }, 5);
+        printf("8 vectors plain read               : %8.3f ms  %7.2f TB/s\n", t, bytes / t / 1e9);
+        for (int64_t G : {456789ll, 456704ll, 594161ll, 877855ll, 1324789ll}) {
+            const int K = (int)((d + G - 1) / G);
+            const unsigned nwaves = (unsigned)((G + 127) / 128);
+            const unsigned wg2 = ((nwaves + 1) / 2 + 31) / 32 * 32, wg4 = ((nwaves + 3) / 4 + 31) / 32 * 32;
+            t = time_ms([&] { k_visit_reads<0, 2, 0><<<wg2, 128>>>(v8, d, G, K, sink); }, 5);
+            printf("visits G=%7lld K=%3d 8 B/lane                 : %8.3f ms  %7.2f TB/s\n", (long long)G, K, t, bytes / t / 1e9);
+            t = time_ms([&] { k_visit_reads<1, 2, 0><<<wg2, 128>>>(v8, d, G, K, sink); }, 5);
+            printf("visits G=%7lld K=%3d 16 B/lane                : %8.3f ms  %7.2f TB/s\n", (long long)G, K, t, bytes / t / 1e9);
+            t = time_ms([&] { k_visit_reads<1, 2, 1><<<wg2, 128>>>(v8, d, G, K, sink); }, 5);
+            printf("visits G=%7lld K=%3d 16 B/lane, dealt in fours: %8.3f ms  %7.2f TB/s\n", (long long)G, K, t, bytes / t / 1e9);
+            t = time_ms([&] { k_visit_reads<1, 4, 0><<<wg4, 256>>>(v8, d, G, K, sink); }, 5);
+            printf("visits G=%7lld K=%3d 16 B/lane, 4 wavefronts  : %8.3f ms  %7.2f TB/s\n", (long long)G, K, t, bytes / t / 1e9);
+            fflush(stdout);
+        }
+        for (int w = 0; w < 8; ++w) CK(hipFree((void*)v8.g[w]));
     }
     // lane-strided streaming: 64 lane-blocks of D floats each; all waves together cover them once
     {
