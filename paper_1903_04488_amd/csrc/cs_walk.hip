@@ -462,12 +462,26 @@ k_accumulate_visits(VisitRows rows, VisitWorkers a) {
         if (active) load_visit(0, room_of(0, static_cast<int64_t>(pick(code, g0, g1, g2, g3))));
         for (uint32_t k = 0; k < v.K; ++k) {
             // visit k: its values are on their way (requested one turn earlier)
-            bool bad = false;
-            if (active) {
+            const bool was_active = active;
+            if (was_active) {
 #pragma unroll
                 for (int w = 0; w < kLoads; ++w)
 #pragma unroll
                     for (int t = 0; t < kPer; ++t) tile_dst[w * kRowStep + t] = pre[w][t];
+            }
+            // request visit k + 1 as soon as the registers of visit k are free, to fly while
+            // visit k is hashed and added up
+            const uint32_t code_k = code;
+            s += static_cast<int64_t>(pick(code_k, g0, g1, g2, g3));
+            active = false;
+            if (k + 1 < v.K) {
+                code = code_of(k + 1);
+                const int64_t room = room_of(s, static_cast<int64_t>(pick(code, g0, g1, g2, g3)));
+                active = room > 0;
+                if (active) load_visit(s, room);
+            }
+            bool bad = false;
+            if (was_active) {
                 uint64_t tb = yb, ts = ys;
 #pragma unroll
                 for (int q = 0; q < PPL; ++q) {
@@ -492,7 +506,7 @@ k_accumulate_visits(VisitRows rows, VisitWorkers a) {
             // cs_params_init; the check is kept so that a wrong list costs time, never
             // correctness: such a visit's values go to memory one by one, and the tile is
             // cleared so that the sums below take nothing from it.
-            const bool stray = active && __builtin_amdgcn_ballot_w64(bad) != 0;
+            const bool stray = was_active && __builtin_amdgcn_ballot_w64(bad) != 0;
             if (stray) {
                 uint64_t tb = yb, ts = ys;
 #pragma unroll
@@ -504,19 +518,8 @@ k_accumulate_visits(VisitRows rows, VisitWorkers a) {
                     }
                 }
             }
-            const int64_t gap = static_cast<int64_t>(pick(code, g0, g1, g2, g3));
-            yb = hash_advance(yb, pick(code, A0, A1, A2, A3));
-            ys = hash_advance(ys, pick(code, B0, B1, B2, B3));
-            // request visit k + 1, to fly while visit k is added up
-            const bool was_active = active;
-            s += gap;
-            active = false;
-            if (k + 1 < v.K) {
-                code = code_of(k + 1);
-                const int64_t room = room_of(s, static_cast<int64_t>(pick(code, g0, g1, g2, g3)));
-                active = room > 0;
-                if (active) load_visit(s, room);
-            }
+            yb = hash_advance(yb, pick(code_k, A0, A1, A2, A3));
+            ys = hash_advance(ys, pick(code_k, B0, B1, B2, B3));
             __builtin_amdgcn_wave_barrier();
             if (stray) {
                 const uint32_t* raw = raw_lds + h * RUN;
