@@ -601,7 +601,8 @@ int launch_visits(const cs_params* p, const VisitWorkers& a, const uint32_t* js,
     }
     const int64_t cap = 256 * 64 / NWAVE;
     int64_t gx = most < cap ? most : cap;
-    gx = (gx + 7) / 8 * 8;                   // the kernel deals workgroups to XCDs in eights
+    gx = (gx + 31) / 32 * 32;                // the kernel deals sets to the 8 XCDs in blocks of 4:
+                                             // whole blocks, so that no workgroup takes a second set
     const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(nrows)), block(64 * NWAVE);
     switch (ncell) {
         case 2: k_accumulate_visits<WL, RUN, NWAVE, 2><<<grid, block, 0, stream>>>(rows, a); break;
