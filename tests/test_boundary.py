@@ -165,3 +165,34 @@ def test_binding_refuses_cpu_tensors(lib):
     p = cs.cs_params_init(5, 16, 1)
     with pytest.raises(cs.CsError):
         cs.cs_sketch_zero(p, torch.zeros(5, 16))
+
+
+def test_binding_structs_have_the_layout_of_the_header(tmp_path):
+    """The ctypes mirrors of cs_params and its members have the sizes and field offsets that a C
+    compiler gives the declarations in include/csketch.h."""
+    import subprocess
+    fields = {"cs_row_plan": ["D", "AD", "ADs", "Dw", "ADw", "ADws", "lanes", "scan_steps"],
+              "cs_visit_plan": ["K", "ncell", "cover", "gmax", "cost", "cost_walk", "gap", "A", "As", "code"],
+              "cs_params": ["r", "c", "c_pow2", "flags", "seed", "a", "b", "as", "bs", "plan", "visit"]}
+    mirror = {"cs_row_plan": binding.CsRowPlan, "cs_visit_plan": binding.CsVisitPlan,
+              "cs_params": binding.CsParams}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "csketch.h"', 'int main(void) {']
+    for s, fs in fields.items():
+        lines.append(f'printf("{s} %zu\\n", sizeof({s}));')
+        for f in fs:
+            lines.append(f'printf("{s}.{f} %zu\\n", offsetof({s}, {f}));')
+    lines += ['printf("CS_MAX_R %d\\nCS_MAX_VISITS %d\\nCS_BUNDLE_GROUP %d\\n", CS_MAX_R, CS_MAX_VISITS, CS_BUNDLE_GROUP);',
+              'return 0; }']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), "-o", str(exe), str(src)])
+    got = dict(line.split() for line in subprocess.check_output([str(exe)], text=True).splitlines())
+    for s, fs in fields.items():
+        assert int(got[s]) == ctypes.sizeof(mirror[s]), s
+        for f in fs:
+            name = "as_" if f == "as" else f          # `as` is a Python keyword
+            assert int(got[f"{s}.{f}"]) == getattr(mirror[s], name).offset, f"{s}.{f}"
+    assert int(got["CS_MAX_R"]) == binding.CS_MAX_R
+    assert int(got["CS_MAX_VISITS"]) == binding.CS_MAX_VISITS
+    assert int(got["CS_BUNDLE_GROUP"]) == binding.CS_BUNDLE_GROUP
