@@ -231,7 +231,7 @@ int main() {
         const double bytes = 8.0 * d * 4;
         float t = time_ms([&] { k_plain8<<<dim3(512, 8), 256>>>(v8, d, sink); }, 5);
         printf("8 vectors plain read               : %8.3f ms  %7.2f TB/s\n", t, bytes / t / 1e9);
-        for (int64_t G : {456789ll, 456704ll, 594161ll, 877855ll, 1324789ll}) {
+        for (int64_t G : {456789ll, 456788ll, 456792ll, 456800ll, 456704ll, 594161ll, 594160ll, 594176ll, 877855ll, 1324789ll}) {
             const int K = (int)((d + G - 1) / G);
             const unsigned nwaves = (unsigned)((G + 127) / 128);
             const unsigned wg2 = ((nwaves + 1) / 2 + 31) / 32 * 32, wg4 = ((nwaves + 3) / 4 + 31) / 32 * 32;
