@@ -134,7 +134,8 @@ def test_accumulate_batch(W):
                                            (15, 180_000, 4, 400_003, 1 << 40),    # a sketch shape of Table 1
                                            (7, 40, 6, 100_003, 0), (7, 40, 6, 784, 0),   # App. E's sketch
                                            (5, 100, 8, 300_001, 7), (1, 100, 8, 300_001, 7),
-                                           (3, 32, 5, 70_001, 0)])         # table in LDS
+                                           (3, 32, 5, 70_001, 0),          # table in LDS
+                                           (15, 127, 2, 50_001, 9)])       # the largest LDS table (61 KB)
 @pytest.mark.parametrize("lds_table", [True, False])
 def test_accumulate_bundle(W, r, c, seed, d, i0, lds_table):
     if W > 8 and d > 500_000:
