@@ -229,6 +229,24 @@ def test_accumulate_bundle_every_traversal(W):
         assert_cells_close(tab, refs[w], what=f"longer than planned, worker {w}", terms_per_cell=d / c)
 
 
+def test_accumulate_bundle_vectors_at_any_dword_address():
+    """Worker vectors need only 4-byte alignment (views into larger tensors)."""
+    r, c, seed, d = 5, 1 << 12, 21, 300_001
+    p = cs.cs_params_init(r, c, seed, d)
+    assert any(p.visit[j].K > 0 for j in range(r))
+    sk = orc.SketchOracle(r, c, seed)
+    rng = np.random.default_rng(5)
+    big = [(rng.standard_normal(d + 3) * 0.01).astype(np.float32) for _ in range(3)]
+    views = [dev(x)[off:off + d] for off, x in zip((1, 2, 3), big)]
+    assert all(v.data_ptr() % 16 != 0 for v in views)
+    T = torch.zeros(cs.cs_bundle_floats(p, 3), dtype=torch.float32, device=DEV)
+    cs.cs_sketch_accumulate_bundle(p, T, views)
+    Th = T.cpu().numpy().reshape(-1, r, c, cs.CS_BUNDLE_GROUP)
+    for w, (off, x) in enumerate(zip((1, 2, 3), big)):
+        assert_cells_close(Th[0, :, :, w], sk.sketch(x[off:off + d]), what=f"worker {w}",
+                           terms_per_cell=d / c)
+
+
 def test_accumulate_bundle_nan_and_inf_stay_in_their_cells():
     """Device data are not validated: a NaN or an infinity in a vector must end up in exactly the
     r cells of its coordinate (as in the reference), not in neighbouring running sums."""
