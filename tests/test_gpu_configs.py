@@ -327,3 +327,59 @@ def test_step_replayed_from_a_hip_graph_matches_eager(stateful):
         else:
             np.testing.assert_array_equal(idx_g.cpu().numpy(), idx_e.cpu().numpy())
             np.testing.assert_array_equal(x_g.cpu().numpy(), x_e.cpu().numpy())
+
+
+# ----------------------------------------------------------------------------- state
+def test_resume_from_saved_sketch_state():
+    """The whole state of the method between steps is (seed, r, c, S_u, S_v): a run that is cut
+    after 3 steps, saved to the host and restored into a fresh HotPath continues as the uncut
+    run does (fp32 atomics reorder sums, so tables are compared within tolerance and the
+    selections outside near-ties)."""
+    import io
+    c = wl.scaled(4, d=(1 << 20) + 77, W=4, c=1 << 13, k=1000, steps=6, n_heavy=300)
+    work = wl.Workload(c, DEV)
+    sk = orc.SketchOracle(c.r, c.c, c.hash_seed)
+
+    def steps(hp, ts):
+        out = None
+        for t in ts:
+            out = hp.step([work.gradient(t, w) for w in range(c.W)])
+        return out
+
+    whole = HotPath(c.d, c.W, c.r, c.c, c.k, c.hash_seed, rho=c.rho, device=DEV)
+    idx_a, x_a = steps(whole, range(6))
+    first = HotPath(c.d, c.W, c.r, c.c, c.k, c.hash_seed, rho=c.rho, device=DEV)
+    steps(first, range(3))
+    blob = io.BytesIO()
+    torch.save({"S_u": first.S_u.cpu(), "S_v": first.S_v.cpu()}, blob)
+    del first
+    blob.seek(0)
+    saved = torch.load(blob, weights_only=True)
+    second = HotPath(c.d, c.W, c.r, c.c, c.k, c.hash_seed, rho=c.rho, device=DEV)
+    second.S_u.copy_(saved["S_u"])
+    second.S_v.copy_(saved["S_v"])
+    idx_b, x_b = steps(second, range(3, 6))
+    Sv_a, Sv_b = whole.S_v.cpu().numpy().astype(np.float64), second.S_v.cpu().numpy().astype(np.float64)
+    scale = np.abs(Sv_a).max()
+    assert np.abs(Sv_a - Sv_b).max() <= 1e-5 * scale
+    # the resumed run's last selection is valid for the uncut run's last estimates
+    est_a = whole.est.cpu().numpy().astype(np.float64)
+    assert_valid_topk(idx_b.cpu().numpy(), est_a, c.k, rms(Sv_a), what="resumed selection")
+    same = np.intersect1d(idx_a.cpu().numpy(), idx_b.cpu().numpy()).size
+    assert same >= c.k - 5
+
+
+def test_merge_without_a_lost_worker_is_the_sketch_of_the_remaining_mean():
+    """Linearity (Sec. 3) makes a lost worker harmless: merging the sketches that arrived with
+    1 / (W - 1) is the sketch of the mean of the remaining gradients."""
+    c = wl.scaled(2, d=400_003, W=5, c=1 << 12, k=500, steps=1, n_heavy=100)
+    work = wl.Workload(c, DEV)
+    sk = orc.SketchOracle(c.r, c.c, c.hash_seed)
+    g_w = [work.gradient(0, w) for w in range(c.W)]
+    lost = 2
+    arrived = [g for w, g in enumerate(g_w) if w != lost]
+    hp = HotPath(c.d, c.W - 1, c.r, c.c, c.k, c.hash_seed, device=DEV)
+    hp.accumulate(arrived)
+    hp.merge()
+    ref = sk.sketch(host_sum(arrived), scale=1.0 / (c.W - 1))
+    assert_cells_close(hp.S_t.cpu().numpy(), ref, what="merge of the workers that arrived")
