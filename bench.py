@@ -245,6 +245,10 @@ def main():
         "stream_read": {"one_vector_GBs": stream_one, "one_input_set_GBs": stream_set,
                         "kernel": "cs_probe_stream_read (plain 16-byte loads)"},
         "stage_ms": stage_ms,
+        "stage_Gcoords_s": {name: (cfg.W if name in ("accumulate", "dense_momentum") else 1) * cfg.d
+                            / (stage_ms[name] * 1e-3) / 1e9
+                            for name in ("accumulate", "dense_momentum", "estimate", "topk", "heavymix_select")
+                            if stage_ms.get(name)},
         "roofline": {
             "kernel": "k_accumulate_visits (all launches of cs_sketch_accumulate_bundle)",
             "bound": "hbm",
