@@ -20,6 +20,7 @@ __device__ __forceinline__ uint32_t mix(uint32_t x) {
 // mode 0: every lane its own random cell. mode 1: wave picks a random base, lanes base+lane.
 // mode 2: lanes base + floor(lane*1.3). mode 3: base aligned to 64 floats, + lane.
 // mode 4: groups of 16 lanes contiguous (4 random bases per wave)
+// modes 5-7: groups of 8 / 16 / 32 lanes at random addresses aligned to 32 / 64 / 128 bytes
 template <int MODE, bool ATOMIC>
 __global__ void __launch_bounds__(256) k_scatter(float* table, uint32_t mask, int iters, float* sink) {
     const uint32_t gtid = blockIdx.x * 256 + threadIdx.x;
@@ -33,7 +34,14 @@ __global__ void __launch_bounds__(256) k_scatter(float* table, uint32_t mask, in
             if (MODE == 1) cell = (base + lane) & mask;
             else if (MODE == 2) cell = (base + (lane * 13u) / 10u) & mask;
             else if (MODE == 3) cell = ((base & ~63u) + lane) & mask;
-            else { base = mix((wave * 4 + (lane >> 4)) * 9781u + it * 0x9e3779b9u); cell = (base + (lane & 15)) & mask; }
+            else if (MODE == 4) { base = mix((wave * 4 + (lane >> 4)) * 9781u + it * 0x9e3779b9u); cell = (base + (lane & 15)) & mask; }
+            else {
+                // modes 5, 6, 7: groups of 8, 16, 32 lanes, each group at a random address
+                // aligned to its own size (32, 64, 128 bytes)
+                const uint32_t gl = MODE == 5 ? 8u : MODE == 6 ? 16u : 32u;
+                base = mix((wave * (64u / gl) + lane / gl) * 9781u + it * 0x9e3779b9u);
+                cell = ((base & ~(gl - 1u)) + (lane & (gl - 1u))) & mask;
+            }
         }
         if (ATOMIC) __hip_atomic_fetch_add(table + cell, 1.0f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         else acc += table[cell];
@@ -206,6 +214,9 @@ int main() {
         ms = time_ms([&] { k_scatter<3, true><<<blocks, 256>>>(table, mask, iters, sink); });  printf("  atomic wave-contig align : %8.3f ms  %7.1f Gop/s\n", ms, nops / ms / 1e6);
         ms = time_ms([&] { k_scatter<2, true><<<blocks, 256>>>(table, mask, iters, sink); });  printf("  atomic stride 1.3        : %8.3f ms  %7.1f Gop/s\n", ms, nops / ms / 1e6);
         ms = time_ms([&] { k_scatter<4, true><<<blocks, 256>>>(table, mask, iters, sink); });  printf("  atomic 16-lane groups    : %8.3f ms  %7.1f Gop/s\n", ms, nops / ms / 1e6);
+        ms = time_ms([&] { k_scatter<5, true><<<blocks, 256>>>(table, mask, iters, sink); });  printf("  atomic 8 x 32 B aligned  : %8.3f ms  %7.1f Gop/s  %6.1f G groups/s\n", ms, nops / ms / 1e6, nops / 8 / ms / 1e6);
+        ms = time_ms([&] { k_scatter<6, true><<<blocks, 256>>>(table, mask, iters, sink); });  printf("  atomic 4 x 64 B aligned  : %8.3f ms  %7.1f Gop/s  %6.1f G groups/s\n", ms, nops / ms / 1e6, nops / 16 / ms / 1e6);
+        ms = time_ms([&] { k_scatter<7, true><<<blocks, 256>>>(table, mask, iters, sink); });  printf("  atomic 2 x 128 B aligned : %8.3f ms  %7.1f Gop/s  %6.1f G groups/s\n", ms, nops / ms / 1e6, nops / 32 / ms / 1e6);
         ms = time_ms([&] { k_scatter<0, false><<<blocks, 256>>>(table, mask, iters, sink); }); printf("  gather random lanes      : %8.3f ms  %7.1f Gop/s\n", ms, nops / ms / 1e6);
         ms = time_ms([&] { k_scatter<1, false><<<blocks, 256>>>(table, mask, iters, sink); }); printf("  gather wave-contiguous   : %8.3f ms  %7.1f Gop/s\n", ms, nops / ms / 1e6);
         ms = time_ms([&] { k_scatter<2, false><<<blocks, 256>>>(table, mask, iters, sink); }); printf("  gather stride 1.3        : %8.3f ms  %7.1f Gop/s\n", ms, nops / ms / 1e6);
