@@ -2,8 +2,8 @@
 // elementwise kernels.
 //
 // Done naively the update is one atomic add per coordinate, row and worker, and this machine
-// executes fp32 atomics at the memory side at a fixed ~21-24 G requests of 32 bytes per second
-// (measured, whatever the table size).  Three facts cut the requests by a factor of ~300, after
+// executes fp32 atomics at the memory side at a fixed ~21-24 G requests per second (measured,
+// whatever the table size; a request is one aligned 64-byte block touched by one instruction).  Three facts cut the requests by a factor of ~300, after
 // which the kernel is bound by reading the vectors:
 //
 //  1. The bucket hash is affine modulo p = 2^61 - 1, so moving s coordinates on moves a
@@ -16,7 +16,7 @@
 //     kernel that normally runs).
 //  2. All workers use the same hash functions, so in the bundle layout T[w/8][j][b][w%8] the
 //     sums of 8 workers for one cell are 32 contiguous bytes: 8 lanes (one per worker) flush
-//     them as one full 32-byte request.
+//     them as one request.
 //  3. Every row needs its own visiting order, so a group's vectors are read once per row; the
 //     rows of a group run in one launch.
 //
