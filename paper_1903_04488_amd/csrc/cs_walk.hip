@@ -710,15 +710,18 @@ int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* con
 // The same stride serves the query: a lane that walks i, i + Dw, i + 2 Dw, ... stays in one
 // cell for ~1/sigma visits, so it keeps that cell's value in a register and gathers again
 // only when it leaves the cell (one gather per ~10 coordinates instead of one per
-// coordinate).  The 64 lanes of a wavefront own 64 neighbouring chunks of 16 residues, so
-// every visit writes 4 KB of contiguous output (transposed through LDS into whole 16-byte
-// pieces).  A second kernel takes the median over rows.
+// coordinate).  The 64 lanes of a wavefront own 64 neighbouring chunks of 4 residues, so
+// every visit writes 1 KB of contiguous output, 16 bytes per lane.  A second kernel takes the
+// median over rows.
 // ---------------------------------------------------------------------------------------
 namespace {
 
-constexpr int kQRun = 16;
+// Coordinates per lane and visit.  Four: a lane's values are one 16-byte piece of output, so no
+// transpose is needed, and the registers that 16 coordinates took (cell and value of each) are
+// better spent on twice as many resident wavefronts -- the kernel waits on its gathers.
+constexpr int kQRun = 4;
 
-// A short vector leaves a row with few chunks (Dw / 1024 wavefronts) and a long serial chain
+// A short vector leaves a row with few chunks (Dw / 256 wavefronts) and a long serial chain
 // of visits each; the chain is then cut into segments that separate wavefronts walk
 // (blockIdx.z), at the price of one more gather per lane and segment.
 struct RowSegments {
@@ -728,9 +731,7 @@ struct RowSegments {
 __global__ void __launch_bounds__(64)
 k_row_values_walk(KParams p, RowSegments segs, const float* __restrict__ S, int64_t d, int64_t i0,
                   float* __restrict__ rows) {
-    constexpr int kStride = kQRun + 1;
-    constexpr int kPieces = kQRun / 4, kRunsPerPass = 64 / kPieces, kPasses = kPieces;
-    __shared__ float tile_lds[64 * kStride];
+    static_assert(kQRun == 4, "one 16-byte piece per lane");
     const int lane = threadIdx.x;
     const int j = blockIdx.y;
     const int nseg = segs.n[j];
@@ -746,7 +747,6 @@ k_row_values_walk(KParams p, RowSegments segs, const float* __restrict__ S, int6
     const uint32_t mask = p.c - 1u;
     const float* __restrict__ Sj = S + static_cast<size_t>(j) * p.c;
     float* __restrict__ out = rows + static_cast<size_t>(j) * d;
-    const int m4 = (lane % kPieces) * 4, r0 = lane / kPieces;
 
     const int64_t per_xcd = (nwaves + 7) / 8;
     const int64_t xcd_first = static_cast<int64_t>(blockIdx.x & 7) * per_xcd;
@@ -766,6 +766,7 @@ k_row_values_walk(KParams p, RowSegments segs, const float* __restrict__ S, int6
             int64_t my_len = D - my_off;                         // coordinates of mine that exist
             if (d - (nD + my_off) < my_len) my_len = d - (nD + my_off);
             uint64_t tb = yb, ts = ys;
+            float o[kQRun];
 #pragma unroll
             for (int m = 0; m < kQRun; ++m) {
                 const uint32_t cell = (static_cast<uint32_t>(tb) - 1u) & mask;
@@ -773,35 +774,25 @@ k_row_values_walk(KParams p, RowSegments segs, const float* __restrict__ S, int6
                     cur[m] = cell;
                     val[m] = Sj[cell];
                 }
-                tile_lds[lane * kStride + m] = apply_sign(val[m], sign_flip_of(ts));
+                o[m] = apply_sign(val[m], sign_flip_of(ts));
                 tb = hash_advance(tb, Ab);
                 ts = hash_advance(ts, As);
             }
             yb = hash_advance(yb, ADb);
             ys = hash_advance(ys, ADs);
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int q = 0; q < kPasses; ++q) {
-                const int rho = q * kRunsPerPass + r0;           // run = lane that owns it
-                const int64_t off = (chunk0 + rho) * kQRun;
-                const int64_t rel = nD + off;
-                int64_t len = D - off;
-                if (d - rel < len) len = d - rel;
-                const float* src = tile_lds + rho * kStride + m4;
-                float* dst = out + rel + m4;
-                if (m4 + 4 <= len) {
-                    vec4f u;
-                    u.x = src[0]; u.y = src[1]; u.z = src[2]; u.w = src[3];
-                    // streamed out, read once by the median kernel: kept out of the way of
-                    // the table row that the gathers want to find in L2
-                    __builtin_nontemporal_store(u, reinterpret_cast<vec4f_u*>(dst));
-                } else if (m4 < len) {
-                    dst[0] = src[0];
-                    if (m4 + 1 < len) dst[1] = src[1];
-                    if (m4 + 2 < len) dst[2] = src[2];
-                }
+            // the wavefront's 64 pieces are 1 KB of contiguous rows[j][i]
+            float* dst = out + nD + my_off;
+            if (my_len >= kQRun) {
+                vec4f u;
+                u.x = o[0]; u.y = o[1]; u.z = o[2]; u.w = o[3];
+                // streamed out, read once by the median kernel: kept out of the way of the
+                // table row that the gathers want to find in L2
+                __builtin_nontemporal_store(u, reinterpret_cast<vec4f_u*>(dst));
+            } else if (my_len > 0) {
+                dst[0] = o[0];
+                if (my_len > 1) dst[1] = o[1];
+                if (my_len > 2) dst[2] = o[2];
             }
-            __builtin_amdgcn_wave_barrier();
         }
     }
 }
