@@ -83,10 +83,15 @@ template <int PASS, bool VEC, typename KEY>
 __global__ void __launch_bounds__(kBlock)
 k_topk_hist(const float* __restrict__ est, int64_t d, TopkWs* ws, KEY kf) {
     kf.init();
-    __shared__ uint32_t lh[kBins];
+    // Magnitudes crowd into a few of the pass-0 bins (same exponent), and lanes that hit the same
+    // LDS word are served one after the other: pass 0 keeps kCopies histograms and lane l adds
+    // into copy l mod kCopies.
+    constexpr int kCopies = (PASS == 0) ? 4 : 1;
     constexpr int nb = (PASS == 0) ? 2048 : 1024;
-    for (int t = threadIdx.x; t < nb; t += kBlock) lh[t] = 0;
+    __shared__ uint32_t lh_all[kCopies][nb];
+    for (int t = threadIdx.x; t < kCopies * nb; t += kBlock) (&lh_all[0][0])[t] = 0;
     __syncthreads();
+    uint32_t* lh = lh_all[threadIdx.x % kCopies];
     const uint32_t prefix = ws->sel.prefix;
     auto tally = [&](uint32_t key) {
         if (PASS == 0) {
@@ -119,7 +124,9 @@ k_topk_hist(const float* __restrict__ est, int64_t d, TopkWs* ws, KEY kf) {
     for (int64_t t = done + t0; t < d; t += stride) tally(kf(est[t], t));
     __syncthreads();
     for (int t = threadIdx.x; t < nb; t += kBlock) {
-        const uint32_t v = lh[t];
+        uint32_t v = 0;
+#pragma unroll
+        for (int q = 0; q < kCopies; ++q) v += lh_all[q][t];
         if (v) atomicAdd(reinterpret_cast<unsigned long long*>(&ws->hist[PASS][t]),
                          static_cast<unsigned long long>(v));
     }
