@@ -45,8 +45,8 @@ bool walk_applies(const cs_params* p, int64_t d);
 int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* const* g_w,
                            int64_t d, int64_t i0, float scale, hipStream_t stream);
 int count_accumulate_walk_launches(const cs_params* p, int W, int64_t d);
-int launch_row_values_walk(const cs_params* p, const float* S, int64_t d, int64_t i0,
-                           float* rows, hipStream_t stream);
+int launch_estimate_walk(const cs_params* p, const float* S, int64_t d, int64_t i0,
+                         float* est, float* rows, bool fuse_last, hipStream_t stream);
 int launch_bundle_zero(float* T, int64_t n, hipStream_t stream);
 int launch_bundle_merge(float* dst, float beta, const float* T, int groups, float alpha,
                         int64_t cells, hipStream_t stream);

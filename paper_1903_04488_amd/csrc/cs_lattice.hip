@@ -314,8 +314,9 @@ int launch_accumulate_lattice(const cs_params* p, const LatticePtrs& ptrs, int n
 int launch_estimate_lattice(const cs_params* p, const float* S, int64_t d, int64_t i0,
                             float* est, float* rows, hipStream_t stream) {
     if (walk_applies(p, d)) {
-        const int rc = launch_row_values_walk(p, S, d, i0, rows, stream);
-        if (rc != CS_OK) return rc;
+        const bool fuse_last = d >= (static_cast<int64_t>(1) << 24);
+        const int rc = launch_estimate_walk(p, S, d, i0, est, rows, fuse_last, stream);
+        if (rc != CS_OK || fuse_last) return rc;
     } else {
         const dim3 grid(lattice_grid_x(p, d), p->r);
         k_row_values_lattice<<<grid, 64, 0, stream>>>(kparams(p), S, d, i0, rows);

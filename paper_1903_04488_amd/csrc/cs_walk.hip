@@ -728,12 +728,16 @@ struct RowSegments {
     int n[CS_MAX_R];
 };
 
+// RF = 0: rows[j][i] for the rows j = blockIdx.y.  RF = R (the row count): the walk of the last
+// row, which instead of storing its values reads those of rows 0 .. R-2 at the same coordinates
+// and writes their median, est[i] -- the last row never goes through memory.
+template <int RF>
 __global__ void __launch_bounds__(64)
 k_row_values_walk(KParams p, RowSegments segs, const float* __restrict__ S, int64_t d, int64_t i0,
-                  float* __restrict__ rows) {
+                  float* __restrict__ rows, float* __restrict__ est) {
     static_assert(kQRun == 4, "one 16-byte piece per lane");
     const int lane = threadIdx.x;
-    const int j = blockIdx.y;
+    const int j = RF ? RF - 1 : blockIdx.y;
     const int nseg = segs.n[j];
     if (static_cast<int>(blockIdx.z) >= nseg) return;
     const int64_t D = static_cast<int64_t>(p.plan[j].Dw);
@@ -765,6 +769,15 @@ k_row_values_walk(KParams p, RowSegments segs, const float* __restrict__ S, int6
         for (int64_t nD = nD0; nD < nD1 && nD + chunk0 * kQRun < d; nD += D) {
             int64_t my_len = D - my_off;                         // coordinates of mine that exist
             if (d - (nD + my_off) < my_len) my_len = d - (nD + my_off);
+            [[maybe_unused]] vec4f other[RF > 1 ? RF - 1 : 1];       // the other rows' values, requested early
+            if constexpr (RF > 1) {
+                if (my_len >= kQRun) {
+#pragma unroll
+                    for (int q = 0; q < RF - 1; ++q)
+                        other[q] = __builtin_nontemporal_load(reinterpret_cast<const vec4f_u*>(
+                            rows + static_cast<size_t>(q) * d + nD + my_off));
+                }
+            }
             uint64_t tb = yb, ts = ys;
             float o[kQRun];
 #pragma unroll
@@ -780,6 +793,31 @@ k_row_values_walk(KParams p, RowSegments segs, const float* __restrict__ S, int6
             }
             yb = hash_advance(yb, ADb);
             ys = hash_advance(ys, ADs);
+            if constexpr (RF > 0) {
+                float* dst = est + nD + my_off;
+                if (my_len >= kQRun) {
+                    float vx[RF], vy[RF], vz[RF], vw[RF];
+#pragma unroll
+                    for (int q = 0; q < RF - 1; ++q) {
+                        vx[q] = other[q].x; vy[q] = other[q].y; vz[q] = other[q].z; vw[q] = other[q].w;
+                    }
+                    vx[RF - 1] = o[0]; vy[RF - 1] = o[1]; vz[RF - 1] = o[2]; vw[RF - 1] = o[3];
+                    vec4f u;
+                    u.x = median_odd<RF>(vx); u.y = median_odd<RF>(vy);
+                    u.z = median_odd<RF>(vz); u.w = median_odd<RF>(vw);
+                    *reinterpret_cast<vec4f_u*>(dst) = u;
+                } else {
+                    for (int m = 0; m < kQRun; ++m) {
+                        if (m >= my_len) break;
+                        float v[RF];
+#pragma unroll
+                        for (int q = 0; q < RF - 1; ++q) v[q] = rows[static_cast<size_t>(q) * d + nD + my_off + m];
+                        v[RF - 1] = o[m];
+                        dst[m] = median_odd<RF>(v);
+                    }
+                }
+                continue;
+            }
             // the wavefront's 64 pieces are 1 KB of contiguous rows[j][i]
             float* dst = out + nD + my_off;
             if (my_len >= kQRun) {
@@ -799,8 +837,11 @@ k_row_values_walk(KParams p, RowSegments segs, const float* __restrict__ S, int6
 
 }  // namespace
 
-int launch_row_values_walk(const cs_params* p, const float* S, int64_t d, int64_t i0,
-                           float* rows, hipStream_t stream) {
+// fuse_last = false: all rows into the scratch (the caller takes the median).  fuse_last = true:
+// the last row's walk takes the median itself; worth it for long vectors, where the scratch
+// traffic it saves (write and read of one row) outweighs a second, narrower launch.
+int launch_estimate_walk(const cs_params* p, const float* S, int64_t d, int64_t i0,
+                         float* est, float* rows, bool fuse_last, hipStream_t stream) {
     int64_t most = 1;
     for (uint32_t j = 0; j < p->r; ++j) {
         const int64_t chunks = (static_cast<int64_t>(p->plan[j].Dw) + kQRun - 1) / kQRun;
@@ -824,8 +865,24 @@ int launch_row_values_walk(const cs_params* p, const float* S, int64_t d, int64_
         segs.n[j] = static_cast<int>(n);
         if (segs.n[j] > most_segs) most_segs = segs.n[j];
     }
-    const dim3 grid(static_cast<unsigned>(gx), p->r, static_cast<unsigned>(most_segs));
-    k_row_values_walk<<<grid, 64, 0, stream>>>(kparams(p), segs, S, d, i0, rows);
+    if (!fuse_last) {
+        const dim3 grid(static_cast<unsigned>(gx), p->r, static_cast<unsigned>(most_segs));
+        k_row_values_walk<0><<<grid, 64, 0, stream>>>(kparams(p), segs, S, d, i0, rows, est);
+        return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
+    }
+    // rows 0 .. r-2 into the scratch, then the last row together with the median
+    if (p->r > 1) {
+        const dim3 grid(static_cast<unsigned>(gx), p->r - 1, static_cast<unsigned>(most_segs));
+        k_row_values_walk<0><<<grid, 64, 0, stream>>>(kparams(p), segs, S, d, i0, rows, est);
+    }
+    const dim3 grid(static_cast<unsigned>(gx), 1, static_cast<unsigned>(segs.n[p->r - 1]));
+#define CS_LAST(R_)                                                                          \
+    case R_: k_row_values_walk<R_><<<grid, 64, 0, stream>>>(kparams(p), segs, S, d, i0, rows, est); break;
+    switch (p->r) {
+        CS_LAST(1) CS_LAST(3) CS_LAST(5) CS_LAST(7) CS_LAST(9) CS_LAST(11) CS_LAST(13) CS_LAST(15)
+        default: return CS_EINVAL;
+    }
+#undef CS_LAST
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
 

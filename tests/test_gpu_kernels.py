@@ -342,6 +342,21 @@ def test_estimate_bit_exact_from_same_table(r, c, seed, d, i0):
     np.testing.assert_array_equal(out.cpu().numpy(), ref[idx - i0].astype(np.float32))
 
 
+@pytest.mark.parametrize("r,c,seed,d,i0", [(5, 1 << 16, 3, (1 << 24) + 5, 7), (7, 1 << 14, 4, (1 << 24) + 4096, 0),
+                                           (1, 1 << 12, 5, 1 << 24, 1)])
+def test_estimate_long_vector_bit_exact(r, c, seed, d, i0):
+    """Vectors of 2^24 coordinates and more: the last row's walk takes the median itself."""
+    p = cs.cs_params_init(r, c, seed, d)
+    sk = orc.SketchOracle(r, c, seed)
+    T32 = (np.random.default_rng(seed).standard_normal((r, c))).astype(np.float32)
+    est = torch.empty(d, dtype=torch.float32, device=DEV)
+    n_ws = cs.cs_estimate_workspace_bytes(p, d)
+    ws = torch.empty(n_ws, dtype=torch.uint8, device=DEV) if n_ws else None
+    cs.cs_sketch_estimate(p, dev(T32), est, i0=i0, workspace=ws)
+    ref = sk.estimate(T32.astype(np.float64), d, i0=i0)
+    np.testing.assert_array_equal(est.cpu().numpy(), ref.astype(np.float32))
+
+
 # ------------------------------------------------------------------------------ top-k
 def run_topk(est32, k):
     d = est32.size
