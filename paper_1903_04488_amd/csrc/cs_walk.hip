@@ -44,9 +44,7 @@ namespace cs {
 namespace {
 
 constexpr int kGroup = CS_BUNDLE_GROUP;  // workers per bundle group
-#ifndef CS_WALK_NWAVE8
-#define CS_WALK_NWAVE8 2
-#endif
+constexpr int kWavesPerGroupOf8 = 2;      // wavefronts per workgroup of the 8-worker kernels
 
 // Vectors are addressed as global memory explicitly: the pointers pass through an LDS table,
 // and a generic ("flat") load would count against the LDS counter as well and force the
@@ -65,11 +63,11 @@ struct WalkArgs {
     float scale;
 };
 
-// WL  = lanes per walker = workers served together (1, 2, 4, 8 or 16);
+// WL  = lanes per walker = workers served together (1, 2, 4 or 8);
 // RUN = consecutive coordinates per walker and visit (16 or 32).
 // A wavefront holds WPW = 64 / WL walkers on neighbouring chunks of RUN residues, so one visit
-// reads WPW * RUN * 4 contiguous bytes of every worker's vector (512 bytes for WL = 8, RUN = 16
-// and for WL = 16, RUN = 32: measured to stream at 5.7 TB/s, against 4.5 TB/s with 256-byte and
+// reads WPW * RUN * 4 contiguous bytes of every worker's vector (512 bytes for WL = 8,
+// RUN = 16: measured to stream at 5.7 TB/s, against 4.5 TB/s with 256-byte and
 // 3.5 TB/s with 128-byte pieces).
 // NWAVE = wavefronts per workgroup; they work on neighbouring sets of walkers at about the same
 // time (nothing is shared and nothing is synchronised between them), which widens the
@@ -669,7 +667,7 @@ int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* con
                 if (j < p->r && visits_apply(p, j, d)) js[nrows++] = j;
                 if (nrows == kRowsPerLaunch || (j == p->r && nrows > 0)) {
                     int rc;
-                    if (nw > 4) rc = launch_visits<8, 16, CS_WALK_NWAVE8>(p, vw, js, nrows, ncell, stream);
+                    if (nw > 4) rc = launch_visits<8, 16, kWavesPerGroupOf8>(p, vw, js, nrows, ncell, stream);
                     else if (nw > 2) rc = launch_visits<4, 16, 1>(p, vw, js, nrows, ncell, stream);
                     else if (nw > 1) rc = launch_visits<2, 16, 1>(p, vw, js, nrows, ncell, stream);
                     else rc = launch_visits<1, 16, 1>(p, vw, js, nrows, ncell, stream);
@@ -690,11 +688,7 @@ int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* con
             a.j = static_cast<int32_t>(j);
             a.Trow = Tg + j * row_floats;
             int rc;
-#if CS_BUNDLE_GROUP >= 16
-            if (nw > 8) rc = launch_walk<16, 16, 2>(p, a, stream);
-            else
-#endif
-            if (nw > 4) rc = launch_walk<8, 16, CS_WALK_NWAVE8>(p, a, stream);
+            if (nw > 4) rc = launch_walk<8, 16, kWavesPerGroupOf8>(p, a, stream);
             else if (nw > 2) rc = launch_walk<4, 16, 1>(p, a, stream);
             else if (nw > 1) rc = launch_walk<2, 16, 1>(p, a, stream);
             else rc = launch_walk<1, 16, 1>(p, a, stream);
