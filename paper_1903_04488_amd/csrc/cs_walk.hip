@@ -657,24 +657,29 @@ int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* con
         // All rows with a visit list go into one launch (per 8 rows), compiled for the largest
         // number of running sums among them: a row that needs fewer simply never touches the
         // extra ones.  One launch overlaps the rows' serial chains of visits and has one tail.
+        // Rows with the longest lists go first: workgroups are started in order, so the launch
+        // then ends on the wavefronts that live shortest and the chip drains quickly (measured
+        // against the rows in index order: 1.5 % at d = 100 M with 5 rows, 4 % at d = 25 M
+        // with 7; the opposite order costs as much again).
         uint32_t ncell = 2;
-        for (uint32_t j = 0; j < p->r; ++j)
-            if (visits_apply(p, j, d) && p->visit[j].ncell > ncell) ncell = p->visit[j].ncell;
-        {
-            uint32_t js[kRowsPerLaunch];
-            int nrows = 0;
-            for (uint32_t j = 0; j <= p->r; ++j) {
-                if (j < p->r && visits_apply(p, j, d)) js[nrows++] = j;
-                if (nrows == kRowsPerLaunch || (j == p->r && nrows > 0)) {
-                    int rc;
-                    if (nw > 4) rc = launch_visits<8, 16, kWavesPerGroupOf8>(p, vw, js, nrows, ncell, stream);
-                    else if (nw > 2) rc = launch_visits<4, 16, 1>(p, vw, js, nrows, ncell, stream);
-                    else if (nw > 1) rc = launch_visits<2, 16, 1>(p, vw, js, nrows, ncell, stream);
-                    else rc = launch_visits<1, 16, 1>(p, vw, js, nrows, ncell, stream);
-                    if (rc != CS_OK) return rc;
-                    nrows = 0;
-                }
-            }
+        uint32_t listed[CS_MAX_R];
+        int nlisted = 0;
+        for (uint32_t j = 0; j < p->r; ++j) {
+            if (!visits_apply(p, j, d)) continue;
+            if (p->visit[j].ncell > ncell) ncell = p->visit[j].ncell;
+            int at = nlisted++;
+            for (; at > 0 && p->visit[listed[at - 1]].K < p->visit[j].K; --at) listed[at] = listed[at - 1];
+            listed[at] = j;
+        }
+        for (int q0 = 0; q0 < nlisted; q0 += kRowsPerLaunch) {
+            const int nrows = nlisted - q0 < kRowsPerLaunch ? nlisted - q0 : kRowsPerLaunch;
+            const uint32_t* js = listed + q0;
+            int rc;
+            if (nw > 4) rc = launch_visits<8, 16, kWavesPerGroupOf8>(p, vw, js, nrows, ncell, stream);
+            else if (nw > 2) rc = launch_visits<4, 16, 1>(p, vw, js, nrows, ncell, stream);
+            else if (nw > 1) rc = launch_visits<2, 16, 1>(p, vw, js, nrows, ncell, stream);
+            else rc = launch_visits<1, 16, 1>(p, vw, js, nrows, ncell, stream);
+            if (rc != CS_OK) return rc;
         }
         // the other rows: stride walk, one launch per row
         WalkArgs a{};

@@ -181,7 +181,7 @@ def _bundle_tables(p, gs, r, c, i0=0, scale=1.0):
     return [Th[w // G, :, :, w % G] for w in range(W)]
 
 
-@pytest.mark.parametrize("W", [1, 2, 3, 8, 13])
+@pytest.mark.parametrize("W", [1, 2, 3, 8, 12, 13, 70])    # 12: a narrow last group; 70: two launches
 def test_accumulate_bundle_every_traversal(W):
     """The same vectors through the visit-list update (the default when a list exists), the
     stride walk (list switched off by flag), a forged list whose offsets do not keep a lane
