@@ -135,21 +135,42 @@ k_topk_hist(const float* __restrict__ est, int64_t d, TopkWs* ws, KEY kf) {
 // One workgroup: walk the histogram of this pass from the top bin down to the bin that holds
 // the k_rem-th largest entry; append that bin to the prefix, and drop from k_rem the entries
 // in higher bins (they are all selected).
+// Sum of v over the threads before this one in the workgroup (shuffles within a wavefront, one
+// LDS word per wavefront); *total receives the sum over all threads.
+__device__ __forceinline__ uint64_t block_exclusive_sum64(uint64_t v, uint64_t* lds, uint64_t* total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint64_t inc = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint64_t up = __shfl_up(inc, off, 64);
+        if (lane >= off) inc += up;
+    }
+    if (lane == 63) lds[wave] = inc;
+    __syncthreads();
+    uint64_t before = 0, all = 0;
+#pragma unroll
+    for (int wv = 0; wv < kBlock / 64; ++wv) {
+        const uint64_t s = lds[wv];
+        if (wv < wave) before += s;
+        all += s;
+    }
+    *total = all;
+    return before + inc - v;
+}
+
 template <int PASS>
 __global__ void __launch_bounds__(kBlock) k_topk_find(TopkWs* ws) {
     constexpr int nb = (PASS == 0) ? 2048 : 1024;
     constexpr int per = nb / kBlock;              // bins per thread: 8 or 4
-    __shared__ uint64_t seg[kBlock];
+    __shared__ uint64_t wave_sum[kBlock / 64];
     const uint64_t* h = ws->hist[PASS];
     const uint64_t k_rem = ws->sel.k_rem;
     const uint32_t prefix = ws->sel.prefix;
     uint64_t mine = 0;
     for (int q = 0; q < per; ++q) mine += h[threadIdx.x * per + q];
-    seg[threadIdx.x] = mine;
-    __syncthreads();
-    uint64_t above = 0;                            // entries in bins above my segment
-    for (int u = threadIdx.x + 1; u < kBlock; ++u) above += seg[u];
-    __syncthreads();
+    uint64_t all;
+    const uint64_t below = block_exclusive_sum64(mine, wave_sum, &all);
+    const uint64_t above = all - below - mine;     // entries in bins above my segment
     if (above < k_rem && k_rem <= above + mine) {  // true for exactly one thread
         uint64_t acc = above;
         for (int q = per - 1; q >= 0; --q) {
@@ -244,7 +265,7 @@ k_topk_count(const float* __restrict__ est, int64_t d, int64_t chunk, TopkWs* ws
 
 // one workgroup: exclusive scan of the per-block counts, in place
 __global__ void __launch_bounds__(kBlock) k_topk_scan(TopkWs* ws, int nblocks) {
-    __shared__ uint64_t part_gt[kBlock], part_eq[kBlock];
+    __shared__ uint64_t wave_gt[kBlock / 64], wave_eq[kBlock / 64];
     constexpr int per = kMaxSelBlocks / kBlock;     // 16 consecutive blocks per thread
     uint64_t g[per], e[per], sg = 0, se = 0;
     for (int q = 0; q < per; ++q) {
@@ -254,11 +275,9 @@ __global__ void __launch_bounds__(kBlock) k_topk_scan(TopkWs* ws, int nblocks) {
         sg += g[q];
         se += e[q];
     }
-    part_gt[threadIdx.x] = sg;
-    part_eq[threadIdx.x] = se;
-    __syncthreads();
-    uint64_t bg = 0, be = 0;
-    for (int u = 0; u < static_cast<int>(threadIdx.x); ++u) { bg += part_gt[u]; be += part_eq[u]; }
+    uint64_t all;
+    uint64_t bg = block_exclusive_sum64(sg, wave_gt, &all);
+    uint64_t be = block_exclusive_sum64(se, wave_eq, &all);
     for (int q = 0; q < per; ++q) {
         const int b = threadIdx.x * per + q;
         if (b < nblocks) { ws->gt[b] = bg; ws->eq[b] = be; }

@@ -56,8 +56,8 @@ typedef const __attribute__((address_space(1))) vec4f_u* gvec4_ptr;
 
 struct WalkArgs {
     const float* g[kGroup];      // vectors of the workers of this group
-    float* Trow;                 // row j of the group's table, float[c][kGroup]
-    int32_t j;                   // sketch row
+    float* T;                    // the group's table, float[r][c][kGroup]
+    int32_t js[CS_MAX_R];        // sketch rows of this launch; blockIdx.y picks one
     int32_t nw;                  // workers in this group (<= kGroup)
     int64_t d, i0;
     float scale;
@@ -90,7 +90,7 @@ __global__ void __launch_bounds__(64 * NWAVE) k_accumulate_walk(KParams p, WalkA
     float* tile_lds = tile_lds_all[wq];
     uint32_t (*hash_lds)[WPW * RUN] = hash_lds_all[wq];
     gfloat_ptr* gptr_lds = gptr_lds_all[wq];
-    const int j = a.j;
+    const int j = a.js[blockIdx.y];
     const int h = lane / WL, wl = lane % WL;           // my walker, my worker slot
     if (lane < kGroup) gptr_lds[lane] = (gfloat_ptr)a.g[lane < a.nw ? lane : 0];
     __builtin_amdgcn_wave_barrier();
@@ -101,7 +101,7 @@ __global__ void __launch_bounds__(64 * NWAVE) k_accumulate_walk(KParams p, WalkA
     const int64_t nwaves = (chunks + WPW - 1) / WPW;
     const uint32_t mask = p.c - 1u;
     const int64_t d = a.d;
-    float* __restrict__ Tcol = a.Trow + wl;
+    float* __restrict__ Tcol = a.T + static_cast<size_t>(j) * p.c * kGroup + wl;
 
     // loader role: piece m4 of runs r0, r0 + kRunsPerPass, ...; run rho = worker * WPW + walker,
     // so that one load instruction covers neighbouring walkers (contiguous bytes) of few workers
@@ -238,16 +238,22 @@ __global__ void __launch_bounds__(64 * NWAVE) k_accumulate_walk(KParams p, WalkA
     }
 }
 
+// one launch: the rows a.js[0 .. nrows-1] of one group of workers (blockIdx.y = row of the set)
 template <int WL, int RUN, int NWAVE>
-int launch_walk(const cs_params* p, const WalkArgs& a, hipStream_t stream) {
+int launch_walk(const cs_params* p, const WalkArgs& a, int nrows, hipStream_t stream) {
     constexpr int WPW = 64 / WL;
-    const int64_t chunks = (static_cast<int64_t>(p->plan[a.j].Dw) + RUN - 1) / RUN;
-    const int64_t nwaves = (chunks + WPW - 1) / WPW;
-    const int64_t ngroups = (nwaves + NWAVE - 1) / NWAVE;
+    int64_t most = 1;
+    for (int q = 0; q < nrows; ++q) {
+        const int64_t chunks = (static_cast<int64_t>(p->plan[a.js[q]].Dw) + RUN - 1) / RUN;
+        const int64_t nwaves = (chunks + WPW - 1) / WPW;
+        const int64_t ngroups = (nwaves + NWAVE - 1) / NWAVE;
+        if (ngroups > most) most = ngroups;
+    }
     const int64_t cap = 256 * 64 / NWAVE;
-    int64_t gx = ngroups < cap ? ngroups : cap;
+    int64_t gx = most < cap ? most : cap;
     gx = (gx + 7) / 8 * 8;                   // the kernel deals workgroups to XCDs in eights
-    k_accumulate_walk<WL, RUN, NWAVE><<<static_cast<unsigned>(gx), 64 * NWAVE, 0, stream>>>(kparams(p), a);
+    const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(nrows));
+    k_accumulate_walk<WL, RUN, NWAVE><<<grid, 64 * NWAVE, 0, stream>>>(kparams(p), a);
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
 
@@ -636,8 +642,8 @@ int count_accumulate_walk_launches(const cs_params* p, int W, int64_t d) {
         if (visits_apply(p, j, d)) ++listed;
         else ++per_group;
     }
-    per_group += (listed + kRowsPerLaunch - 1) / kRowsPerLaunch;
-    return per_group * ((W + kGroup - 1) / kGroup);
+    const int launches = (listed + kRowsPerLaunch - 1) / kRowsPerLaunch + (per_group > 0 ? 1 : 0);
+    return launches * ((W + kGroup - 1) / kGroup);
 }
 
 int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* const* g_w,
@@ -681,22 +687,28 @@ int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* con
             else rc = launch_visits<1, 16, 1>(p, vw, js, nrows, ncell, stream);
             if (rc != CS_OK) return rc;
         }
-        // the other rows: stride walk, one launch per row
+        // the other rows: stride walk, all in one launch, the longest chains of visits
+        // (smallest strides) first
         WalkArgs a{};
         a.nw = nw;
         for (int w = 0; w < nw; ++w) a.g[w] = g_w[w0 + w];
+        a.T = Tg;
         a.d = d;
         a.i0 = i0;
         a.scale = scale;
+        int nwalked = 0;
         for (uint32_t j = 0; j < p->r; ++j) {
             if (visits_apply(p, j, d)) continue;
-            a.j = static_cast<int32_t>(j);
-            a.Trow = Tg + j * row_floats;
+            int at = nwalked++;
+            for (; at > 0 && p->plan[a.js[at - 1]].Dw > p->plan[j].Dw; --at) a.js[at] = a.js[at - 1];
+            a.js[at] = static_cast<int32_t>(j);
+        }
+        if (nwalked > 0) {
             int rc;
-            if (nw > 4) rc = launch_walk<8, 16, kWavesPerGroupOf8>(p, a, stream);
-            else if (nw > 2) rc = launch_walk<4, 16, 1>(p, a, stream);
-            else if (nw > 1) rc = launch_walk<2, 16, 1>(p, a, stream);
-            else rc = launch_walk<1, 16, 1>(p, a, stream);
+            if (nw > 4) rc = launch_walk<8, 16, kWavesPerGroupOf8>(p, a, nwalked, stream);
+            else if (nw > 2) rc = launch_walk<4, 16, 1>(p, a, nwalked, stream);
+            else if (nw > 1) rc = launch_walk<2, 16, 1>(p, a, nwalked, stream);
+            else rc = launch_walk<1, 16, 1>(p, a, nwalked, stream);
             if (rc != CS_OK) return rc;
         }
     }
