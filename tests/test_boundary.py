@@ -153,6 +153,26 @@ def test_invalid_arguments_are_rejected_without_a_gpu(lib):
     assert lib.cs_heavymix_select(fake, 10, 5, fake, 1, fake, null, null, fake, 8, null) == -2
 
 
+def test_update_launch_count_follows_the_grouping(lib):
+    """cs_bundle_update_launches: per group of 8 workers one launch for the rows with a visit list
+    (8 rows at most per launch) and one for the rows walked by stride; one launch per 32 workers
+    for sketches the walk does not serve; none for an empty vector."""
+    for r, c, seed, d in [(5, 1 << 20, 190304492, 10**8), (5, 1 << 15, 190304489, 1 << 20),
+                          (7, 1 << 19, 190304493, 25_000_000), (15, 1 << 12, 4, 3_000_000)]:
+        p = cs.cs_params_init(r, c, seed, d)
+        listed = sum(1 for j in range(r) if p.visit[j].K > 0 and p.visit[j].cost < p.visit[j].cost_walk)
+        per_group = -(-listed // 8) + (1 if listed < r else 0)
+        for W in (1, 8, 9, 32, 250):
+            assert cs.cs_bundle_update_launches(p, W, d) == per_group * -(-W // 8), (r, c, W)
+        assert cs.cs_bundle_update_launches(p, 8, 0) == 0
+        walk = binding.CsParams.from_buffer_copy(p)
+        walk.flags = binding.CS_FLAG_NO_VISIT_LIST
+        assert cs.cs_bundle_update_launches(walk, 16, d) == 2
+    p = cs.cs_params_init(5, 180_000, 1, 6_500_000)
+    for W, n in ((1, 1), (32, 1), (33, 2), (100, 4)):
+        assert cs.cs_bundle_update_launches(p, W, 6_500_000) == n
+
+
 def test_status_strings(lib):
     assert cs.cs_status_string(0) == "ok"
     assert "invalid" in cs.cs_status_string(-1)
