@@ -25,7 +25,7 @@ METRIC = "sketch+estimate+top-k throughput, Gcoords/s and % HBM peak at d=100M, 
 # of 8 workers), measured with rocprofv3 --pmc: FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
 # factors being what the same counters read for a plain 1 GiB copy.
 # Source: profiles/accumulate_visits_cfg4_pmc.md.  None for other configs.
-MEASURED_TRAFFIC_BYTES = {4: 1.741e10}
+MEASURED_TRAFFIC_BYTES = {4: 1.736e10}
 
 
 def cpu_baseline(cfg, work, sample_acc=64_000_000, sample_est=32_000_000):
