@@ -25,7 +25,7 @@ METRIC = "sketch+estimate+top-k throughput, Gcoords/s and % HBM peak at d=100M, 
 # of 8 workers), measured with rocprofv3 --pmc: FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
 # factors being what the same counters read for a plain 1 GiB copy.
 # Source: profiles/accumulate_visits_cfg4_pmc.md.  None for other configs.
-MEASURED_TRAFFIC_BYTES = {4: 1.740e10}
+MEASURED_TRAFFIC_BYTES = {4: 1.731e10}
 
 
 def cpu_baseline(cfg, work, sample_acc=64_000_000, sample_est=32_000_000):
@@ -64,34 +64,33 @@ def cpu_baseline(cfg, work, sample_acc=64_000_000, sample_est=32_000_000):
 
 
 def input_arenas_in_fast_memory(torch, B, hp, cfg, dev, n_sets):
-    """Device memory placement.  On MI355X the memory a fresh process is handed first (about the
-    first 100 GB) streams measurably slower than what it is handed later: the same update on the
-    same data takes 13.0 ms in the former and 11.8 ms in the latter, the plain read 5.75 against
-    5.88 TB/s.  So the input sets are not simply allocated first.  This step allocates chunks of
-    the size of one input set one after the other, fills them, and times a probe on each (the
-    stride-walk update of the first and of the last 8 workers' share of the chunk: the access
+    """Device memory placement.  Device memory on MI355X comes in parts of about 100 GB (in the
+    order a fresh process is handed memory), and the update is 9 % slower when the worker vectors
+    lie in the same part as the tables they are added into: with the tables allocated first, the
+    same update on the same data takes 13.0 ms on vectors within the first 100 GB and 11.8 ms on
+    vectors beyond.  So the input sets are not simply allocated next.  This step allocates chunks
+    of the size of one input set one after the other, fills them, and times a probe on each (the
+    stride-walk update of the chunk's W vectors into the step's own worker tables: the access
     pattern of the step's update, under a kernel name of its own in a trace), until n_sets
-    chunks are within 1.5 % of the fastest and at least 5 % faster than the slowest.  Those
+    chunks are within 0.6 % of the fastest and at least 5 % faster than the slowest.  Those
     become the input sets; the other chunks are freed.  The search goes on for n_sets + 10 chunks
-    (the slower memory alone is 8 chunks of 12.8 GB); when no chunk stands out by then, the first
-    n_sets chunks are used.  Returns (arenas, probe times in ms, indices chosen), or
-    (None, [], []) for inputs too small to place."""
+    (one part alone is 8 chunks of 12.8 GB); when no chunk stands out by then, the first n_sets
+    chunks are used.  Returns (arenas, probe times in ms, indices chosen), or (None, [], []) for
+    inputs too small to place."""
     chunk_bytes = 4 * cfg.d * cfg.W
     if cfg.W < 8 or chunk_bytes < (2 << 30) or not B.cs_bundle_update_launches(hp.params, 8, cfg.d):
         return None, [], []
     walk = B.CsParams.from_buffer_copy(hp.params)
     walk.flags |= B.CS_FLAG_NO_VISIT_LIST
-    T8 = hp.T[:B.cs_bundle_floats(hp.params, 8)]
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
     def probe(vecs):
-        B.cs_sketch_accumulate_bundle(walk, T8, vecs)
+        B.cs_sketch_accumulate_bundle(walk, hp.T, vecs)
         e0.record()
-        for _ in range(2):
-            B.cs_sketch_accumulate_bundle(walk, T8, vecs)
+        B.cs_sketch_accumulate_bundle(walk, hp.T, vecs)
         e1.record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / 2
+        return e0.elapsed_time(e1)
 
     chunks, times = [], []
     for _ in range(n_sets + 10):
@@ -102,9 +101,9 @@ def input_arenas_in_fast_memory(torch, B, hp, cfg, dev, n_sets):
         big.normal_(0.0, 0.01)
         vecs = [big[w * cfg.d:(w + 1) * cfg.d] for w in range(cfg.W)]
         chunks.append(big)
-        times.append(max(probe(vecs[:8]), probe(vecs[-8:])))
+        times.append(probe(vecs))
         ranked = sorted(times)
-        if len(ranked) >= n_sets and ranked[n_sets - 1] <= 1.015 * ranked[0] and ranked[0] < 0.95 * ranked[-1]:
+        if len(ranked) >= n_sets and ranked[n_sets - 1] <= 1.006 * ranked[0] and ranked[0] < 0.95 * ranked[-1]:
             break                                    # enough fast chunks, clearly faster than others
     order = sorted(range(len(times)), key=lambda q: (times[q], q))
     if len(order) < n_sets:
@@ -137,7 +136,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--plain-placement", action="store_true",
                     help="allocate the inputs in the plain order of a fresh process, without "
-                         "first looking for the device memory that streams fastest")
+                         "first looking for the device memory where the update runs fastest")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known HBM traffic) "
                          "so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE can be scaled")
@@ -261,6 +260,10 @@ def main():
     # every worker table written once) are spread evenly over those launches
     n_launch = B.cs_bundle_update_launches(hp.params, cfg.W, cfg.d)
     acc_kernel_ms = sum(ev[8].elapsed_time(ev[9]) for ev in events) / args.steps / n_launch
+    per_set = [[] for _ in range(n_sets)]         # the update's time on each resident input set
+    for t, ev in enumerate(events):
+        per_set[(args.warmup + t) % n_sets].append(ev[8].elapsed_time(ev[9]))
+    update_ms_per_set = [round(sum(v) / len(v), 3) if v else None for v in per_set]
     value = cfg.W * cfg.d / (ms_per_step * 1e-3) / 1e9
 
     alg_bytes = (4.0 * cfg.W * cfg.d + 4.0 * cfg.r * cfg.c * cfg.W) / n_launch
@@ -310,9 +313,10 @@ def main():
         "pct_stream_read_whole_step": 100.0 * step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / stream_set,
         "stream_read": {"one_vector_GBs": stream_one, "one_input_set_GBs": stream_set,
                         "kernel": "cs_probe_stream_read (plain 16-byte loads)"},
-        "placement": {"probe": "stride-walk update of 8 workers, on successive chunks of one input set's size",
+        "placement": {"probe": "stride-walk update of successive chunks of one input set's size",
                       "probe_ms": [round(t, 3) for t in probe_ms],
-                      "chunks_used_for_inputs": chosen},
+                      "chunks_used_for_inputs": chosen,
+                      "update_ms_per_input_set": update_ms_per_set},
         "stage_ms": stage_ms,
         "stage_Gcoords_s": {name: (cfg.W if name in ("accumulate", "dense_momentum") else 1) * cfg.d
                             / (stage_ms[name] * 1e-3) / 1e9
