@@ -72,7 +72,7 @@ def input_arenas_in_fast_memory(torch, B, hp, cfg, dev, n_sets):
     of the size of one input set one after the other, fills them, and times a probe on each (the
     stride-walk update of the chunk's W vectors into the step's own worker tables: the access
     pattern of the step's update, under a kernel name of its own in a trace), until n_sets
-    chunks are within 0.6 % of the fastest and at least 5 % faster than the slowest.  Those
+    chunks are within 0.6 % of the fastest and at least 4 % faster than the slowest.  Those
     become the input sets; the other chunks are freed.  The search goes on for n_sets + 10 chunks
     (one part alone is 8 chunks of 12.8 GB); when no chunk stands out by then, the first n_sets
     chunks are used.  Returns (arenas, probe times in ms, indices chosen), or (None, [], []) for
@@ -103,12 +103,12 @@ def input_arenas_in_fast_memory(torch, B, hp, cfg, dev, n_sets):
         chunks.append(big)
         times.append(probe(vecs))
         ranked = sorted(times)
-        if len(ranked) >= n_sets and ranked[n_sets - 1] <= 1.006 * ranked[0] and ranked[0] < 0.95 * ranked[-1]:
+        if len(ranked) >= n_sets and ranked[n_sets - 1] <= 1.006 * ranked[0] and ranked[0] < 0.96 * ranked[-1]:
             break                                    # enough fast chunks, clearly faster than others
     order = sorted(range(len(times)), key=lambda q: (times[q], q))
     if len(order) < n_sets:
         return None, times, []
-    if sorted(times)[0] >= 0.95 * sorted(times)[-1]:
+    if sorted(times)[0] >= 0.96 * sorted(times)[-1]:
         order = list(range(len(times)))              # nothing stands out: plain order
     chosen = sorted(order[:n_sets])
     arenas = [chunks[q] for q in chosen]
