@@ -63,6 +63,25 @@ def cpu_baseline(cfg, work, sample_acc=64_000_000, sample_est=32_000_000):
     }
 
 
+def enough_fast_chunks(times, n_sets):
+    """True when n_sets of the probe times are within 0.6 % of the fastest and the fastest is at
+    least 4 % below the slowest: the search of input_arenas_in_fast_memory can stop."""
+    ranked = sorted(times)
+    return (len(ranked) >= n_sets and ranked[n_sets - 1] <= 1.006 * ranked[0]
+            and ranked[0] < 0.96 * ranked[-1])
+
+
+def choose_chunks(times, n_sets):
+    """Indices (ascending) of the chunks that become the input sets: the n_sets fastest, or the
+    first n_sets when no probe time stands out by 4 %; None when there are fewer than n_sets."""
+    if len(times) < n_sets:
+        return None
+    if min(times) >= 0.96 * max(times):
+        return list(range(n_sets))
+    order = sorted(range(len(times)), key=lambda q: (times[q], q))
+    return sorted(order[:n_sets])
+
+
 def input_arenas_in_fast_memory(torch, B, hp, cfg, dev, n_sets):
     """Device memory placement.  Device memory on MI355X comes in parts of about 100 GB (in the
     order a fresh process is handed memory), and the update is 9 % slower when the worker vectors
@@ -102,15 +121,11 @@ def input_arenas_in_fast_memory(torch, B, hp, cfg, dev, n_sets):
         vecs = [big[w * cfg.d:(w + 1) * cfg.d] for w in range(cfg.W)]
         chunks.append(big)
         times.append(probe(vecs))
-        ranked = sorted(times)
-        if len(ranked) >= n_sets and ranked[n_sets - 1] <= 1.006 * ranked[0] and ranked[0] < 0.96 * ranked[-1]:
-            break                                    # enough fast chunks, clearly faster than others
-    order = sorted(range(len(times)), key=lambda q: (times[q], q))
-    if len(order) < n_sets:
+        if enough_fast_chunks(times, n_sets):
+            break
+    chosen = choose_chunks(times, n_sets)
+    if chosen is None:
         return None, times, []
-    if sorted(times)[0] >= 0.96 * sorted(times)[-1]:
-        order = list(range(len(times)))              # nothing stands out: plain order
-    chosen = sorted(order[:n_sets])
     arenas = [chunks[q] for q in chosen]
     del chunks, big, vecs
     torch.cuda.empty_cache()

@@ -58,3 +58,21 @@ def test_value_structure():
     g2 = w2.gradient(0, 0).numpy()
     # Student-t(3) * 1e-3: heavier tails than a Gaussian of the same scale
     assert (np.abs(g2) > 5e-3).mean() > 1e-3
+
+
+def test_bench_placement_choice():
+    """The host logic with which bench.py picks, from probe times of successive chunks of device
+    memory, the chunks that hold the input sets (sequences as measured on MI355X)."""
+    import bench
+    fresh = [15.46, 15.47, 15.46, 15.48, 15.46, 15.45, 15.45, 15.01, 13.93, 13.94, 13.94, 13.92]
+    for n in range(1, len(fresh) + 1):
+        assert bench.enough_fast_chunks(fresh[:n], 4) == (n == 12)
+    assert bench.choose_chunks(fresh, 4) == [8, 9, 10, 11]
+    mixed = [14.10, 14.10, 14.89, 14.87, 14.01, 14.11, 14.16, 14.08, 14.26, 14.25, 14.24, 13.96, 13.92, 14.13]
+    assert not bench.enough_fast_chunks(mixed, 4)            # the four fastest are not alike
+    assert bench.choose_chunks(mixed, 4) == [4, 7, 11, 12]
+    alike = [44.4, 44.2, 44.3, 44.6, 44.3, 44.0, 45.0, 45.2, 45.5, 44.3, 44.0]
+    assert not bench.enough_fast_chunks(alike, 2)
+    assert bench.choose_chunks(alike, 2) == [0, 1]           # nothing stands out: plain order
+    assert bench.choose_chunks([15.4, 13.9], 4) is None      # fewer chunks than input sets
+    assert bench.choose_chunks([15.4, 13.9], 1) == [1]
