@@ -132,6 +132,46 @@ def input_arenas_in_fast_memory(torch, B, hp, cfg, dev, n_sets):
     return arenas, times, chosen
 
 
+def placement_scan(torch, B, cfg, dev, tables_after):
+    """Evidence for the placement step (--placement-scan): allocates the worker tables, then
+    arenas of one input set's size one after the other, keeping them all, and times the update
+    and the plain read on each; with tables_after > 0 the tables are allocated only after that
+    many arenas.  Prints one line per arena."""
+    p = B.cs_params_init(cfg.r, cfg.c, cfg.hash_seed, cfg.d)
+    out = torch.zeros(1, dtype=torch.float32, device=dev)
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    arenas, T = [], None
+    q = 0
+    while True:
+        free_bytes, _total = torch.cuda.mem_get_info()
+        if free_bytes < 4 * cfg.d * cfg.W + (16 << 30) or q >= 18:
+            break
+        if T is None and q >= tables_after:
+            T = torch.zeros(B.cs_bundle_floats(p, cfg.W), dtype=torch.float32, device=dev)
+            print(f"tables allocated after {q} arenas", flush=True)
+        big = torch.empty(cfg.d * cfg.W, dtype=torch.float32, device=dev)
+        big.normal_(0.0, 0.01)
+        arenas.append(big)
+        q += 1
+        if T is None:
+            continue
+        for first in range(len(arenas) - 1 if tables_after == 0 or q > tables_after + 1 else 0, len(arenas)):
+            a = arenas[first]
+            vecs = [a[w * cfg.d:(w + 1) * cfg.d] for w in range(cfg.W)]
+            B.cs_sketch_accumulate_bundle(p, T, vecs)
+            e[0].record()
+            for _ in range(4):
+                B.cs_sketch_accumulate_bundle(p, T, vecs)
+            e[1].record()
+            for _ in range(4):
+                B.cs_probe_stream_read(vecs, out)
+            e[2].record()
+            torch.cuda.synchronize()
+            print(f"arena {first} ({first * 4 * cfg.d * cfg.W / 1e9:.0f} GB of arenas before it): "
+                  f"update {e[0].elapsed_time(e[1]) / 4:.3f} ms, plain read "
+                  f"{4 * cfg.d * cfg.W / (e[1].elapsed_time(e[2]) / 4) / 1e9:.2f} TB/s", flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -152,6 +192,10 @@ def main():
     ap.add_argument("--plain-placement", action="store_true",
                     help="allocate the inputs in the plain order of a fresh process, without "
                          "first looking for the device memory where the update runs fastest")
+    ap.add_argument("--placement-scan", type=int, default=None, metavar="N",
+                    help="instead of the benchmark: time the update and the plain read on arenas "
+                         "allocated one after the other, the worker tables being allocated after "
+                         "the first N arenas (0: before all of them)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known HBM traffic) "
                          "so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE can be scaled")
@@ -172,6 +216,9 @@ def main():
         sys.exit(1)
     dev = "cuda:0"
     cfg = wl.CONFIGS[args.config]
+    if args.placement_scan is not None:
+        placement_scan(torch, B, cfg, dev, args.placement_scan)
+        return
     work = wl.Workload(cfg, dev)
     variant = args.variant
     if variant == "dense-state":
