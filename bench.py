@@ -3,9 +3,13 @@
 A step is one pass of the whole path over one batch of W synthetic worker gradients that are
 already resident in HBM: W Count-Sketch updates, merge, sketch-space momentum / error
 accumulation, estimate of every coordinate, top-k, exact second-round gather, sketch-space
-feedback.  Prints ONE JSON line (see the keys below).
+feedback.  Prints ONE JSON line (see the keys below).  Before the inputs are allocated, the
+placement step (input_arenas_in_fast_memory) looks for the device memory in which the update runs
+fastest against the step's own tables; --plain-placement skips it, --placement-scan N prints the
+measurement behind it instead of running the benchmark.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu-baseline]
+                    [--variant V] [--graph] [--plain-placement] [--placement-scan N]
 """
 from __future__ import annotations
 
