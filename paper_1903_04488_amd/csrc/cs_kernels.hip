@@ -277,15 +277,16 @@ struct MergePtrs {
     const float* src[kMaxMerge];
 };
 
-// dst = beta * dst + alpha * (src[0] + src[1] + ...), the sum taken in ascending order.
+// dst = beta * dst + alpha * (src[0] + src[1] + ...), the sum taken in ascending order in
+// binary64 and the result rounded to binary32 once (see k_bundle_merge for why).
 __global__ void __launch_bounds__(kBlock)
 k_merge(float* __restrict__ dst, float beta, MergePtrs ptrs, int nw, float alpha, int64_t n) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
     for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < n; t += stride) {
-        float s = ptrs.src[0][t];
-        for (int w = 1; w < nw; ++w) s += ptrs.src[w][t];
-        const float base = (beta == 0.0f) ? 0.0f : beta * dst[t];
-        dst[t] = base + alpha * s;
+        double s = static_cast<double>(ptrs.src[0][t]);
+        for (int w = 1; w < nw; ++w) s += static_cast<double>(ptrs.src[w][t]);
+        const double base = (beta == 0.0f) ? 0.0 : static_cast<double>(beta) * static_cast<double>(dst[t]);
+        dst[t] = static_cast<float>(base + static_cast<double>(alpha) * s);
     }
 }
 

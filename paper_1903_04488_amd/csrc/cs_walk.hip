@@ -918,23 +918,29 @@ __global__ void __launch_bounds__(kBlock) k_bundle_zero(float4* __restrict__ T4,
 }
 
 // one thread per cell: adds the 8 slots of every group (32 contiguous bytes per group, and
-// neighbouring lanes read neighbouring cells, so every load instruction is coalesced)
+// neighbouring lanes read neighbouring cells, so every load instruction is coalesced).
+// The sum over workers is accumulated in binary64 and rounded to binary32 once, together with
+// alpha and beta.  A binary32 running sum of W values of similar size loses up to log2(W) bits
+// on cells that hold a heavy coordinate; with momentum and error feedback kept as sketches
+// that loss is fed back every step and grows (measured at W = 256: the state cells drift
+// past 1e-5 of their operands within 8 steps).  The kernel waits on its reads either way.
 __global__ void __launch_bounds__(kBlock)
 k_bundle_merge(float* __restrict__ dst, float beta, const float4* __restrict__ T4, int groups,
                float alpha, int64_t cells) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
     for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < cells; t += stride) {
-        float s = 0.0f;
+        double s = 0.0;
         for (int g = 0; g < groups; ++g) {
             const float4* src = T4 + (static_cast<size_t>(g) * cells + t) * (kGroup / 4);
 #pragma unroll
             for (int q = 0; q < kGroup / 4; ++q) {
                 const float4 u = src[q];
-                s += (u.x + u.y) + (u.z + u.w);
+                s += (static_cast<double>(u.x) + static_cast<double>(u.y)) +
+                     (static_cast<double>(u.z) + static_cast<double>(u.w));
             }
         }
-        const float base = (beta == 0.0f) ? 0.0f : beta * dst[t];
-        dst[t] = base + alpha * s;
+        const double base = (beta == 0.0f) ? 0.0 : static_cast<double>(beta) * static_cast<double>(dst[t]);
+        dst[t] = static_cast<float>(base + static_cast<double>(alpha) * s);
     }
 }
 
@@ -946,17 +952,19 @@ k_bundle_merge16(float* __restrict__ dst, float beta, const uint4* __restrict__ 
     static_assert(kGroup == 8, "8 cells of 16 bits are one 16-byte load");
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
     for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < cells; t += stride) {
-        float s = 0.0f;
+        double s = 0.0;
         for (int g = 0; g < groups; ++g) {
             const uint4 q = T16[static_cast<size_t>(g) * cells + t];
             const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
             for (int h = 0; h < 4; h += 2)
-                s += (from_16<FMT>(static_cast<uint16_t>(w[h])) + from_16<FMT>(static_cast<uint16_t>(w[h] >> 16))) +
-                     (from_16<FMT>(static_cast<uint16_t>(w[h + 1])) + from_16<FMT>(static_cast<uint16_t>(w[h + 1] >> 16)));
+                s += (static_cast<double>(from_16<FMT>(static_cast<uint16_t>(w[h]))) +
+                      static_cast<double>(from_16<FMT>(static_cast<uint16_t>(w[h] >> 16)))) +
+                     (static_cast<double>(from_16<FMT>(static_cast<uint16_t>(w[h + 1]))) +
+                      static_cast<double>(from_16<FMT>(static_cast<uint16_t>(w[h + 1] >> 16))));
         }
-        const float base = (beta == 0.0f) ? 0.0f : beta * dst[t];
-        dst[t] = base + alpha * s;
+        const double base = (beta == 0.0f) ? 0.0 : static_cast<double>(beta) * static_cast<double>(dst[t]);
+        dst[t] = static_cast<float>(base + static_cast<double>(alpha) * s);
     }
 }
 

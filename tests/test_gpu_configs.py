@@ -17,24 +17,29 @@ import torch
 import workloads as wl
 from oracle import cs_oracle as orc
 from paper_1903_04488_amd.pipeline import DenseStatePath, GraphedStep, HotPath
-from parity_util import assert_cells_close, assert_valid_topk, assert_values_close
+from parity_util import (assert_cells_close, assert_valid_topk, assert_values_close, cancelled_cells,
+                         estimate_in_slices, estimate_sparse_in_slices, host_sum_f64,
+                         operand_scale_all, operand_scale_at, sketch_in_slices)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
 def host_sum(g_w):
-    acc = np.zeros(g_w[0].numel(), dtype=np.float64)
-    for g in g_w:
-        acc += g.cpu().numpy()
-    return acc
+    return host_sum_f64(g_w)
 
 
 def rms(T):
     return float(np.sqrt((np.asarray(T) ** 2).mean()))
 
 
-def run(config, steps, check_workers=(0,), sample_only_after_first=False, log=print):
+def run(config, steps, check_workers=(0,), workers_first_step_only=False, full_steps=None, log=print):
+    """`steps` steps of the path on the device and in the reference, everything compared.
+    check_workers: whose own table is compared with the sketch of that worker's vector (at
+    step 0 only with workers_first_step_only).  full_steps: the steps at which every
+    coordinate's estimate is compared and the selection is judged on all of them (None: every
+    step); at the other steps the selected coordinates and a sample of 2 M others are.
+    One line per step reports the worst error of each comparison as a fraction of its bound."""
     c = config
     work = wl.Workload(c, DEV)
     hp = HotPath(c.d, c.W, c.r, c.c, c.k, c.hash_seed, rho=c.rho, device=DEV)
@@ -48,60 +53,75 @@ def run(config, steps, check_workers=(0,), sample_only_after_first=False, log=pr
     mag_v = np.zeros((c.r, c.c))
     for t in range(steps):
         log(f"[cfg{c.cfg}] step {t}: d={c.d} W={c.W} r={c.r} c={c.c} k={c.k}", flush=True)
+        worst = {}
         g_w = [work.gradient(t, w) for w in range(c.W)]
         # ---- worker sketches
         hp.accumulate(g_w)
-        for w in check_workers:
-            ref_w = sk.sketch(g_w[w].cpu().numpy())
-            assert_cells_close(hp.worker_table(w).cpu().numpy(), ref_w, what=f"step {t} worker {w} table")
+        if t == 0 or not workers_first_step_only:
+            for w in check_workers:
+                ref_w = sketch_in_slices(sk, g_w[w].cpu().numpy())
+                worst[f"table{w}"] = assert_cells_close(hp.worker_table(w).cpu().numpy(), ref_w,
+                                                        what=f"step {t} worker {w} table")
         # ---- aggregate
         hp.merge()
         gsum = host_sum(g_w)
-        S_t = sk.sketch(gsum, scale=1.0 / c.W)
-        assert_cells_close(hp.S_t.cpu().numpy(), S_t, what=f"step {t} merged table")
+        S_t = sketch_in_slices(sk, gsum, scale=1.0 / c.W)
+        worst["S_t"] = assert_cells_close(hp.S_t.cpu().numpy(), S_t, what=f"step {t} merged table")
         # ---- momentum / error accumulation in sketch space
         if st is not None:
             hp.momentum()
             st.momentum(S_t)
             mag_u = np.maximum(mag_u * st.rho, np.abs(st.S_u))
             mag_v = np.maximum(mag_v, np.abs(st.S_v))
-            assert_cells_close(hp.S_u.cpu().numpy(), st.S_u, what=f"step {t} S_u", operand_mag=mag_u)
-            assert_cells_close(hp.S_v.cpu().numpy(), st.S_v, what=f"step {t} S_v", operand_mag=mag_v)
+            worst["S_u"] = assert_cells_close(hp.S_u.cpu().numpy(), st.S_u, what=f"step {t} S_u", operand_mag=mag_u)
+            worst["S_v"] = assert_cells_close(hp.S_v.cpu().numpy(), st.S_v, what=f"step {t} S_v", operand_mag=mag_v)
             if dense is not None:
                 dense.momentum(gsum / c.W)
         query = st.S_v if st is not None else S_t
         sigma = rms(query)
+        # state cells that a feedback has cancelled a heavy value out of: estimates that read
+        # them are compared relative to the operands of that cancellation, as the cells are
+        left_v = cancelled_cells(mag_v, st.S_v) if st is not None else None
+        left_u = cancelled_cells(mag_u, st.S_u) if st is not None else None
         # ---- query every coordinate, choose the largest
         hp.estimate()
         hp.topk()
         idx = hp.idx.cpu().numpy()
-        if t == 0 or not sample_only_after_first:
-            est_ref = sk.estimate(query, c.d)
-            assert_values_close(hp.est.cpu().numpy(), est_ref, sigma, what=f"step {t} estimates")
-            swapped_total += assert_valid_topk(idx, est_ref, c.k, sigma, what=f"step {t} top-k")
+        est_gpu = hp.est.cpu().numpy()
+        if full_steps is None or t in full_steps:
+            est_ref = estimate_in_slices(sk, query, c.d)
+            worst["est"] = assert_values_close(est_gpu, est_ref, sigma, what=f"step {t} estimates",
+                                               operand_mag=operand_scale_all(sk, left_v, c.d) if st is not None else None)
+            swapped = assert_valid_topk(idx, est_ref, c.k, sigma, what=f"step {t} top-k")
+            swapped_total += swapped
+            worst["near-tie swaps"] = swapped
+            del est_ref
         else:
-            # sampled form of the same checks: all selected magnitudes are at least the
-            # smallest selected one (trivially) and within tolerance of the reference; a large
-            # random sample of unselected coordinates lies below that threshold (+ eps)
-            est_gpu = hp.est.cpu().numpy()
-            sel_ref = sk.estimate_sparse(query, idx)
-            assert_values_close(est_gpu[idx], sel_ref, sigma, what=f"step {t} selected estimates")
+            # sampled form of the same checks: the selected estimates are within tolerance of
+            # the reference; a large random sample of unselected coordinates lies below the
+            # smallest selected magnitude (+ eps)
+            sel_ref = estimate_sparse_in_slices(sk, query, idx)
+            worst["est[idx]"] = assert_values_close(est_gpu[idx], sel_ref, sigma, what=f"step {t} selected estimates",
+                                                    operand_mag=operand_scale_at(sk, left_v, idx) if st is not None else None)
             theta = np.abs(sel_ref).min()
             rng = np.random.default_rng(t)
             probe = rng.integers(0, c.d, size=2_000_000)
-            probe_ref = sk.estimate_sparse(query, probe)
-            assert_values_close(est_gpu[probe], probe_ref, sigma, what=f"step {t} sampled estimates")
+            probe_ref = estimate_sparse_in_slices(sk, query, probe)
+            worst["est[sample]"] = assert_values_close(est_gpu[probe], probe_ref, sigma,
+                                                       what=f"step {t} sampled estimates",
+                                                       operand_mag=operand_scale_at(sk, left_v, probe) if st is not None else None)
             chosen = np.zeros(c.d, dtype=bool)
             chosen[idx] = True
             eps = 2e-5 * max(theta, sigma)
             assert (np.abs(probe_ref[~chosen[probe]]) <= theta + eps).all()
             assert idx.shape == (c.k,) and (np.diff(idx) > 0).all()
-        np.testing.assert_array_equal(hp.est_at_idx.cpu().numpy(), hp.est.cpu().numpy()[idx])
+        np.testing.assert_array_equal(hp.est_at_idx.cpu().numpy(), est_gpu[idx])
+        del est_gpu
         # ---- second round
         hp.gather(g_w)
         x_ref = gsum[idx] / c.W
-        assert_values_close(hp.x.cpu().numpy(), x_ref, float(np.sqrt((gsum ** 2).mean())) / c.W + 1e-30,
-                            what=f"step {t} exact values")
+        worst["x"] = assert_values_close(hp.x.cpu().numpy(), x_ref, float(np.sqrt((gsum ** 2).mean())) / c.W + 1e-30,
+                                         what=f"step {t} exact values")
         # ---- feedback (the reference adopts the device's valid selection)
         if st is not None:
             hp.feedback()
@@ -113,12 +133,14 @@ def run(config, steps, check_workers=(0,), sample_only_after_first=False, log=pr
                 bj = bkt[j].astype(np.int64)
                 mag_v[j] = np.maximum(mag_v[j], np.bincount(bj, weights=np.abs(delta), minlength=c.c))
                 mag_u[j] = np.maximum(mag_u[j], np.bincount(bj, weights=np.abs(uhat), minlength=c.c))
-            assert_values_close(hp.delta.cpu().numpy(), delta, sigma, what=f"step {t} delta")
-            assert_values_close(hp.uhat.cpu().numpy(), uhat, rms(st.S_u) + 1e-30, what=f"step {t} uhat")
-            assert_cells_close(hp.S_u.cpu().numpy(), st.S_u, what=f"step {t} S_u after feedback",
-                               operand_mag=mag_u)
-            assert_cells_close(hp.S_v.cpu().numpy(), st.S_v, what=f"step {t} S_v after feedback",
-                               operand_mag=mag_v)
+            worst["delta"] = assert_values_close(hp.delta.cpu().numpy(), delta, sigma, what=f"step {t} delta",
+                                                 operand_mag=operand_scale_at(sk, left_v, idx))
+            worst["uhat"] = assert_values_close(hp.uhat.cpu().numpy(), uhat, rms(st.S_u) + 1e-30, what=f"step {t} uhat",
+                                                operand_mag=operand_scale_at(sk, left_u, idx))
+            worst["S_u fb"] = assert_cells_close(hp.S_u.cpu().numpy(), st.S_u, what=f"step {t} S_u after feedback",
+                                                 operand_mag=mag_u)
+            worst["S_v fb"] = assert_cells_close(hp.S_v.cpu().numpy(), st.S_v, what=f"step {t} S_v after feedback",
+                                                 operand_mag=mag_v)
             if dense is not None:
                 dense.feedback(idx, delta, uhat)
                 # the device tables are the sketch of a well-defined dense state (linearity)
@@ -126,7 +148,9 @@ def run(config, steps, check_workers=(0,), sample_only_after_first=False, log=pr
                                    operand_mag=mag_v)
                 assert_cells_close(hp.S_u.cpu().numpy(), sk.sketch(dense.u), what=f"step {t} S(u)",
                                    operand_mag=mag_u)
-        del g_w
+        log(f"[cfg{c.cfg}] step {t} worst error / bound: "
+            + ", ".join(f"{name} {val:.3g}" for name, val in worst.items()), flush=True)
+        del g_w, gsum
     return swapped_total, work, hp
 
 
@@ -166,13 +190,21 @@ def test_config3_full():
 
 
 @pytest.mark.timeout(1500)
-def test_config4_full_two_steps():
-    run(wl.CONFIGS[4], 2, check_workers=(31,), sample_only_after_first=True)
+def test_config4_full_ten_steps():
+    """d = 10^8, W = 32, momentum and error feedback in sketch space over all 10 steps; every
+    coordinate's estimate and the whole selection are checked at every step."""
+    c = wl.CONFIGS[4]
+    assert c.steps == 10
+    run(c, c.steps, check_workers=(31,), workers_first_step_only=True)
 
 
 @pytest.mark.timeout(1500)
-def test_config5_full_two_steps():
-    run(wl.CONFIGS[5], 2, check_workers=(255,), sample_only_after_first=True)
+def test_config5_full_twenty_steps():
+    """d = 2.5 * 10^7, W = 256, all 20 steps with sketch-space state, complete checks at
+    every step."""
+    c = wl.CONFIGS[5]
+    assert c.steps == 20
+    run(c, c.steps, check_workers=(255,), workers_first_step_only=True)
 
 
 # ----------------------------------------------------------------------------- P > 1
