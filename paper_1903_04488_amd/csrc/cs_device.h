@@ -141,27 +141,30 @@ __device__ __forceinline__ bool segment_sum16(uint32_t key, float& v, int nsteps
     return row_shl1(head, 1u) != 0u;                         // next lane starts a new run
 }
 
-// median of an odd number R of floats held in registers (compile-time R): odd-even
-// transposition sort, fully unrolled, then the middle element.
+// Median of an odd number R of floats held in registers (compile-time R), as Alg. 4's estimate
+// takes it: sort, then the middle element.  The sort is an insertion sort written as a fixed
+// sequence of compare-exchanges on "left > right": element x is exchanged downwards through
+// the sorted prefix; once a comparison fails the remaining ones of that pass compare
+// neighbours of the prefix, which are in order, and change nothing.  With ordinary numbers
+// any sorting network gives the same middle element; with a NaN among the values (every
+// comparison with it is false) the result depends on the sequence of comparisons, and this
+// sequence is the one a plain insertion sort with ">" makes: a NaN stays where it was put and
+// blocks what lies above it from moving down.  Infinities order as usual; -0 and +0 compare
+// equal and keep their order.
 template <int R>
 __device__ __forceinline__ float median_odd(float (&v)[R]) {
-    if constexpr (R == 1) {
-        return v[0];
-    } else if constexpr (R == 3) {
-        return fmaxf(fminf(v[0], v[1]), fminf(fmaxf(v[0], v[1]), v[2]));
-    } else {
 #pragma unroll
-    for (int pass = 0; pass < R; ++pass) {
+    for (int x = 1; x < R; ++x) {
 #pragma unroll
-        for (int x = pass & 1; x + 1 < R; x += 2) {
-            const float lo = fminf(v[x], v[x + 1]);
-            const float hi = fmaxf(v[x], v[x + 1]);
-            v[x] = lo;
-            v[x + 1] = hi;
+        for (int y = x - 1; y >= 0; --y) {
+            const bool exchange = v[y] > v[y + 1];
+            const float lo = exchange ? v[y + 1] : v[y];
+            const float hi = exchange ? v[y] : v[y + 1];
+            v[y] = lo;
+            v[y + 1] = hi;
         }
     }
     return v[R / 2];
-    }
 }
 
 }  // namespace cs

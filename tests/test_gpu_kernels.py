@@ -357,6 +357,45 @@ def test_estimate_long_vector_bit_exact(r, c, seed, d, i0):
     np.testing.assert_array_equal(est.cpu().numpy(), ref.astype(np.float32))
 
 
+@pytest.mark.parametrize("r,c,seed,d", [(5, 1 << 12, 21, 300_007),          # median pass over stored rows
+                                        (7, 1 << 10, 22, (1 << 24) + 33),  # median inside the last row's walk
+                                        (5, 1000, 23, 50_001),             # one thread per coordinate
+                                        (15, 180, 24, 20_003), (3, 64, 25, 4_099)])
+def test_estimate_with_nan_and_infinite_cells(r, c, seed, d):
+    """Alg. 4's estimate when the table holds NaN and infinities (a diverged run): the median is
+    the middle of the r signed cells after a sort, and with a NaN among them the sort's own
+    sequence of comparisons decides what ends up in the middle.  The device makes the comparisons
+    the reference's insertion sort makes, so NaN appears in exactly the same estimates and every
+    other estimate is equal bit for bit (signed zeros included)."""
+    p = cs.cs_params_init(r, c, seed, d)
+    sk = orc.SketchOracle(r, c, seed)
+    rng = np.random.default_rng(seed)
+    T32 = rng.standard_normal((r, c)).astype(np.float32)
+    flat = T32.reshape(-1)
+    n = flat.size
+    for value, share in [(np.nan, 0.08), (np.inf, 0.05), (-np.inf, 0.05), (0.0, 0.05), (-0.0, 0.05)]:
+        flat[rng.choice(n, size=max(1, int(share * n)), replace=False)] = value
+    S = dev(T32)
+    est = torch.empty(d, dtype=torch.float32, device=DEV)
+    n_ws = cs.cs_estimate_workspace_bytes(p, d)
+    ws = torch.empty(n_ws, dtype=torch.uint8, device=DEV) if n_ws else None
+    cs.cs_sketch_estimate(p, S, est, i0=0, workspace=ws)
+    ref = sk.estimate(T32.astype(np.float64), d).astype(np.float32)
+    got = est.cpu().numpy()
+    assert np.isnan(ref).any() and np.isinf(ref).any()
+
+    def same(a, b, what):
+        np.testing.assert_array_equal(np.isnan(a), np.isnan(b), err_msg=what)
+        ok = ~np.isnan(b)
+        np.testing.assert_array_equal(a[ok].view(np.uint32), b[ok].view(np.uint32), err_msg=what)
+
+    same(got, ref, "all coordinates")
+    idx = rng.integers(0, d, size=5000)
+    out = torch.empty(idx.size, dtype=torch.float32, device=DEV)
+    cs.cs_sketch_estimate_sparse(p, S, dev(idx), out)
+    same(out.cpu().numpy(), ref[idx], "listed coordinates")
+
+
 # ------------------------------------------------------------------------------ top-k
 def run_topk(est32, k):
     d = est32.size
@@ -386,6 +425,41 @@ def test_topk_exact(d, k, kind):
     idx, val = run_topk(est, k)
     np.testing.assert_array_equal(idx, want)
     np.testing.assert_array_equal(val.view(np.uint32), est[want].view(np.uint32))
+
+
+@pytest.mark.parametrize("case", ["spread", "one block full of heavy entries", "unaligned", "all in one bin"])
+def test_topk_candidate_list_and_five_pass_form_agree(case):
+    """With room for a candidate list in the workspace the selection reads est twice, without it
+    five times; both must return the reference's selection.  Covered: the ordinary case, a
+    stretch of heavy entries longer than one block can stage (the list is abandoned on the
+    device and the five-pass form takes over), an input at an odd dword address, and
+    magnitudes that all fall into the bin of the k-th largest (the list overflows as a whole)."""
+    rng = np.random.default_rng(len(case))
+    d, k = 20_000_003, 30_000
+    est = (rng.standard_normal(d) * 0.01).astype(np.float32)
+    if case == "one block full of heavy entries":
+        est[7_000_000:7_009_000] = rng.uniform(0.5, 1.0, size=9000).astype(np.float32)
+    elif case == "all in one bin":
+        est = rng.uniform(1.0, 1.05, size=d).astype(np.float32) * rng.choice([-1.0, 1.0], size=d).astype(np.float32)
+    elif case == "unaligned":
+        d, k = 700_001, 500
+        est = est[:d].copy()
+    want = orc.topk_threshold(est, k)
+    base = torch.empty(d + 1, dtype=torch.float32, device=DEV)
+    off = 1 if case == "unaligned" else 0
+    view = base[off:off + d]
+    view.copy_(dev(est))
+    full = cs.cs_topk_workspace_bytes(d, k)
+    bare = cs.cs_topk_workspace_bytes(1, 1)            # the fixed part alone: no list
+    assert full > bare + 12 * (2 * k + 4096)
+    for nbytes in (full, bare):
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+        ws.fill_(0x5C)
+        idx = torch.full((k,), -1, dtype=torch.int64, device=DEV)
+        val = torch.empty(k, dtype=torch.float32, device=DEV)
+        cs.cs_heavy_hitters_topk(view, k, idx, val, ws)
+        np.testing.assert_array_equal(idx.cpu().numpy(), want)
+        np.testing.assert_array_equal(val.cpu().numpy().view(np.uint32), est[want].view(np.uint32))
 
 
 def test_topk_extreme_values_and_unaligned_input():
