@@ -117,7 +117,12 @@ typedef struct cs_params {
 
 /* Alg. 4 init: fills *p for an r x c sketch from `seed` (host, no GPU needed).
  * `d_hint` is the vector length the sketch will mostly be used with (0 = unknown); it only
- * steers the traversal plan.  CS_EINVAL: p null, r even or outside 1..CS_MAX_R, c == 0,
+ * steers the traversal plan.  Cost: the plan is found by scanning, per row, every candidate
+ * stride up to d_hint / 2 and every offset below d_hint (capped at 2^28 each), about 3.5 ns per
+ * coordinate of d_hint and row on one host core: 1.7 s for r = 5, d_hint = 10^8; a few
+ * milliseconds for d_hint = 0 or vectors below 10^6.  Call it once per sketch shape and keep
+ * the struct.  Vectors longer than 2^28 get no visit list (the stride walk serves them).
+ * CS_EINVAL: p null, r even or outside 1..CS_MAX_R, c == 0,
  * c > 2^31 or r * c >= 2^32 (a 16 GiB table). */
 int cs_params_init(cs_params* p, uint32_t r, uint32_t c, uint64_t seed, int64_t d_hint);
 
@@ -165,7 +170,11 @@ int cs_sketch_accumulate_batch(const cs_params* p, float* const* S_w, const floa
  *                        that owns both can time the call on candidate buffers and choose.)
  * cs_bundle_merge:       dst[j][b] = beta * dst[j][b] + alpha * sum_{w<W} S^w[j][b]
  *                        (the aggregation step of Alg. 3 with alpha = 1/W); dst: device
- *                        float[r][c], not read when beta == 0; fp32 sum in a fixed order.
+ *                        float[r][c], not read when beta == 0; the sum over workers is
+ *                        accumulated in binary64 in a fixed order and the result rounded to
+ *                        binary32 once (a binary32 running sum over hundreds of workers loses
+ *                        bits that momentum and error feedback in sketch space feed back
+ *                        every step).
  * The bundle must be below 2^40 floats and 16-byte aligned. */
 #define CS_BUNDLE_GROUP 8
 int cs_bundle_floats(const cs_params* p, int32_t W, int64_t* n);
@@ -190,7 +199,7 @@ int cs_sketch_accumulate_sparse(const cs_params* p, float* S, const int64_t* idx
  *     dst = beta * dst + alpha * sum_{w<W} src[w]
  * dst: device float[r][c]; with beta == 0 it is not read.  src: HOST array of W device
  * pointers; dst may not alias any src[w] unless W == 1.  The sum over w is taken in
- * ascending w in fp32. */
+ * ascending w in binary64 and the result is rounded to binary32 once. */
 int cs_sketch_merge(const cs_params* p, float* dst, float beta, const float* const* src,
                     int32_t W, float alpha, void* stream);
 
@@ -208,6 +217,10 @@ int cs_sketch_momentum(const cs_params* p, float* S_u, float* S_v, const float* 
  * coordinates rather than running a heavy-hitter search):
  *     est[t] = median_{j<r} s_j(i0 + t) * S[j][h_j(i0 + t)]       t in [0, d)
  * S: device float[r][c]; est: device float[d].
+ * The median is the middle of the r signed cells after an insertion sort on ">" (what a plain
+ * reading of Alg. 4 does).  Infinite cells order as usual.  A NaN cell compares false with
+ * everything, so it stays where the sort put it and the estimate is NaN exactly when that
+ * position is the middle one; this is a deterministic function of the r values in row order.
  * rows_ws: device scratch of cs_estimate_workspace_bytes(p, d) bytes (may be NULL when that
  * size is 0).  */
 int cs_estimate_workspace_bytes(const cs_params* p, int64_t d, size_t* bytes);
@@ -223,8 +236,12 @@ int cs_sketch_estimate_sparse(const cs_params* p, const float* S, const int64_t*
  * largest |est[t]|; equal magnitudes are resolved towards the lower index; the result is in
  * ascending index order.  idx_out: device int64[k] (index t, NOT offset by any i0);
  * val_out: device float[k], val_out[n] = est[idx_out[n]] (may be NULL).
- * workspace: device, at least cs_topk_workspace_bytes(d, k) bytes, contents irrelevant on
- * entry.  1 <= k <= d. */
+ * workspace: device, 8-byte aligned, contents irrelevant on entry.  cs_topk_workspace_bytes(d, k)
+ * is what makes the call fastest: about 114 KiB of histograms and counters plus, when k is
+ * small against d, room for a list of 8 k + 65 536 candidates (12 bytes each), with which est
+ * is read twice instead of five times.  Any size from cs_topk_workspace_bytes(1, 1) (the fixed
+ * part alone) upwards is accepted and gives the same result; below that CS_EWORKSPACE.
+ * 1 <= k <= d. */
 int cs_topk_workspace_bytes(int64_t d, int64_t k, size_t* bytes);
 int cs_heavy_hitters_topk(const float* est, int64_t d, int64_t k,
                           int64_t* idx_out, float* val_out,
@@ -256,7 +273,8 @@ int cs_select_exact_topk(const int64_t* cand, const float* x, int64_t n, int64_t
  * cs_quantize16 / cs_dequantize16: elementwise over n values (a table float[r][c] or a whole
  *   worker bundle -- the layout is kept).  x, out, q: device.
  * cs_bundle_merge16: cs_bundle_merge reading a quantised bundle (uint16[ceil(W/8)][r][c][8],
- *   16-byte aligned): dst = beta * dst + alpha * sum_w value(S16^w); fp32 sum, fixed order. */
+ *   16-byte aligned): dst = beta * dst + alpha * sum_w value(S16^w); binary64 sum in a
+ *   fixed order, rounded once. */
 #define CS_FMT_BF16 0
 #define CS_FMT_F16 1
 int cs_quantize16(const float* x, int64_t n, uint16_t* out, int32_t fmt, void* stream);

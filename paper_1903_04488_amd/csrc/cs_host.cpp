@@ -12,6 +12,11 @@ namespace {
 constexpr uint64_t kP61 = (1ull << 61) - 1;
 typedef unsigned __int128 u128;
 
+// The traversal plans are found by scanning candidate strides / offsets one by one (about a
+// nanosecond each).  The scans stop here, so that cs_params_init returns in seconds whatever
+// d_hint is: a longer vector gets the best stride below the cap and no visit list.
+constexpr uint64_t kPlanScanMax = 1ull << 28;
+
 // SplitMix64 (Steele, Lea, Flood 2014): the generator that the hash constants are drawn from.
 uint64_t splitmix64(uint64_t* s) {
     uint64_t z = (*s += 0x9E3779B97F4A7C15ull);
@@ -93,7 +98,7 @@ void plan_walk(cs_row_plan* rp, uint64_t a, uint64_t as, uint32_t c, bool pow2, 
     uint64_t best_D = 1;
     if (pow2 && c >= 64) {
         const uint64_t d_eff = d_hint ? d_hint : 64ull * c;
-        const uint64_t d_max = d_eff / 2;
+        const uint64_t d_max = d_eff / 2 < kPlanScanMax ? d_eff / 2 : kPlanScanMax;
         double best_cost = 1e300;
         uint64_t x = 0;                                 // (a * D) mod p
         const double inv_p = 1.0 / (double)kP61, inv_d = 1.0 / (double)d_eff;
@@ -143,7 +148,7 @@ double update_time_ns(double visits, double residues, double requests, double d)
 void plan_visits(cs_visit_plan* vp, const cs_row_plan* rp, uint64_t a, uint64_t as, uint32_t c,
                  bool pow2, uint64_t d_hint) {
     memset(vp, 0, sizeof(*vp));
-    if (!pow2 || c < 64 || d_hint < 4096 || d_hint >= (1ull << 40)) return;
+    if (!pow2 || c < 64 || d_hint < 4096 || d_hint > kPlanScanMax) return;
     int lc = 0;
     while ((1u << lc) < c) ++lc;
     const int sh = 61 - lc;

@@ -1,12 +1,22 @@
-// heavy_hitters_topk: "query the sketch for every gradient coordinate, and then choose the
-// largest elements" (Sec. 5.2 of the paper) -- the selection half.
+// heavy_hitters_topk: the selection half of Sec. 5.2 of the paper, where every coordinate is
+// queried and the k estimates of largest magnitude are kept.
 //
 // Exact radix select on the 31-bit magnitude key  bits(est) & 0x7fffffff  (monotone in |est|
-// for IEEE binary32): three histogram passes (11 + 10 + 10 bits) find the key theta of the
+// for IEEE binary32): three histograms (11 + 10 + 10 bits) find the key theta of the
 // k-th largest magnitude and how many entries equal to theta are still needed; an ordered
 // compaction (per-block counts, scan over blocks, write) then emits, in ascending index
 // order, every index with key > theta plus the lowest-index entries with key == theta.
 // Everything is integer work, so the result is a deterministic function of est.
+//
+// Passes over est.  Done plainly that is five reads of est (three histograms, count, write).
+// After the first histogram the bin of the k-th largest key is known, and only entries in that
+// bin or above can be selected: with k << d they are a small multiple of k.  One pass copies
+// them, block by block in index order, into a candidate list (k_topk_compact), and the two
+// remaining histograms, the count and the write run over that list only: two reads of est
+// (one when the caller brings the first histogram, which the estimate kernel can fill as it
+// writes est).  The list has a fixed capacity; if the input does not fit it (many equal
+// magnitudes, k close to d) a flag is raised on the device and the five-pass form, whose
+// kernels are enqueued behind and return at once otherwise, does the work instead.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -26,13 +36,27 @@ struct TopkSel {
     uint64_t k_rem;       // how many of the entries sharing `prefix` are still wanted
 };
 
-// workspace layout (all 8-byte aligned)
+constexpr int kStage = 4096;          // candidates one block can hold in LDS for its chunk
+
+// workspace layout (all 8-byte aligned); the candidate list follows the struct
 struct TopkWs {
     uint64_t hist[3][kBins];
     TopkSel sel;
+    TopkSel sel0;                   // sel as it was after the first histogram (for the fallback)
+    uint32_t failed;                // != 0: the candidate list overflowed, the five-pass form runs
+    uint32_t ncand;                 // candidates appended so far
     uint64_t gt[kMaxSelBlocks];     // per block: entries with key > theta  -> exclusive scan
     uint64_t eq[kMaxSelBlocks];     // per block: entries with key == theta -> exclusive scan
+    uint32_t seg_base[kMaxSelBlocks];    // block b's candidates are cand[seg_base[b] .. + seg_count[b])
+    uint32_t seg_count[kMaxSelBlocks];
 };
+constexpr size_t kCandBytes = sizeof(int64_t) + sizeof(float);   // index and value of a candidate
+
+// candidates worth providing for: a few times k, never a large part of d
+__host__ inline int64_t candidate_capacity_for(int64_t d, int64_t k) {
+    const int64_t want = 8 * k + 65536;
+    return want <= d / 4 ? want : 0;
+}
 
 // Selection keys (31 bits, larger = selected first; equal keys: lower index first).
 // KeyMagnitude: the magnitude bits of the estimate (top-k by |est|).
@@ -74,14 +98,27 @@ __global__ void __launch_bounds__(kBlock) k_topk_clear(TopkWs* ws, uint64_t k) {
         ws->sel.prefix = 0;
         ws->sel.pad = 0;
         ws->sel.k_rem = k;
+        ws->failed = 0;
+        ws->ncand = 0;
     }
+}
+
+// Start of the five-pass form behind a candidate list: nothing to do unless the list
+// overflowed; then the histograms of passes 1 and 2 start empty and the selection state is
+// what the first histogram left.
+__global__ void __launch_bounds__(kBlock) k_topk_fallback_begin(TopkWs* ws) {
+    if (ws->failed == 0) return;
+    for (int t = threadIdx.x; t < 2 * kBins; t += kBlock) (&ws->hist[1][0])[t] = 0;
+    if (threadIdx.x == 0) ws->sel = ws->sel0;
 }
 
 // PASS 0: bin = key >> 20 (2048 bins); PASS 1: entries with key >> 20 == prefix, bin = bits
 // 19..10; PASS 2: entries with key >> 10 == prefix, bin = bits 9..0.
+// `fallback`: the launch stands behind a candidate list and works only if that overflowed.
 template <int PASS, bool VEC, typename KEY>
 __global__ void __launch_bounds__(kBlock)
-k_topk_hist(const float* __restrict__ est, int64_t d, TopkWs* ws, KEY kf) {
+k_topk_hist(const float* __restrict__ est, int64_t d, TopkWs* ws, KEY kf, bool fallback) {
+    if (fallback && ws->failed == 0) return;
     kf.init();
     // Magnitudes crowd into a few of the pass-0 bins (same exponent), and lanes that hit the same
     // LDS word are served one after the other: pass 0 keeps kCopies histograms and lane l adds
@@ -158,12 +195,14 @@ __device__ __forceinline__ uint64_t block_exclusive_sum64(uint64_t v, uint64_t* 
     return before + inc - v;
 }
 
+// hist0: the first histogram when the caller brought it (PASS 0 only), else null.
 template <int PASS>
-__global__ void __launch_bounds__(kBlock) k_topk_find(TopkWs* ws) {
+__global__ void __launch_bounds__(kBlock) k_topk_find(TopkWs* ws, const uint64_t* hist0, bool fallback) {
+    if (fallback && ws->failed == 0) return;
     constexpr int nb = (PASS == 0) ? 2048 : 1024;
     constexpr int per = nb / kBlock;              // bins per thread: 8 or 4
     __shared__ uint64_t wave_sum[kBlock / 64];
-    const uint64_t* h = ws->hist[PASS];
+    const uint64_t* h = (PASS == 0 && hist0) ? hist0 : ws->hist[PASS];
     const uint64_t k_rem = ws->sel.k_rem;
     const uint32_t prefix = ws->sel.prefix;
     uint64_t mine = 0;
@@ -181,6 +220,11 @@ __global__ void __launch_bounds__(kBlock) k_topk_find(TopkWs* ws) {
                 ws->sel.prefix = (PASS == 0) ? static_cast<uint32_t>(bin)
                                              : ((prefix << bits) | static_cast<uint32_t>(bin));
                 ws->sel.k_rem = k_rem - acc;
+                if (PASS == 0) {
+                    ws->sel0.prefix = static_cast<uint32_t>(bin);
+                    ws->sel0.pad = 0;
+                    ws->sel0.k_rem = k_rem - acc;
+                }
                 break;
             }
             acc += cnt;
@@ -236,7 +280,8 @@ __device__ __forceinline__ void load_items(const float* __restrict__ est, int64_
 // per block: how many entries of its chunk are above / equal to theta
 template <bool VEC, typename KEY>
 __global__ void __launch_bounds__(kBlock)
-k_topk_count(const float* __restrict__ est, int64_t d, int64_t chunk, TopkWs* ws, KEY kf) {
+k_topk_count(const float* __restrict__ est, int64_t d, int64_t chunk, TopkWs* ws, KEY kf, bool fallback) {
+    if (fallback && ws->failed == 0) return;
     kf.init();
     __shared__ uint32_t lds[kBlock / 64];
     const uint32_t theta = ws->sel.prefix;
@@ -264,7 +309,8 @@ k_topk_count(const float* __restrict__ est, int64_t d, int64_t chunk, TopkWs* ws
 }
 
 // one workgroup: exclusive scan of the per-block counts, in place
-__global__ void __launch_bounds__(kBlock) k_topk_scan(TopkWs* ws, int nblocks) {
+__global__ void __launch_bounds__(kBlock) k_topk_scan(TopkWs* ws, int nblocks, bool fallback) {
+    if (fallback && ws->failed == 0) return;
     __shared__ uint64_t wave_gt[kBlock / 64], wave_eq[kBlock / 64];
     constexpr int per = kMaxSelBlocks / kBlock;     // 16 consecutive blocks per thread
     uint64_t g[per], e[per], sg = 0, se = 0;
@@ -292,7 +338,8 @@ __global__ void __launch_bounds__(kBlock) k_topk_scan(TopkWs* ws, int nblocks) {
 template <bool VEC, typename KEY>
 __global__ void __launch_bounds__(kBlock)
 k_topk_write(const float* __restrict__ est, int64_t d, int64_t chunk, const TopkWs* ws,
-             int64_t k, int64_t* __restrict__ idx_out, float* __restrict__ val_out, KEY kf) {
+             int64_t k, int64_t* __restrict__ idx_out, float* __restrict__ val_out, KEY kf, bool fallback) {
+    if (fallback && ws->failed == 0) return;
     kf.init();
     __shared__ uint32_t lds[kBlock / 64];
     const uint32_t theta = ws->sel.prefix;
@@ -333,6 +380,176 @@ k_topk_write(const float* __restrict__ est, int64_t d, int64_t chunk, const Topk
         }
         gt_before += total & 0xffffu;
         eq_before += total >> 16;
+    }
+}
+
+
+// The candidate list.  Block b scans its chunk of est (the chunks of the count / write passes)
+// and keeps, in index order, every entry whose key lies in the bin of the k-th largest key or
+// above (sel.prefix after the first histogram): staged in LDS, then appended to the list as
+// one segment whose place comes from a single atomic add.  Segments lie in the list in the
+// order the blocks finished; (seg_base[b], seg_count[b]) lets later kernels visit them in
+// block order, i.e. in index order.  A block with more than kStage candidates, or a list that
+// would exceed `cap`, raises ws->failed.
+template <bool VEC, typename KEY>
+__global__ void __launch_bounds__(kBlock)
+k_topk_compact(const float* __restrict__ est, int64_t d, int64_t chunk, TopkWs* ws, uint32_t cap,
+               int64_t* __restrict__ cand_idx, float* __restrict__ cand_val, KEY kf) {
+    kf.init();
+    __shared__ uint32_t lds[kBlock / 64];
+    __shared__ uint32_t st_off[kStage];
+    __shared__ float st_val[kStage];
+    __shared__ uint32_t seg[2];                     // base, ok
+    const uint32_t bin0 = ws->sel.prefix;
+    const int64_t lo = static_cast<int64_t>(blockIdx.x) * chunk;
+    const int64_t hi = (lo + chunk < d) ? lo + chunk : d;
+    uint32_t staged = 0;                            // the same in every thread
+    bool overflow = false;
+    for (int64_t tile = lo; tile < hi; tile += kTile) {
+        float v[kItems];
+        int nvalid;
+        const int64_t base = tile + static_cast<int64_t>(threadIdx.x) * kItems;
+        load_items<VEC>(est, base, hi, v, nvalid);
+        uint32_t c = 0;
+#pragma unroll
+        for (int q = 0; q < kItems; ++q)
+            if (q < nvalid && (kf(v[q], base + q) >> 20) >= bin0) ++c;
+        uint32_t total;
+        const uint32_t incl = block_inclusive_scan(c, lds, &total);
+        if (staged + total > static_cast<uint32_t>(kStage)) { overflow = true; break; }
+        uint32_t pos = staged + incl - c;
+#pragma unroll
+        for (int q = 0; q < kItems; ++q)
+            if (q < nvalid && (kf(v[q], base + q) >> 20) >= bin0) {
+                st_off[pos] = static_cast<uint32_t>(base + q - lo);
+                st_val[pos] = v[q];
+                ++pos;
+            }
+        staged += total;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t base = 0;
+        bool ok = !overflow;
+        if (ok && staged) {
+            base = atomicAdd(&ws->ncand, staged);
+            ok = static_cast<uint64_t>(base) + staged <= cap;
+        }
+        if (!ok) atomicOr(&ws->failed, 1u);
+        ws->seg_base[blockIdx.x] = base;
+        ws->seg_count[blockIdx.x] = ok ? staged : 0u;
+        seg[0] = base;
+        seg[1] = ok ? 1u : 0u;
+    }
+    __syncthreads();
+    if (seg[1] == 0u) return;
+    const uint32_t base = seg[0];
+    for (uint32_t t = threadIdx.x; t < staged; t += kBlock) {
+        cand_idx[base + t] = lo + st_off[t];
+        cand_val[base + t] = st_val[t];
+    }
+}
+
+// histogram of pass 1 or 2 over the candidate list
+template <int PASS, typename KEY>
+__global__ void __launch_bounds__(kBlock)
+k_cand_hist(TopkWs* ws, const int64_t* __restrict__ cand_idx, const float* __restrict__ cand_val, KEY kf) {
+    static_assert(PASS == 1 || PASS == 2, "the first histogram is taken over est");
+    if (ws->failed != 0) return;
+    kf.init();
+    __shared__ uint32_t lh[1024];
+    for (int t = threadIdx.x; t < 1024; t += kBlock) lh[t] = 0;
+    __syncthreads();
+    const uint32_t prefix = ws->sel.prefix;
+    const uint32_t n = ws->ncand;
+    for (uint32_t t = blockIdx.x * kBlock + threadIdx.x; t < n; t += gridDim.x * kBlock) {
+        const uint32_t key = kf(cand_val[t], cand_idx[t]);
+        if (PASS == 1) {
+            if ((key >> 20) == prefix) atomicAdd(&lh[(key >> 10) & 1023u], 1u);
+        } else {
+            if ((key >> 10) == prefix) atomicAdd(&lh[key & 1023u], 1u);
+        }
+    }
+    __syncthreads();
+    for (int t = threadIdx.x; t < 1024; t += kBlock) {
+        const uint32_t v = lh[t];
+        if (v) atomicAdd(reinterpret_cast<unsigned long long*>(&ws->hist[PASS][t]),
+                         static_cast<unsigned long long>(v));
+    }
+}
+
+// per block of the compaction (one wavefront each): how many of its candidates are above /
+// equal to theta
+template <typename KEY>
+__global__ void __launch_bounds__(kBlock)
+k_cand_count(TopkWs* ws, int nblocks, const int64_t* __restrict__ cand_idx,
+             const float* __restrict__ cand_val, KEY kf) {
+    if (ws->failed != 0) return;
+    kf.init();
+    const int b = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
+    if (b >= nblocks) return;
+    const int lane = threadIdx.x & 63;
+    const uint32_t theta = ws->sel.prefix;
+    const uint32_t base = ws->seg_base[b], n = ws->seg_count[b];
+    uint32_t n_gt = 0, n_eq = 0;
+    for (uint32_t t = lane; t < n; t += 64) {
+        const uint32_t key = kf(cand_val[base + t], cand_idx[base + t]);
+        n_gt += key > theta ? 1u : 0u;
+        n_eq += key == theta ? 1u : 0u;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        n_gt += __shfl_down(n_gt, off, 64);
+        n_eq += __shfl_down(n_eq, off, 64);
+    }
+    if (lane == 0) {
+        ws->gt[b] = n_gt;
+        ws->eq[b] = n_eq;
+    }
+}
+
+// ordered write from the candidate list: the rule of k_topk_write, one wavefront per block
+// of the compaction, 64 candidates at a time
+template <typename KEY>
+__global__ void __launch_bounds__(kBlock)
+k_cand_write(const TopkWs* ws, int nblocks, const int64_t* __restrict__ cand_idx,
+             const float* __restrict__ cand_val, int64_t k, int64_t* __restrict__ idx_out,
+             float* __restrict__ val_out, KEY kf) {
+    if (ws->failed != 0) return;
+    kf.init();
+    const int b = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
+    if (b >= nblocks) return;
+    const int lane = threadIdx.x & 63;
+    const uint32_t theta = ws->sel.prefix;
+    const uint64_t need_eq = ws->sel.k_rem;
+    uint64_t g = ws->gt[b], e = ws->eq[b];          // greater / equal entries before this batch
+    const uint32_t base = ws->seg_base[b], n = ws->seg_count[b];
+    const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));   // lanes before mine
+    for (uint32_t t0 = 0; t0 < n; t0 += 64) {
+        const uint32_t t = t0 + lane;
+        bool is_gt = false, is_eq = false;
+        int64_t i = 0;
+        float v = 0.0f;
+        if (t < n) {
+            i = cand_idx[base + t];
+            v = cand_val[base + t];
+            const uint32_t key = kf(v, i);
+            is_gt = key > theta;
+            is_eq = key == theta;
+        }
+        const uint64_t m_gt = __builtin_amdgcn_ballot_w64(is_gt);
+        const uint64_t m_eq = __builtin_amdgcn_ballot_w64(is_eq);
+        const uint64_t my_g = g + __builtin_popcountll(m_gt & below);
+        const uint64_t my_e = e + __builtin_popcountll(m_eq & below);
+        if (is_gt || (is_eq && my_e < need_eq)) {
+            const uint64_t slot = my_g + (my_e < need_eq ? my_e : need_eq);
+            if (slot < static_cast<uint64_t>(k)) {
+                idx_out[slot] = i;
+                if (val_out) val_out[slot] = v;
+            }
+        }
+        g += __builtin_popcountll(m_gt);
+        e += __builtin_popcountll(m_eq);
     }
 }
 
@@ -422,48 +639,79 @@ static void topk_geometry(int64_t d, int* nblocks, int64_t* chunk) {
 
 extern "C" int cs_topk_workspace_bytes(int64_t d, int64_t k, size_t* bytes) {
     if (!bytes || d < 1 || k < 1 || k > d) return CS_EINVAL;
-    *bytes = sizeof(TopkWs);
+    *bytes = sizeof(TopkWs) + static_cast<size_t>(candidate_capacity_for(d, k)) * kCandBytes;
     return CS_OK;
 }
 
-// the k entries with the largest keys, ascending by index (see the header of this file)
+// the k entries with the largest keys, ascending by index (see the header of this file).
+// hist0: device uint64[2048], the histogram of key >> 20 over est, when the caller has it.
 template <typename KEY>
-static int select_largest(const float* est, int64_t d, int64_t k, int64_t* idx_out, float* val_out,
-                          void* workspace, size_t ws_bytes, hipStream_t s, KEY kf) {
+static int select_largest(const float* est, int64_t d, int64_t k, const uint64_t* hist0,
+                          int64_t* idx_out, float* val_out, void* workspace, size_t ws_bytes,
+                          hipStream_t s, KEY kf) {
     if (d < 1 || k < 1 || k > d || !est || !idx_out || !workspace) return CS_EINVAL;
     if (reinterpret_cast<uintptr_t>(workspace) % 8 != 0) return CS_EINVAL;
+    if (hist0 && reinterpret_cast<uintptr_t>(hist0) % 8 != 0) return CS_EINVAL;
     if (ws_bytes < sizeof(TopkWs)) return CS_EWORKSPACE;
     TopkWs* ws = static_cast<TopkWs*>(workspace);
+    // The candidate list takes what the workspace holds beyond the struct, up to what is worth
+    // having; it is used when that is at least 2 k + kStage entries (the k-th largest key's own
+    // bin has to fit beside the k entries above it) and clearly less than d.
+    int64_t cap = static_cast<int64_t>((ws_bytes - sizeof(TopkWs)) / kCandBytes);
+    if (cap > candidate_capacity_for(d, k)) cap = candidate_capacity_for(d, k);
+    if (cap > 0xffffffffll) cap = 0xffffffffll;
+    const bool listed = cap >= 2 * k + kStage;
+    int64_t* cand_idx = reinterpret_cast<int64_t*>(ws + 1);
+    float* cand_val = reinterpret_cast<float*>(cand_idx + cap);
     const unsigned hgrid = static_cast<unsigned>(
         (d + kBlock * 16 - 1) / (kBlock * 16) < 2048 ? (d + kBlock * 16 - 1) / (kBlock * 16) : 2048);
     const bool vec = reinterpret_cast<uintptr_t>(est) % 16 == 0;
-    k_topk_clear<<<1, kBlock, 0, s>>>(ws, static_cast<uint64_t>(k));
-    if (vec) {
-        k_topk_hist<0, true, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf);
-        k_topk_find<0><<<1, kBlock, 0, s>>>(ws);
-        k_topk_hist<1, true, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf);
-        k_topk_find<1><<<1, kBlock, 0, s>>>(ws);
-        k_topk_hist<2, true, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf);
-        k_topk_find<2><<<1, kBlock, 0, s>>>(ws);
-    } else {
-        k_topk_hist<0, false, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf);
-        k_topk_find<0><<<1, kBlock, 0, s>>>(ws);
-        k_topk_hist<1, false, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf);
-        k_topk_find<1><<<1, kBlock, 0, s>>>(ws);
-        k_topk_hist<2, false, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf);
-        k_topk_find<2><<<1, kBlock, 0, s>>>(ws);
-    }
     int nblocks;
     int64_t chunk;
     topk_geometry(d, &nblocks, &chunk);
+
+    k_topk_clear<<<1, kBlock, 0, s>>>(ws, static_cast<uint64_t>(k));
+    if (!hist0) {
+        if (vec) k_topk_hist<0, true, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf, false);
+        else k_topk_hist<0, false, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf, false);
+    }
+    k_topk_find<0><<<1, kBlock, 0, s>>>(ws, hist0, false);
+    if (listed) {
+        if (vec)
+            k_topk_compact<true, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, static_cast<uint32_t>(cap),
+                                                                 cand_idx, cand_val, kf);
+        else
+            k_topk_compact<false, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, static_cast<uint32_t>(cap),
+                                                                  cand_idx, cand_val, kf);
+        const unsigned cgrid = 256;
+        const unsigned wgrid = static_cast<unsigned>((nblocks + kBlock / 64 - 1) / (kBlock / 64));
+        k_cand_hist<1, KEY><<<cgrid, kBlock, 0, s>>>(ws, cand_idx, cand_val, kf);
+        k_topk_find<1><<<1, kBlock, 0, s>>>(ws, nullptr, false);
+        k_cand_hist<2, KEY><<<cgrid, kBlock, 0, s>>>(ws, cand_idx, cand_val, kf);
+        k_topk_find<2><<<1, kBlock, 0, s>>>(ws, nullptr, false);
+        k_cand_count<KEY><<<wgrid, kBlock, 0, s>>>(ws, nblocks, cand_idx, cand_val, kf);
+        k_topk_scan<<<1, kBlock, 0, s>>>(ws, nblocks, false);
+        k_cand_write<KEY><<<wgrid, kBlock, 0, s>>>(ws, nblocks, cand_idx, cand_val, k, idx_out, val_out, kf);
+        k_topk_fallback_begin<<<1, kBlock, 0, s>>>(ws);
+    }
+    // the five-pass form: the whole selection without a list, or what runs if the list overflowed
+    const bool fb = listed;
     if (vec) {
-        k_topk_count<true, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, kf);
-        k_topk_scan<<<1, kBlock, 0, s>>>(ws, nblocks);
-        k_topk_write<true, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, k, idx_out, val_out, kf);
+        k_topk_hist<1, true, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf, fb);
+        k_topk_find<1><<<1, kBlock, 0, s>>>(ws, nullptr, fb);
+        k_topk_hist<2, true, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf, fb);
+        k_topk_find<2><<<1, kBlock, 0, s>>>(ws, nullptr, fb);
+        k_topk_count<true, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, kf, fb);
+        k_topk_scan<<<1, kBlock, 0, s>>>(ws, nblocks, fb);
+        k_topk_write<true, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, k, idx_out, val_out, kf, fb);
     } else {
-        k_topk_count<false, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, kf);
-        k_topk_scan<<<1, kBlock, 0, s>>>(ws, nblocks);
-        k_topk_write<false, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, k, idx_out, val_out, kf);
+        k_topk_hist<1, false, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf, fb);
+        k_topk_find<1><<<1, kBlock, 0, s>>>(ws, nullptr, fb);
+        k_topk_hist<2, false, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf, fb);
+        k_topk_find<2><<<1, kBlock, 0, s>>>(ws, nullptr, fb);
+        k_topk_count<false, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, kf, fb);
+        k_topk_scan<<<1, kBlock, 0, s>>>(ws, nblocks, fb);
+        k_topk_write<false, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, k, idx_out, val_out, kf, fb);
     }
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
@@ -471,7 +719,7 @@ static int select_largest(const float* est, int64_t d, int64_t k, int64_t* idx_o
 extern "C" int cs_heavy_hitters_topk(const float* est, int64_t d, int64_t k, int64_t* idx_out,
                                      float* val_out, void* workspace, size_t ws_bytes,
                                      void* stream) {
-    return select_largest(est, d, k, idx_out, val_out, workspace, ws_bytes,
+    return select_largest(est, d, k, nullptr, idx_out, val_out, workspace, ws_bytes,
                           reinterpret_cast<hipStream_t>(stream), KeyMagnitude{});
 }
 
@@ -493,7 +741,7 @@ extern "C" int cs_heavymix_select(const float* est, int64_t d, int64_t k, const 
     if (n_heavy && reinterpret_cast<uintptr_t>(n_heavy) % 8 != 0) return CS_EINVAL;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     KeyHeavymix kf{l2sq, static_cast<double>(k), rng_seed, 0.0};
-    const int rc = select_largest(est, d, k, idx_out, val_out, workspace, ws_bytes, s, kf);
+    const int rc = select_largest(est, d, k, nullptr, idx_out, val_out, workspace, ws_bytes, s, kf);
     if (rc != CS_OK || !n_heavy) return rc;
     unsigned long long* cnt = reinterpret_cast<unsigned long long*>(n_heavy);
     k_clear_u64<<<1, 1, 0, s>>>(cnt);
