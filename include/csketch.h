@@ -51,7 +51,8 @@ typedef enum cs_status {
     CS_OK = 0,
     CS_EINVAL = -1,       /* bad argument (null pointer, size out of range, even r, ...) */
     CS_EWORKSPACE = -2,   /* workspace smaller than cs_topk_workspace_bytes() says */
-    CS_EHIP = -3          /* a HIP runtime call or kernel launch failed */
+    CS_EHIP = -3,         /* a HIP runtime call or kernel launch failed */
+    CS_ELIMIT = -4        /* input larger than an entry point with built-in scratch accepts */
 } cs_status;
 
 /* Traversal of one row (derived from a_j and c; does not change any result).  Because the
@@ -246,6 +247,21 @@ int cs_topk_workspace_bytes(int64_t d, int64_t k, size_t* bytes);
 int cs_heavy_hitters_topk(const float* est, int64_t d, int64_t k,
                           int64_t* idx_out, float* val_out,
                           void* workspace, size_t ws_bytes, void* stream);
+
+/* cs_heavy_hitters_topk for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same result as cs_heavy_hitters_topk (same kernels); the workspace is a fixed
+ * array of 1.7 MB inside the library's device image (histograms, counters and room for
+ * 131 072 candidates), which every GPU the library runs on holds until the process ends.  The call allocates and frees nothing, clears what it
+ * needs with a kernel (no memset node under capture), and looks up the array's address once
+ * per device, on the first call with that device current (`stream` must belong to the current
+ * device).  All calls on one GPU share the array: calls that overlap on one GPU (different
+ * streams, different threads) race and give wrong selections -- serialise them.
+ * CS_ELIMIT when d > CS_TOPK_STATIC_MAX_D (2^32: the supported range of this entry point;
+ * the array's size does not grow with d); other arguments and errors as cs_heavy_hitters_topk. */
+#define CS_TOPK_STATIC_MAX_D (((int64_t)1) << 32)
+int cs_heavy_hitters_topk_static(const float* est, int64_t d, int64_t k,
+                                 int64_t* idx_out, float* val_out, void* stream);
 
 /* Second round (Sec. 4; the worker-query step of Alg. 3, which keeps the sum over workers):
  *     out[n] = alpha * sum_{w<W} vec[w][idx[n]]          (sum in ascending w, fp32)

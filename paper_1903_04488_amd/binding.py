@@ -101,6 +101,8 @@ _SIGNATURES = {
     "cs_heavy_hitters_topk": [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
                               ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                               ctypes.c_void_p],
+    "cs_heavy_hitters_topk_static": [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                                     ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p],
     "cs_select_exact_topk": [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                              ctypes.c_void_p],
@@ -338,6 +340,14 @@ def cs_heavy_hitters_topk(est, k: int, idx_out, val_out, workspace):
         _dev(val_out, torch.float32, "val_out", k) if val_out is not None else ctypes.c_void_p(0),
         _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(est)),
         "cs_heavy_hitters_topk")
+
+
+def cs_heavy_hitters_topk_static(est, k: int, idx_out, val_out):
+    d = est.numel()
+    _check(load_library().cs_heavy_hitters_topk_static(
+        _dev(est, torch.float32, "est"), d, k, _dev(idx_out, torch.int64, "idx_out", k),
+        _dev(val_out, torch.float32, "val_out", k) if val_out is not None else ctypes.c_void_p(0),
+        _stream(est)), "cs_heavy_hitters_topk_static")
 
 
 def cs_select_exact_topk(cand, x, k: int, idx_out, val_out, workspace):

@@ -274,6 +274,7 @@ extern "C" const char* cs_status_string(int status) {
         case CS_EINVAL: return "invalid argument";
         case CS_EWORKSPACE: return "workspace too small";
         case CS_EHIP: return "HIP runtime error";
+        case CS_ELIMIT: return "input exceeds the limit of this entry point's built-in scratch";
         default: return "unknown status";
     }
 }

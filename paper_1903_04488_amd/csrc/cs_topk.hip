@@ -20,6 +20,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "cs_device.h"
 #include "csketch.h"
 
@@ -720,6 +722,43 @@ extern "C" int cs_heavy_hitters_topk(const float* est, int64_t d, int64_t k, int
                                      float* val_out, void* workspace, size_t ws_bytes,
                                      void* stream) {
     return select_largest(est, d, k, nullptr, idx_out, val_out, workspace, ws_bytes,
+                          reinterpret_cast<hipStream_t>(stream), KeyMagnitude{});
+}
+
+// ---------------------------------------------------------------------------------------
+// The selection for callers that cannot allocate: its workspace is an array in the library's
+// own device image.  Every GPU holds its own copy at its own address, so the address is asked
+// for once per device (with that device current) and kept; host code never passes the array's
+// name to a kernel.
+// ---------------------------------------------------------------------------------------
+constexpr size_t kStaticCandidates = 131072;     // room for a candidate list: selections up to k ~ 60 000 read est twice
+static __device__ __align__(256) unsigned char
+    scratch[(sizeof(cs::TopkWs) + kStaticCandidates * cs::kCandBytes + 255) / 256 * 256];
+
+static int static_scratch(void** out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* ptr_of_device[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return CS_EHIP;
+    if (dev < 0 || dev >= kMaxDevices) return CS_EINVAL;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr_of_device[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return CS_EHIP;
+        ptr_of_device[dev] = ptr;
+    }
+    *out = ptr_of_device[dev];
+    return CS_OK;
+}
+
+extern "C" int cs_heavy_hitters_topk_static(const float* est, int64_t d, int64_t k,
+                                            int64_t* idx_out, float* val_out, void* stream) {
+    if (d > CS_TOPK_STATIC_MAX_D) return CS_ELIMIT;
+    void* ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != CS_OK) return rc;
+    return select_largest(est, d, k, nullptr, idx_out, val_out, ws, sizeof(scratch),
                           reinterpret_cast<hipStream_t>(stream), KeyMagnitude{});
 }
 
