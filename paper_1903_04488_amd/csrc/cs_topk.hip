@@ -44,8 +44,7 @@ constexpr int kStage = 4096;          // candidates one block can hold in LDS fo
 struct TopkWs {
     uint64_t hist[3][kBins];
     TopkSel sel;
-    TopkSel sel0;                   // sel as it was after the first histogram (for the fallback)
-    uint32_t failed;                // != 0: the candidate list overflowed, the five-pass form runs
+    uint32_t failed;                // != 0: the candidate list could not be built, est is read instead
     uint32_t ncand;                 // candidates appended so far
     uint64_t gt[kMaxSelBlocks];     // per block: entries with key > theta  -> exclusive scan
     uint64_t eq[kMaxSelBlocks];     // per block: entries with key == theta -> exclusive scan
@@ -105,22 +104,21 @@ __global__ void __launch_bounds__(kBlock) k_topk_clear(TopkWs* ws, uint64_t k) {
     }
 }
 
-// Start of the five-pass form behind a candidate list: nothing to do unless the list
-// overflowed; then the histograms of passes 1 and 2 start empty and the selection state is
-// what the first histogram left.
-__global__ void __launch_bounds__(kBlock) k_topk_fallback_begin(TopkWs* ws) {
-    if (ws->failed == 0) return;
-    for (int t = threadIdx.x; t < 2 * kBins; t += kBlock) (&ws->hist[1][0])[t] = 0;
-    if (threadIdx.x == 0) ws->sel = ws->sel0;
+// The histogram, count and write kernels below exist once and work either on the candidate
+// list or on est itself: `listed` says that a list was asked for, and ws->failed, which the
+// compaction sets on the device, that it could not be built -- then the same launches fall
+// back to reading est (the five-pass form), without the host having to know.
+__device__ __forceinline__ bool use_list(const TopkWs* ws, bool listed) {
+    return listed && ws->failed == 0;
 }
 
 // PASS 0: bin = key >> 20 (2048 bins); PASS 1: entries with key >> 20 == prefix, bin = bits
 // 19..10; PASS 2: entries with key >> 10 == prefix, bin = bits 9..0.
-// `fallback`: the launch stands behind a candidate list and works only if that overflowed.
 template <int PASS, bool VEC, typename KEY>
 __global__ void __launch_bounds__(kBlock)
-k_topk_hist(const float* __restrict__ est, int64_t d, TopkWs* ws, KEY kf, bool fallback) {
-    if (fallback && ws->failed == 0) return;
+k_topk_hist(const float* __restrict__ est, int64_t d, TopkWs* ws, uint64_t* __restrict__ hist_out,
+            bool listed, const int64_t* __restrict__ cand_idx, const float* __restrict__ cand_val,
+            KEY kf) {
     kf.init();
     // Magnitudes crowd into a few of the pass-0 bins (same exponent), and lanes that hit the same
     // LDS word are served one after the other: pass 0 keeps kCopies histograms and lane l adds
@@ -128,6 +126,9 @@ k_topk_hist(const float* __restrict__ est, int64_t d, TopkWs* ws, KEY kf, bool f
     constexpr int kCopies = (PASS == 0) ? 4 : 1;
     constexpr int nb = (PASS == 0) ? 2048 : 1024;
     __shared__ uint32_t lh_all[kCopies][nb];
+    const bool from_list = PASS > 0 && use_list(ws, listed);
+    constexpr unsigned kListBlocks = 128;           // the list is short: a few blocks are plenty
+    if (from_list && blockIdx.x >= kListBlocks) return;
     for (int t = threadIdx.x; t < kCopies * nb; t += kBlock) (&lh_all[0][0])[t] = 0;
     __syncthreads();
     uint32_t* lh = lh_all[threadIdx.x % kCopies];
@@ -141,32 +142,39 @@ k_topk_hist(const float* __restrict__ est, int64_t d, TopkWs* ws, KEY kf, bool f
             if ((key >> 10) == prefix) atomicAdd(&lh[key & 1023u], 1u);
         }
     };
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
-    const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
-    int64_t done = 0;
-    if (VEC) {                                   // est is 16-byte aligned: four elements per load
-        const int64_t n4 = d / 4;
-        const float4* est4 = reinterpret_cast<const float4*>(est);
-        int64_t t = t0;
-        for (; t + stride < n4; t += 2 * stride) {   // two loads in flight
-            const float4 u = est4[t], w = est4[t + stride];
-            tally(kf(u.x, 4 * t)); tally(kf(u.y, 4 * t + 1)); tally(kf(u.z, 4 * t + 2)); tally(kf(u.w, 4 * t + 3));
-            const int64_t t2 = t + stride;
-            tally(kf(w.x, 4 * t2)); tally(kf(w.y, 4 * t2 + 1)); tally(kf(w.z, 4 * t2 + 2)); tally(kf(w.w, 4 * t2 + 3));
+    if (from_list) {
+        const uint32_t n = ws->ncand;
+        const unsigned blocks = gridDim.x < kListBlocks ? gridDim.x : kListBlocks;
+        for (uint32_t t = blockIdx.x * kBlock + threadIdx.x; t < n; t += blocks * kBlock)
+            tally(kf(cand_val[t], cand_idx[t]));
+    } else {
+        const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+        const int64_t t0 = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+        int64_t done = 0;
+        if (VEC) {                                   // est is 16-byte aligned: four elements per load
+            const int64_t n4 = d / 4;
+            const float4* est4 = reinterpret_cast<const float4*>(est);
+            int64_t t = t0;
+            for (; t + stride < n4; t += 2 * stride) {   // two loads in flight
+                const float4 u = est4[t], w = est4[t + stride];
+                tally(kf(u.x, 4 * t)); tally(kf(u.y, 4 * t + 1)); tally(kf(u.z, 4 * t + 2)); tally(kf(u.w, 4 * t + 3));
+                const int64_t t2 = t + stride;
+                tally(kf(w.x, 4 * t2)); tally(kf(w.y, 4 * t2 + 1)); tally(kf(w.z, 4 * t2 + 2)); tally(kf(w.w, 4 * t2 + 3));
+            }
+            if (t < n4) {
+                const float4 u = est4[t];
+                tally(kf(u.x, 4 * t)); tally(kf(u.y, 4 * t + 1)); tally(kf(u.z, 4 * t + 2)); tally(kf(u.w, 4 * t + 3));
+            }
+            done = n4 * 4;
         }
-        if (t < n4) {
-            const float4 u = est4[t];
-            tally(kf(u.x, 4 * t)); tally(kf(u.y, 4 * t + 1)); tally(kf(u.z, 4 * t + 2)); tally(kf(u.w, 4 * t + 3));
-        }
-        done = n4 * 4;
+        for (int64_t t = done + t0; t < d; t += stride) tally(kf(est[t], t));
     }
-    for (int64_t t = done + t0; t < d; t += stride) tally(kf(est[t], t));
     __syncthreads();
     for (int t = threadIdx.x; t < nb; t += kBlock) {
         uint32_t v = 0;
 #pragma unroll
         for (int q = 0; q < kCopies; ++q) v += lh_all[q][t];
-        if (v) atomicAdd(reinterpret_cast<unsigned long long*>(&ws->hist[PASS][t]),
+        if (v) atomicAdd(reinterpret_cast<unsigned long long*>(&hist_out[t]),
                          static_cast<unsigned long long>(v));
     }
 }
@@ -197,14 +205,12 @@ __device__ __forceinline__ uint64_t block_exclusive_sum64(uint64_t v, uint64_t* 
     return before + inc - v;
 }
 
-// hist0: the first histogram when the caller brought it (PASS 0 only), else null.
+// h: the histogram of this pass (for PASS 0 possibly one the caller brought)
 template <int PASS>
-__global__ void __launch_bounds__(kBlock) k_topk_find(TopkWs* ws, const uint64_t* hist0, bool fallback) {
-    if (fallback && ws->failed == 0) return;
+__global__ void __launch_bounds__(kBlock) k_topk_find(TopkWs* ws, const uint64_t* __restrict__ h) {
     constexpr int nb = (PASS == 0) ? 2048 : 1024;
     constexpr int per = nb / kBlock;              // bins per thread: 8 or 4
     __shared__ uint64_t wave_sum[kBlock / 64];
-    const uint64_t* h = (PASS == 0 && hist0) ? hist0 : ws->hist[PASS];
     const uint64_t k_rem = ws->sel.k_rem;
     const uint32_t prefix = ws->sel.prefix;
     uint64_t mine = 0;
@@ -222,11 +228,6 @@ __global__ void __launch_bounds__(kBlock) k_topk_find(TopkWs* ws, const uint64_t
                 ws->sel.prefix = (PASS == 0) ? static_cast<uint32_t>(bin)
                                              : ((prefix << bits) | static_cast<uint32_t>(bin));
                 ws->sel.k_rem = k_rem - acc;
-                if (PASS == 0) {
-                    ws->sel0.prefix = static_cast<uint32_t>(bin);
-                    ws->sel0.pad = 0;
-                    ws->sel0.k_rem = k_rem - acc;
-                }
                 break;
             }
             acc += cnt;
@@ -279,14 +280,132 @@ __device__ __forceinline__ void load_items(const float* __restrict__ est, int64_
     }
 }
 
-// per block: how many entries of its chunk are above / equal to theta
+// The candidate list.  Block b scans its chunk of est (the chunks of the count / write passes)
+// and keeps, in index order, every entry whose key lies in the bin of the k-th largest key or
+// above (sel.prefix after the first histogram).  Each wavefront takes a consecutive quarter of
+// the chunk, 256 entries at a time, and stages its candidates in its own part of LDS (their
+// places come from wavefront ballots, no barrier inside the loop); the block then appends
+// them to the list as one segment, whose place comes from a single atomic add.  Segments lie
+// in the list in the order the blocks finished; (seg_base[b], seg_count[b]) lets the later
+// kernels visit them in block order, i.e. in index order.  A wavefront with more than
+// kStage / 4 candidates, or a list that would exceed `cap`, raises ws->failed.
 template <bool VEC, typename KEY>
 __global__ void __launch_bounds__(kBlock)
-k_topk_count(const float* __restrict__ est, int64_t d, int64_t chunk, TopkWs* ws, KEY kf, bool fallback) {
-    if (fallback && ws->failed == 0) return;
+k_topk_compact(const float* __restrict__ est, int64_t d, int64_t chunk, TopkWs* ws, uint32_t cap,
+               int64_t* __restrict__ cand_idx, float* __restrict__ cand_val, KEY kf) {
     kf.init();
-    __shared__ uint32_t lds[kBlock / 64];
+    constexpr int kWaves = kBlock / 64;
+    constexpr int kWaveStage = kStage / kWaves;
+    constexpr int kWaveTile = 64 * kItems;
+    __shared__ uint32_t st_off[kStage];
+    __shared__ float st_val[kStage];
+    __shared__ uint32_t wave_n[kWaves];
+    __shared__ uint32_t seg[2];                     // base, ok
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t bin0 = ws->sel.prefix;
+    const int64_t lo = static_cast<int64_t>(blockIdx.x) * chunk;
+    const int64_t hi = (lo + chunk < d) ? lo + chunk : d;
+    const int64_t part = (chunk / kWaves + kWaveTile - 1) / kWaveTile * kWaveTile;
+    const int64_t wlo = lo + wave * part;
+    const int64_t whi = (wlo + part < hi) ? wlo + part : hi;
+    uint32_t* my_off = st_off + wave * kWaveStage;
+    float* my_val = st_val + wave * kWaveStage;
+    const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));   // lanes before mine
+    uint32_t staged = 0;                            // the same in every lane of the wavefront
+    bool overflow = false;
+    auto take = [&](const float (&v)[kItems], int nvalid, int64_t base) {
+        bool f[kItems];
+        uint32_t before = 0, total = 0;
+#pragma unroll
+        for (int q = 0; q < kItems; ++q) {
+            f[q] = q < nvalid && (kf(v[q], base + q) >> 20) >= bin0;
+            const uint64_t m = __builtin_amdgcn_ballot_w64(f[q]);
+            before += __builtin_popcountll(m & below);
+            total += __builtin_popcountll(m);
+        }
+        if (total == 0) return;
+        if (staged + total > static_cast<uint32_t>(kWaveStage)) { overflow = true; return; }
+        uint32_t pos = staged + before;
+#pragma unroll
+        for (int q = 0; q < kItems; ++q)
+            if (f[q]) {
+                my_off[pos] = static_cast<uint32_t>(base + q - lo);
+                my_val[pos] = v[q];
+                ++pos;
+            }
+        staged += total;
+    };
+    for (int64_t tile = wlo; tile < whi && !overflow; tile += 2 * kWaveTile) {   // two loads in flight
+        float v0[kItems], v1[kItems];
+        int n0, n1 = 0;
+        const int64_t b0 = tile + static_cast<int64_t>(lane) * kItems, b1 = b0 + kWaveTile;
+        load_items<VEC>(est, b0, whi, v0, n0);
+        if (tile + kWaveTile < whi) load_items<VEC>(est, b1, whi, v1, n1);
+        take(v0, n0, b0);
+        if (tile + kWaveTile < whi && !overflow) take(v1, n1, b1);
+    }
+    if (lane == 0) wave_n[wave] = overflow ? 0xffffffffu : staged;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t total = 0;
+        bool ok = true;
+        for (int w = 0; w < kWaves; ++w) {
+            if (wave_n[w] == 0xffffffffu) ok = false;
+            else total += wave_n[w];
+        }
+        uint32_t base = 0;
+        if (ok && total) {
+            base = atomicAdd(&ws->ncand, total);
+            ok = static_cast<uint64_t>(base) + total <= cap;
+        }
+        if (!ok) atomicOr(&ws->failed, 1u);
+        ws->seg_base[blockIdx.x] = base;
+        ws->seg_count[blockIdx.x] = ok ? total : 0u;
+        seg[0] = base;
+        seg[1] = ok ? 1u : 0u;
+    }
+    __syncthreads();
+    if (seg[1] == 0u) return;
+    uint32_t at = seg[0];
+    for (int w = 0; w < wave; ++w) at += wave_n[w];
+    for (uint32_t t = lane; t < staged; t += 64) {
+        cand_idx[at + t] = lo + my_off[t];
+        cand_val[at + t] = my_val[t];
+    }
+}
+
+// per block: how many entries of its chunk (or of its segment of the list) are above / equal
+// to theta
+template <bool VEC, typename KEY>
+__global__ void __launch_bounds__(kBlock)
+k_topk_count(const float* __restrict__ est, int64_t d, int64_t chunk, TopkWs* ws, int nblocks,
+             bool listed, const int64_t* __restrict__ cand_idx, const float* __restrict__ cand_val,
+             KEY kf) {
+    kf.init();
     const uint32_t theta = ws->sel.prefix;
+    if (use_list(ws, listed)) {                     // one wavefront per segment
+        const int b = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
+        if (b >= nblocks) return;
+        const int lane = threadIdx.x & 63;
+        const uint32_t base = ws->seg_base[b], n = ws->seg_count[b];
+        uint32_t n_gt = 0, n_eq = 0;
+        for (uint32_t t = lane; t < n; t += 64) {
+            const uint32_t key = kf(cand_val[base + t], cand_idx[base + t]);
+            n_gt += key > theta ? 1u : 0u;
+            n_eq += key == theta ? 1u : 0u;
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            n_gt += __shfl_down(n_gt, off, 64);
+            n_eq += __shfl_down(n_eq, off, 64);
+        }
+        if (lane == 0) {
+            ws->gt[b] = n_gt;
+            ws->eq[b] = n_eq;
+        }
+        return;
+    }
+    __shared__ uint32_t lds[kBlock / 64];
     const int64_t lo = static_cast<int64_t>(blockIdx.x) * chunk;
     const int64_t hi = (lo + chunk < d) ? lo + chunk : d;
     uint64_t n_gt = 0, n_eq = 0;
@@ -311,8 +430,7 @@ k_topk_count(const float* __restrict__ est, int64_t d, int64_t chunk, TopkWs* ws
 }
 
 // one workgroup: exclusive scan of the per-block counts, in place
-__global__ void __launch_bounds__(kBlock) k_topk_scan(TopkWs* ws, int nblocks, bool fallback) {
-    if (fallback && ws->failed == 0) return;
+__global__ void __launch_bounds__(kBlock) k_topk_scan(TopkWs* ws, int nblocks) {
     __shared__ uint64_t wave_gt[kBlock / 64], wave_eq[kBlock / 64];
     constexpr int per = kMaxSelBlocks / kBlock;     // 16 consecutive blocks per thread
     uint64_t g[per], e[per], sg = 0, se = 0;
@@ -339,13 +457,48 @@ __global__ void __launch_bounds__(kBlock) k_topk_scan(TopkWs* ws, int nblocks, b
 // before t, need_eq), which is its rank among the selected in ascending index order.
 template <bool VEC, typename KEY>
 __global__ void __launch_bounds__(kBlock)
-k_topk_write(const float* __restrict__ est, int64_t d, int64_t chunk, const TopkWs* ws,
-             int64_t k, int64_t* __restrict__ idx_out, float* __restrict__ val_out, KEY kf, bool fallback) {
-    if (fallback && ws->failed == 0) return;
+k_topk_write(const float* __restrict__ est, int64_t d, int64_t chunk, const TopkWs* ws, int nblocks,
+             int64_t k, int64_t* __restrict__ idx_out, float* __restrict__ val_out, bool listed,
+             const int64_t* __restrict__ cand_idx, const float* __restrict__ cand_val, KEY kf) {
     kf.init();
-    __shared__ uint32_t lds[kBlock / 64];
     const uint32_t theta = ws->sel.prefix;
     const uint64_t need_eq = ws->sel.k_rem;
+    if (use_list(ws, listed)) {                     // one wavefront per segment, 64 candidates at a time
+        const int b = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
+        if (b >= nblocks) return;
+        const int lane = threadIdx.x & 63;
+        uint64_t g = ws->gt[b], e = ws->eq[b];      // greater / equal entries before this batch
+        const uint32_t base = ws->seg_base[b], n = ws->seg_count[b];
+        const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));   // lanes before mine
+        for (uint32_t t0 = 0; t0 < n; t0 += 64) {
+            const uint32_t t = t0 + lane;
+            bool is_gt = false, is_eq = false;
+            int64_t i = 0;
+            float v = 0.0f;
+            if (t < n) {
+                i = cand_idx[base + t];
+                v = cand_val[base + t];
+                const uint32_t key = kf(v, i);
+                is_gt = key > theta;
+                is_eq = key == theta;
+            }
+            const uint64_t m_gt = __builtin_amdgcn_ballot_w64(is_gt);
+            const uint64_t m_eq = __builtin_amdgcn_ballot_w64(is_eq);
+            const uint64_t my_g = g + __builtin_popcountll(m_gt & below);
+            const uint64_t my_e = e + __builtin_popcountll(m_eq & below);
+            if (is_gt || (is_eq && my_e < need_eq)) {
+                const uint64_t slot = my_g + (my_e < need_eq ? my_e : need_eq);
+                if (slot < static_cast<uint64_t>(k)) {
+                    idx_out[slot] = i;
+                    if (val_out) val_out[slot] = v;
+                }
+            }
+            g += __builtin_popcountll(m_gt);
+            e += __builtin_popcountll(m_eq);
+        }
+        return;
+    }
+    __shared__ uint32_t lds[kBlock / 64];
     uint64_t gt_before = ws->gt[blockIdx.x];
     uint64_t eq_before = ws->eq[blockIdx.x];
     const int64_t lo = static_cast<int64_t>(blockIdx.x) * chunk;
@@ -382,176 +535,6 @@ k_topk_write(const float* __restrict__ est, int64_t d, int64_t chunk, const Topk
         }
         gt_before += total & 0xffffu;
         eq_before += total >> 16;
-    }
-}
-
-
-// The candidate list.  Block b scans its chunk of est (the chunks of the count / write passes)
-// and keeps, in index order, every entry whose key lies in the bin of the k-th largest key or
-// above (sel.prefix after the first histogram): staged in LDS, then appended to the list as
-// one segment whose place comes from a single atomic add.  Segments lie in the list in the
-// order the blocks finished; (seg_base[b], seg_count[b]) lets later kernels visit them in
-// block order, i.e. in index order.  A block with more than kStage candidates, or a list that
-// would exceed `cap`, raises ws->failed.
-template <bool VEC, typename KEY>
-__global__ void __launch_bounds__(kBlock)
-k_topk_compact(const float* __restrict__ est, int64_t d, int64_t chunk, TopkWs* ws, uint32_t cap,
-               int64_t* __restrict__ cand_idx, float* __restrict__ cand_val, KEY kf) {
-    kf.init();
-    __shared__ uint32_t lds[kBlock / 64];
-    __shared__ uint32_t st_off[kStage];
-    __shared__ float st_val[kStage];
-    __shared__ uint32_t seg[2];                     // base, ok
-    const uint32_t bin0 = ws->sel.prefix;
-    const int64_t lo = static_cast<int64_t>(blockIdx.x) * chunk;
-    const int64_t hi = (lo + chunk < d) ? lo + chunk : d;
-    uint32_t staged = 0;                            // the same in every thread
-    bool overflow = false;
-    for (int64_t tile = lo; tile < hi; tile += kTile) {
-        float v[kItems];
-        int nvalid;
-        const int64_t base = tile + static_cast<int64_t>(threadIdx.x) * kItems;
-        load_items<VEC>(est, base, hi, v, nvalid);
-        uint32_t c = 0;
-#pragma unroll
-        for (int q = 0; q < kItems; ++q)
-            if (q < nvalid && (kf(v[q], base + q) >> 20) >= bin0) ++c;
-        uint32_t total;
-        const uint32_t incl = block_inclusive_scan(c, lds, &total);
-        if (staged + total > static_cast<uint32_t>(kStage)) { overflow = true; break; }
-        uint32_t pos = staged + incl - c;
-#pragma unroll
-        for (int q = 0; q < kItems; ++q)
-            if (q < nvalid && (kf(v[q], base + q) >> 20) >= bin0) {
-                st_off[pos] = static_cast<uint32_t>(base + q - lo);
-                st_val[pos] = v[q];
-                ++pos;
-            }
-        staged += total;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t base = 0;
-        bool ok = !overflow;
-        if (ok && staged) {
-            base = atomicAdd(&ws->ncand, staged);
-            ok = static_cast<uint64_t>(base) + staged <= cap;
-        }
-        if (!ok) atomicOr(&ws->failed, 1u);
-        ws->seg_base[blockIdx.x] = base;
-        ws->seg_count[blockIdx.x] = ok ? staged : 0u;
-        seg[0] = base;
-        seg[1] = ok ? 1u : 0u;
-    }
-    __syncthreads();
-    if (seg[1] == 0u) return;
-    const uint32_t base = seg[0];
-    for (uint32_t t = threadIdx.x; t < staged; t += kBlock) {
-        cand_idx[base + t] = lo + st_off[t];
-        cand_val[base + t] = st_val[t];
-    }
-}
-
-// histogram of pass 1 or 2 over the candidate list
-template <int PASS, typename KEY>
-__global__ void __launch_bounds__(kBlock)
-k_cand_hist(TopkWs* ws, const int64_t* __restrict__ cand_idx, const float* __restrict__ cand_val, KEY kf) {
-    static_assert(PASS == 1 || PASS == 2, "the first histogram is taken over est");
-    if (ws->failed != 0) return;
-    kf.init();
-    __shared__ uint32_t lh[1024];
-    for (int t = threadIdx.x; t < 1024; t += kBlock) lh[t] = 0;
-    __syncthreads();
-    const uint32_t prefix = ws->sel.prefix;
-    const uint32_t n = ws->ncand;
-    for (uint32_t t = blockIdx.x * kBlock + threadIdx.x; t < n; t += gridDim.x * kBlock) {
-        const uint32_t key = kf(cand_val[t], cand_idx[t]);
-        if (PASS == 1) {
-            if ((key >> 20) == prefix) atomicAdd(&lh[(key >> 10) & 1023u], 1u);
-        } else {
-            if ((key >> 10) == prefix) atomicAdd(&lh[key & 1023u], 1u);
-        }
-    }
-    __syncthreads();
-    for (int t = threadIdx.x; t < 1024; t += kBlock) {
-        const uint32_t v = lh[t];
-        if (v) atomicAdd(reinterpret_cast<unsigned long long*>(&ws->hist[PASS][t]),
-                         static_cast<unsigned long long>(v));
-    }
-}
-
-// per block of the compaction (one wavefront each): how many of its candidates are above /
-// equal to theta
-template <typename KEY>
-__global__ void __launch_bounds__(kBlock)
-k_cand_count(TopkWs* ws, int nblocks, const int64_t* __restrict__ cand_idx,
-             const float* __restrict__ cand_val, KEY kf) {
-    if (ws->failed != 0) return;
-    kf.init();
-    const int b = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
-    if (b >= nblocks) return;
-    const int lane = threadIdx.x & 63;
-    const uint32_t theta = ws->sel.prefix;
-    const uint32_t base = ws->seg_base[b], n = ws->seg_count[b];
-    uint32_t n_gt = 0, n_eq = 0;
-    for (uint32_t t = lane; t < n; t += 64) {
-        const uint32_t key = kf(cand_val[base + t], cand_idx[base + t]);
-        n_gt += key > theta ? 1u : 0u;
-        n_eq += key == theta ? 1u : 0u;
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        n_gt += __shfl_down(n_gt, off, 64);
-        n_eq += __shfl_down(n_eq, off, 64);
-    }
-    if (lane == 0) {
-        ws->gt[b] = n_gt;
-        ws->eq[b] = n_eq;
-    }
-}
-
-// ordered write from the candidate list: the rule of k_topk_write, one wavefront per block
-// of the compaction, 64 candidates at a time
-template <typename KEY>
-__global__ void __launch_bounds__(kBlock)
-k_cand_write(const TopkWs* ws, int nblocks, const int64_t* __restrict__ cand_idx,
-             const float* __restrict__ cand_val, int64_t k, int64_t* __restrict__ idx_out,
-             float* __restrict__ val_out, KEY kf) {
-    if (ws->failed != 0) return;
-    kf.init();
-    const int b = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
-    if (b >= nblocks) return;
-    const int lane = threadIdx.x & 63;
-    const uint32_t theta = ws->sel.prefix;
-    const uint64_t need_eq = ws->sel.k_rem;
-    uint64_t g = ws->gt[b], e = ws->eq[b];          // greater / equal entries before this batch
-    const uint32_t base = ws->seg_base[b], n = ws->seg_count[b];
-    const uint64_t below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));   // lanes before mine
-    for (uint32_t t0 = 0; t0 < n; t0 += 64) {
-        const uint32_t t = t0 + lane;
-        bool is_gt = false, is_eq = false;
-        int64_t i = 0;
-        float v = 0.0f;
-        if (t < n) {
-            i = cand_idx[base + t];
-            v = cand_val[base + t];
-            const uint32_t key = kf(v, i);
-            is_gt = key > theta;
-            is_eq = key == theta;
-        }
-        const uint64_t m_gt = __builtin_amdgcn_ballot_w64(is_gt);
-        const uint64_t m_eq = __builtin_amdgcn_ballot_w64(is_eq);
-        const uint64_t my_g = g + __builtin_popcountll(m_gt & below);
-        const uint64_t my_e = e + __builtin_popcountll(m_eq & below);
-        if (is_gt || (is_eq && my_e < need_eq)) {
-            const uint64_t slot = my_g + (my_e < need_eq ? my_e : need_eq);
-            if (slot < static_cast<uint64_t>(k)) {
-                idx_out[slot] = i;
-                if (val_out) val_out[slot] = v;
-            }
-        }
-        g += __builtin_popcountll(m_gt);
-        e += __builtin_popcountll(m_eq);
     }
 }
 
@@ -647,6 +630,34 @@ extern "C" int cs_topk_workspace_bytes(int64_t d, int64_t k, size_t* bytes) {
 
 // the k entries with the largest keys, ascending by index (see the header of this file).
 // hist0: device uint64[2048], the histogram of key >> 20 over est, when the caller has it.
+template <typename KEY, bool VEC>
+static void enqueue_selection(const float* est, int64_t d, int64_t k, const uint64_t* hist0,
+                              int64_t* idx_out, float* val_out, TopkWs* ws, int64_t cap, bool listed,
+                              hipStream_t s, KEY kf) {
+    int64_t* cand_idx = reinterpret_cast<int64_t*>(ws + 1);
+    float* cand_val = reinterpret_cast<float*>(cand_idx + cap);
+    const unsigned hgrid = static_cast<unsigned>(
+        (d + kBlock * 16 - 1) / (kBlock * 16) < 2048 ? (d + kBlock * 16 - 1) / (kBlock * 16) : 2048);
+    int nblocks;
+    int64_t chunk;
+    topk_geometry(d, &nblocks, &chunk);
+    k_topk_clear<<<1, kBlock, 0, s>>>(ws, static_cast<uint64_t>(k));
+    if (!hist0)
+        k_topk_hist<0, VEC, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, ws->hist[0], false, cand_idx, cand_val, kf);
+    k_topk_find<0><<<1, kBlock, 0, s>>>(ws, hist0 ? hist0 : ws->hist[0]);
+    if (listed)
+        k_topk_compact<VEC, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, static_cast<uint32_t>(cap),
+                                                            cand_idx, cand_val, kf);
+    k_topk_hist<1, VEC, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, ws->hist[1], listed, cand_idx, cand_val, kf);
+    k_topk_find<1><<<1, kBlock, 0, s>>>(ws, ws->hist[1]);
+    k_topk_hist<2, VEC, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, ws->hist[2], listed, cand_idx, cand_val, kf);
+    k_topk_find<2><<<1, kBlock, 0, s>>>(ws, ws->hist[2]);
+    k_topk_count<VEC, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, nblocks, listed, cand_idx, cand_val, kf);
+    k_topk_scan<<<1, kBlock, 0, s>>>(ws, nblocks);
+    k_topk_write<VEC, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, nblocks, k, idx_out, val_out, listed,
+                                                      cand_idx, cand_val, kf);
+}
+
 template <typename KEY>
 static int select_largest(const float* est, int64_t d, int64_t k, const uint64_t* hist0,
                           int64_t* idx_out, float* val_out, void* workspace, size_t ws_bytes,
@@ -663,58 +674,10 @@ static int select_largest(const float* est, int64_t d, int64_t k, const uint64_t
     if (cap > candidate_capacity_for(d, k)) cap = candidate_capacity_for(d, k);
     if (cap > 0xffffffffll) cap = 0xffffffffll;
     const bool listed = cap >= 2 * k + kStage;
-    int64_t* cand_idx = reinterpret_cast<int64_t*>(ws + 1);
-    float* cand_val = reinterpret_cast<float*>(cand_idx + cap);
-    const unsigned hgrid = static_cast<unsigned>(
-        (d + kBlock * 16 - 1) / (kBlock * 16) < 2048 ? (d + kBlock * 16 - 1) / (kBlock * 16) : 2048);
-    const bool vec = reinterpret_cast<uintptr_t>(est) % 16 == 0;
-    int nblocks;
-    int64_t chunk;
-    topk_geometry(d, &nblocks, &chunk);
-
-    k_topk_clear<<<1, kBlock, 0, s>>>(ws, static_cast<uint64_t>(k));
-    if (!hist0) {
-        if (vec) k_topk_hist<0, true, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf, false);
-        else k_topk_hist<0, false, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf, false);
-    }
-    k_topk_find<0><<<1, kBlock, 0, s>>>(ws, hist0, false);
-    if (listed) {
-        if (vec)
-            k_topk_compact<true, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, static_cast<uint32_t>(cap),
-                                                                 cand_idx, cand_val, kf);
-        else
-            k_topk_compact<false, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, static_cast<uint32_t>(cap),
-                                                                  cand_idx, cand_val, kf);
-        const unsigned cgrid = 256;
-        const unsigned wgrid = static_cast<unsigned>((nblocks + kBlock / 64 - 1) / (kBlock / 64));
-        k_cand_hist<1, KEY><<<cgrid, kBlock, 0, s>>>(ws, cand_idx, cand_val, kf);
-        k_topk_find<1><<<1, kBlock, 0, s>>>(ws, nullptr, false);
-        k_cand_hist<2, KEY><<<cgrid, kBlock, 0, s>>>(ws, cand_idx, cand_val, kf);
-        k_topk_find<2><<<1, kBlock, 0, s>>>(ws, nullptr, false);
-        k_cand_count<KEY><<<wgrid, kBlock, 0, s>>>(ws, nblocks, cand_idx, cand_val, kf);
-        k_topk_scan<<<1, kBlock, 0, s>>>(ws, nblocks, false);
-        k_cand_write<KEY><<<wgrid, kBlock, 0, s>>>(ws, nblocks, cand_idx, cand_val, k, idx_out, val_out, kf);
-        k_topk_fallback_begin<<<1, kBlock, 0, s>>>(ws);
-    }
-    // the five-pass form: the whole selection without a list, or what runs if the list overflowed
-    const bool fb = listed;
-    if (vec) {
-        k_topk_hist<1, true, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf, fb);
-        k_topk_find<1><<<1, kBlock, 0, s>>>(ws, nullptr, fb);
-        k_topk_hist<2, true, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf, fb);
-        k_topk_find<2><<<1, kBlock, 0, s>>>(ws, nullptr, fb);
-        k_topk_count<true, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, kf, fb);
-        k_topk_scan<<<1, kBlock, 0, s>>>(ws, nblocks, fb);
-        k_topk_write<true, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, k, idx_out, val_out, kf, fb);
-    } else {
-        k_topk_hist<1, false, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf, fb);
-        k_topk_find<1><<<1, kBlock, 0, s>>>(ws, nullptr, fb);
-        k_topk_hist<2, false, KEY><<<hgrid, kBlock, 0, s>>>(est, d, ws, kf, fb);
-        k_topk_find<2><<<1, kBlock, 0, s>>>(ws, nullptr, fb);
-        k_topk_count<false, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, kf, fb);
-        k_topk_scan<<<1, kBlock, 0, s>>>(ws, nblocks, fb);
-        k_topk_write<false, KEY><<<nblocks, kBlock, 0, s>>>(est, d, chunk, ws, k, idx_out, val_out, kf, fb);
-    }
+    if (reinterpret_cast<uintptr_t>(est) % 16 == 0)
+        enqueue_selection<KEY, true>(est, d, k, hist0, idx_out, val_out, ws, cap, listed, s, kf);
+    else
+        enqueue_selection<KEY, false>(est, d, k, hist0, idx_out, val_out, ws, cap, listed, s, kf);
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
 
