@@ -222,11 +222,19 @@ int cs_sketch_momentum(const cs_params* p, float* S_u, float* S_v, const float* 
  * reading of Alg. 4 does).  Infinite cells order as usual.  A NaN cell compares false with
  * everything, so it stays where the sort put it and the estimate is NaN exactly when that
  * position is the middle one; this is a deterministic function of the r values in row order.
+ * hist_or_null: NULL, or device uint64[CS_TOPK_HIST_BINS], 8-byte aligned, which receives the
+ * number of estimates per magnitude bin, hist[b] = #{ t : (bits(est[t]) & 0x7fffffff) >> 20 == b }
+ * (cleared by the call).  It is the first histogram of the selection that follows (Sec. 5.2
+ * queries every coordinate and keeps the largest); handing it to cs_heavy_hitters_topk saves
+ * that call one read of est.  For long vectors the kernel that writes est counts as it goes;
+ * otherwise est is read once more here.
  * rows_ws: device scratch of cs_estimate_workspace_bytes(p, d) bytes (may be NULL when that
  * size is 0).  */
+#define CS_TOPK_HIST_BINS 2048
 int cs_estimate_workspace_bytes(const cs_params* p, int64_t d, size_t* bytes);
 int cs_sketch_estimate(const cs_params* p, const float* S, int64_t d, int64_t i0,
-                       float* est, void* rows_ws, size_t ws_bytes, void* stream);
+                       float* est, uint64_t* hist_or_null, void* rows_ws, size_t ws_bytes,
+                       void* stream);
 
 /* Alg. 4 estimate of listed coordinates: out[t] = median_j s_j(idx[t]) * S[j][h_j(idx[t])].
  * idx: device int64[n]; out: device float[n]. */
@@ -237,14 +245,17 @@ int cs_sketch_estimate_sparse(const cs_params* p, const float* S, const int64_t*
  * largest |est[t]|; equal magnitudes are resolved towards the lower index; the result is in
  * ascending index order.  idx_out: device int64[k] (index t, NOT offset by any i0);
  * val_out: device float[k], val_out[n] = est[idx_out[n]] (may be NULL).
+ * hist_or_null: NULL, or the histogram cs_sketch_estimate filled for exactly this est[0..d)
+ * (device uint64[CS_TOPK_HIST_BINS], read only); a histogram of other data gives a wrong
+ * selection.
  * workspace: device, 8-byte aligned, contents irrelevant on entry.  cs_topk_workspace_bytes(d, k)
  * is what makes the call fastest: about 114 KiB of histograms and counters plus, when k is
  * small against d, room for a list of 8 k + 65 536 candidates (12 bytes each), with which est
- * is read twice instead of five times.  Any size from cs_topk_workspace_bytes(1, 1) (the fixed
+ * is read twice (once with hist_or_null) instead of five times.  Any size from cs_topk_workspace_bytes(1, 1) (the fixed
  * part alone) upwards is accepted and gives the same result; below that CS_EWORKSPACE.
  * 1 <= k <= d. */
 int cs_topk_workspace_bytes(int64_t d, int64_t k, size_t* bytes);
-int cs_heavy_hitters_topk(const float* est, int64_t d, int64_t k,
+int cs_heavy_hitters_topk(const float* est, int64_t d, int64_t k, const uint64_t* hist_or_null,
                           int64_t* idx_out, float* val_out,
                           void* workspace, size_t ws_bytes, void* stream);
 

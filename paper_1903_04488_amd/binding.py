@@ -93,13 +93,13 @@ _SIGNATURES = {
     "cs_estimate_workspace_bytes": [ctypes.POINTER(CsParams), ctypes.c_int64,
                                     ctypes.POINTER(ctypes.c_size_t)],
     "cs_sketch_estimate": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_int64,
-                           ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
-                           ctypes.c_void_p],
+                           ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                           ctypes.c_size_t, ctypes.c_void_p],
     "cs_sketch_estimate_sparse": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_void_p,
                                   ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p],
     "cs_topk_workspace_bytes": [ctypes.c_int64, ctypes.c_int64, ctypes.POINTER(ctypes.c_size_t)],
     "cs_heavy_hitters_topk": [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
-                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                              ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                               ctypes.c_void_p],
     "cs_heavy_hitters_topk_static": [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p],
@@ -308,7 +308,16 @@ def cs_estimate_workspace_bytes(p, d: int) -> int:
     return int(out.value)
 
 
-def cs_sketch_estimate(p, S, est, i0: int = 0, workspace=None):
+CS_TOPK_HIST_BINS = 2048
+
+
+def _hist(hist):
+    if hist is None:
+        return ctypes.c_void_p(0)
+    return _dev(hist, torch.int64, "hist", CS_TOPK_HIST_BINS)
+
+
+def cs_sketch_estimate(p, S, est, i0: int = 0, workspace=None, hist=None):
     d = est.numel()
     ws_ptr, ws_bytes = ctypes.c_void_p(0), 0
     if workspace is not None:
@@ -316,7 +325,8 @@ def cs_sketch_estimate(p, S, est, i0: int = 0, workspace=None):
         ws_bytes = workspace.numel()
     _check(load_library().cs_sketch_estimate(
         ctypes.byref(p), _dev(S, torch.float32, "S", _cells(p)), d, i0,
-        _dev(est, torch.float32, "est"), ws_ptr, ws_bytes, _stream(S)), "cs_sketch_estimate")
+        _dev(est, torch.float32, "est"), _hist(hist), ws_ptr, ws_bytes, _stream(S)),
+        "cs_sketch_estimate")
 
 
 def cs_sketch_estimate_sparse(p, S, idx, out):
@@ -333,10 +343,10 @@ def cs_topk_workspace_bytes(d: int, k: int) -> int:
     return int(out.value)
 
 
-def cs_heavy_hitters_topk(est, k: int, idx_out, val_out, workspace):
+def cs_heavy_hitters_topk(est, k: int, idx_out, val_out, workspace, hist=None):
     d = est.numel()
     _check(load_library().cs_heavy_hitters_topk(
-        _dev(est, torch.float32, "est"), d, k, _dev(idx_out, torch.int64, "idx_out", k),
+        _dev(est, torch.float32, "est"), d, k, _hist(hist), _dev(idx_out, torch.int64, "idx_out", k),
         _dev(val_out, torch.float32, "val_out", k) if val_out is not None else ctypes.c_void_p(0),
         _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(est)),
         "cs_heavy_hitters_topk")

@@ -35,8 +35,14 @@ bool lattice_applies(const cs_params* p, int64_t d);
 
 int launch_accumulate_lattice(const cs_params* p, const LatticePtrs& ptrs, int nw, int64_t d,
                               int64_t i0, float scale, hipStream_t stream);
+// *hist_done = true when the kernels that wrote est also filled hist (see launch_estimate_walk)
 int launch_estimate_lattice(const cs_params* p, const float* S, int64_t d, int64_t i0,
-                            float* est, float* rows, hipStream_t stream);
+                            float* est, float* rows, uint64_t* hist, bool* hist_done,
+                            hipStream_t stream);
+// hist[b] = number of t < d with (bits(est[t]) & 0x7fffffff) >> 20 == b, b < 2048 (cs_topk.hip);
+// the _zero form only clears the 2048 counters
+int launch_magnitude_hist_zero(uint64_t* hist, hipStream_t stream);
+int launch_magnitude_hist(const float* est, int64_t d, uint64_t* hist, hipStream_t stream);
 int launch_hash_range_lattice(const cs_params* p, int64_t i0, int64_t n, uint32_t* bucket,
                               int8_t* sign, hipStream_t stream);
 
@@ -46,7 +52,7 @@ int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* con
                            int64_t d, int64_t i0, float scale, hipStream_t stream);
 int count_accumulate_walk_launches(const cs_params* p, int W, int64_t d);
 int launch_estimate_walk(const cs_params* p, const float* S, int64_t d, int64_t i0,
-                         float* est, float* rows, bool fuse_last, hipStream_t stream);
+                         float* est, float* rows, bool fuse_last, uint64_t* hist, hipStream_t stream);
 int launch_bundle_zero(float* T, int64_t n, hipStream_t stream);
 int launch_bundle_merge(float* dst, float beta, const float* T, int groups, float alpha,
                         int64_t cells, hipStream_t stream);

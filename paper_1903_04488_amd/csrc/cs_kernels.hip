@@ -734,16 +734,16 @@ extern "C" int cs_estimate_workspace_bytes(const cs_params* p, int64_t d, size_t
     return CS_OK;
 }
 
-extern "C" int cs_sketch_estimate(const cs_params* p, const float* S, int64_t d, int64_t i0,
-                                  float* est, void* rows_ws, size_t ws_bytes, void* stream) {
-    if (!params_ok(p) || d < 0 || i0 < 0 || i0 > (int64_t)kP61 - d) return CS_EINVAL;
-    if (d == 0) return CS_OK;
-    if (!S || !est) return CS_EINVAL;
+static int estimate_all(const cs_params* p, const float* S, int64_t d, int64_t i0, float* est,
+                        uint64_t* hist, bool* hist_done, void* rows_ws, size_t ws_bytes,
+                        void* stream) {
+    *hist_done = false;
     if (lattice_applies(p, d)) {
         const size_t need = sizeof(float) * static_cast<size_t>(p->r) * static_cast<size_t>(d);
         if (!rows_ws || reinterpret_cast<uintptr_t>(rows_ws) % 4 != 0) return CS_EINVAL;
         if (ws_bytes < need) return CS_EWORKSPACE;
-        return launch_estimate_lattice(p, S, d, i0, est, static_cast<float*>(rows_ws), as_stream(stream));
+        return launch_estimate_lattice(p, S, d, i0, est, static_cast<float*>(rows_ws), hist, hist_done,
+                                       as_stream(stream));
     }
     const unsigned grid = grid_for(d, kBlock * 8, 256 * 8);
 #define CALL(R_, P2_) \
@@ -751,6 +751,24 @@ extern "C" int cs_sketch_estimate(const cs_params* p, const float* S, int64_t d,
     CS_DISPATCH_R(p, CALL);
 #undef CALL
     return launch_status();
+}
+
+extern "C" int cs_sketch_estimate(const cs_params* p, const float* S, int64_t d, int64_t i0,
+                                  float* est, uint64_t* hist_or_null, void* rows_ws,
+                                  size_t ws_bytes, void* stream) {
+    if (!params_ok(p) || d < 0 || i0 < 0 || i0 > (int64_t)kP61 - d) return CS_EINVAL;
+    if (hist_or_null && reinterpret_cast<uintptr_t>(hist_or_null) % 8 != 0) return CS_EINVAL;
+    if (d > 0 && (!S || !est)) return CS_EINVAL;
+    if (hist_or_null) {
+        const int rc = launch_magnitude_hist_zero(hist_or_null, as_stream(stream));
+        if (rc != CS_OK) return rc;
+    }
+    if (d == 0) return CS_OK;
+    bool hist_done = false;
+    const int rc = estimate_all(p, S, d, i0, est, hist_or_null, &hist_done, rows_ws, ws_bytes, stream);
+    if (rc != CS_OK || !hist_or_null || hist_done) return rc;
+    // the kernels that wrote est did not count it: one more read of est
+    return launch_magnitude_hist(est, d, hist_or_null, as_stream(stream));
 }
 
 extern "C" int cs_sketch_estimate_sparse(const cs_params* p, const float* S, const int64_t* idx,

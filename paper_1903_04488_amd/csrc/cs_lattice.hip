@@ -312,10 +312,13 @@ int launch_accumulate_lattice(const cs_params* p, const LatticePtrs& ptrs, int n
 }
 
 int launch_estimate_lattice(const cs_params* p, const float* S, int64_t d, int64_t i0,
-                            float* est, float* rows, hipStream_t stream) {
+                            float* est, float* rows, uint64_t* hist, bool* hist_done,
+                            hipStream_t stream) {
+    *hist_done = false;
     if (walk_applies(p, d)) {
         const bool fuse_last = d >= (static_cast<int64_t>(1) << 24);
-        const int rc = launch_estimate_walk(p, S, d, i0, est, rows, fuse_last, stream);
+        const int rc = launch_estimate_walk(p, S, d, i0, est, rows, fuse_last, fuse_last ? hist : nullptr, stream);
+        *hist_done = fuse_last && hist != nullptr;
         if (rc != CS_OK || fuse_last) return rc;
     } else {
         const dim3 grid(lattice_grid_x(p, d), p->r);

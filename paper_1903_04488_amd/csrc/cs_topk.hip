@@ -23,6 +23,7 @@
 #include <mutex>
 
 #include "cs_device.h"
+#include "cs_internal.h"
 #include "csketch.h"
 
 namespace cs {
@@ -132,7 +133,7 @@ k_topk_hist(const float* __restrict__ est, int64_t d, TopkWs* ws, uint64_t* __re
     for (int t = threadIdx.x; t < kCopies * nb; t += kBlock) (&lh_all[0][0])[t] = 0;
     __syncthreads();
     uint32_t* lh = lh_all[threadIdx.x % kCopies];
-    const uint32_t prefix = ws->sel.prefix;
+    const uint32_t prefix = PASS > 0 ? ws->sel.prefix : 0u;
     auto tally = [&](uint32_t key) {
         if (PASS == 0) {
             atomicAdd(&lh[key >> 20], 1u);
@@ -608,6 +609,27 @@ k_count_heavy(const float* __restrict__ est, const int64_t* __restrict__ idx, in
 
 __global__ void k_clear_u64(unsigned long long* x) { *x = 0; }
 
+__global__ void __launch_bounds__(kBlock) k_hist_zero(uint64_t* hist) {
+    for (int t = threadIdx.x; t < kBins; t += kBlock) hist[t] = 0;
+}
+
+int launch_magnitude_hist_zero(uint64_t* hist, hipStream_t stream) {
+    k_hist_zero<<<1, kBlock, 0, stream>>>(hist);
+    return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
+}
+
+int launch_magnitude_hist(const float* est, int64_t d, uint64_t* hist, hipStream_t stream) {
+    const unsigned hgrid = static_cast<unsigned>(
+        (d + kBlock * 16 - 1) / (kBlock * 16) < 2048 ? (d + kBlock * 16 - 1) / (kBlock * 16) : 2048);
+    if (reinterpret_cast<uintptr_t>(est) % 16 == 0)
+        k_topk_hist<0, true, KeyMagnitude><<<hgrid, kBlock, 0, stream>>>(est, d, nullptr, hist, false, nullptr,
+                                                                        nullptr, KeyMagnitude{});
+    else
+        k_topk_hist<0, false, KeyMagnitude><<<hgrid, kBlock, 0, stream>>>(est, d, nullptr, hist, false, nullptr,
+                                                                         nullptr, KeyMagnitude{});
+    return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
+}
+
 }  // namespace cs
 
 using namespace cs;
@@ -681,10 +703,11 @@ static int select_largest(const float* est, int64_t d, int64_t k, const uint64_t
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
 
-extern "C" int cs_heavy_hitters_topk(const float* est, int64_t d, int64_t k, int64_t* idx_out,
+extern "C" int cs_heavy_hitters_topk(const float* est, int64_t d, int64_t k,
+                                     const uint64_t* hist_or_null, int64_t* idx_out,
                                      float* val_out, void* workspace, size_t ws_bytes,
                                      void* stream) {
-    return select_largest(est, d, k, nullptr, idx_out, val_out, workspace, ws_bytes,
+    return select_largest(est, d, k, hist_or_null, idx_out, val_out, workspace, ws_bytes,
                           reinterpret_cast<hipStream_t>(stream), KeyMagnitude{});
 }
 
@@ -759,7 +782,7 @@ extern "C" int cs_select_exact_topk(const int64_t* cand, const float* x, int64_t
     if (!cand) return CS_EINVAL;
     // positions of the k largest |x| (ascending), then positions -> coordinates; cand is
     // ascending, so the result is ascending too
-    const int rc = cs_heavy_hitters_topk(x, n, k, idx_out, val_out, workspace, ws_bytes, stream);
+    const int rc = cs_heavy_hitters_topk(x, n, k, nullptr, idx_out, val_out, workspace, ws_bytes, stream);
     if (rc != CS_OK) return rc;
     int64_t b = (k + kBlock - 1) / kBlock;
     if (b > 4096) b = 4096;

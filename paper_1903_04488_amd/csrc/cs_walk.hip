@@ -749,15 +749,34 @@ struct RowSegments {
 // RF = 0: rows[j][i] for the rows j = blockIdx.y.  RF = R (the row count): the walk of the last
 // row, which instead of storing its values reads those of rows 0 .. R-2 at the same coordinates
 // and writes their median, est[i] -- the last row never goes through memory.
-template <int RF>
-__global__ void __launch_bounds__(64)
+// HIST (with RF > 0): the kernel also counts the estimates it writes by the top 11 bits of their
+// magnitude (bits 30..20 of the binary32 pattern) into hist[2048], which is the first
+// histogram of the selection that follows (Sec. 5.2: query every coordinate, keep the
+// largest): one read of est less.  Counts are kept per workgroup in LDS and added to hist at
+// the end; a workgroup of kHistWaves wavefronts shares one set of counters (8 KB), so that LDS
+// does not limit how many wavefronts a CU holds.
+constexpr int kHistWaves = 4;
+template <int RF, bool HIST>
+__global__ void __launch_bounds__(HIST ? 64 * kHistWaves : 64)
 k_row_values_walk(KParams p, RowSegments segs, const float* __restrict__ S, int64_t d, int64_t i0,
-                  float* __restrict__ rows, float* __restrict__ est) {
+                  float* __restrict__ rows, float* __restrict__ est,
+                  unsigned long long* __restrict__ hist) {
     static_assert(kQRun == 4, "one 16-byte piece per lane");
-    const int lane = threadIdx.x;
+    static_assert(!HIST || RF > 0, "only the kernel that writes est can count it");
+    constexpr int NW = HIST ? kHistWaves : 1;          // wavefronts per workgroup
+    const int lane = threadIdx.x & 63;
+    const int wq = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = RF ? RF - 1 : blockIdx.y;
     const int nseg = segs.n[j];
     if (static_cast<int>(blockIdx.z) >= nseg) return;
+    __shared__ uint32_t lh[HIST ? 2048 : 1];
+    if (HIST) {
+        for (int t = threadIdx.x; t < 2048; t += 64 * NW) lh[t] = 0;
+        __syncthreads();
+    }
+    auto tally = [&](float v) {
+        if (HIST) atomicAdd(&lh[(__float_as_uint(v) & 0x7fffffffu) >> 20], 1u);
+    };
     const int64_t D = static_cast<int64_t>(p.plan[j].Dw);
     const int64_t visits = (d + D - 1) / D;
     const int64_t nD0 = visits * blockIdx.z / nseg * D;          // my segment of the chain
@@ -772,7 +791,8 @@ k_row_values_walk(KParams p, RowSegments segs, const float* __restrict__ S, int6
 
     const int64_t per_xcd = (nwaves + 7) / 8;
     const int64_t xcd_first = static_cast<int64_t>(blockIdx.x & 7) * per_xcd;
-    for (int64_t k = blockIdx.x >> 3; k < per_xcd; k += gridDim.x >> 3) {
+    for (int64_t k = static_cast<int64_t>(blockIdx.x >> 3) * NW + wq; k < per_xcd;
+         k += static_cast<int64_t>(gridDim.x >> 3) * NW) {
         const int64_t wv = xcd_first + k;
         if (wv >= nwaves) break;
         const int64_t chunk0 = wv * 64;
@@ -824,6 +844,7 @@ k_row_values_walk(KParams p, RowSegments segs, const float* __restrict__ S, int6
                     u.x = median_odd<RF>(vx); u.y = median_odd<RF>(vy);
                     u.z = median_odd<RF>(vz); u.w = median_odd<RF>(vw);
                     *reinterpret_cast<vec4f_u*>(dst) = u;
+                    tally(u.x); tally(u.y); tally(u.z); tally(u.w);
                 } else {
                     for (int m = 0; m < kQRun; ++m) {
                         if (m >= my_len) break;
@@ -831,7 +852,9 @@ k_row_values_walk(KParams p, RowSegments segs, const float* __restrict__ S, int6
 #pragma unroll
                         for (int q = 0; q < RF - 1; ++q) v[q] = rows[static_cast<size_t>(q) * d + nD + my_off + m];
                         v[RF - 1] = o[m];
-                        dst[m] = median_odd<RF>(v);
+                        const float med = median_odd<RF>(v);
+                        dst[m] = med;
+                        tally(med);
                     }
                 }
                 continue;
@@ -851,6 +874,13 @@ k_row_values_walk(KParams p, RowSegments segs, const float* __restrict__ S, int6
             }
         }
     }
+    if (HIST) {
+        __syncthreads();
+        for (int t = threadIdx.x; t < 2048; t += 64 * NW) {
+            const uint32_t n = lh[t];
+            if (n) atomicAdd(&hist[t], static_cast<unsigned long long>(n));
+        }
+    }
 }
 
 }  // namespace
@@ -858,8 +888,9 @@ k_row_values_walk(KParams p, RowSegments segs, const float* __restrict__ S, int6
 // fuse_last = false: all rows into the scratch (the caller takes the median).  fuse_last = true:
 // the last row's walk takes the median itself; worth it for long vectors, where the scratch
 // traffic it saves (write and read of one row) outweighs a second, narrower launch.
+// hist (with fuse_last): zeroed by the caller; receives the counts of est by magnitude bin.
 int launch_estimate_walk(const cs_params* p, const float* S, int64_t d, int64_t i0,
-                         float* est, float* rows, bool fuse_last, hipStream_t stream) {
+                         float* est, float* rows, bool fuse_last, uint64_t* hist, hipStream_t stream) {
     int64_t most = 1;
     for (uint32_t j = 0; j < p->r; ++j) {
         const int64_t chunks = (static_cast<int64_t>(p->plan[j].Dw) + kQRun - 1) / kQRun;
@@ -885,17 +916,22 @@ int launch_estimate_walk(const cs_params* p, const float* S, int64_t d, int64_t 
     }
     if (!fuse_last) {
         const dim3 grid(static_cast<unsigned>(gx), p->r, static_cast<unsigned>(most_segs));
-        k_row_values_walk<0><<<grid, 64, 0, stream>>>(kparams(p), segs, S, d, i0, rows, est);
+        k_row_values_walk<0, false><<<grid, 64, 0, stream>>>(kparams(p), segs, S, d, i0, rows, est, nullptr);
         return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
     }
     // rows 0 .. r-2 into the scratch, then the last row together with the median
     if (p->r > 1) {
         const dim3 grid(static_cast<unsigned>(gx), p->r - 1, static_cast<unsigned>(most_segs));
-        k_row_values_walk<0><<<grid, 64, 0, stream>>>(kparams(p), segs, S, d, i0, rows, est);
+        k_row_values_walk<0, false><<<grid, 64, 0, stream>>>(kparams(p), segs, S, d, i0, rows, est, nullptr);
     }
     const dim3 grid(static_cast<unsigned>(gx), 1, static_cast<unsigned>(segs.n[p->r - 1]));
-#define CS_LAST(R_)                                                                          \
-    case R_: k_row_values_walk<R_><<<grid, 64, 0, stream>>>(kparams(p), segs, S, d, i0, rows, est); break;
+    unsigned long long* h = reinterpret_cast<unsigned long long*>(hist);
+    const dim3 hgrid(static_cast<unsigned>(((gx + kHistWaves - 1) / kHistWaves + 7) / 8 * 8), 1, grid.z);
+#define CS_LAST(R_)                                                                                    \
+    case R_:                                                                                           \
+        if (h) k_row_values_walk<R_, true><<<hgrid, 64 * kHistWaves, 0, stream>>>(kparams(p), segs, S, d, i0, rows, est, h); \
+        else k_row_values_walk<R_, false><<<grid, 64, 0, stream>>>(kparams(p), segs, S, d, i0, rows, est, h);  \
+        break;
     switch (p->r) {
         CS_LAST(1) CS_LAST(3) CS_LAST(5) CS_LAST(7) CS_LAST(9) CS_LAST(11) CS_LAST(13) CS_LAST(15)
         default: return CS_EINVAL;

@@ -46,6 +46,8 @@ class HotPath:
         self.uhat = torch.empty(k, **f32)
         self.topk_ws = torch.empty(B.cs_topk_workspace_bytes(d, self.kq), dtype=torch.uint8,
                                    device=self.device)
+        # counts of the estimates by magnitude bin: filled by the estimate, read by the selection
+        self.hist = torch.zeros(B.CS_TOPK_HIST_BINS, dtype=torch.int64, device=self.device)
         n_est = B.cs_estimate_workspace_bytes(self.params, d)
         self.est_ws = (torch.empty(n_est, dtype=torch.uint8, device=self.device)
                        if n_est else None)
@@ -71,10 +73,10 @@ class HotPath:
         return self.S_v if self.rho is not None else self.S_t
 
     def estimate(self):
-        B.cs_sketch_estimate(self.params, self.query_table(), self.est, 0, self.est_ws)
+        B.cs_sketch_estimate(self.params, self.query_table(), self.est, 0, self.est_ws, self.hist)
 
     def topk(self):
-        B.cs_heavy_hitters_topk(self.est, self.kq, self.cand, self.est_at_cand, self.topk_ws)
+        B.cs_heavy_hitters_topk(self.est, self.kq, self.cand, self.est_at_cand, self.topk_ws, self.hist)
 
     def gather(self, g_w):
         B.cs_gather_exact(g_w, self.cand, self.x_cand, alpha=1.0 / self.W)

@@ -127,11 +127,11 @@ def test_invalid_arguments_are_rejected_without_a_gpu(lib):
     assert lib.cs_sketch_accumulate(ctypes.byref(p), fake, fake, 10, -1, 1.0, null) == -1
     assert lib.cs_sketch_accumulate(ctypes.byref(p), fake, fake, 10, 1 << 61, 1.0, null) == -1
     assert lib.cs_sketch_accumulate(ctypes.byref(p), fake, fake, 0, 0, 1.0, null) == 0   # no-op
-    assert lib.cs_sketch_estimate(ctypes.byref(p), null, 10, 0, fake, null, 0, null) == -1
+    assert lib.cs_sketch_estimate(ctypes.byref(p), null, 10, 0, fake, null, null, 0, null) == -1
     assert lib.cs_sketch_merge(ctypes.byref(p), fake, 0.0, None, 2, 1.0, null) == -1
-    assert lib.cs_heavy_hitters_topk(fake, 10, 11, fake, fake, fake, 1 << 20, null) == -1
-    assert lib.cs_heavy_hitters_topk(fake, 10, 0, fake, fake, fake, 1 << 20, null) == -1
-    assert lib.cs_heavy_hitters_topk(fake, 10, 5, fake, fake, fake, 8, null) == -2
+    assert lib.cs_heavy_hitters_topk(fake, 10, 11, null, fake, fake, fake, 1 << 20, null) == -1
+    assert lib.cs_heavy_hitters_topk(fake, 10, 0, null, fake, fake, fake, 1 << 20, null) == -1
+    assert lib.cs_heavy_hitters_topk(fake, 10, 5, null, fake, fake, fake, 8, null) == -2
     size = ctypes.c_size_t(0)
     assert lib.cs_topk_workspace_bytes(10, 11, ctypes.byref(size)) == -1
     assert lib.cs_topk_workspace_bytes(10, 10, ctypes.byref(size)) == 0 and size.value > 0

@@ -357,6 +357,38 @@ def test_estimate_long_vector_bit_exact(r, c, seed, d, i0):
     np.testing.assert_array_equal(est.cpu().numpy(), ref.astype(np.float32))
 
 
+@pytest.mark.parametrize("r,c,seed,d,k", [(5, 1 << 16, 31, (1 << 24) + 1029, 20_000),   # counted by the kernel that writes est
+                                          (5, 1 << 12, 32, 1_200_003, 1_000),          # counted by one more read of est
+                                          (7, 1000, 33, 600_001, 700), (3, 64, 34, 1, 1)])
+def test_estimate_fills_the_first_histogram_of_the_selection(r, c, seed, d, k):
+    """cs_sketch_estimate with hist: the counts of the estimates by the top 11 bits of their
+    magnitude are exact (integer work on bit-exact estimates), a stale histogram is cleared, and
+    the selection that is handed the histogram returns what the selection without it returns."""
+    p = cs.cs_params_init(r, c, seed, d)
+    sk = orc.SketchOracle(r, c, seed)
+    T32 = (np.random.default_rng(seed).standard_normal((r, c)) * 0.01).astype(np.float32)
+    T32.reshape(-1)[::17] *= 64.0                     # a few octaves of magnitudes
+    est = torch.empty(d, dtype=torch.float32, device=DEV)
+    hist = torch.full((binding.CS_TOPK_HIST_BINS,), 12345, dtype=torch.int64, device=DEV)
+    n_ws = cs.cs_estimate_workspace_bytes(p, d)
+    ws = torch.empty(n_ws, dtype=torch.uint8, device=DEV) if n_ws else None
+    cs.cs_sketch_estimate(p, dev(T32), est, i0=0, workspace=ws, hist=hist)
+    ref = sk.estimate(T32.astype(np.float64), d).astype(np.float32)
+    np.testing.assert_array_equal(est.cpu().numpy(), ref)
+    want = np.bincount((ref.view(np.uint32) & np.uint32(0x7FFFFFFF)) >> np.uint32(20), minlength=2048)
+    np.testing.assert_array_equal(hist.cpu().numpy(), want)
+    tws = torch.empty(cs.cs_topk_workspace_bytes(d, k), dtype=torch.uint8, device=DEV)
+    out = []
+    for h in (hist, None):
+        idx = torch.empty(k, dtype=torch.int64, device=DEV)
+        val = torch.empty(k, dtype=torch.float32, device=DEV)
+        cs.cs_heavy_hitters_topk(est, k, idx, val, tws, hist=h)
+        out.append((idx.cpu().numpy(), val.cpu().numpy()))
+    np.testing.assert_array_equal(out[0][0], out[1][0])
+    np.testing.assert_array_equal(out[0][1].view(np.uint32), out[1][1].view(np.uint32))
+    np.testing.assert_array_equal(out[0][0], orc.topk_threshold(ref, k))
+
+
 @pytest.mark.parametrize("r,c,seed,d", [(5, 1 << 12, 21, 300_007),          # median pass over stored rows
                                         (7, 1 << 10, 22, (1 << 24) + 33),  # median inside the last row's walk
                                         (5, 1000, 23, 50_001),             # one thread per coordinate
