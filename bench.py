@@ -5,11 +5,12 @@ already resident in HBM: W Count-Sketch updates, merge, sketch-space momentum / 
 accumulation, estimate of every coordinate, top-k, exact second-round gather, sketch-space
 feedback.  Prints ONE JSON line (see the keys below).  Before the inputs are allocated, the
 placement step (input_arenas_in_fast_memory) looks for the device memory in which the update runs
-fastest against the step's own tables; --plain-placement skips it, --placement-scan N prints the
-measurement behind it instead of running the benchmark.
+fastest against the step's own tables; the same steps are also timed on inputs allocated in
+the plain order of a fresh process (`placement.plain_ms_per_step` in the JSON line), and
+--plain-placement makes that the only measurement.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu-baseline]
-                    [--variant V] [--graph] [--plain-placement] [--placement-scan N]
+                    [--variant V] [--graph] [--plain-placement]
 """
 from __future__ import annotations
 
@@ -32,10 +33,33 @@ METRIC = "sketch+estimate+top-k throughput, Gcoords/s and % HBM peak at d=100M, 
 MEASURED_TRAFFIC_BYTES = {4: 1.731e10}
 
 
+def host_cpu():
+    """(model name, logical CPUs the process may use, logical CPUs of the machine)"""
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count() or 1
+    return model, usable, os.cpu_count() or usable
+
+
 def cpu_baseline(cfg, work, sample_acc=64_000_000, sample_est=32_000_000):
-    """The CPU reference as it stands, single-threaded, on a bounded sample of the same
-    workload (sized for 10-30 s of CPU work at config 4); scaled to the cost of one full step."""
+    """The CPU reference as it stands, on a bounded sample of the same workload (sized for
+    10-30 s of CPU work at config 4), scaled to the cost of one full step.  `value` is one
+    thread, which is how the reference is written.  `all_cores` is the same code called from
+    several threads at once, one simulated worker's vector (or one slice of the coordinates to
+    query) per thread, as independent reference processes would run; the thread count is capped
+    at 16, the CPU share of a one-GPU machine, and at the number of workers."""
     import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
     from oracle import cs_oracle as orc
 
     sk = orc.SketchOracle(cfg.r, cfg.c, cfg.hash_seed)
@@ -57,6 +81,20 @@ def cpu_baseline(cfg, work, sample_acc=64_000_000, sample_est=32_000_000):
     orc.merge(tabs)
     t_merge = (time.perf_counter() - t0) / 2 * (cfg.W + (5 if cfg.stateful else 0))
     step_s = cfg.W * cfg.d * t_acc + cfg.d * (t_est + t_top) + t_merge
+
+    model, usable, logical = host_cpu()
+    threads = max(1, min(16, usable, cfg.W))
+    n_mt = min(n_acc, 16_000_000)
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        t0 = time.perf_counter()
+        list(pool.map(lambda q: sk.sketch(g[:n_mt]), range(threads)))
+        t_acc_mt = (time.perf_counter() - t0) / (threads * n_mt)
+        n_est_mt = min(n_est, 8_000_000)
+        t0 = time.perf_counter()
+        list(pool.map(lambda q: sk.estimate(T, n_est_mt, i0=q * n_est_mt % max(1, cfg.d - n_est_mt)),
+                      range(threads)))
+        t_est_mt = (time.perf_counter() - t0) / (threads * n_est_mt)
+    step_s_mt = cfg.W * cfg.d * t_acc_mt + cfg.d * (t_est_mt + t_top) + t_merge
     return {
         "value": cfg.W * cfg.d / step_s / 1e9,
         "unit": "Gcoords/s",
@@ -64,6 +102,13 @@ def cpu_baseline(cfg, work, sample_acc=64_000_000, sample_est=32_000_000):
         "kind": "oracle",
         "sample": (f"update of {n_acc} coords of one worker, estimate+top-k of {n_est} coords, "
                    f"one table merge; scaled to W={cfg.W}, d={cfg.d} (est. {step_s:.1f} s/step)"),
+        "all_cores": {"value": cfg.W * cfg.d / step_s_mt / 1e9, "unit": "Gcoords/s", "cores": threads,
+                      "sample": (f"{threads} threads at once, each the update of {n_mt} coords of a worker, "
+                                 f"then each the estimate of {n_est_mt} coords; selection and merge "
+                                 f"single-threaded (est. {step_s_mt:.1f} s/step)")},
+        "cpu_model": model,
+        "cpus_usable": usable,
+        "cpus_logical": logical,
     }
 
 
@@ -98,11 +143,13 @@ def input_arenas_in_fast_memory(torch, B, hp, cfg, dev, n_sets):
     chunks are within 0.6 % of the fastest and at least 4 % faster than the slowest.  Those
     become the input sets; the other chunks are freed.  The search goes on for n_sets + 10 chunks
     (one part alone is 8 chunks of 12.8 GB); when no chunk stands out by then, the first n_sets
-    chunks are used.  Returns (arenas, probe times in ms, indices chosen), or (None, [], []) for
-    inputs too small to place."""
+    chunks are used.  Returns (arenas, probe times in ms, indices chosen, plain), or
+    (None, [], [], None) for inputs too small to place; `plain` are the first n_sets chunks (where
+    a fresh process that allocates its inputs right after its tables would have them) when the
+    choice fell on others, kept so that the same steps can be timed on them, else None."""
     chunk_bytes = 4 * cfg.d * cfg.W
     if cfg.W < 8 or chunk_bytes < (2 << 30) or not B.cs_bundle_update_launches(hp.params, 8, cfg.d):
-        return None, [], []
+        return None, [], [], None
     walk = B.CsParams.from_buffer_copy(hp.params)
     walk.flags |= B.CS_FLAG_NO_VISIT_LIST
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -129,51 +176,12 @@ def input_arenas_in_fast_memory(torch, B, hp, cfg, dev, n_sets):
             break
     chosen = choose_chunks(times, n_sets)
     if chosen is None:
-        return None, times, []
+        return None, times, [], None
     arenas = [chunks[q] for q in chosen]
+    plain = [chunks[q] for q in range(n_sets)] if chosen != list(range(n_sets)) else None
     del chunks, big, vecs
     torch.cuda.empty_cache()
-    return arenas, times, chosen
-
-
-def placement_scan(torch, B, cfg, dev, tables_after):
-    """Evidence for the placement step (--placement-scan): allocates the worker tables, then
-    arenas of one input set's size one after the other, keeping them all, and times the update
-    and the plain read on each; with tables_after > 0 the tables are allocated only after that
-    many arenas.  Prints one line per arena."""
-    p = B.cs_params_init(cfg.r, cfg.c, cfg.hash_seed, cfg.d)
-    out = torch.zeros(1, dtype=torch.float32, device=dev)
-    e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
-    arenas, T = [], None
-    q = 0
-    while True:
-        free_bytes, _total = torch.cuda.mem_get_info()
-        if free_bytes < 4 * cfg.d * cfg.W + (16 << 30) or q >= 18:
-            break
-        if T is None and q >= tables_after:
-            T = torch.zeros(B.cs_bundle_floats(p, cfg.W), dtype=torch.float32, device=dev)
-            print(f"tables allocated after {q} arenas", flush=True)
-        big = torch.empty(cfg.d * cfg.W, dtype=torch.float32, device=dev)
-        big.normal_(0.0, 0.01)
-        arenas.append(big)
-        q += 1
-        if T is None:
-            continue
-        for first in range(len(arenas) - 1 if tables_after == 0 or q > tables_after + 1 else 0, len(arenas)):
-            a = arenas[first]
-            vecs = [a[w * cfg.d:(w + 1) * cfg.d] for w in range(cfg.W)]
-            B.cs_sketch_accumulate_bundle(p, T, vecs)
-            e[0].record()
-            for _ in range(4):
-                B.cs_sketch_accumulate_bundle(p, T, vecs)
-            e[1].record()
-            for _ in range(4):
-                B.cs_probe_stream_read(vecs, out)
-            e[2].record()
-            torch.cuda.synchronize()
-            print(f"arena {first} ({first * 4 * cfg.d * cfg.W / 1e9:.0f} GB of arenas before it): "
-                  f"update {e[0].elapsed_time(e[1]) / 4:.3f} ms, plain read "
-                  f"{4 * cfg.d * cfg.W / (e[1].elapsed_time(e[2]) / 4) / 1e9:.2f} TB/s", flush=True)
+    return arenas, times, chosen, plain
 
 
 def main():
@@ -196,13 +204,6 @@ def main():
     ap.add_argument("--plain-placement", action="store_true",
                     help="allocate the inputs in the plain order of a fresh process, without "
                          "first looking for the device memory where the update runs fastest")
-    ap.add_argument("--placement-scan", type=int, default=None, metavar="N",
-                    help="instead of the benchmark: time the update and the plain read on arenas "
-                         "allocated one after the other, the worker tables being allocated after "
-                         "the first N arenas (0: before all of them)")
-    ap.add_argument("--calibration-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy (a kernel of known HBM traffic) "
-                         "so that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -220,9 +221,6 @@ def main():
         sys.exit(1)
     dev = "cuda:0"
     cfg = wl.CONFIGS[args.config]
-    if args.placement_scan is not None:
-        placement_scan(torch, B, cfg, dev, args.placement_scan)
-        return
     work = wl.Workload(cfg, dev)
     variant = args.variant
     if variant == "dense-state":
@@ -240,15 +238,21 @@ def main():
     # inputs resident in HBM before the timed region: a few distinct steps' worth, cycled
     bytes_per_set = 4 * cfg.d * cfg.W
     n_sets = max(1, min(args.steps + args.warmup, int(60e9 // bytes_per_set), 4))
-    arenas, probe_ms, chosen = (None, [], []) if args.plain_placement else input_arenas_in_fast_memory(
-        torch, B, hp, cfg, dev, n_sets)
+    arenas, probe_ms, chosen, plain_arenas = (
+        (None, [], [], None) if args.plain_placement
+        else input_arenas_in_fast_memory(torch, B, hp, cfg, dev, n_sets))
+
+    def sets_in(chunks):
+        out = [[chunks[t][w * cfg.d:(w + 1) * cfg.d] for w in range(cfg.W)] for t in range(n_sets)]
+        for t in range(n_sets):
+            for w in range(cfg.W):
+                work.gradient(t, w, out=out[t][w])
+        return out
+
     if arenas is None:
         sets = [[work.gradient(t, w) for w in range(cfg.W)] for t in range(n_sets)]
     else:
-        sets = [[arenas[t][w * cfg.d:(w + 1) * cfg.d] for w in range(cfg.W)] for t in range(n_sets)]
-        for t in range(n_sets):
-            for w in range(cfg.W):
-                work.gradient(t, w, out=sets[t][w])
+        sets = sets_in(arenas)
     torch.cuda.synchronize()
 
     # stage names per variant; stage i runs between events i and i + 1.  Stage 0 is always the
@@ -297,27 +301,33 @@ def main():
             hp.gather(g_w); mark(6)
             hp.feedback(); mark(7)
 
-    if args.calibration_copy:
-        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
+    def timed_steps(input_sets):
+        """args.warmup untimed steps, then args.steps timed ones; (ms per step, events)"""
+        for t in range(args.warmup):
+            one_step(input_sets[t % n_sets])
         torch.cuda.synchronize()
-        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(10)] for _ in range(args.steps)]
         torch.cuda.synchronize()
-        del src, dst
+        t0 = time.perf_counter()
+        for t in range(args.steps):
+            one_step(input_sets[(args.warmup + t) % n_sets], evs[t])
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / args.steps * 1e3, evs
 
-    for t in range(args.warmup):
-        one_step(sets[t % n_sets])
-    torch.cuda.synchronize()
+    # the same steps on inputs where a fresh process would plainly have them, for the record
+    # (state tables are reset in between so that both runs do the same work)
+    plain_ms_per_step = None
+    if plain_arenas is not None:
+        state = [t.clone() for t in (getattr(hp, "S_u", None), getattr(hp, "S_v", None)) if t is not None]
+        plain_ms_per_step, _ = timed_steps(sets_in(plain_arenas))
+        for t, saved in zip([t for t in (getattr(hp, "S_u", None), getattr(hp, "S_v", None)) if t is not None], state):
+            t.copy_(saved)
+        del plain_arenas, state
+        torch.cuda.empty_cache()
 
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(10)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for t in range(args.steps):
-        one_step(sets[(args.warmup + t) % n_sets], events[t])
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-
-    ms_per_step = elapsed / args.steps * 1e3
+    ms_per_step, events = timed_steps(sets)
+    if args.plain_placement or (arenas is not None and plain_ms_per_step is None):
+        plain_ms_per_step = ms_per_step          # the inputs are in the plain order
     stage_ms = {}
     for i, name in enumerate(stages):
         stage_ms[name] = sum(ev[i].elapsed_time(ev[i + 1]) for ev in events) / args.steps
@@ -382,7 +392,12 @@ def main():
         "placement": {"probe": "stride-walk update of successive chunks of one input set's size",
                       "probe_ms": [round(t, 3) for t in probe_ms],
                       "chunks_used_for_inputs": chosen,
-                      "update_ms_per_input_set": update_ms_per_set},
+                      "update_ms_per_input_set": update_ms_per_set,
+                      "plain_ms_per_step": plain_ms_per_step,
+                      "plain_value": (cfg.W * cfg.d / (plain_ms_per_step * 1e-3) / 1e9
+                                      if plain_ms_per_step else None),
+                      "note": "plain_*: the same timed steps with the inputs allocated in the plain "
+                              "order of a fresh process (the first chunks), before the headline run"},
         "stage_ms": stage_ms,
         "stage_Gcoords_s": {name: (cfg.W if name in ("accumulate", "dense_momentum") else 1) * cfg.d
                             / (stage_ms[name] * 1e-3) / 1e9

@@ -357,13 +357,6 @@ int cs_dense_mask(float* const* u_w, float* const* v_w, int32_t W, const int64_t
 int cs_sketch_feedback(const cs_params* p, float* S, const int64_t* idx, int64_t k,
                        float* val, void* stream);
 
-/* Measurement aid, no part of the method: reads the W vectors x_w[w][0..d) once, as plainly as
- * the hardware allows, and adds the sum of all values to out[0] (device float, accumulated
- * into, fp32 in no fixed order).  The rate of this call is the streaming-read ceiling that the
- * bandwidth-bound kernels of the path are reported against (Sec. 5.2 gives no kernel design and
- * no rates of its own).  x_w: HOST array of W device pointers to float[d].  W >= 1, d >= 0. */
-int cs_probe_stream_read(const float* const* x_w, int32_t W, int64_t d, float* out, void* stream);
-
 const char* cs_status_string(int status);
 
 #ifdef __cplusplus

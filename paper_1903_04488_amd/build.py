@@ -29,17 +29,6 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
-def build_microbench() -> str:
-    """Builds the standalone memory-system microbenchmark (csrc/cs_microbench.hip)."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    out = os.path.join(PKG, "cs_microbench.bin")
-    subprocess.check_call([hipcc, "-O3", "--offload-arch=gfx950", "-munsafe-fp-atomics",
-                           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-                           "-Wno-unused-command-line-argument",
-                           "-o", out, os.path.join(CSRC, "cs_microbench.hip")])
-    return out
-
-
 def needs_build() -> bool:
     if not os.path.exists(LIB):
         return True
@@ -49,7 +38,4 @@ def needs_build() -> bool:
 
 
 if __name__ == "__main__":
-    import sys
     print(build_library(verbose=True))
-    if "--microbench" in sys.argv:
-        print(build_microbench())

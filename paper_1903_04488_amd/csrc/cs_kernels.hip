@@ -6,6 +6,7 @@
 #include "cs_device.h"
 #include "cs_internal.h"
 #include "csketch.h"
+#include "csketch_probe.h"
 
 namespace cs {
 
