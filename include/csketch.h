@@ -100,6 +100,26 @@ typedef struct cs_visit_plan {
     uint32_t code[CS_MAX_VISITS / 16];   /* 2 bits per visit, visit k in word k / 16 */
 } cs_visit_plan;
 
+/* Visit list of one row for column counts that are not a power of two (the paper's sketches of
+ * 180 000 columns, Table 1).  Here h_j(i + s) = (x(i) + X(s) - [wrap] p) mod c with
+ * X(s) = (a_j s) mod p and [wrap] = 1 when x(i) + X(s) >= p, so for an offset s with
+ * X(s) mod c = delta < omega the bucket of i + s is h_j(i) + delta, or, after a wrap,
+ * h_j(i) + delta - (p mod c)  (mod c): one of 2 omega cells that depend on i only.  Such offsets
+ * occur about every c / omega coordinates; the list is a subset of them, picked so that the
+ * gaps are as even as they come (gaps are stored one by one: they take no three values here).
+ * A lane that visits i + s_0, i + s_1, ... keeps 2 omega running sums per coordinate and sends
+ * each to memory once.  K = 0: no list, the update sends one request per coordinate and row. */
+#define CS_ANYC_MAX_VISITS 144
+typedef struct cs_anyc_plan {
+    uint32_t K;                 /* number of visits; 0 = no list */
+    uint32_t omega;             /* 1 or 2 */
+    uint64_t cover;             /* the list covers vectors of length <= cover (= d_hint) */
+    uint64_t gmax;              /* largest gap = number of residues that lanes own */
+    uint64_t cost;              /* estimated time of one launch with this list, nanoseconds */
+    uint64_t cost_direct;       /* the same for one request per coordinate */
+    uint32_t gap[CS_ANYC_MAX_VISITS];   /* gap_k = s_{k+1} - s_k, s_0 = 0, s_K = d_hint */
+} cs_anyc_plan;
+
 #define CS_FLAG_NO_VISIT_LIST 1u   /* cs_params.flags: always use the stride walk (testing) */
 #define CS_FLAG_NO_LDS_TABLE 2u    /* cs_params.flags: tiny tables are updated in memory, not in a
                                       workgroup-private LDS copy (testing) */
@@ -114,6 +134,7 @@ typedef struct cs_params {
     uint64_t as[CS_MAX_R], bs[CS_MAX_R];   /* sign hashes */
     cs_row_plan plan[CS_MAX_R];
     cs_visit_plan visit[CS_MAX_R];
+    cs_anyc_plan anyc[CS_MAX_R];
 } cs_params;
 
 /* Alg. 4 init: fills *p for an r x c sketch from `seed` (host, no GPU needed).

@@ -45,6 +45,19 @@ class CsVisitPlan(ctypes.Structure):
         return [int(self.gap[(self.code[k // 16] >> (2 * (k % 16))) & 3]) for k in range(self.K)]
 
 
+CS_ANYC_MAX_VISITS = 144
+
+
+class CsAnycPlan(ctypes.Structure):
+    _fields_ = [("K", ctypes.c_uint32), ("omega", ctypes.c_uint32),
+                ("cover", ctypes.c_uint64), ("gmax", ctypes.c_uint64),
+                ("cost", ctypes.c_uint64), ("cost_direct", ctypes.c_uint64),
+                ("gap", ctypes.c_uint32 * CS_ANYC_MAX_VISITS)]
+
+    def gaps(self):
+        return [int(self.gap[k]) for k in range(self.K)]
+
+
 class CsParams(ctypes.Structure):
     _fields_ = [("r", ctypes.c_uint32), ("c", ctypes.c_uint32),
                 ("c_pow2", ctypes.c_uint32), ("flags", ctypes.c_uint32),
@@ -52,7 +65,8 @@ class CsParams(ctypes.Structure):
                 ("a", ctypes.c_uint64 * CS_MAX_R), ("b", ctypes.c_uint64 * CS_MAX_R),
                 ("as_", ctypes.c_uint64 * CS_MAX_R), ("bs", ctypes.c_uint64 * CS_MAX_R),
                 ("plan", CsRowPlan * CS_MAX_R),
-                ("visit", CsVisitPlan * CS_MAX_R)]
+                ("visit", CsVisitPlan * CS_MAX_R),
+                ("anyc", CsAnycPlan * CS_MAX_R)]
 
 
 def library_path() -> str:

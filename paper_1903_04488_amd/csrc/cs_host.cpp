@@ -3,6 +3,7 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <algorithm>
 #include <vector>
 
 #include "csketch.h"
@@ -237,6 +238,85 @@ void plan_visits(cs_visit_plan* vp, const cs_row_plan* rp, uint64_t a, uint64_t 
     vp->K = K;
 }
 
+// Visit list for a column count that is not a power of two (cs_anyc_plan).
+//
+// One scan of s = 1 .. d - 1 keeps x = (a s) mod p and x mod c side by side (both step by a
+// constant, minus p resp. p mod c on a wrap, so no division is needed) and collects the offsets
+// whose x mod c is 0 or 1.  For omega = 1 and 2 and a few target gaps T, visits are then picked
+// greedily: the last qualifying offset within T of the previous visit, or, if there is none,
+// the first one beyond.  The list with the lowest estimated time (same model as for the
+// power-of-two lists, 2 omega requests per residue) is kept if it beats one request per
+// coordinate.
+void plan_anyc(cs_anyc_plan* vp, uint64_t a, uint32_t c, bool pow2, uint64_t d_hint) {
+    memset(vp, 0, sizeof(*vp));
+    if (pow2 || c < 64 || d_hint < 65536 || d_hint > kPlanScanMax) return;
+    const uint64_t ac = a % c, pc = kP61 % c;
+    std::vector<uint32_t> pos[2];                          // offsets with x mod c == 0, == 1
+    {
+        uint64_t x = 0, r = 0;
+        for (uint64_t s = 1; s < d_hint; ++s) {
+            x += a;
+            r += ac;
+            if (r >= c) r -= c;
+            if (x >= kP61) {
+                x -= kP61;
+                r = r >= pc ? r - pc : r + c - pc;
+            }
+            if (r < 2) {
+                pos[r].push_back((uint32_t)s);
+                if (pos[0].size() + pos[1].size() > (4u << 20)) return;    // c far too small for d
+            }
+        }
+    }
+    vp->cost_direct = (uint64_t)update_time_ns(1.0, 128.0, (double)d_hint, (double)d_hint);
+    uint64_t best_cost = ~0ull;
+    std::vector<uint32_t> best_gaps;
+    uint32_t best_omega = 0;
+    for (uint32_t omega = 1; omega <= 2; ++omega) {
+        std::vector<uint32_t> q(pos[0]);
+        if (omega == 2) {
+            q.insert(q.end(), pos[1].begin(), pos[1].end());
+            std::sort(q.begin(), q.end());
+        }
+        if (q.size() < 4) continue;
+        for (uint32_t Kt : {12u, 16u, 24u, 32u, 48u, 64u, 96u, 128u, 143u}) {
+            const uint64_t T = d_hint / Kt;
+            if (T == 0) continue;
+            std::vector<uint32_t> gaps;
+            uint64_t prev = 0, gmax = 0;
+            size_t at = 0;                                 // first qualifying offset > prev
+            bool ok = true;
+            while (prev + T < d_hint) {
+                while (at < q.size() && q[at] <= prev) ++at;
+                if (at == q.size()) break;
+                size_t pick = at;                          // the first one beyond, unless ...
+                while (pick + 1 < q.size() && q[pick + 1] <= prev + T) ++pick;   // ... one lies within T
+                const uint64_t next = q[pick];
+                gaps.push_back((uint32_t)(next - prev));
+                if (next - prev > gmax) gmax = next - prev;
+                prev = next;
+                if (gaps.size() >= CS_ANYC_MAX_VISITS) { ok = false; break; }
+            }
+            if (!ok) continue;
+            gaps.push_back((uint32_t)(d_hint - prev));
+            if (d_hint - prev > gmax) gmax = d_hint - prev;
+            if (gaps.size() < 4) continue;
+            const uint64_t cost = (uint64_t)update_time_ns((double)gaps.size(), (double)gmax,
+                                                           2.0 * omega * (double)gmax, (double)d_hint);
+            if (cost < best_cost) { best_cost = cost; best_gaps = gaps; best_omega = omega; }
+        }
+    }
+    if (best_gaps.empty()) return;
+    vp->K = (uint32_t)best_gaps.size();
+    vp->omega = best_omega;
+    vp->cover = d_hint;
+    vp->cost = best_cost;
+    for (size_t k = 0; k < best_gaps.size(); ++k) {
+        vp->gap[k] = best_gaps[k];
+        if (best_gaps[k] > vp->gmax) vp->gmax = best_gaps[k];
+    }
+}
+
 }  // namespace
 
 extern "C" int cs_params_init(cs_params* p, uint32_t r, uint32_t c, uint64_t seed,
@@ -264,6 +344,7 @@ extern "C" int cs_params_init(cs_params* p, uint32_t r, uint32_t c, uint64_t see
         plan_walk(&p->plan[j], p->a[j], p->as[j], c, p->c_pow2 != 0, (uint64_t)d_hint);
         plan_visits(&p->visit[j], &p->plan[j], p->a[j], p->as[j], c, p->c_pow2 != 0,
                     (uint64_t)d_hint);
+        plan_anyc(&p->anyc[j], p->a[j], c, p->c_pow2 != 0, (uint64_t)d_hint);
     }
     return CS_OK;
 }

@@ -586,6 +586,7 @@ extern "C" int cs_sketch_accumulate_bundle(const cs_params* p, float* T, int32_t
         if (!g_w[w] && d > 0) return CS_EINVAL;
     if (d == 0) return CS_OK;
     if (walk_applies(p, d)) return launch_accumulate_walk(p, T, W, g_w, d, i0, scale, as_stream(stream));
+    if (anyc_visits_apply(p, d)) return launch_accumulate_anyc(p, T, W, g_w, d, i0, scale, as_stream(stream));
     // any other sketch: a slot of 8 lanes per coordinate, one lane per worker of a group
     const size_t group_floats = static_cast<size_t>(p->r) * p->c * CS_BUNDLE_GROUP;
     constexpr int kSlots = kBlock / CS_BUNDLE_GROUP;
@@ -621,6 +622,7 @@ extern "C" int cs_bundle_update_launches(const cs_params* p, int32_t W, int64_t 
     if (!bundle_ok(p, W) || d < 0 || !n) return CS_EINVAL;
     if (d == 0) { *n = 0; return CS_OK; }
     if (walk_applies(p, d)) { *n = count_accumulate_walk_launches(p, W, d); return CS_OK; }
+    if (anyc_visits_apply(p, d)) { *n = count_accumulate_anyc_launches(p, W); return CS_OK; }
     *n = (W + kMaxBatch - 1) / kMaxBatch;
     return CS_OK;
 }

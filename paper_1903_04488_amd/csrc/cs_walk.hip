@@ -35,6 +35,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "cs_device.h"
 #include "cs_internal.h"
 #include "csketch.h"
@@ -288,6 +290,21 @@ constexpr int kRowsPerLaunch = 8;
 constexpr int kVisitSetBlock = 5;
 struct VisitRows {
     VisitArgs row[kRowsPerLaunch];
+    __device__ __forceinline__ const VisitArgs& at(unsigned y) const { return row[y]; }
+};
+// The list of one row when the column count is not a power of two (cs_anyc_plan): gaps and hash
+// advances visit by visit.  One row per launch: with 144 visits the struct is 2.9 KB of the
+// 4 KB that kernel arguments may take.
+struct VisitListAny {
+    uint32_t K;
+    int32_t j;
+    uint64_t gmax;
+    uint64_t a, b, as, bs;
+    uint32_t omega;              // running sums: omega cells from the first one, omega more after a wrap
+    uint32_t pc;                 // p mod c: how far back a wrap past p sets the bucket
+    uint32_t gap[CS_ANYC_MAX_VISITS];
+    uint64_t A[CS_ANYC_MAX_VISITS], As[CS_ANYC_MAX_VISITS];
+    __device__ __forceinline__ const VisitListAny& at(unsigned) const { return *this; }
 };
 struct VisitWorkers {
     const float* g[kGroup];      // vectors of the workers of this group
@@ -323,10 +340,14 @@ __device__ __forceinline__ void load_floats(gfloat_ptr src, float (&out)[N]) {
     }
 }
 
-template <int WL, int RUN, int NWAVE, int NC>
+// LIST = VisitRows (power-of-two column counts: three gaps and 2-bit codes, the NC cells are
+// neighbours) or VisitListAny (any column count: gaps one by one, NC = 2 omega cells of which
+// the second half lies p mod c cells back).
+template <int WL, int RUN, int NWAVE, int NC, typename LIST>
 __global__ void __launch_bounds__(64 * NWAVE)
-k_accumulate_visits(VisitRows rows, VisitWorkers a) {
-    const VisitArgs& v = rows.row[blockIdx.y];
+k_accumulate_visits(LIST rows, VisitWorkers a) {
+    constexpr bool POW2 = std::is_same<LIST, VisitRows>::value;
+    const auto& v = rows.at(blockIdx.y);
     constexpr int WPW = 64 / WL;                       // walkers per wavefront
     constexpr int PPL = RUN / WL;                      // hash values each lane computes
     constexpr int FPL = RUN / WL;                      // floats each lane requests per worker
@@ -362,8 +383,32 @@ k_accumulate_visits(VisitRows rows, VisitWorkers a) {
     const int64_t chunks = (static_cast<int64_t>(v.gmax) + RUN - 1) / RUN;
     const int64_t nwaves = (chunks + WPW - 1) / WPW;
     const uint32_t mask = a.c - 1u;
+    const Columns col = columns_of<POW2>(a.c);
     const int64_t d = a.d;
     float* __restrict__ Tcol = a.T + static_cast<size_t>(v.j) * a.c * kGroup + wl;
+    // which running sum a coordinate now in `cell` belongs to, given the cell it started in;
+    // >= NC: none of them (never with a list of cs_params_init)
+    auto sum_of = [&](uint32_t cell, uint32_t first) -> uint32_t {
+        if constexpr (POW2) {
+            return (cell - first) & mask;
+        } else {
+            const uint32_t c = a.c, omega = v.omega;
+            const uint32_t t = cell >= first ? cell - first : cell + c - first;    // (cell - first) mod c
+            if (t < omega) return t;
+            const uint32_t t2 = t + v.pc >= c ? t + v.pc - c : t + v.pc;            // after a wrap past p
+            return t2 < omega ? omega + t2 : static_cast<uint32_t>(NC);
+        }
+    };
+    // the cell of running sum q of a coordinate that started in cell `first`
+    auto cell_of_sum = [&](uint32_t first, int q) -> uint32_t {
+        if constexpr (POW2) {
+            return (first + static_cast<uint32_t>(q)) & mask;
+        } else {
+            const uint32_t c = a.c, omega = v.omega;
+            uint32_t x = static_cast<uint32_t>(q) < omega ? first + q : first + (q - omega) + (c - v.pc);
+            return x >= c ? x - c : x;
+        }
+    };
     const int m0 = wl * PPL;                           // hash role: coordinates m0 .. m0 + PPL - 1
     float* my_row = tile_lds + lane * kStride;         // consumer role: my walker's run of my worker
     const uint32_t* my_rec = rec_lds + h * kRecWalker;
@@ -382,13 +427,27 @@ k_accumulate_visits(VisitRows rows, VisitWorkers a) {
     const int lspan = PAIR ? (lane & 31) * kPer : lane * FPL;
     float* tile_dst = tile_lds + ((lspan / RUN) * WL + half) * kStride + lspan % RUN;
     constexpr int kRowStep = PAIR ? 2 * kStride : kStride;   // tile rows between my loads
-    // the list's three gaps and the cut last one, with their hash advances, in scalar registers
-    const uint64_t g0 = v.gap[0], g1 = v.gap[1], g2 = v.gap[2], g3 = v.gap[3];
-    const uint64_t A0 = v.A[0], A1 = v.A[1], A2 = v.A[2], A3 = v.A[3];
-    const uint64_t B0 = v.As[0], B1 = v.As[1], B2 = v.As[2], B3 = v.As[3];
-    auto code_of = [&](uint32_t k) { return (v.code[k >> 4] >> ((k & 15u) * 2u)) & 3u; };
+    // gap and hash advances of visit k.  Power-of-two lists: three gaps and the cut last one
+    // live in scalar registers and a 2-bit code per visit picks among them; other lists are
+    // read visit by visit from the kernel arguments.
     auto pick = [](uint32_t code, uint64_t x0, uint64_t x1, uint64_t x2, uint64_t x3) {
         return code == 0u ? x0 : code == 1u ? x1 : code == 2u ? x2 : x3;
+    };
+    auto code_of = [&](uint32_t k) -> uint32_t {
+        if constexpr (POW2) return (v.code[k >> 4] >> ((k & 15u) * 2u)) & 3u;
+        else return k;
+    };
+    auto gap_of = [&](uint32_t code) -> int64_t {
+        if constexpr (POW2) return static_cast<int64_t>(pick(code, v.gap[0], v.gap[1], v.gap[2], v.gap[3]));
+        else return static_cast<int64_t>(v.gap[code]);
+    };
+    auto A_of = [&](uint32_t code) -> uint64_t {
+        if constexpr (POW2) return pick(code, v.A[0], v.A[1], v.A[2], v.A[3]);
+        else return v.A[code];
+    };
+    auto As_of = [&](uint32_t code) -> uint64_t {
+        if constexpr (POW2) return pick(code, v.As[0], v.As[1], v.As[2], v.As[3]);
+        else return v.As[code];
     };
 
     // Walkers with small residues take part in every visit, those with large ones only in
@@ -411,7 +470,7 @@ k_accumulate_visits(VisitRows rows, VisitWorkers a) {
             uint64_t tb = yb;
 #pragma unroll
             for (int q = 0; q < PPL; ++q) {
-                first_cell[q] = (static_cast<uint32_t>(tb) - 1u) & mask;
+                first_cell[q] = bucket_of<POW2>(tb, col);
                 first_lds[h * RUN + m0 + q] = first_cell[q];
                 if (q + 1 < PPL) tb = hash_advance(tb, Aj);
             }
@@ -468,8 +527,8 @@ k_accumulate_visits(VisitRows rows, VisitWorkers a) {
 
         int64_t s = 0;                                 // offset of visit k
         uint32_t code = code_of(0);
-        bool active = room_of(0, static_cast<int64_t>(pick(code, g0, g1, g2, g3))) > 0;
-        if (active) load_visit(0, room_of(0, static_cast<int64_t>(pick(code, g0, g1, g2, g3))));
+        bool active = room_of(0, gap_of(code)) > 0;
+        if (active) load_visit(0, room_of(0, gap_of(code)));
         for (uint32_t k = 0; k < v.K; ++k) {
             // visit k: its values are on their way (requested one turn earlier)
             const bool was_active = active;
@@ -482,11 +541,11 @@ k_accumulate_visits(VisitRows rows, VisitWorkers a) {
             // request visit k + 1 as soon as the registers of visit k are free, to fly while
             // visit k is hashed and added up
             const uint32_t code_k = code;
-            s += static_cast<int64_t>(pick(code_k, g0, g1, g2, g3));
+            s += gap_of(code_k);
             active = false;
             if (k + 1 < v.K) {
                 code = code_of(k + 1);
-                const int64_t room = room_of(s, static_cast<int64_t>(pick(code, g0, g1, g2, g3)));
+                const int64_t room = room_of(s, gap_of(code));
                 active = room > 0;
                 if (active) load_visit(s, room);
             }
@@ -495,8 +554,8 @@ k_accumulate_visits(VisitRows rows, VisitWorkers a) {
                 uint64_t tb = yb, ts = ys;
 #pragma unroll
                 for (int q = 0; q < PPL; ++q) {
-                    const uint32_t cell = (static_cast<uint32_t>(tb) - 1u) & mask;
-                    const uint32_t rel = (cell - first_cell[q]) & mask;
+                    const uint32_t cell = bucket_of<POW2>(tb, col);
+                    const uint32_t rel = sum_of(cell, first_cell[q]);
                     const uint32_t flip = sign_flip_of(ts);
                     bad |= rel >= static_cast<uint32_t>(NC);
                     if (NC == 2) {
@@ -521,15 +580,15 @@ k_accumulate_visits(VisitRows rows, VisitWorkers a) {
                 uint64_t tb = yb, ts = ys;
 #pragma unroll
                 for (int q = 0; q < PPL; ++q) {
-                    raw_lds[h * RUN + m0 + q] = ((static_cast<uint32_t>(tb) - 1u) & mask) | sign_flip_of(ts);
+                    raw_lds[h * RUN + m0 + q] = bucket_of<POW2>(tb, col) | sign_flip_of(ts);
                     if (q + 1 < PPL) {
                         tb = hash_advance(tb, Aj);
                         ts = hash_advance(ts, Asj);
                     }
                 }
             }
-            yb = hash_advance(yb, pick(code_k, A0, A1, A2, A3));
-            ys = hash_advance(ys, pick(code_k, B0, B1, B2, B3));
+            yb = hash_advance(yb, A_of(code_k));
+            ys = hash_advance(ys, As_of(code_k));
             __builtin_amdgcn_wave_barrier();
             if (stray) {
                 const uint32_t* raw = raw_lds + h * RUN;
@@ -580,7 +639,7 @@ k_accumulate_visits(VisitRows rows, VisitWorkers a) {
 #pragma unroll
             for (int q = 0; q < NC; ++q)
                 if (live && acc[q][m] != 0.0f)
-                    atomic_add_noret(Tcol + static_cast<size_t>((c0 + q) & mask) * kGroup,
+                    atomic_add_noret(Tcol + static_cast<size_t>(cell_of_sum(c0, q)) * kGroup,
                                      a.scale * acc[q][m]);
         }
         __builtin_amdgcn_wave_barrier();
@@ -616,9 +675,9 @@ int launch_visits(const cs_params* p, const VisitWorkers& a, const uint32_t* js,
     gx = (gx + 8 * kVisitSetBlock - 1) / (8 * kVisitSetBlock) * (8 * kVisitSetBlock);
     const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(nrows)), block(64 * NWAVE);
     switch (ncell) {
-        case 2: k_accumulate_visits<WL, RUN, NWAVE, 2><<<grid, block, 0, stream>>>(rows, a); break;
-        case 3: k_accumulate_visits<WL, RUN, NWAVE, 3><<<grid, block, 0, stream>>>(rows, a); break;
-        case 4: k_accumulate_visits<WL, RUN, NWAVE, 4><<<grid, block, 0, stream>>>(rows, a); break;
+        case 2: k_accumulate_visits<WL, RUN, NWAVE, 2, VisitRows><<<grid, block, 0, stream>>>(rows, a); break;
+        case 3: k_accumulate_visits<WL, RUN, NWAVE, 3, VisitRows><<<grid, block, 0, stream>>>(rows, a); break;
+        case 4: k_accumulate_visits<WL, RUN, NWAVE, 4, VisitRows><<<grid, block, 0, stream>>>(rows, a); break;
         default: return CS_EINVAL;
     }
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
@@ -633,7 +692,81 @@ bool visits_apply(const cs_params* p, uint32_t j, int64_t d) {
     return vp.cost < vp.cost_walk;
 }
 
+// one launch: row j of one group of workers along its list for any column count
+template <int WL, int RUN, int NWAVE>
+int launch_visits_anyc(const cs_params* p, const VisitWorkers& a, uint32_t j, hipStream_t stream) {
+    constexpr int WPW = 64 / WL;
+    const cs_anyc_plan& vp = p->anyc[j];
+    VisitListAny v{};
+    v.K = vp.K;
+    v.j = static_cast<int32_t>(j);
+    v.gmax = vp.gmax;
+    v.a = p->a[j]; v.b = p->b[j]; v.as = p->as[j]; v.bs = p->bs[j];
+    v.omega = vp.omega;
+    v.pc = static_cast<uint32_t>(kP61 % p->c);
+    for (uint32_t k = 0; k < vp.K; ++k) {
+        v.gap[k] = vp.gap[k];
+        v.A[k] = static_cast<uint64_t>((static_cast<unsigned __int128>(p->a[j]) * vp.gap[k]) % kP61);
+        v.As[k] = static_cast<uint64_t>((static_cast<unsigned __int128>(p->as[j]) * vp.gap[k]) % kP61);
+    }
+    const int64_t chunks = (static_cast<int64_t>(vp.gmax) + RUN - 1) / RUN;
+    const int64_t nwaves = (chunks + WPW - 1) / WPW;
+    const int64_t ngroups = (nwaves + NWAVE - 1) / NWAVE;
+    const int64_t cap = 256 * 64 / NWAVE;
+    int64_t gx = ngroups < cap ? ngroups : cap;
+    gx = (gx + 8 * kVisitSetBlock - 1) / (8 * kVisitSetBlock) * (8 * kVisitSetBlock);
+    const dim3 grid(static_cast<unsigned>(gx), 1), block(64 * NWAVE);
+    if (vp.omega == 1) k_accumulate_visits<WL, RUN, NWAVE, 2, VisitListAny><<<grid, block, 0, stream>>>(v, a);
+    else if (vp.omega == 2) k_accumulate_visits<WL, RUN, NWAVE, 4, VisitListAny><<<grid, block, 0, stream>>>(v, a);
+    else return CS_EINVAL;
+    return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
+}
+
 }  // namespace
+
+// Every row has a list for this column count and vector length, and by its own estimate the
+// list beats one request per coordinate.
+bool anyc_visits_apply(const cs_params* p, int64_t d) {
+    if (p->c_pow2 || (p->flags & CS_FLAG_NO_VISIT_LIST) != 0) return false;
+    for (uint32_t j = 0; j < p->r; ++j) {
+        const cs_anyc_plan& vp = p->anyc[j];
+        if (vp.K == 0 || vp.K > CS_ANYC_MAX_VISITS || (vp.omega != 1 && vp.omega != 2)) return false;
+        if (static_cast<uint64_t>(d) > vp.cover || vp.cost >= vp.cost_direct) return false;
+    }
+    return true;
+}
+
+int count_accumulate_anyc_launches(const cs_params* p, int W) {
+    return static_cast<int>(p->r) * ((W + kGroup - 1) / kGroup);
+}
+
+// One launch per row and group of 8 workers: every row has its own visiting order, so the
+// group's vectors are read once per row (where the direct form reads them once in all but
+// sends d requests per row to the atomic unit, which is what bounds it).
+int launch_accumulate_anyc(const cs_params* p, float* T, int W, const float* const* g_w,
+                           int64_t d, int64_t i0, float scale, hipStream_t stream) {
+    const size_t row_floats = static_cast<size_t>(p->c) * kGroup;
+    for (int w0 = 0; w0 < W; w0 += kGroup) {
+        const int nw = (W - w0 < kGroup) ? (W - w0) : kGroup;
+        VisitWorkers vw{};
+        for (int w = 0; w < nw; ++w) vw.g[w] = g_w[w0 + w];
+        vw.T = T + static_cast<size_t>(w0 / kGroup) * p->r * row_floats;
+        vw.d = d;
+        vw.i0 = i0;
+        vw.c = p->c;
+        vw.nw = nw;
+        vw.scale = scale;
+        for (uint32_t j = 0; j < p->r; ++j) {
+            int rc;
+            if (nw > 4) rc = launch_visits_anyc<8, 16, kWavesPerGroupOf8>(p, vw, j, stream);
+            else if (nw > 2) rc = launch_visits_anyc<4, 16, 1>(p, vw, j, stream);
+            else if (nw > 1) rc = launch_visits_anyc<2, 16, 1>(p, vw, j, stream);
+            else rc = launch_visits_anyc<1, 16, 1>(p, vw, j, stream);
+            if (rc != CS_OK) return rc;
+        }
+    }
+    return CS_OK;
+}
 
 bool walk_applies(const cs_params* p, int64_t d) {
     if (!p->c_pow2 || p->c < 64 || d < 4096) return false;

@@ -115,6 +115,46 @@ def test_visit_list_is_consistent(lib, r, c, seed, d):
         assert v.cost > 0 and v.cost_walk > 0
 
 
+@pytest.mark.parametrize("r,c,seed,d", [(5, 180_000, 41, 6_500_000), (15, 180_000, 42, 3_000_000),
+                                        (3, 50_021, 44, 3_000_001), (5, 3 << 15, 45, 5_000_000),
+                                        (5, 1000, 9, 50_001), (5, 1 << 15, 2, 1 << 20)])
+def test_visit_list_for_any_column_count_is_consistent(lib, r, c, seed, d):
+    """The visit list for column counts that are not a power of two: gaps tile [0, d_hint), and
+    -- what the kernel's 2 omega running sums rest on -- moving any coordinate by any listed
+    offset advances its bucket by fewer than omega cells, or by that minus p mod c when the hash
+    value wrapped past p (Python integers; random coordinates and coordinates whose hash value
+    sits just below p)."""
+    p = cs.cs_params_init(r, c, seed, d)
+    rng = np.random.default_rng(seed)
+    pc = P % c
+    for j in range(r):
+        v = p.anyc[j]
+        if c & (c - 1) == 0 or d < 65536:
+            assert v.K == 0
+            continue
+        if v.K == 0:
+            continue
+        assert 4 <= v.K <= binding.CS_ANYC_MAX_VISITS and v.omega in (1, 2) and v.cover == d
+        gaps = v.gaps()
+        assert all(g > 0 for g in gaps) and sum(gaps) == d and v.gmax == max(gaps)
+        assert v.cost > 0 and v.cost_direct > 0
+        a, b = int(p.a[j]), int(p.b[j])
+        inv_a = pow(a, P - 2, P)
+        near_p = [((P - 1 - t - b) * inv_a) % P for t in (0, 1, 2, 1000)]   # hash value P-1-t: wraps at once
+        coords = near_p + rng.integers(0, 1 << 40, size=60).tolist() + [0, 1, d - 1]
+        offsets = np.cumsum([0] + gaps[:-1]).tolist()
+        wrapped = 0
+        for i in coords:
+            h0 = ((a * i + b) % P) % c
+            for s in offsets:
+                t = ((((a * (i + s) + b) % P) % c) - h0) % c
+                ok_plain = t < v.omega
+                ok_wrap = (t + pc) % c < v.omega
+                assert ok_plain or ok_wrap, (j, i, s, t)
+                wrapped += (not ok_plain) and ok_wrap
+        assert wrapped > 0          # the second set of sums is exercised
+
+
 def test_invalid_arguments_are_rejected_without_a_gpu(lib):
     p = binding.CsParams()
     assert lib.cs_params_init(None, 5, 16, 1, 0) == -1
@@ -157,8 +197,9 @@ def test_invalid_arguments_are_rejected_without_a_gpu(lib):
 
 def test_update_launch_count_follows_the_grouping(lib):
     """cs_bundle_update_launches: per group of 8 workers one launch for the rows with a visit list
-    (8 rows at most per launch) and one for the rows walked by stride; one launch per 32 workers
-    for sketches the walk does not serve; none for an empty vector."""
+    (8 rows at most per launch) and one for the rows walked by stride; for other column counts
+    one launch per row and group with visit lists, one per 32 workers without; none for an empty
+    vector."""
     for r, c, seed, d in [(5, 1 << 20, 190304492, 10**8), (5, 1 << 15, 190304489, 1 << 20),
                           (7, 1 << 19, 190304493, 25_000_000), (15, 1 << 12, 4, 3_000_000)]:
         p = cs.cs_params_init(r, c, seed, d)
@@ -170,7 +211,13 @@ def test_update_launch_count_follows_the_grouping(lib):
         walk = binding.CsParams.from_buffer_copy(p)
         walk.flags = binding.CS_FLAG_NO_VISIT_LIST
         assert cs.cs_bundle_update_launches(walk, 16, d) == 2
+    # a column count that is not a power of two: one launch per row and group of 8 workers along
+    # the rows' visit lists, one launch per 32 workers without them
     p = cs.cs_params_init(5, 180_000, 1, 6_500_000)
+    assert all(p.anyc[j].K > 0 for j in range(5))
+    for W, n in ((1, 5), (8, 5), (9, 10), (100, 65)):
+        assert cs.cs_bundle_update_launches(p, W, 6_500_000) == n
+    p.flags = binding.CS_FLAG_NO_VISIT_LIST
     for W, n in ((1, 1), (32, 1), (33, 2), (100, 4)):
         assert cs.cs_bundle_update_launches(p, W, 6_500_000) == n
 
@@ -195,9 +242,10 @@ def test_binding_structs_have_the_layout_of_the_header(tmp_path):
     import subprocess
     fields = {"cs_row_plan": ["D", "AD", "ADs", "Dw", "ADw", "ADws", "lanes", "scan_steps"],
               "cs_visit_plan": ["K", "ncell", "cover", "gmax", "cost", "cost_walk", "gap", "A", "As", "code"],
-              "cs_params": ["r", "c", "c_pow2", "flags", "seed", "a", "b", "as", "bs", "plan", "visit"]}
+              "cs_anyc_plan": ["K", "omega", "cover", "gmax", "cost", "cost_direct", "gap"],
+              "cs_params": ["r", "c", "c_pow2", "flags", "seed", "a", "b", "as", "bs", "plan", "visit", "anyc"]}
     mirror = {"cs_row_plan": binding.CsRowPlan, "cs_visit_plan": binding.CsVisitPlan,
-              "cs_params": binding.CsParams}
+              "cs_anyc_plan": binding.CsAnycPlan, "cs_params": binding.CsParams}
     lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "csketch.h"', 'int main(void) {']
     for s, fs in fields.items():
         lines.append(f'printf("{s} %zu\\n", sizeof({s}));')

@@ -173,6 +173,49 @@ def test_accumulate_bundle(W, r, c, seed, d, i0, lds_table):
     assert (T == 0).all()
 
 
+@pytest.mark.parametrize("r,c,seed,d,d_hint,W,i0", [
+    (5, 180_000, 41, 6_500_000, 6_500_000, 9, 0),        # Table 1: 5 x 180 000; two groups, the second partial
+    (15, 180_000, 42, 6_500_000, 6_500_000, 3, 12_345),  # Table 1: 15 x 180 000
+    (5, 180_000, 43, 2_000_003, 6_500_000, 8, 1 << 40),  # a vector shorter than the list was made for
+    (3, 50_021, 44, 3_000_001, 3_000_001, 2, 7),         # a prime column count
+    (5, 3 << 15, 45, 5_000_000, 5_000_000, 1, 0)])       # 3 * 2^15 columns
+def test_accumulate_bundle_visit_lists_for_any_column_count(r, c, seed, d, d_hint, W, i0):
+    """Column counts that are not a power of two, long vectors: the update follows per-row visit
+    lists (offsets whose hash advance is 0 or 1 cells modulo c) and keeps 2 or 4 running sums
+    per coordinate, the second half for coordinates whose hash value wrapped past p.  Every
+    worker's table against the reference, and the same call with the lists switched off."""
+    p = cs.cs_params_init(r, c, seed, d_hint)
+    assert all(p.anyc[j].K > 0 for j in range(r)), "no list was planned for this shape"
+    assert cs.cs_bundle_update_launches(p, W, d) == r * -(-W // cs.CS_BUNDLE_GROUP)
+    sk = orc.SketchOracle(r, c, seed)
+    rng = np.random.default_rng(seed)
+    gs = [(rng.standard_normal(d) * 0.01).astype(np.float32) for _ in range(W)]
+    for g in gs:
+        g[rng.integers(0, d, size=50)] += 1.0
+    tables = _bundle_tables(p, gs, r, c, i0=i0, scale=0.5)
+    for w in range(W):
+        ref = sketch_in_slices_i0(sk, gs[w], i0, 0.5)
+        assert_cells_close(tables[w], ref, what=f"worker {w}", terms_per_cell=d / c)
+    direct = cs.CsParams.from_buffer_copy(p)
+    direct.flags = binding.CS_FLAG_NO_VISIT_LIST
+    assert cs.cs_bundle_update_launches(direct, W, d) == -(-W // 32)
+    tables_direct = _bundle_tables(direct, gs[:1], r, c, i0=i0, scale=0.5)
+    assert_cells_close(tables_direct[0], sketch_in_slices_i0(sk, gs[0], i0, 0.5), what="lists off")
+
+
+def sketch_in_slices_i0(sk, g, i0, scale):
+    """the reference's sketch of g with global index i0 of g[0], computed slice by slice on threads"""
+    from concurrent.futures import ThreadPoolExecutor
+    n = 1 << 20
+    cuts = list(range(0, g.size, n))
+    with ThreadPoolExecutor(max_workers=8) as pool:
+        parts = list(pool.map(lambda lo: sk.sketch(g[lo:lo + n], i0=i0 + lo, scale=scale), cuts))
+    T = sk.zeros()
+    for part in parts:
+        T += part
+    return T
+
+
 def _bundle_tables(p, gs, r, c, i0=0, scale=1.0):
     W, G = len(gs), cs.CS_BUNDLE_GROUP
     T = torch.zeros(cs.cs_bundle_floats(p, W), dtype=torch.float32, device=DEV)
