@@ -56,6 +56,8 @@ bool anyc_visits_apply(const cs_params* p, int64_t d);
 int launch_accumulate_anyc(const cs_params* p, float* T, int W, const float* const* g_w,
                            int64_t d, int64_t i0, float scale, hipStream_t stream);
 int count_accumulate_anyc_launches(const cs_params* p, int W);
+int launch_estimate_anyc(const cs_params* p, const float* S, int64_t d, int64_t i0, float* est,
+                         float* rows, hipStream_t stream);
 int launch_estimate_walk(const cs_params* p, const float* S, int64_t d, int64_t i0,
                          float* est, float* rows, bool fuse_last, uint64_t* hist, hipStream_t stream);
 int launch_bundle_zero(float* T, int64_t n, hipStream_t stream);

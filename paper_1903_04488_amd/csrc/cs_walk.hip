@@ -692,23 +692,15 @@ bool visits_apply(const cs_params* p, uint32_t j, int64_t d) {
     return vp.cost < vp.cost_walk;
 }
 
+void fill_visit_list_any(const cs_params* p, uint32_t j, VisitListAny& v);
+
 // one launch: row j of one group of workers along its list for any column count
 template <int WL, int RUN, int NWAVE>
 int launch_visits_anyc(const cs_params* p, const VisitWorkers& a, uint32_t j, hipStream_t stream) {
     constexpr int WPW = 64 / WL;
     const cs_anyc_plan& vp = p->anyc[j];
     VisitListAny v{};
-    v.K = vp.K;
-    v.j = static_cast<int32_t>(j);
-    v.gmax = vp.gmax;
-    v.a = p->a[j]; v.b = p->b[j]; v.as = p->as[j]; v.bs = p->bs[j];
-    v.omega = vp.omega;
-    v.pc = static_cast<uint32_t>(kP61 % p->c);
-    for (uint32_t k = 0; k < vp.K; ++k) {
-        v.gap[k] = vp.gap[k];
-        v.A[k] = static_cast<uint64_t>((static_cast<unsigned __int128>(p->a[j]) * vp.gap[k]) % kP61);
-        v.As[k] = static_cast<uint64_t>((static_cast<unsigned __int128>(p->as[j]) * vp.gap[k]) % kP61);
-    }
+    fill_visit_list_any(p, j, v);
     const int64_t chunks = (static_cast<int64_t>(vp.gmax) + RUN - 1) / RUN;
     const int64_t nwaves = (chunks + WPW - 1) / WPW;
     const int64_t ngroups = (nwaves + NWAVE - 1) / NWAVE;
@@ -1016,7 +1008,190 @@ k_row_values_walk(KParams p, RowSegments segs, const float* __restrict__ S, int6
     }
 }
 
+
+// ---------------------------------------------------------------------------------------
+// Alg. 4 estimate along a visit list, for column counts that are not a power of two.
+//
+// The list that serves the update serves the query: whatever a lane meets at i + s_k lies in
+// one of the NC = 2 omega cells that the cell of i fixes, so the lane fetches those NC cell
+// values once, keeps them in registers, and for the rest of the vector picks one of them per
+// visit -- no gather inside the loop.  (Without a list the query is r random gathers per
+// coordinate from a table that L2 does not hold: ~80 G gathers/s.  For power-of-two column
+// counts the stride walk above does the same job faster than this kernel's form with three
+// gaps: both are then bound by their hashing and the walk balances its load better.)
+// A lane owns 4 neighbouring residues below the largest gap, a wavefront 256, and every visit
+// writes 1 KB of contiguous rows[j][i] (RF = 0) or, for the last row (RF = R), reads the other
+// rows' values there, takes the median and writes est.  A coordinate outside the NC cells
+// cannot occur with a list from cs_params_init; it is checked all the same and such a value
+// is gathered from the table directly.
+// ---------------------------------------------------------------------------------------
+template <int RF, int NC>
+__global__ void __launch_bounds__(64)
+k_row_values_visits(VisitListAny v, const float* __restrict__ S, uint32_t c, int64_t d, int64_t i0,
+                    float* __restrict__ rows, float* __restrict__ est) {
+    static_assert(kQRun == 4, "one 16-byte piece per lane");
+    static_assert(NC == 2 || NC == 4, "omega = 1 or 2");
+    const int lane = threadIdx.x;
+    const int j = v.j;
+    const Columns col = columns_of<false>(c);
+    const float* __restrict__ Sj = S + static_cast<size_t>(j) * c;
+    float* __restrict__ out = rows + static_cast<size_t>(j) * d;
+    const uint64_t Aj = v.a, Asj = v.as;
+    const uint32_t omega = v.omega, pc = v.pc;
+    auto sum_of = [&](uint32_t cell, uint32_t first) -> uint32_t {
+        const uint32_t t = cell >= first ? cell - first : cell + c - first;
+        if (t < omega) return t;
+        const uint32_t t2 = t + pc >= c ? t + pc - c : t + pc;
+        return t2 < omega ? omega + t2 : static_cast<uint32_t>(NC);
+    };
+    auto cell_of_sum = [&](uint32_t first, int q) -> uint32_t {
+        const uint32_t x = static_cast<uint32_t>(q) < omega ? first + q : first + (q - omega) + (c - pc);
+        return x >= c ? x - c : x;
+    };
+    const int64_t nwaves = (static_cast<int64_t>(v.gmax) + 64 * kQRun - 1) / (64 * kQRun);
+    const int64_t per_xcd = (nwaves + 7) / 8;
+    const int64_t xcd_first = static_cast<int64_t>(blockIdx.x & 7) * per_xcd;
+    for (int64_t kk = blockIdx.x >> 3; kk < per_xcd; kk += gridDim.x >> 3) {
+        const int64_t wv = xcd_first + kk;
+        if (wv >= nwaves) break;
+        const int64_t wave_res = wv * 64 * kQRun;                   // first residue of the wavefront
+        const int64_t my_res = wave_res + static_cast<int64_t>(lane) * kQRun;
+        uint64_t yb = hash_state(v.a, v.b, static_cast<uint64_t>(i0 + my_res));
+        uint64_t ys = hash_state(v.as, v.bs, static_cast<uint64_t>(i0 + my_res));
+        uint32_t first_cell[kQRun];
+        float cellv[kQRun][NC];
+        {
+            uint64_t tb = yb;
+#pragma unroll
+            for (int m = 0; m < kQRun; ++m) {
+                first_cell[m] = bucket_of<false>(tb, col);
+#pragma unroll
+                for (int n = 0; n < NC; ++n) cellv[m][n] = Sj[cell_of_sum(first_cell[m], n)];
+                tb = hash_advance(tb, Aj);
+            }
+        }
+        int64_t s = 0;
+        for (uint32_t k = 0; k < v.K; ++k) {
+            const int64_t gap = static_cast<int64_t>(v.gap[k]);
+            // residues from wave_res on that take part in this visit and exist in the vector
+            const int64_t in_gap = gap - wave_res, in_vec = d - s - wave_res;
+            const int64_t room = in_gap < in_vec ? in_gap : in_vec;
+            if (room > 0) {
+                const int64_t my_len = room - static_cast<int64_t>(lane) * kQRun;   // of my 4: >= 4 all, <= 0 none
+                [[maybe_unused]] vec4f other[RF > 1 ? RF - 1 : 1];
+                if constexpr (RF > 1) {
+                    if (my_len >= kQRun) {
+#pragma unroll
+                        for (int q = 0; q < RF - 1; ++q)
+                            other[q] = __builtin_nontemporal_load(reinterpret_cast<const vec4f_u*>(
+                                rows + static_cast<size_t>(q) * d + s + my_res));
+                    }
+                }
+                uint64_t tb = yb, ts = ys;
+                float o[kQRun];
+#pragma unroll
+                for (int m = 0; m < kQRun; ++m) {
+                    const uint32_t cell = bucket_of<false>(tb, col);
+                    const uint32_t rel = sum_of(cell, first_cell[m]);
+                    float x = cellv[m][NC - 1];
+#pragma unroll
+                    for (int n = NC - 2; n >= 0; --n) x = rel == static_cast<uint32_t>(n) ? cellv[m][n] : x;
+                    if (rel >= static_cast<uint32_t>(NC) && m < my_len) x = Sj[cell];
+                    o[m] = apply_sign(x, sign_flip_of(ts));
+                    tb = hash_advance(tb, Aj);
+                    ts = hash_advance(ts, Asj);
+                }
+                if constexpr (RF > 0) {
+                    float* dst = est + s + my_res;
+                    if (my_len >= kQRun) {
+                        float vx[RF], vy[RF], vz[RF], vw[RF];
+#pragma unroll
+                        for (int q = 0; q < RF - 1; ++q) {
+                            vx[q] = other[q].x; vy[q] = other[q].y; vz[q] = other[q].z; vw[q] = other[q].w;
+                        }
+                        vx[RF - 1] = o[0]; vy[RF - 1] = o[1]; vz[RF - 1] = o[2]; vw[RF - 1] = o[3];
+                        vec4f u;
+                        u.x = median_odd<RF>(vx); u.y = median_odd<RF>(vy);
+                        u.z = median_odd<RF>(vz); u.w = median_odd<RF>(vw);
+                        *reinterpret_cast<vec4f_u*>(dst) = u;
+                    } else {
+                        for (int m = 0; m < kQRun; ++m) {
+                            if (m >= my_len) break;
+                            float t[RF];
+#pragma unroll
+                            for (int q = 0; q < RF - 1; ++q) t[q] = rows[static_cast<size_t>(q) * d + s + my_res + m];
+                            t[RF - 1] = o[m];
+                            dst[m] = median_odd<RF>(t);
+                        }
+                    }
+                } else {
+                    float* dst = out + s + my_res;
+                    if (my_len >= kQRun) {
+                        vec4f u;
+                        u.x = o[0]; u.y = o[1]; u.z = o[2]; u.w = o[3];
+                        __builtin_nontemporal_store(u, reinterpret_cast<vec4f_u*>(dst));
+                    } else if (my_len > 0) {
+                        dst[0] = o[0];
+                        if (my_len > 1) dst[1] = o[1];
+                        if (my_len > 2) dst[2] = o[2];
+                    }
+                }
+            }
+            s += gap;
+            yb = hash_advance(yb, v.A[k]);
+            ys = hash_advance(ys, v.As[k]);
+        }
+    }
+}
+
+void fill_visit_list_any(const cs_params* p, uint32_t j, VisitListAny& v) {
+    const cs_anyc_plan& vp = p->anyc[j];
+    v.K = vp.K;
+    v.j = static_cast<int32_t>(j);
+    v.gmax = vp.gmax;
+    v.a = p->a[j]; v.b = p->b[j]; v.as = p->as[j]; v.bs = p->bs[j];
+    v.omega = vp.omega;
+    v.pc = static_cast<uint32_t>(kP61 % p->c);
+    for (uint32_t k = 0; k < vp.K; ++k) {
+        v.gap[k] = vp.gap[k];
+        v.A[k] = static_cast<uint64_t>((static_cast<unsigned __int128>(p->a[j]) * vp.gap[k]) % kP61);
+        v.As[k] = static_cast<uint64_t>((static_cast<unsigned __int128>(p->as[j]) * vp.gap[k]) % kP61);
+    }
+}
+
 }  // namespace
+
+// The query along the rows' visit lists for any column count: rows 0 .. r-2 into the scratch,
+// one launch each, then the last row together with the median.
+int launch_estimate_anyc(const cs_params* p, const float* S, int64_t d, int64_t i0, float* est,
+                         float* rows, hipStream_t stream) {
+    auto grid_x = [](uint64_t gmax) {
+        const int64_t nwaves = (static_cast<int64_t>(gmax) + 64 * kQRun - 1) / (64 * kQRun);
+        const int64_t cap = 256 * 64;
+        const int64_t gx = nwaves < cap ? nwaves : cap;
+        return static_cast<unsigned>((gx + 7) / 8 * 8);
+    };
+    const uint32_t last = p->r - 1;
+    VisitListAny v{};
+    for (uint32_t j = 0; j < last; ++j) {
+        fill_visit_list_any(p, j, v);
+        if (v.omega == 1) k_row_values_visits<0, 2><<<grid_x(v.gmax), 64, 0, stream>>>(v, S, p->c, d, i0, rows, est);
+        else k_row_values_visits<0, 4><<<grid_x(v.gmax), 64, 0, stream>>>(v, S, p->c, d, i0, rows, est);
+    }
+    fill_visit_list_any(p, last, v);
+    const unsigned gx = grid_x(v.gmax);
+#define CS_LASTR(R_)                                                                                 \
+    case R_:                                                                                         \
+        if (v.omega == 1) k_row_values_visits<R_, 2><<<gx, 64, 0, stream>>>(v, S, p->c, d, i0, rows, est); \
+        else k_row_values_visits<R_, 4><<<gx, 64, 0, stream>>>(v, S, p->c, d, i0, rows, est);             \
+        break;
+    switch (p->r) {
+        CS_LASTR(1) CS_LASTR(3) CS_LASTR(5) CS_LASTR(7) CS_LASTR(9) CS_LASTR(11) CS_LASTR(13) CS_LASTR(15)
+        default: return CS_EINVAL;
+    }
+#undef CS_LASTR
+    return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
+}
 
 // fuse_last = false: all rows into the scratch (the caller takes the median).  fuse_last = true:
 // the last row's walk takes the median itself; worth it for long vectors, where the scratch

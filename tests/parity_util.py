@@ -60,17 +60,24 @@ def estimate_sparse_in_slices(sk, T, idx):
 
 
 def host_sum_f64(g_w):
-    """sum over workers of their fp32 device vectors, in binary64 on the host (worker by worker;
-    the additions of one worker are spread over threads by coordinate range)"""
+    """sum over workers of their fp32 vectors, in binary64 on the host (worker by worker; the
+    additions of one worker are spread over threads by coordinate range; device vectors come
+    over through a pinned staging buffer)"""
+    import torch
     d = g_w[0].numel()
     acc = np.zeros(d, dtype=np.float64)
+    sl = _slices(d)
+    stage = torch.empty(d, dtype=torch.float32, pin_memory=True) if g_w[0].is_cuda else None
 
     def add(s, h):
         acc[s[0]:s[1]] += h[s[0]:s[1]]
 
-    sl = _slices(d)
     for g in g_w:
-        h = g.cpu().numpy()
+        if stage is not None:
+            stage.copy_(g)                     # synchronous device-to-host copy
+            h = stage.numpy()
+        else:
+            h = g.numpy()
         if d <= _SLICE:
             acc += h
         else:

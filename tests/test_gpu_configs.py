@@ -51,8 +51,9 @@ def run(config, steps, check_workers=(0,), workers_first_step_only=False, full_s
     # feedback cancels a heavy value out of its cell
     mag_u = np.zeros((c.r, c.c))
     mag_v = np.zeros((c.r, c.c))
+    import time
     for t in range(steps):
-        log(f"[cfg{c.cfg}] step {t}: d={c.d} W={c.W} r={c.r} c={c.c} k={c.k}", flush=True)
+        t_step = time.perf_counter()
         worst = {}
         g_w = [work.gradient(t, w) for w in range(c.W)]
         # ---- worker sketches
@@ -148,8 +149,8 @@ def run(config, steps, check_workers=(0,), workers_first_step_only=False, full_s
                                    operand_mag=mag_v)
                 assert_cells_close(hp.S_u.cpu().numpy(), sk.sketch(dense.u), what=f"step {t} S(u)",
                                    operand_mag=mag_u)
-        log(f"[cfg{c.cfg}] step {t} worst error / bound: "
-            + ", ".join(f"{name} {val:.3g}" for name, val in worst.items()), flush=True)
+        log(f"[cfg{c.cfg} d={c.d} W={c.W} {c.r}x{c.c} k={c.k}] step {t} ({time.perf_counter() - t_step:.1f} s) "
+            "worst error / bound: " + ", ".join(f"{name} {val:.3g}" for name, val in worst.items()))
         del g_w, gsum
     return swapped_total, work, hp
 
@@ -190,21 +191,21 @@ def test_config3_full():
 
 
 @pytest.mark.timeout(1500)
-def test_config4_full_ten_steps():
+def test_config4_full_ten_steps(progress):
     """d = 10^8, W = 32, momentum and error feedback in sketch space over all 10 steps; every
     coordinate's estimate and the whole selection are checked at every step."""
     c = wl.CONFIGS[4]
     assert c.steps == 10
-    run(c, c.steps, check_workers=(31,), workers_first_step_only=True)
+    run(c, c.steps, check_workers=(31,), workers_first_step_only=True, log=progress)
 
 
 @pytest.mark.timeout(1500)
-def test_config5_full_twenty_steps():
+def test_config5_full_twenty_steps(progress):
     """d = 2.5 * 10^7, W = 256, all 20 steps with sketch-space state, complete checks at
     every step."""
     c = wl.CONFIGS[5]
     assert c.steps == 20
-    run(c, c.steps, check_workers=(255,), workers_first_step_only=True)
+    run(c, c.steps, check_workers=(255,), workers_first_step_only=True, log=progress)
 
 
 # ----------------------------------------------------------------------------- P > 1

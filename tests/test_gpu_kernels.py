@@ -201,6 +201,36 @@ def test_accumulate_bundle_visit_lists_for_any_column_count(r, c, seed, d, d_hin
     assert cs.cs_bundle_update_launches(direct, W, d) == -(-W // 32)
     tables_direct = _bundle_tables(direct, gs[:1], r, c, i0=i0, scale=0.5)
     assert_cells_close(tables_direct[0], sketch_in_slices_i0(sk, gs[0], i0, 0.5), what="lists off")
+    # the query follows the same lists (a lane keeps the 2 or 4 cell values a coordinate can
+    # meet): bit-exact from the same table, also with NaN and infinite cells, and equal to the
+    # query without lists
+    T32 = rng.standard_normal((r, c)).astype(np.float32)
+    T32.reshape(-1)[rng.choice(r * c, size=r * c // 50, replace=False)] = np.nan
+    T32.reshape(-1)[rng.choice(r * c, size=r * c // 50, replace=False)] = -np.inf
+    S = dev(T32)
+    ref = estimate_in_slices_i0(sk, T32.astype(np.float64), d, i0).astype(np.float32)
+    for params in (p, direct):
+        est = torch.empty(d, dtype=torch.float32, device=DEV)
+        n_ws = cs.cs_estimate_workspace_bytes(params, d)
+        assert (n_ws > 0) == (params is p)
+        ws = torch.empty(n_ws, dtype=torch.uint8, device=DEV) if n_ws else None
+        hist = torch.empty(binding.CS_TOPK_HIST_BINS, dtype=torch.int64, device=DEV)
+        cs.cs_sketch_estimate(params, S, est, i0=i0, workspace=ws, hist=hist)
+        got = est.cpu().numpy()
+        np.testing.assert_array_equal(np.isnan(got), np.isnan(ref))
+        ok = ~np.isnan(ref)
+        np.testing.assert_array_equal(got[ok].view(np.uint32), ref[ok].view(np.uint32))
+        want = np.bincount((got.view(np.uint32) & np.uint32(0x7FFFFFFF)) >> np.uint32(20), minlength=2048)
+        np.testing.assert_array_equal(hist.cpu().numpy(), want)
+
+
+def estimate_in_slices_i0(sk, T, d, i0):
+    from concurrent.futures import ThreadPoolExecutor
+    n = 1 << 20
+    cuts = list(range(0, d, n))
+    with ThreadPoolExecutor(max_workers=8) as pool:
+        parts = list(pool.map(lambda lo: sk.estimate(T, min(n, d - lo), i0=i0 + lo), cuts))
+    return np.concatenate(parts)
 
 
 def sketch_in_slices_i0(sk, g, i0, scale):
