@@ -53,6 +53,7 @@ int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* con
 int count_accumulate_walk_launches(const cs_params* p, int W, int64_t d);
 // the same along visit lists for column counts that are not a power of two
 bool anyc_visits_apply(const cs_params* p, int64_t d);
+bool anyc_visits_serve_query(const cs_params* p, int64_t d);
 int launch_accumulate_anyc(const cs_params* p, float* T, int W, const float* const* g_w,
                            int64_t d, int64_t i0, float scale, hipStream_t stream);
 int count_accumulate_anyc_launches(const cs_params* p, int W);

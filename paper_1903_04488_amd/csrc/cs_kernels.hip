@@ -733,7 +733,7 @@ extern "C" int cs_sketch_momentum(const cs_params* p, float* S_u, float* S_v, co
 extern "C" int cs_estimate_workspace_bytes(const cs_params* p, int64_t d, size_t* bytes) {
     if (!params_ok(p) || d < 0 || !bytes) return CS_EINVAL;
     // the stride-aligned path stores the r signed cells of every coordinate before the median
-    *bytes = (lattice_applies(p, d) || anyc_visits_apply(p, d))
+    *bytes = (lattice_applies(p, d) || anyc_visits_serve_query(p, d))
                  ? sizeof(float) * static_cast<size_t>(p->r) * static_cast<size_t>(d) : 0;
     return CS_OK;
 }
@@ -749,7 +749,7 @@ static int estimate_all(const cs_params* p, const float* S, int64_t d, int64_t i
         return launch_estimate_lattice(p, S, d, i0, est, static_cast<float*>(rows_ws), hist, hist_done,
                                        as_stream(stream));
     }
-    if (anyc_visits_apply(p, d)) {
+    if (anyc_visits_serve_query(p, d)) {
         const size_t need = sizeof(float) * static_cast<size_t>(p->r) * static_cast<size_t>(d);
         if (!rows_ws || reinterpret_cast<uintptr_t>(rows_ws) % 4 != 0) return CS_EINVAL;
         if (ws_bytes < need) return CS_EWORKSPACE;

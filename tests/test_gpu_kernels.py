@@ -178,7 +178,8 @@ def test_accumulate_bundle(W, r, c, seed, d, i0, lds_table):
     (15, 180_000, 42, 6_500_000, 6_500_000, 3, 12_345),  # Table 1: 15 x 180 000
     (5, 180_000, 43, 2_000_003, 6_500_000, 8, 1 << 40),  # a vector shorter than the list was made for
     (3, 50_021, 44, 3_000_001, 3_000_001, 2, 7),         # a prime column count
-    (5, 3 << 15, 45, 5_000_000, 5_000_000, 1, 0)])       # 3 * 2^15 columns
+    (5, 3 << 15, 45, 5_000_000, 5_000_000, 1, 0),        # 3 * 2^15 columns
+    (5, 180_000, 46, 17_000_000, 17_000_000, 1, 3)])     # long enough for the query to follow the lists too
 def test_accumulate_bundle_visit_lists_for_any_column_count(r, c, seed, d, d_hint, W, i0):
     """Column counts that are not a power of two, long vectors: the update follows per-row visit
     lists (offsets whose hash advance is 0 or 1 cells modulo c) and keeps 2 or 4 running sums
@@ -212,7 +213,7 @@ def test_accumulate_bundle_visit_lists_for_any_column_count(r, c, seed, d, d_hin
     for params in (p, direct):
         est = torch.empty(d, dtype=torch.float32, device=DEV)
         n_ws = cs.cs_estimate_workspace_bytes(params, d)
-        assert (n_ws > 0) == (params is p)
+        assert (n_ws > 0) == (params is p and d * (r - 1) >= 1 << 26)
         ws = torch.empty(n_ws, dtype=torch.uint8, device=DEV) if n_ws else None
         hist = torch.empty(binding.CS_TOPK_HIST_BINS, dtype=torch.int64, device=DEV)
         cs.cs_sketch_estimate(params, S, est, i0=i0, workspace=ws, hist=hist)
