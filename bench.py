@@ -28,9 +28,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 METRIC = "sketch+estimate+top-k throughput, Gcoords/s and % HBM peak at d=100M, r=5"
 # HBM bytes per launch of the dominant kernel at config 4 (4 launches per step, one per group
 # of 8 workers), measured with rocprofv3 --pmc: FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
-# factors being what the same counters read for a plain 1 GiB copy.
+# factors being what the same counters read for kernels of known traffic in the same run (the
+# plain read of one input set, 12.8 GB, and the clearing of the worker tables, 671 MB).
 # Source: profiles/accumulate_visits_cfg4_pmc.md.  None for other configs.
-MEASURED_TRAFFIC_BYTES = {4: 1.731e10}
+MEASURED_TRAFFIC_BYTES = {4: 1.735e10}
 
 
 def host_cpu():
@@ -189,7 +190,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=4)
+    ap.add_argument("--config", type=int, default=4,
+                    help="1-5: the benchmark configurations (4 is the headline); 6-8: the sketch "
+                         "shapes of the paper's Table 1 (5 x 10^6 / 15 x 180 000 over 90 M, 5 x 180 000 "
+                         "over 73 M coordinates; W = 4, k = 100 000, their P), run as --variant top-pk")
     ap.add_argument("--variant", default="sketch-state",
                     choices=["sketch-state", "dense-state", "heavymix", "top-pk"],
                     help="sketch-state: the headline path (momentum / error feedback as sketches; "
@@ -220,14 +224,17 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     dev = "cuda:0"
-    cfg = wl.CONFIGS[args.config]
+    cfg = wl.ALL_CONFIGS[args.config]
+    if cfg.P > 1 and args.variant == "sketch-state":
+        args.variant = "top-pk"      # the paper's own shapes come with their P (Table 1 footnotes)
     work = wl.Workload(cfg, dev)
     variant = args.variant
     if variant == "dense-state":
         hp = DenseStatePath(cfg.d, cfg.W, cfg.r, cfg.c, cfg.k, cfg.hash_seed,
                             rho=cfg.rho if cfg.rho is not None else 0.9, device=dev)
     elif variant == "top-pk":
-        hp = HotPath(cfg.d, cfg.W, cfg.r, cfg.c, cfg.k, cfg.hash_seed, rho=cfg.rho, device=dev, P=16)
+        hp = HotPath(cfg.d, cfg.W, cfg.r, cfg.c, cfg.k, cfg.hash_seed, rho=cfg.rho, device=dev,
+                     P=cfg.P if cfg.P > 1 else 16)
     elif variant == "heavymix":
         hp = HotPath(cfg.d, cfg.W, cfg.r, cfg.c, cfg.k, cfg.hash_seed, rho=None, device=dev)
         l2sq = torch.empty(1 + cfg.r, dtype=torch.float64, device=dev)
@@ -384,6 +391,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"cfg{cfg.cfg} {cfg.name}", "variant": variant, "d": cfg.d,
                    "W": cfg.W, "r": cfg.r, "c": cfg.c, "k": cfg.k, "rho": cfg.rho,
+                   "P": getattr(hp, "P", 1),
                    "input_sets_resident": n_sets},
         "pct_hbm_peak_whole_step": 100.0 * step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "pct_stream_read_whole_step": 100.0 * step_alg_bytes / (ms_per_step * 1e-3) / 1e9 / stream_set,
