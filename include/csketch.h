@@ -217,6 +217,12 @@ int cs_bundle_merge(const cs_params* p, float* dst, float beta, const float* T, 
 int cs_sketch_accumulate_sparse(const cs_params* p, float* S, const int64_t* idx,
                                 const float* val, int64_t n, float scale, void* stream);
 
+/* Failure detector for a diverged run (no passage of the paper; a sketch is linear, so one
+ * NaN or infinite gradient element poisons r cells and, through them, every estimate that
+ * reads those cells): *count = number of cells of S that are NaN or infinite.
+ * S: device float[r][c]; count: device int64, 8-byte aligned, overwritten. */
+int cs_sketch_count_nonfinite(const cs_params* p, const float* S, int64_t* count, void* stream);
+
 /* Mergeability (Sec. 3; the aggregation step of Alg. 3, S_t = (1/W) sum_i S_t^i):
  *     dst = beta * dst + alpha * sum_{w<W} src[w]
  * dst: device float[r][c]; with beta == 0 it is not read.  src: HOST array of W device

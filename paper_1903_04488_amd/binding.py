@@ -100,6 +100,8 @@ _SIGNATURES = {
     "cs_sketch_merge": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_float,
                         ctypes.POINTER(ctypes.c_void_p), ctypes.c_int32, ctypes.c_float,
                         ctypes.c_void_p],
+    "cs_sketch_count_nonfinite": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_void_p,
+                                  ctypes.c_void_p],
     "cs_sketch_axpby": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_float,
                         ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p],
     "cs_sketch_momentum": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_void_p,
@@ -313,6 +315,12 @@ def cs_sketch_momentum(p, S_u, S_v, S_t, rho: float):
         ctypes.byref(p), _dev(S_u, torch.float32, "S_u", _cells(p)),
         _dev(S_v, torch.float32, "S_v", _cells(p)), _dev(S_t, torch.float32, "S_t", _cells(p)),
         rho, _stream(S_u)), "cs_sketch_momentum")
+
+
+def cs_sketch_count_nonfinite(p, S, count):
+    _check(load_library().cs_sketch_count_nonfinite(
+        ctypes.byref(p), _dev(S, torch.float32, "S", _cells(p)), _dev(count, torch.int64, "count", 1),
+        _stream(S)), "cs_sketch_count_nonfinite")
 
 
 def cs_estimate_workspace_bytes(p, d: int) -> int:

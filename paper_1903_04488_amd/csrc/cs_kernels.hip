@@ -300,6 +300,20 @@ k_axpby(float* __restrict__ y, float a, const float* __restrict__ x, float b, in
     }
 }
 
+// cells that are NaN or infinite: exponent bits all ones
+__global__ void __launch_bounds__(kBlock)
+k_count_nonfinite(const float* __restrict__ S, int64_t n, unsigned long long* __restrict__ count) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    unsigned long long mine = 0;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < n; t += stride)
+        mine += (__float_as_uint(S[t]) & 0x7f800000u) == 0x7f800000u ? 1u : 0u;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mine += __shfl_down(mine, off, 64);
+    if ((threadIdx.x & 63) == 0 && mine) atomicAdd(count, mine);
+}
+
+__global__ void k_clear_count(unsigned long long* count) { *count = 0; }
+
 __global__ void __launch_bounds__(kBlock)
 k_momentum(float* __restrict__ Su, float* __restrict__ Sv, const float* __restrict__ St,
            float rho, int64_t n) {
@@ -719,6 +733,16 @@ extern "C" int cs_sketch_axpby(const cs_params* p, float* y, float a, const floa
     if (!params_ok(p) || !y || !x) return CS_EINVAL;
     const int64_t n = static_cast<int64_t>(p->r) * p->c;
     k_axpby<<<grid_for(n), kBlock, 0, as_stream(stream)>>>(y, a, x, b, n);
+    return launch_status();
+}
+
+extern "C" int cs_sketch_count_nonfinite(const cs_params* p, const float* S, int64_t* count,
+                                         void* stream) {
+    if (!params_ok(p) || !S || !count || reinterpret_cast<uintptr_t>(count) % 8 != 0) return CS_EINVAL;
+    const int64_t n = static_cast<int64_t>(p->r) * p->c;
+    unsigned long long* out = reinterpret_cast<unsigned long long*>(count);
+    k_clear_count<<<1, 1, 0, as_stream(stream)>>>(out);
+    k_count_nonfinite<<<grid_for(n), kBlock, 0, as_stream(stream)>>>(S, n, out);
     return launch_status();
 }
 

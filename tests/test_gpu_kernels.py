@@ -395,6 +395,30 @@ def test_merge_axpby_momentum_zero(W):
     assert (su == 0).all()
 
 
+def test_count_nonfinite_cells():
+    """the failure detector counts exactly the NaN and infinite cells (numpy's isfinite), and a
+    single infinite gradient element shows up in r cells of the worker's table"""
+    r, c = 5, 1 << 12
+    p = cs.cs_params_init(r, c, 3, 100_003)
+    rng = np.random.default_rng(0)
+    T32 = rng.standard_normal((r, c)).astype(np.float32)
+    T32.reshape(-1)[rng.choice(r * c, size=37, replace=False)] = np.nan
+    T32.reshape(-1)[rng.choice(r * c, size=11, replace=False)] = -np.inf
+    T32[0, 0] = np.float32(3.4e38)
+    T32[1, 1] = np.float32(1e-45)
+    count = torch.full((1,), -7, dtype=torch.int64, device=DEV)
+    cs.cs_sketch_count_nonfinite(p, dev(T32), count)
+    assert count.item() == int((~np.isfinite(T32)).sum())
+    g = (rng.standard_normal(100_003) * 0.01).astype(np.float32)
+    g[4242] = np.inf
+    T = torch.zeros(cs.cs_bundle_floats(p, 1), dtype=torch.float32, device=DEV)
+    cs.cs_sketch_accumulate_bundle(p, T, [dev(g)])
+    S = torch.zeros(r, c, dtype=torch.float32, device=DEV)
+    cs.cs_bundle_merge(p, S, T, 1, alpha=1.0, beta=0.0)
+    cs.cs_sketch_count_nonfinite(p, S, count)
+    assert count.item() == r
+
+
 # ------------------------------------------------------------------------------ estimate
 @pytest.mark.parametrize("r,c,seed", SHAPES)
 @pytest.mark.parametrize("d,i0", [(1_000_003, 0), (4097, 3_000_000_000)])
