@@ -225,6 +225,37 @@ def test_accumulate_bundle_visit_lists_for_any_column_count(r, c, seed, d, d_hin
         np.testing.assert_array_equal(hist.cpu().numpy(), want)
 
 
+def test_forged_visit_list_for_any_column_count_costs_time_not_correctness():
+    """A list whose offsets do not keep a coordinate within its 2 omega cells (arbitrary gaps):
+    the update sends such visits' values to memory one by one and the query gathers them from
+    the table directly, so the results are still the reference's."""
+    r, c, seed, d, W = 5, 180_000, 51, 17_000_000, 2
+    p = cs.cs_params_init(r, c, seed, d)
+    assert all(p.anyc[j].K > 0 for j in range(r))
+    sk = orc.SketchOracle(r, c, seed)
+    rng = np.random.default_rng(seed)
+    forged = cs.CsParams.from_buffer_copy(p)
+    for j in range(r):
+        v = forged.anyc[j]
+        gaps = [1_000_003 + 7 * j, 2_500_001, 3_000_017, 999_999]
+        gaps.append(d - sum(gaps))
+        v.K, v.omega, v.cover, v.gmax, v.cost, v.cost_direct = len(gaps), 1 + j % 2, d, max(gaps), 1, 2
+        for k, g in enumerate(gaps):
+            v.gap[k] = g
+    gs = [(rng.standard_normal(d) * 0.01).astype(np.float32) for _ in range(W)]
+    for w, tab in enumerate(_bundle_tables(forged, gs, r, c, i0=3, scale=1.0)):
+        assert_cells_close(tab, sketch_in_slices_i0(sk, gs[w], 3, 1.0), what=f"forged list, worker {w}",
+                           terms_per_cell=d / c)
+    T32 = rng.standard_normal((r, c)).astype(np.float32)
+    est = torch.empty(d, dtype=torch.float32, device=DEV)
+    n_ws = cs.cs_estimate_workspace_bytes(forged, d)
+    assert n_ws > 0
+    ws = torch.empty(n_ws, dtype=torch.uint8, device=DEV)
+    cs.cs_sketch_estimate(forged, dev(T32), est, i0=3, workspace=ws)
+    ref = estimate_in_slices_i0(sk, T32.astype(np.float64), d, 3).astype(np.float32)
+    np.testing.assert_array_equal(est.cpu().numpy(), ref)
+
+
 def estimate_in_slices_i0(sk, T, d, i0):
     from concurrent.futures import ThreadPoolExecutor
     n = 1 << 20
