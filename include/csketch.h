@@ -223,6 +223,35 @@ int cs_sketch_accumulate_sparse(const cs_params* p, float* S, const int64_t* idx
  * S: device float[r][c]; count: device int64, 8-byte aligned, overwritten. */
 int cs_sketch_count_nonfinite(const cs_params* p, const float* S, int64_t* count, void* stream);
 
+/* Alg. 4 update with sums that do not depend on the order of the additions.  The float
+ * updates above add with atomic operations in whatever order the hardware takes them, so two
+ * runs agree only to rounding.  Here every contribution is rounded once to a multiple of
+ * 2^-frac_bits and summed as a 64-bit integer, which is associative: equal inputs give equal
+ * bits whatever the launch shape, and a reference can be matched bit for bit (a debugging and
+ * checkpointing aid that separates "wrong" from "reordered"; about one atomic request per
+ * coordinate and row, so far slower than the float path).
+ *     q        = (double)scale * (double)g[t] * 2^frac_bits   rounded to an integer, ties to even
+ *                (the product is exact in binary64, so this is the only rounding)
+ *     acc[j][h_j(i0+t)] += s_j(i0+t) * q                      in int64 (wraps on overflow)
+ * A coordinate whose q is not finite or not below 2^62 in magnitude contributes nothing and
+ * is counted: *dropped += number of such coordinates (dropped may be NULL).  The caller picks
+ * frac_bits (0 .. CS_FIXED_MAX_FRAC_BITS) so that the sums fit: magnitudes below 2^m and at
+ * most n coordinates per cell need frac_bits + m + log2(n) <= 62.  Sums over workers are the
+ * same integer sums: accumulate every worker into one acc.
+ * acc: device int64[r][c], updated (the caller clears it); g: device float[d]; idx, val as
+ * for cs_sketch_accumulate_sparse; dropped: device int64, 8-byte aligned, or NULL.
+ * cs_fixed_to_float:  S[j][b] = (float)( (double)acc[j][b] * 2^-frac_bits * (double)alpha ),
+ * the integer converted to binary64 (exact below 2^53), scaled exactly, multiplied once and
+ * rounded once to binary32.  S: device float[r][c], overwritten. */
+#define CS_FIXED_MAX_FRAC_BITS 62
+int cs_fixed_accumulate(const cs_params* p, int64_t* acc, const float* g, int64_t d, int64_t i0,
+                        float scale, int32_t frac_bits, int64_t* dropped, void* stream);
+int cs_fixed_accumulate_sparse(const cs_params* p, int64_t* acc, const int64_t* idx,
+                               const float* val, int64_t n, float scale, int32_t frac_bits,
+                               int64_t* dropped, void* stream);
+int cs_fixed_to_float(const cs_params* p, const int64_t* acc, int32_t frac_bits, float alpha,
+                      float* S, void* stream);
+
 /* Mergeability (Sec. 3; the aggregation step of Alg. 3, S_t = (1/W) sum_i S_t^i):
  *     dst = beta * dst + alpha * sum_{w<W} src[w]
  * dst: device float[r][c]; with beta == 0 it is not read.  src: HOST array of W device

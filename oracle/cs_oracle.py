@@ -141,6 +141,47 @@ class SketchOracle:
     def sketch(self, g, i0: int = 0, scale: float = 1.0):
         return self.accumulate(self.zeros(), g, i0, scale)
 
+    # -- update with order-independent sums -------------------------------
+    # Not in the paper: the same update of Alg. 4 with every contribution rounded once to a
+    # multiple of 2^-frac_bits and summed as a 64-bit integer, so that the result does not
+    # depend on the order of the additions and a float implementation's "reordered" can be
+    # told from "wrong".  Pinned by exact rational arithmetic on small inputs and by the
+    # fp64 update above on inputs that are multiples of 2^-frac_bits (tests/test_oracle_pins.py).
+    @staticmethod
+    def fixed_contributions(val, scale: float, frac_bits: int):
+        """(q, ok): q[t] = scale * val[t] * 2^frac_bits rounded to an integer, ties to even (the
+        product of two binary32 numbers and a power of two is exact in fp64); ok[t] is False,
+        and q[t] = 0, where that value is not finite or not below 2^62 in magnitude."""
+        val = np.asarray(val, dtype=np.float32).astype(np.float64)
+        with np.errstate(invalid="ignore", over="ignore"):
+            x = val * np.float64(np.float32(scale)) * np.float64(2.0) ** int(frac_bits)
+            ok = np.abs(x) < 2.0 ** 62
+        q = np.zeros(val.shape, dtype=np.int64)
+        q[ok] = np.rint(x[ok]).astype(np.int64)
+        return q, ok
+
+    def accumulate_fixed(self, acc, g, frac_bits: int, i0: int = 0, scale: float = 1.0) -> int:
+        """acc[j, h_j(i0+t)] += s_j(i0+t) * q[t] in int64; returns the number of coordinates left out."""
+        g = np.asarray(g)
+        idx = np.arange(i0, i0 + g.size, dtype=np.int64)
+        return self.accumulate_fixed_sparse(acc, idx, g, frac_bits, scale)
+
+    def accumulate_fixed_sparse(self, acc, idx, val, frac_bits: int, scale: float = 1.0) -> int:
+        assert acc.dtype == np.int64 and acc.shape == (self.r, self.c)
+        idx = np.ascontiguousarray(idx, dtype=np.int64)
+        q, ok = self.fixed_contributions(val, scale, frac_bits)
+        step = 1 << 20
+        for t0 in range(0, idx.size, step):
+            bucket, sign = self.hash(idx[t0:t0 + step])
+            for j in range(self.r):
+                np.add.at(acc[j], bucket[j], sign[j].astype(np.int64) * q[t0:t0 + step])
+        return int(idx.size - np.count_nonzero(ok))
+
+    def fixed_to_float(self, acc, frac_bits: int, alpha: float = 1.0) -> np.ndarray:
+        """float32( float64(acc) * 2^-frac_bits * float64(alpha) ), one rounding per step."""
+        cells = acc.astype(np.float64) * np.float64(2.0) ** (-int(frac_bits))
+        return (cells * np.float64(np.float32(alpha))).astype(np.float32)
+
     # -- query ------------------------------------------------------------
     def estimate(self, T, d: int, i0: int = 0) -> np.ndarray:
         """est[t] = median_j s_j(i0+t) * T[j, h_j(i0+t)] for t in [0, d) (Alg. 4 estimate)."""

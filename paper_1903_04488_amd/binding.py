@@ -102,6 +102,14 @@ _SIGNATURES = {
                         ctypes.c_void_p],
     "cs_sketch_count_nonfinite": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_void_p,
                                   ctypes.c_void_p],
+    "cs_fixed_accumulate": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_void_p,
+                            ctypes.c_int64, ctypes.c_int64, ctypes.c_float, ctypes.c_int32,
+                            ctypes.c_void_p, ctypes.c_void_p],
+    "cs_fixed_accumulate_sparse": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_void_p,
+                                   ctypes.c_void_p, ctypes.c_int64, ctypes.c_float,
+                                   ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p],
+    "cs_fixed_to_float": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_int32,
+                          ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p],
     "cs_sketch_axpby": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_float,
                         ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p],
     "cs_sketch_momentum": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_void_p,
@@ -321,6 +329,35 @@ def cs_sketch_count_nonfinite(p, S, count):
     _check(load_library().cs_sketch_count_nonfinite(
         ctypes.byref(p), _dev(S, torch.float32, "S", _cells(p)), _dev(count, torch.int64, "count", 1),
         _stream(S)), "cs_sketch_count_nonfinite")
+
+
+CS_FIXED_MAX_FRAC_BITS = 62
+
+
+def _dropped(dropped):
+    if dropped is None:
+        return ctypes.c_void_p(0)
+    return _dev(dropped, torch.int64, "dropped", 1)
+
+
+def cs_fixed_accumulate(p, acc, g, frac_bits: int, i0: int = 0, scale: float = 1.0, dropped=None):
+    _check(load_library().cs_fixed_accumulate(
+        ctypes.byref(p), _dev(acc, torch.int64, "acc", _cells(p)), _dev(g, torch.float32, "g"),
+        g.numel(), i0, scale, frac_bits, _dropped(dropped), _stream(acc)), "cs_fixed_accumulate")
+
+
+def cs_fixed_accumulate_sparse(p, acc, idx, val, frac_bits: int, scale: float = 1.0, dropped=None):
+    n = idx.numel()
+    _check(load_library().cs_fixed_accumulate_sparse(
+        ctypes.byref(p), _dev(acc, torch.int64, "acc", _cells(p)), _dev(idx, torch.int64, "idx"),
+        _dev(val, torch.float32, "val", n), n, scale, frac_bits, _dropped(dropped),
+        _stream(acc)), "cs_fixed_accumulate_sparse")
+
+
+def cs_fixed_to_float(p, acc, frac_bits: int, S, alpha: float = 1.0):
+    _check(load_library().cs_fixed_to_float(
+        ctypes.byref(p), _dev(acc, torch.int64, "acc", _cells(p)), frac_bits, alpha,
+        _dev(S, torch.float32, "S", _cells(p)), _stream(acc)), "cs_fixed_to_float")
 
 
 def cs_estimate_workspace_bytes(p, d: int) -> int:

@@ -264,6 +264,97 @@ k_accumulate_sparse(KParams p, float* __restrict__ S, const int64_t* __restrict_
 }
 
 // ---------------------------------------------------------------------------------------
+// Alg. 4 update with order-independent sums: every contribution is rounded once to a multiple
+// of 2^-F and added as a 64-bit integer, so a table does not depend on how the additions were
+// scheduled (a debugging and checkpointing aid; the float kernels above are the product path)
+// ---------------------------------------------------------------------------------------
+// scale * g * 2^F as an integer, ties to even; the product of two binary32 numbers and a power
+// of two is exact in binary64, so the one rounding is the one to an integer.  False (and no
+// contribution) when the value is not finite or not below 2^62 in magnitude.
+__device__ __forceinline__ bool fixed_of(float g, double scale_2F, long long* q) {
+    const double x = static_cast<double>(g) * scale_2F;
+    if (!(fabs(x) < 0x1p62)) return false;
+    *q = __double2ll_rn(x);
+    return true;
+}
+
+__device__ __forceinline__ void fixed_add(long long* acc, long long q, bool negative) {
+    atomicAdd(reinterpret_cast<unsigned long long*>(acc),
+              static_cast<unsigned long long>(negative ? -q : q));
+}
+
+// lanes that dropped a coordinate: one atomic per wavefront that saw any
+__device__ __forceinline__ void count_dropped(unsigned long long* dropped, unsigned long long mine) {
+    if (dropped == nullptr) return;
+    for (int off = 32; off > 0; off >>= 1) mine += __shfl_xor(mine, off);
+    if ((threadIdx.x & 63) == 0 && mine) atomicAdd(dropped, mine);
+}
+
+template <int R, bool POW2>
+__global__ void __launch_bounds__(kBlock)
+k_fixed_accumulate(KParams p, long long* __restrict__ acc, const float* __restrict__ g, int64_t d,
+                   int64_t i0, double scale_2F, unsigned long long* __restrict__ dropped) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    const Columns col = columns_of<POW2>(p.c);
+    int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    unsigned long long bad = 0;
+    if (t < d) {
+        RowStates<R> st;
+        st.init(p, static_cast<uint64_t>(i0 + t), static_cast<uint64_t>(stride));
+        for (; t < d; t += stride) {
+            long long q;
+            if (fixed_of(g[t], scale_2F, &q)) {
+#pragma unroll
+                for (int j = 0; j < R; ++j)
+                    fixed_add(acc + static_cast<size_t>(j) * p.c + bucket_of<POW2>(st.yb[j], col), q,
+                              sign_flip_of(st.ys[j]) != 0u);
+            } else {
+                ++bad;
+            }
+            st.advance();
+        }
+    }
+    count_dropped(dropped, bad);
+}
+
+template <bool POW2>
+__global__ void __launch_bounds__(kBlock)
+k_fixed_accumulate_sparse(KParams p, long long* __restrict__ acc, const int64_t* __restrict__ idx,
+                          const float* __restrict__ val, int64_t n, double scale_2F,
+                          unsigned long long* __restrict__ dropped) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    const Columns col = columns_of<POW2>(p.c);
+    unsigned long long bad = 0;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < n; t += stride) {
+        const uint64_t i = static_cast<uint64_t>(idx[t]);
+        long long q;
+        if (!fixed_of(val[t], scale_2F, &q)) {
+            ++bad;
+            continue;
+        }
+        for (uint32_t j = 0; j < p.r; ++j) {
+            const uint64_t yb = hash_state(p.a[j], p.b[j], i);
+            const uint64_t ys = hash_state(p.as[j], p.bs[j], i);
+            fixed_add(acc + static_cast<size_t>(j) * p.c + bucket_of<POW2>(yb, col), q,
+                      sign_flip_of(ys) != 0u);
+        }
+    }
+    count_dropped(dropped, bad);
+}
+
+// S = binary32( binary64(acc) * 2^-F * alpha ): the integer to binary64 (exact below 2^53), an
+// exact scaling, one multiplication rounded in binary64, one rounding to binary32.
+__global__ void __launch_bounds__(kBlock)
+k_fixed_to_float(const long long* __restrict__ acc, int64_t n, double inv_2F, double alpha,
+                 float* __restrict__ S) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kBlock;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; t < n; t += stride) {
+        const double cell = __ll2double_rn(acc[t]) * inv_2F;
+        S[t] = __double2float_rn(cell * alpha);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // table-wide elementwise kernels: zero, merge, axpby, momentum
 // ---------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kBlock) k_fill_zero(float* __restrict__ S, int64_t n) {
@@ -707,6 +798,50 @@ extern "C" int cs_sketch_accumulate_sparse(const cs_params* p, float* S, const i
         k_accumulate_sparse<true><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(kparams(p), S, idx, val, n, scale);
     else
         k_accumulate_sparse<false><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(kparams(p), S, idx, val, n, scale);
+    return launch_status();
+}
+
+static bool fixed_args_ok(const cs_params* p, const void* acc, int32_t frac_bits) {
+    return params_ok(p) && acc && frac_bits >= 0 && frac_bits <= CS_FIXED_MAX_FRAC_BITS;
+}
+
+extern "C" int cs_fixed_accumulate(const cs_params* p, int64_t* acc, const float* g, int64_t d,
+                                   int64_t i0, float scale, int32_t frac_bits, int64_t* dropped,
+                                   void* stream) {
+    if (!fixed_args_ok(p, acc, frac_bits) || d < 0 || i0 < 0 || (d > 0 && !g)) return CS_EINVAL;
+    if (d == 0) return CS_OK;
+    const double scale_2F = ldexp(static_cast<double>(scale), frac_bits);
+    auto* a = reinterpret_cast<long long*>(acc);
+    auto* bad = reinterpret_cast<unsigned long long*>(dropped);
+#define CS_CALL(R_, P2_) \
+    k_fixed_accumulate<R_, P2_><<<grid_for(d), kBlock, 0, as_stream(stream)>>>(kparams(p), a, g, d, i0, scale_2F, bad)
+    CS_DISPATCH_R(p, CS_CALL);
+#undef CS_CALL
+    return launch_status();
+}
+
+extern "C" int cs_fixed_accumulate_sparse(const cs_params* p, int64_t* acc, const int64_t* idx,
+                                          const float* val, int64_t n, float scale,
+                                          int32_t frac_bits, int64_t* dropped, void* stream) {
+    if (!fixed_args_ok(p, acc, frac_bits) || n < 0 || (n > 0 && (!idx || !val))) return CS_EINVAL;
+    if (n == 0) return CS_OK;
+    const double scale_2F = ldexp(static_cast<double>(scale), frac_bits);
+    auto* a = reinterpret_cast<long long*>(acc);
+    auto* bad = reinterpret_cast<unsigned long long*>(dropped);
+    if (p->c_pow2)
+        k_fixed_accumulate_sparse<true><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(kparams(p), a, idx, val, n, scale_2F, bad);
+    else
+        k_fixed_accumulate_sparse<false><<<grid_for(n), kBlock, 0, as_stream(stream)>>>(kparams(p), a, idx, val, n, scale_2F, bad);
+    return launch_status();
+}
+
+extern "C" int cs_fixed_to_float(const cs_params* p, const int64_t* acc, int32_t frac_bits,
+                                 float alpha, float* S, void* stream) {
+    if (!fixed_args_ok(p, acc, frac_bits) || !S) return CS_EINVAL;
+    const int64_t n = static_cast<int64_t>(p->r) * p->c;
+    k_fixed_to_float<<<grid_for(n), kBlock, 0, as_stream(stream)>>>(
+        reinterpret_cast<const long long*>(acc), n, ldexp(1.0, -frac_bits),
+        static_cast<double>(alpha), S);
     return launch_status();
 }
 

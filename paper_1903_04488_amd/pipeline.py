@@ -101,6 +101,51 @@ class HotPath:
         return self.idx, self.x
 
 
+class ReproduciblePath(HotPath):
+    """The same step with sums that do not depend on the order of the additions, for debugging
+    and for checkpoints that must resume bit for bit: the workers' vectors and the feedback go
+    through the 64-bit fixed-point update (every contribution rounded once to a multiple of
+    2^-frac_bits, integer sums), everything else is elementwise or integer already.  Two runs on
+    equal inputs give equal bits; about one atomic request per coordinate and row, so far
+    slower than HotPath.
+
+        worker sketches   acc += fixed(g^w) for every w            cs_fixed_accumulate
+        aggregate         S_t = float(acc) / W                     cs_fixed_to_float
+        feedback          val = estimate(S, idx); S += float(fixed(-val at idx))
+                          cs_sketch_estimate_sparse, cs_fixed_accumulate_sparse, cs_sketch_axpby
+    `dropped` counts the coordinates that were left out (not finite, or too large for the
+    chosen frac_bits) since the object was made."""
+
+    def __init__(self, d, W, r, c, k, seed, rho=None, device="cuda:0", frac_bits: int = 40):
+        super().__init__(d, 1, r, c, k, seed, rho=rho, device=device)     # no bundle of W tables
+        self.W = W
+        self.frac_bits = frac_bits
+        self.acc = torch.zeros(r, c, dtype=torch.int64, device=self.device)
+        self.dropped = torch.zeros(1, dtype=torch.int64, device=self.device)
+        self.S_fb = torch.empty(r, c, dtype=torch.float32, device=self.device)
+
+    def accumulate(self, g_w):
+        self.acc.zero_()
+        for g in g_w:
+            B.cs_fixed_accumulate(self.params, self.acc, g, self.frac_bits, dropped=self.dropped)
+
+    def merge(self):
+        B.cs_fixed_to_float(self.params, self.acc, self.frac_bits, self.S_t, alpha=1.0 / self.W)
+
+    def _feedback(self, S, val):
+        B.cs_sketch_estimate_sparse(self.params, S, self.idx, val)
+        self.acc.zero_()
+        B.cs_fixed_accumulate_sparse(self.params, self.acc, self.idx, val, self.frac_bits,
+                                     scale=-1.0, dropped=self.dropped)
+        B.cs_fixed_to_float(self.params, self.acc, self.frac_bits, self.S_fb)
+        B.cs_sketch_axpby(self.params, S, 1.0, self.S_fb, 1.0)
+
+    def feedback(self):
+        if self.rho is not None:
+            self._feedback(self.S_v, self.delta)
+            self._feedback(self.S_u, self.uhat)
+
+
 class DenseStatePath(HotPath):
     """Alg. 3 as printed: momentum u^w and error accumulation v^w are dense vectors on every
     worker (2 W d floats), the sketch is taken of v^w, the second round returns exact sums of

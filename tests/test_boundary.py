@@ -188,6 +188,15 @@ def test_invalid_arguments_are_rejected_without_a_gpu(lib):
     assert lib.cs_dense_momentum(None, None, None, 1, 10, 0.9, null) == -1
     assert lib.cs_dense_mask(None, None, 1, fake, 10, null) == -1
     assert lib.cs_probe_stream_read(None, 1, 10, fake, null) == -1
+    assert lib.cs_fixed_accumulate(ctypes.byref(p), fake, fake, 10, 0, 1.0, 63, null, null) == -1
+    assert lib.cs_fixed_accumulate(ctypes.byref(p), fake, fake, 10, 0, 1.0, -1, null, null) == -1
+    assert lib.cs_fixed_accumulate(ctypes.byref(p), null, fake, 10, 0, 1.0, 40, null, null) == -1
+    assert lib.cs_fixed_accumulate(ctypes.byref(p), fake, null, 10, 0, 1.0, 40, null, null) == -1
+    assert lib.cs_fixed_accumulate(ctypes.byref(p), fake, null, 0, 0, 1.0, 40, null, null) == 0   # no-op
+    assert lib.cs_fixed_accumulate_sparse(ctypes.byref(p), fake, null, fake, 10, 1.0, 40, null, null) == -1
+    assert lib.cs_fixed_accumulate_sparse(ctypes.byref(p), fake, null, null, 0, 1.0, 40, null, null) == 0
+    assert lib.cs_fixed_to_float(ctypes.byref(p), fake, 40, 1.0, null, null) == -1
+    assert lib.cs_fixed_to_float(ctypes.byref(bad), fake, 40, 1.0, fake, null) == -1
     assert lib.cs_sketch_l2sq(ctypes.byref(p), fake, null, null) == -1
     assert lib.cs_sketch_l2sq(ctypes.byref(p), fake, ctypes.c_void_p(260), null) == -1    # misaligned
     assert lib.cs_heavymix_select(fake, 10, 5, null, 1, fake, null, null, fake, 1 << 20, null) == -1

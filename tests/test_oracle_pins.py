@@ -5,6 +5,8 @@ paper or the mathematics fixes, not against itself.
                  universality statistics (collision rate 1/c, balanced signs)
   update         S(f) = A f with the dense sign/bucket matrix A (App. C), MNIST-sized sketch
                  7 x 40 over d = 784 (App. E)
+  fixed point    the order-independent update: exact rational arithmetic, big-integer sums,
+                 and the fp64 update on inputs that are multiples of 2^-F
   merge          S(g1) + S(g2) = S(g1 + g2) (Sec. 3, App. C)
   estimate       numpy's median over rows; r = 1; c = 1 (AMS sum, App. C); 1-sparse input
   error bound    row variance (||g||^2 - g_i^2)/c and the +-eps ||g||_2 guarantee (Sec. 3, 5.2)
@@ -179,6 +181,64 @@ def test_accumulate_sparse_equals_dense_of_scattered_vector():
     one = np.zeros(d)
     one[7] = 7.0
     np.testing.assert_allclose(T, sk.sketch(one), atol=1e-13)
+
+
+def test_fixed_point_update_against_exact_rationals_and_the_fp64_update():
+    """The order-independent form of the update: (i) every contribution equals the exact
+    rational scale * g * 2^F rounded half to even (Python Fractions, big integers), including
+    halves, the 2^62 limit and non-finite inputs; (ii) the table is the big-integer sum of the
+    signed contributions over the dense sign/bucket matrix; (iii) on inputs that are multiples
+    of 2^-F nothing is rounded, so the table equals 2^F times the fp64 update of Alg. 4."""
+    from fractions import Fraction
+    r, c, d, i0, F = 5, 16, 400, 77, 20
+    sk = orc.SketchOracle(r, c, 23)
+    rng = np.random.default_rng(9)
+    g = rng.standard_normal(d).astype(np.float32)
+    g[:8] = np.float32([0.5 * 2.0 ** -F, 1.5 * 2.0 ** -F, -0.5 * 2.0 ** -F, -2.5 * 2.0 ** -F,
+                        np.nan, np.inf, -np.inf, 2.0 ** 43])        # halves; dropped; 2^63 >= 2^62
+    scale = np.float32(0.75)
+    q, ok = sk.fixed_contributions(g, scale, F)
+    for t in range(d):
+        if not np.isfinite(g[t]):
+            assert not ok[t] and q[t] == 0
+            continue
+        exact = Fraction(float(g[t])) * Fraction(float(scale)) * 2 ** F
+        if abs(exact) >= 2 ** 62:
+            assert not ok[t] and q[t] == 0
+        else:
+            assert ok[t] and int(q[t]) == round(exact)       # round(Fraction): ties to even
+    assert [int(v) for v in sk.fixed_contributions(g[:4], 1.0, F)[0]] == [0, 2, 0, -2]
+    assert int((~ok).sum()) == 4
+    acc = np.zeros((r, c), dtype=np.int64)
+    dropped = sk.accumulate_fixed(acc, g, F, i0=i0, scale=float(scale))
+    assert dropped == 4
+    A = dense_sketch_matrix(sk, d, i0)                       # entries -1, 0, +1
+    want = [sum(int(A[row, t]) * int(q[t]) for t in range(d) if A[row, t]) for row in range(r * c)]
+    assert [int(v) for v in acc.ravel()] == want
+    # (iii) dyadic inputs: no rounding anywhere, fixed point = 2^F * fp64 update
+    gd = (rng.integers(-2 ** 12, 2 ** 12, d) * 2.0 ** -10).astype(np.float32)
+    acc2 = np.zeros((r, c), dtype=np.int64)
+    assert sk.accumulate_fixed(acc2, gd, F, i0=i0, scale=-0.5) == 0
+    T = sk.sketch(gd, i0=i0, scale=-0.5)
+    assert (acc2.astype(np.float64) == T * 2.0 ** F).all()
+    np.testing.assert_array_equal(sk.fixed_to_float(acc2, F, alpha=0.25), (0.25 * T).astype(np.float32))
+    # sparse form, repeated indices, and sums over "workers" are the same integer sums
+    acc3 = np.zeros((r, c), dtype=np.int64)
+    sk.accumulate_fixed_sparse(acc3, np.arange(i0, i0 + d)[::-1], gd[::-1], F, scale=-0.5)
+    np.testing.assert_array_equal(acc3, acc2)
+    acc4 = np.zeros((r, c), dtype=np.int64)
+    sk.accumulate_fixed(acc4, gd[:150], F, i0=i0, scale=-0.5)
+    sk.accumulate_fixed(acc4, gd[150:], F, i0=i0 + 150, scale=-0.5)
+    np.testing.assert_array_equal(acc4, acc2)
+
+
+def test_fixed_point_conversion_rounds_once_per_step():
+    sk = orc.SketchOracle(1, 4, 1)
+    acc = np.array([[(1 << 53) + 1, -(1 << 24) - 1, 3, 0]], dtype=np.int64)
+    out = sk.fixed_to_float(acc, 0, alpha=1.0)
+    # 2^53 + 1 -> binary64 ties to even 2^53; -(2^24 + 1) -> binary32 ties to even -2^24
+    assert out.dtype == np.float32 and out.tolist() == [[2.0 ** 53, -(2.0 ** 24), 3.0, 0.0]]
+    np.testing.assert_array_equal(sk.fixed_to_float(acc, 2, alpha=0.5)[0, 2:], np.float32([0.375, 0.0]))
 
 
 # ----------------------------------------------------------------------------- linearity / merge
