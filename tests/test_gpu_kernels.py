@@ -128,7 +128,7 @@ def test_accumulate_batch(W):
 
 
 @pytest.mark.parametrize("W", [1, 2, 3, 5, 8, 13, 16, 32, 37])
-@pytest.mark.parametrize("r,c,seed,d,i0", [(5, 1 << 12, 11, 200_003, 17), (7, 1 << 15, 5, 1_000_003, 0),
+@pytest.mark.parametrize("r,c,seed,d,i0", [(5, 1 << 12, 11, 200_003, (1 << 45) + 17), (7, 1 << 15, 5, 1_000_003, 0),
                                            (3, 1000, 9, 50_001, 3), (5, 1 << 10, 2, 1000, 0),
                                            (3, 64, 3, 2_000_003, 5),       # d / c = 31 250: thinned lists
                                            (15, 180_000, 4, 400_003, 1 << 40),    # a sketch shape of Table 1
