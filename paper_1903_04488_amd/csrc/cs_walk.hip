@@ -975,7 +975,7 @@ k_row_values_walk(KParams p, RowSegments segs, const float* __restrict__ S, int6
                     vec4f u;
                     u.x = median_odd<RF>(vx); u.y = median_odd<RF>(vy);
                     u.z = median_odd<RF>(vz); u.w = median_odd<RF>(vw);
-                    *reinterpret_cast<vec4f_u*>(dst) = u;
+                    __builtin_nontemporal_store(u, reinterpret_cast<vec4f_u*>(dst));
                     tally(u.x); tally(u.y); tally(u.z); tally(u.w);
                 } else {
                     for (int m = 0; m < kQRun; ++m) {
