@@ -26,7 +26,10 @@
  *   - Device data are not validated: NaN / Inf propagate.  In cs_heavy_hitters_topk a NaN
  *     magnitude orders above every finite value (comparison is on the bit pattern).
  *   - fp32 atomic adds make sketch cells depend on summation order in the last bits; every
- *     other output is a deterministic function of its inputs.
+ *     other output is a deterministic function of its inputs.  cs_fixed_accumulate is the
+ *     update with order-independent (64-bit fixed-point) sums, for debugging and checkpoints.
+ *   - The one entry point with memory of its own is cs_heavy_hitters_topk_static (a fixed
+ *     array in the library's device image, for callers that cannot allocate).
  *
  * Hash family (Alg. 4 init draws r sign and r bucket hashes; the family itself is fixed by
  * the benchmark definition): with p = 2^61 - 1,
