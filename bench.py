@@ -195,12 +195,15 @@ def main():
                          "shapes of the paper's Table 1 (5 x 10^6 / 15 x 180 000 over 90 M, 5 x 180 000 "
                          "over 73 M coordinates; W = 4, k = 100 000, their P), run as --variant top-pk")
     ap.add_argument("--variant", default="sketch-state",
-                    choices=["sketch-state", "dense-state", "heavymix", "top-pk"],
+                    choices=["sketch-state", "dense-state", "heavymix", "top-pk", "fused-merge"],
                     help="sketch-state: the headline path (momentum / error feedback as sketches; "
                          "stateless for configs 1-3).  dense-state: Alg. 3 as printed, dense u, v "
                          "per worker.  heavymix: Alg. 1 selection (norm estimate, threshold, random "
                          "fill) on the merged sketch, no state.  top-pk: P = 16 candidates per "
-                         "selected coordinate, exact second round, k largest exact sums")
+                         "selected coordinate, exact second round, k largest exact sums.  "
+                         "fused-merge: sketch-state with the workers summed as they are sketched "
+                         "(cs_sketch_accumulate_sum: no worker tables, no merge pass) -- what a "
+                         "device that hosts several workers can do; not the headline path")
     ap.add_argument("--graph", action="store_true",
                     help="also time the same step replayed from a HIP graph (one submission per "
                          "step instead of one per kernel); reported as graph_ms_per_step")
@@ -241,6 +244,8 @@ def main():
         n_heavy = torch.empty(1, dtype=torch.int64, device=dev)
     else:
         hp = HotPath(cfg.d, cfg.W, cfg.r, cfg.c, cfg.k, cfg.hash_seed, rho=cfg.rho, device=dev)
+        # (the worker tables stay allocated either way: the placement probe below uses them)
+        hp.fold_workers = variant == "fused-merge"
 
     # inputs resident in HBM before the timed region: a few distinct steps' worth, cycled
     bytes_per_set = 4 * cfg.d * cfg.W
@@ -266,6 +271,7 @@ def main():
     # update (zeroing the worker tables belongs to it); the batched update itself is bracketed
     # by its own pair of events (ev[8], ev[9]) for the roofline figure.
     stages = {"sketch-state": ["accumulate", "merge", "momentum", "estimate", "topk", "gather", "feedback"],
+              "fused-merge": ["accumulate", "-", "momentum", "estimate", "topk", "gather", "feedback"],
               "top-pk": ["accumulate", "merge", "momentum", "estimate", "topk", "gather+select", "feedback"],
               "dense-state": ["dense_momentum", "accumulate", "merge", "estimate", "topk", "gather", "mask"],
               "heavymix": ["accumulate", "merge", "l2sq", "estimate", "heavymix_select", "gather", "-"]}[variant]
@@ -276,6 +282,12 @@ def main():
                 ev[i].record()
 
         def update(vecs):
+            if hp.fold_workers:
+                B.cs_sketch_zero(hp.params, hp.S_t)
+                mark(8)
+                B.cs_sketch_accumulate_sum(hp.params, hp.S_t, vecs, scale=1.0 / hp.W)
+                mark(9)
+                return
             B.cs_bundle_zero(hp.params, hp.T, hp.W)
             mark(8)
             B.cs_sketch_accumulate_bundle(hp.params, hp.T, vecs)
@@ -349,7 +361,8 @@ def main():
     update_ms_per_set = [round(sum(v) / len(v), 3) if v else None for v in per_set]
     value = cfg.W * cfg.d / (ms_per_step * 1e-3) / 1e9
 
-    alg_bytes = (4.0 * cfg.W * cfg.d + 4.0 * cfg.r * cfg.c * cfg.W) / n_launch
+    tables_written = 1 if variant == "fused-merge" else cfg.W
+    alg_bytes = (4.0 * cfg.W * cfg.d + 4.0 * cfg.r * cfg.c * tables_written) / n_launch
     achieved = alg_bytes / (acc_kernel_ms * 1e-3) / 1e9
     step_alg_bytes = (4.0 * cfg.W * cfg.d + 4.0 * cfg.r * cfg.c * cfg.W          # update
                       + 4.0 * cfg.r * cfg.c * (cfg.W + 1)                        # merge

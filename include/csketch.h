@@ -211,6 +211,19 @@ int cs_bundle_zero(const cs_params* p, float* T, int32_t W, void* stream);
 int cs_sketch_accumulate_bundle(const cs_params* p, float* T, int32_t W,
                                 const float* const* g_w, int64_t d, int64_t i0, float scale,
                                 void* stream);
+
+/* The workers that share a GPU summed as they are sketched (Sec. 3: the sketch of a sum is
+ * the sum of the sketches, so the workers of one device need no tables of their own before
+ * the aggregation step of Alg. 3):
+ *     S[j][h_j(i0+t)] += scale * s_j(i0+t) * sum_{w<W} g_w[w][t]      for all t < d, j < r,
+ * the sum over the workers of a group of 8 taken in registers, in binary32, before the cell
+ * is touched.  Equal to cs_bundle_zero + cs_sketch_accumulate_bundle + cs_bundle_merge
+ * (alpha = scale, beta = 1) up to the order of the binary32 additions, without the
+ * W r c floats of worker tables written and read back, and with one table of r c floats as
+ * the only target of the atomic adds.  S: device float[r][c], updated; g_w: HOST array of W
+ * device pointers to float[d].  W >= 1, d >= 0, i0 as for cs_sketch_accumulate. */
+int cs_sketch_accumulate_sum(const cs_params* p, float* S, int32_t W, const float* const* g_w,
+                             int64_t d, int64_t i0, float scale, void* stream);
 int cs_bundle_merge(const cs_params* p, float* dst, float beta, const float* T, int32_t W,
                     float alpha, void* stream);
 

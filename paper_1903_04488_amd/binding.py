@@ -92,6 +92,9 @@ _SIGNATURES = {
     "cs_sketch_accumulate_bundle": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_int32,
                                     ctypes.POINTER(ctypes.c_void_p), ctypes.c_int64,
                                     ctypes.c_int64, ctypes.c_float, ctypes.c_void_p],
+    "cs_sketch_accumulate_sum": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_int32,
+                                 ctypes.POINTER(ctypes.c_void_p), ctypes.c_int64,
+                                 ctypes.c_int64, ctypes.c_float, ctypes.c_void_p],
     "cs_bundle_merge": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_float,
                         ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p],
     "cs_sketch_accumulate_sparse": [ctypes.POINTER(CsParams), ctypes.c_void_p, ctypes.c_void_p,
@@ -281,6 +284,17 @@ def cs_sketch_accumulate_bundle(p, T, g_w, i0: int = 0, scale: float = 1.0):
         ctypes.byref(p), _dev(T, torch.float32, "T", cs_bundle_floats(p, W)), W,
         _ptr_array(g_w, torch.float32, "g_w", d), d, i0, scale, _stream(T)),
         "cs_sketch_accumulate_bundle")
+
+
+def cs_sketch_accumulate_sum(p, S, g_w, i0: int = 0, scale: float = 1.0):
+    W = len(g_w)
+    if W == 0:
+        raise CsError("g_w must be a non-empty list")
+    d = g_w[0].numel()
+    _check(load_library().cs_sketch_accumulate_sum(
+        ctypes.byref(p), _dev(S, torch.float32, "S", _cells(p)), W,
+        _ptr_array(g_w, torch.float32, "g_w", d), d, i0, scale, _stream(S)),
+        "cs_sketch_accumulate_sum")
 
 
 def cs_bundle_update_launches(p, W: int, d: int) -> int:

@@ -48,14 +48,17 @@ int launch_hash_range_lattice(const cs_params* p, int64_t i0, int64_t n, uint32_
 
 // Walk-order update of a worker bundle T = float[ceil(W/8)][r][c][8] (cs_walk.hip).
 bool walk_applies(const cs_params* p, int64_t d);
+// fold = true: T is one table float[r][c] and receives the sum over the W workers
+// (all_rows_listed(p, d) must hold for launch_accumulate_walk, anyc_visits_apply for the other)
+bool all_rows_listed(const cs_params* p, int64_t d);
 int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* const* g_w,
-                           int64_t d, int64_t i0, float scale, hipStream_t stream);
+                           int64_t d, int64_t i0, float scale, bool fold, hipStream_t stream);
 int count_accumulate_walk_launches(const cs_params* p, int W, int64_t d);
 // the same along visit lists for column counts that are not a power of two
 bool anyc_visits_apply(const cs_params* p, int64_t d);
 bool anyc_visits_serve_query(const cs_params* p, int64_t d);
 int launch_accumulate_anyc(const cs_params* p, float* T, int W, const float* const* g_w,
-                           int64_t d, int64_t i0, float scale, hipStream_t stream);
+                           int64_t d, int64_t i0, float scale, bool fold, hipStream_t stream);
 int count_accumulate_anyc_launches(const cs_params* p, int W);
 int launch_estimate_anyc(const cs_params* p, const float* S, int64_t d, int64_t i0, float* est,
                          float* rows, hipStream_t stream);

@@ -690,8 +690,8 @@ extern "C" int cs_sketch_accumulate_bundle(const cs_params* p, float* T, int32_t
     for (int w = 0; w < W; ++w)
         if (!g_w[w] && d > 0) return CS_EINVAL;
     if (d == 0) return CS_OK;
-    if (walk_applies(p, d)) return launch_accumulate_walk(p, T, W, g_w, d, i0, scale, as_stream(stream));
-    if (anyc_visits_apply(p, d)) return launch_accumulate_anyc(p, T, W, g_w, d, i0, scale, as_stream(stream));
+    if (walk_applies(p, d)) return launch_accumulate_walk(p, T, W, g_w, d, i0, scale, false, as_stream(stream));
+    if (anyc_visits_apply(p, d)) return launch_accumulate_anyc(p, T, W, g_w, d, i0, scale, false, as_stream(stream));
     // any other sketch: a slot of 8 lanes per coordinate, one lane per worker of a group
     const size_t group_floats = static_cast<size_t>(p->r) * p->c * CS_BUNDLE_GROUP;
     constexpr int kSlots = kBlock / CS_BUNDLE_GROUP;
@@ -719,6 +719,31 @@ extern "C" int cs_sketch_accumulate_bundle(const cs_params* p, float* T, int32_t
 #undef CALL
         }
         if (launch_status() != CS_OK) return CS_EHIP;
+    }
+    return CS_OK;
+}
+
+extern "C" int cs_sketch_accumulate_sum(const cs_params* p, float* S, int32_t W,
+                                        const float* const* g_w, int64_t d, int64_t i0,
+                                        float scale, void* stream) {
+    if (!params_ok(p) || W < 1 || d < 0 || i0 < 0 || i0 > (int64_t)kP61 - d) return CS_EINVAL;
+    if (!S || !g_w) return CS_EINVAL;
+    for (int w = 0; w < W; ++w)
+        if (!g_w[w] && d > 0) return CS_EINVAL;
+    if (d == 0) return CS_OK;
+    // along visit lists the 8 workers of a group are added up in registers and a cell receives
+    // one request per group; everything else adds worker by worker into the same table
+    if (all_rows_listed(p, d)) return launch_accumulate_walk(p, S, W, g_w, d, i0, scale, true, as_stream(stream));
+    if (anyc_visits_apply(p, d)) return launch_accumulate_anyc(p, S, W, g_w, d, i0, scale, true, as_stream(stream));
+    for (int w0 = 0; w0 < W; w0 += kMaxBatch) {
+        const int nw = (W - w0 < kMaxBatch) ? (W - w0) : kMaxBatch;
+        BatchPtrs ptrs{};
+        for (int w = 0; w < nw; ++w) {
+            ptrs.S[w] = S;
+            ptrs.g[w] = g_w[w0 + w];
+        }
+        const int rc = accumulate_launch(p, ptrs, nw, d, i0, scale, stream);
+        if (rc != CS_OK) return rc;
     }
     return CS_OK;
 }

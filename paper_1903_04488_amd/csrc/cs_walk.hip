@@ -308,11 +308,13 @@ struct VisitListAny {
 };
 struct VisitWorkers {
     const float* g[kGroup];      // vectors of the workers of this group
-    float* T;                    // the group's table, float[r][c][kGroup]
+    float* T;                    // the group's table, float[r][c][kGroup]; with `fold` one table float[r][c]
     int64_t d, i0;
     uint32_t c;
     int32_t nw;                  // workers in this group (<= kGroup)
     float scale;
+    int32_t fold;                // != 0: the workers' sums of a cell are added up across the lanes
+                                 // of a walker and leave as one 4-byte request into a single table
 };
 
 
@@ -385,7 +387,10 @@ k_accumulate_visits(LIST rows, VisitWorkers a) {
     const uint32_t mask = a.c - 1u;
     const Columns col = columns_of<POW2>(a.c);
     const int64_t d = a.d;
-    float* __restrict__ Tcol = a.T + static_cast<size_t>(v.j) * a.c * kGroup + wl;
+    const bool fold = a.fold != 0;
+    const size_t cell_floats = fold ? 1 : kGroup;      // floats from one cell to the next
+    float* __restrict__ Tcol = fold ? a.T + static_cast<size_t>(v.j) * a.c
+                                    : a.T + static_cast<size_t>(v.j) * a.c * kGroup + wl;
     // which running sum a coordinate now in `cell` belongs to, given the cell it started in;
     // >= NC: none of them (never with a list of cs_params_init)
     auto sum_of = [&](uint32_t cell, uint32_t first) -> uint32_t {
@@ -597,7 +602,7 @@ k_accumulate_visits(LIST rows, VisitWorkers a) {
                     const uint32_t pk = raw[m];
                     const float val = apply_sign(a.scale * my_row[m], pk & 0x80000000u);
                     if (live && val != 0.0f)
-                        atomic_add_noret(Tcol + static_cast<size_t>(pk & 0x7fffffffu) * kGroup, val);
+                        atomic_add_noret(Tcol + static_cast<size_t>(pk & 0x7fffffffu) * cell_floats, val);
                     my_row[m] = 0.0f;
                 }
             }
@@ -637,10 +642,20 @@ k_accumulate_visits(LIST rows, VisitWorkers a) {
         for (int m = 0; m < RUN; ++m) {
             const uint32_t c0 = first[m];
 #pragma unroll
-            for (int q = 0; q < NC; ++q)
-                if (live && acc[q][m] != 0.0f)
-                    atomic_add_noret(Tcol + static_cast<size_t>(cell_of_sum(c0, q)) * kGroup,
-                                     a.scale * acc[q][m]);
+            for (int q = 0; q < NC; ++q) {
+                if (!fold) {
+                    if (live && acc[q][m] != 0.0f)
+                        atomic_add_noret(Tcol + static_cast<size_t>(cell_of_sum(c0, q)) * kGroup,
+                                         a.scale * acc[q][m]);
+                } else {
+                    // the WL lanes of my walker hold the same cell's sums of the WL workers
+                    float sum = live ? acc[q][m] : 0.0f;
+#pragma unroll
+                    for (int off = 1; off < WL; off <<= 1) sum += __shfl_xor(sum, off);
+                    if (wl == 0 && sum != 0.0f)
+                        atomic_add_noret(Tcol + cell_of_sum(c0, q), a.scale * sum);
+                }
+            }
         }
         __builtin_amdgcn_wave_barrier();
     }
@@ -683,13 +698,14 @@ int launch_visits(const cs_params* p, const VisitWorkers& a, const uint32_t* js,
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
 
-// the visit list of row j serves vectors of length d, and is expected to send fewer requests
-bool visits_apply(const cs_params* p, uint32_t j, int64_t d) {
+// the visit list of row j serves vectors of length d, and (unless any_cost) is expected to take
+// less time than the stride walk
+bool visits_apply(const cs_params* p, uint32_t j, int64_t d, bool any_cost = false) {
     const cs_visit_plan& vp = p->visit[j];
     if ((p->flags & CS_FLAG_NO_VISIT_LIST) != 0 || vp.K == 0) return false;
     if (vp.ncell < 2 || vp.ncell > 4 || vp.K > CS_MAX_VISITS) return false;
     if (static_cast<uint64_t>(d) > vp.cover) return false;
-    return vp.cost < vp.cost_walk;
+    return any_cost || vp.cost < vp.cost_walk;
 }
 
 void fill_visit_list_any(const cs_params* p, uint32_t j, VisitListAny& v);
@@ -743,18 +759,19 @@ int count_accumulate_anyc_launches(const cs_params* p, int W) {
 // group's vectors are read once per row (where the direct form reads them once in all but
 // sends d requests per row to the atomic unit, which is what bounds it).
 int launch_accumulate_anyc(const cs_params* p, float* T, int W, const float* const* g_w,
-                           int64_t d, int64_t i0, float scale, hipStream_t stream) {
+                           int64_t d, int64_t i0, float scale, bool fold, hipStream_t stream) {
     const size_t row_floats = static_cast<size_t>(p->c) * kGroup;
     for (int w0 = 0; w0 < W; w0 += kGroup) {
         const int nw = (W - w0 < kGroup) ? (W - w0) : kGroup;
         VisitWorkers vw{};
         for (int w = 0; w < nw; ++w) vw.g[w] = g_w[w0 + w];
-        vw.T = T + static_cast<size_t>(w0 / kGroup) * p->r * row_floats;
+        vw.T = fold ? T : T + static_cast<size_t>(w0 / kGroup) * p->r * row_floats;
         vw.d = d;
         vw.i0 = i0;
         vw.c = p->c;
         vw.nw = nw;
         vw.scale = scale;
+        vw.fold = fold ? 1 : 0;
         for (uint32_t j = 0; j < p->r; ++j) {
             int rc;
             if (nw > 4) rc = launch_visits_anyc<8, 16, kWavesPerGroupOf8>(p, vw, j, stream);
@@ -785,12 +802,25 @@ int count_accumulate_walk_launches(const cs_params* p, int W, int64_t d) {
     return launches * ((W + kGroup - 1) / kGroup);
 }
 
+// every row of the sketch has a visit list for vectors of length d (what the folded form of
+// the update needs: only the list kernel adds the workers up before it writes; a list that the
+// time model likes less than the stride walk is used all the same)
+bool all_rows_listed(const cs_params* p, int64_t d) {
+    if (!walk_applies(p, d)) return false;
+    for (uint32_t j = 0; j < p->r; ++j)
+        if (!visits_apply(p, j, d, true)) return false;
+    return true;
+}
+
+// fold: T is one table float[r][c] that receives the sum over all W workers (all_rows_listed
+// must hold); otherwise T is the bundle and every worker has its own slot.
 int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* const* g_w,
-                           int64_t d, int64_t i0, float scale, hipStream_t stream) {
+                           int64_t d, int64_t i0, float scale, bool fold, hipStream_t stream) {
+    if (fold && !all_rows_listed(p, d)) return CS_EINVAL;
     const size_t row_floats = static_cast<size_t>(p->c) * kGroup;
     for (int w0 = 0; w0 < W; w0 += kGroup) {
         const int nw = (W - w0 < kGroup) ? (W - w0) : kGroup;
-        float* Tg = T + static_cast<size_t>(w0 / kGroup) * p->r * row_floats;
+        float* Tg = fold ? T : T + static_cast<size_t>(w0 / kGroup) * p->r * row_floats;
         VisitWorkers vw{};
         for (int w = 0; w < nw; ++w) vw.g[w] = g_w[w0 + w];
         vw.T = Tg;
@@ -799,6 +829,7 @@ int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* con
         vw.c = p->c;
         vw.nw = nw;
         vw.scale = scale;
+        vw.fold = fold ? 1 : 0;
         // All rows with a visit list go into one launch (per 8 rows), compiled for the largest
         // number of running sums among them: a row that needs fewer simply never touches the
         // extra ones.  One launch overlaps the rows' serial chains of visits and has one tail.
@@ -810,7 +841,7 @@ int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* con
         uint32_t listed[CS_MAX_R];
         int nlisted = 0;
         for (uint32_t j = 0; j < p->r; ++j) {
-            if (!visits_apply(p, j, d)) continue;
+            if (!visits_apply(p, j, d, fold)) continue;
             if (p->visit[j].ncell > ncell) ncell = p->visit[j].ncell;
             int at = nlisted++;
             for (; at > 0 && p->visit[listed[at - 1]].K < p->visit[j].K; --at) listed[at] = listed[at - 1];
@@ -837,7 +868,7 @@ int launch_accumulate_walk(const cs_params* p, float* T, int W, const float* con
         a.scale = scale;
         int nwalked = 0;
         for (uint32_t j = 0; j < p->r; ++j) {
-            if (visits_apply(p, j, d)) continue;
+            if (visits_apply(p, j, d, fold)) continue;
             int at = nwalked++;
             for (; at > 0 && p->plan[a.js[at - 1]].Dw > p->plan[j].Dw; --at) a.js[at] = a.js[at - 1];
             a.js[at] = static_cast<int32_t>(j);

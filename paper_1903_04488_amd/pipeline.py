@@ -3,6 +3,7 @@
 Per step (Alg. 3 of the paper, with the W workers simulated on the one device):
     worker sketches   S^w = S(g^w)                cs_sketch_accumulate_bundle  (T[w/8][j][b][w%8])
     aggregate         S_t = (1/W) sum_w S^w       cs_bundle_merge
+                      (fold_workers: both at once, S_t += (1/W) S(g^w), cs_sketch_accumulate_sum)
     momentum, error   S_u = rho S_u + S_t ; S_v += S_u      cs_sketch_momentum   (stateful only)
     query all         est = estimate(S_v or S_t)  cs_sketch_estimate
     choose largest    idx = top-k |est|           cs_heavy_hitters_topk
@@ -19,18 +20,21 @@ from . import binding as B
 
 class HotPath:
     def __init__(self, d: int, W: int, r: int, c: int, k: int, seed: int,
-                 rho: float | None = None, device="cuda:0", P: int = 1):
+                 rho: float | None = None, device="cuda:0", P: int = 1, fold_workers: bool = False):
         """P > 1: the sketch is queried for the top P*k coordinates, the workers for their exact
-        values, and the k largest exact sums are kept (Alg. 3 as the paper trains with it)."""
+        values, and the k largest exact sums are kept (Alg. 3 as the paper trains with it).
+        fold_workers: the workers, which share this GPU, are summed as they are sketched
+        (cs_sketch_accumulate_sum straight into S_t): no worker tables, no merge."""
         self.d, self.W, self.r, self.c, self.k = d, W, r, c, k
         self.P = P
+        self.fold_workers = fold_workers
         self.kq = min(P * k, d)          # coordinates asked of the sketch
         self.rho = rho
         self.device = torch.device(device)
         self.params = B.cs_params_init(r, c, seed, d)
         f32 = dict(dtype=torch.float32, device=self.device)
         # the W workers' sketches as one bundle: T[w // 8][j][b][w % 8] = S^w[j][b]
-        self.T = torch.zeros(B.cs_bundle_floats(self.params, W), **f32)
+        self.T = torch.zeros(B.cs_bundle_floats(self.params, 1 if fold_workers else W), **f32)
         self.S_t = torch.zeros(r, c, **f32)
         self.S_u = torch.zeros(r, c, **f32) if rho is not None else None
         self.S_v = torch.zeros(r, c, **f32) if rho is not None else None
@@ -59,10 +63,16 @@ class HotPath:
         return self.T.view(-1, self.r, self.c, g)[w // g, :, :, w % g]
 
     def accumulate(self, g_w):
+        if self.fold_workers:
+            B.cs_sketch_zero(self.params, self.S_t)
+            B.cs_sketch_accumulate_sum(self.params, self.S_t, g_w, scale=1.0 / self.W)
+            return
         B.cs_bundle_zero(self.params, self.T, self.W)
         B.cs_sketch_accumulate_bundle(self.params, self.T, g_w)
 
     def merge(self):
+        if self.fold_workers:
+            return                       # S_t is complete already
         B.cs_bundle_merge(self.params, self.S_t, self.T, self.W, alpha=1.0 / self.W, beta=0.0)
 
     def momentum(self):

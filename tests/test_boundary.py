@@ -188,6 +188,12 @@ def test_invalid_arguments_are_rejected_without_a_gpu(lib):
     assert lib.cs_dense_momentum(None, None, None, 1, 10, 0.9, null) == -1
     assert lib.cs_dense_mask(None, None, 1, fake, 10, null) == -1
     assert lib.cs_probe_stream_read(None, 1, 10, fake, null) == -1
+    assert lib.cs_sketch_accumulate_sum(ctypes.byref(p), null, 2, None, 10, 0, 1.0, null) == -1
+    assert lib.cs_sketch_accumulate_sum(ctypes.byref(p), fake, 0, None, 10, 0, 1.0, null) == -1
+    two = (ctypes.c_void_p * 2)(256, 0)
+    assert lib.cs_sketch_accumulate_sum(ctypes.byref(p), fake, 2, two, 10, 0, 1.0, null) == -1   # a null vector
+    assert lib.cs_sketch_accumulate_sum(ctypes.byref(p), fake, 2, two, 0, 0, 1.0, null) == 0    # no-op
+    assert lib.cs_sketch_accumulate_sum(ctypes.byref(p), fake, 2, two, 10, -1, 1.0, null) == -1
     assert lib.cs_fixed_accumulate(ctypes.byref(p), fake, fake, 10, 0, 1.0, 63, null, null) == -1
     assert lib.cs_fixed_accumulate(ctypes.byref(p), fake, fake, 10, 0, 1.0, -1, null, null) == -1
     assert lib.cs_fixed_accumulate(ctypes.byref(p), null, fake, 10, 0, 1.0, 40, null, null) == -1

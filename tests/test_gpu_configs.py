@@ -33,16 +33,21 @@ def rms(T):
     return float(np.sqrt((np.asarray(T) ** 2).mean()))
 
 
-def run(config, steps, check_workers=(0,), workers_first_step_only=False, full_steps=None, log=print):
+def run(config, steps, check_workers=(0,), workers_first_step_only=False, full_steps=None, log=print,
+        fold_workers=False):
     """`steps` steps of the path on the device and in the reference, everything compared.
     check_workers: whose own table is compared with the sketch of that worker's vector (at
     step 0 only with workers_first_step_only).  full_steps: the steps at which every
     coordinate's estimate is compared and the selection is judged on all of them (None: every
     step); at the other steps the selected coordinates and a sample of 2 M others are.
-    One line per step reports the worst error of each comparison as a fraction of its bound."""
+    One line per step reports the worst error of each comparison as a fraction of its bound.
+    fold_workers: the form of the step that sums the workers as it sketches them (there are no
+    worker tables to compare then; the merged table is compared as always)."""
     c = config
     work = wl.Workload(c, DEV)
-    hp = HotPath(c.d, c.W, c.r, c.c, c.k, c.hash_seed, rho=c.rho, device=DEV)
+    hp = HotPath(c.d, c.W, c.r, c.c, c.k, c.hash_seed, rho=c.rho, device=DEV, fold_workers=fold_workers)
+    if fold_workers:
+        check_workers = ()
     sk = orc.SketchOracle(c.r, c.c, c.hash_seed)
     st = orc.SketchSpaceState(sk, c.rho) if c.stateful else None
     dense = orc.DenseState(c.d, st.rho) if (c.stateful and c.d <= (1 << 22)) else None
@@ -163,6 +168,21 @@ def test_small_variant_all_steps(cfg):
                       k=2000, steps=min(base.steps, 4),
                       n_heavy=(500 if base.n_heavy else 0))
     run(small, small.steps, check_workers=range(small.W))
+
+
+@pytest.mark.parametrize("cfg", [1, 4, 5])
+def test_small_variant_with_the_workers_summed_as_they_are_sketched(cfg):
+    """the same steps through cs_sketch_accumulate_sum (no worker tables, no merge pass)"""
+    base = wl.CONFIGS[cfg]
+    small = wl.scaled(cfg, d=(1 << 21) + 12_345, W=min(base.W, 12), c=1 << 14,
+                      k=2000, steps=min(base.steps, 4),
+                      n_heavy=(500 if base.n_heavy else 0))
+    run(small, small.steps, fold_workers=True)
+
+
+def test_config4_first_steps_with_the_workers_summed_as_they_are_sketched(progress):
+    """config 4 at full size (the launch configuration of bench.py --variant fused-merge), two steps"""
+    run(wl.CONFIGS[4], 2, fold_workers=True, full_steps={0, 1}, log=progress)
 
 
 def test_small_variant_non_power_of_two_columns_and_many_rows():

@@ -173,6 +173,51 @@ def test_accumulate_bundle(W, r, c, seed, d, i0, lds_table):
     assert (T == 0).all()
 
 
+@pytest.mark.parametrize("W", [1, 3, 8, 13, 32])
+@pytest.mark.parametrize("r,c,seed,d,i0,listed", [
+    (5, 1 << 12, 11, 200_003, (1 << 45) + 17, True),      # visit lists, power-of-two columns
+    (7, 1 << 15, 5, 1_000_003, 0, True),
+    (5, 180_000, 41, 6_500_003, 1 << 40, True),           # visit lists for any column count (Table 1)
+    (15, 180_000, 4, 400_003, 1 << 40, False),            # too short for such lists
+    (5, 1000, 9, 50_001, 3, False),                       # worker by worker into the one table
+    (7, 40, 6, 784, 0, False),                            # App. E's sketch
+    (5, 1 << 12, 11, 3_000, 0, False)])                   # too short for a traversal plan
+def test_accumulate_sum_of_workers(W, r, c, seed, d, i0, listed):
+    """cs_sketch_accumulate_sum: the workers of one device added up as they are sketched, against
+    the reference's sketch of the binary64 sum of their vectors (linearity, Sec. 3)."""
+    if W > 8 and d > 2_000_000:
+        pytest.skip("covered by the smaller shapes")
+    p = cs.cs_params_init(r, c, seed, d)
+    # which form runs: the list kernel (workers added up in registers) when every row has a list
+    # that covers the vector, else the generic kernels, worker by worker into the one table
+    plans = p.visit if p.c_pow2 else p.anyc
+    assert all(plans[j].K > 0 and plans[j].cover >= d for j in range(r)) == listed
+    sk = orc.SketchOracle(r, c, seed)
+    rng = np.random.default_rng(W * 77 + r)
+    gs = [(rng.standard_normal(d) * 0.01).astype(np.float32) for _ in range(W)]
+    for g in gs:
+        g[rng.integers(0, d, size=20)] += 1.0
+    gs[0][5], gs[-1][d - 1] = np.float32(-3.0), np.float32(2.5)
+    S = torch.full((r, c), 0.25, dtype=torch.float32, device=DEV)       # accumulates into S
+    cs.cs_sketch_accumulate_sum(p, S, [dev(g) for g in gs], i0=i0, scale=0.5)
+    gsum = np.zeros(d)
+    for g in gs:
+        gsum += g.astype(np.float64)
+    ref = sk.accumulate(np.full((r, c), 0.25), gsum, i0=i0, scale=0.5)
+    assert_cells_close(S.cpu().numpy(), ref, what=f"sum of {W} workers", terms_per_cell=W * d / c)
+    # NaN and infinities of any worker reach the cells they belong to
+    gs[W // 2][7] = np.nan
+    gs[0][11] = np.inf
+    S.fill_(0.0)
+    cs.cs_sketch_accumulate_sum(p, S, [dev(g) for g in gs], i0=i0)
+    got = S.cpu().numpy()
+    bkt, _ = sk.hash(np.array([i0 + 7, i0 + 11]))
+    for j in range(r):
+        assert np.isnan(got[j, bkt[j, 0]])
+        assert not np.isfinite(got[j, bkt[j, 1]])
+    assert np.isfinite(got).sum() >= got.size - 2 * r
+
+
 @pytest.mark.parametrize("r,c,seed,d,d_hint,W,i0", [
     (5, 180_000, 41, 6_500_000, 6_500_000, 9, 0),        # Table 1: 5 x 180 000; two groups, the second partial
     (15, 180_000, 42, 6_500_000, 6_500_000, 3, 12_345),  # Table 1: 15 x 180 000
