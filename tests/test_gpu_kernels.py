@@ -367,6 +367,17 @@ def test_accumulate_bundle_every_traversal(W):
         v.A[0], v.As[0] = (p.a[j] * g0) % P, (p.as_[j] * g0) % P
         v.code[0] = 0b110000                      # visits 0, 1: code 0; visit 2: code 3
     check(forged, "forged list")
+    # the same three sets of parameters with the workers summed as they are sketched
+    # (cs_sketch_accumulate_sum): list kernel with the sums folded across lanes, the generic
+    # kernels when the lists are switched off, the folded fallback of the forged list
+    gsum = np.zeros(d)
+    for g in gs:
+        gsum += g.astype(np.float64)
+    ref_sum = sk.sketch(gsum, i0=5, scale=2.0)
+    for params, what in ((p, "visit list"), (walk, "lists off"), (forged, "forged list")):
+        S = torch.zeros(r, c, dtype=torch.float32, device=DEV)
+        cs.cs_sketch_accumulate_sum(params, S, [dev(g) for g in gs], i0=5, scale=2.0)
+        assert_cells_close(S.cpu().numpy(), ref_sum, what=f"sum of workers, {what}", terms_per_cell=W * d / c)
     # shorter than planned: the list still applies; longer: the stride walk takes over
     for d2 in (d - 12_345, 4_100):
         short = [g[:d2] for g in gs]
