@@ -306,6 +306,21 @@ struct VisitListAny {
     uint64_t A[CS_ANYC_MAX_VISITS], As[CS_ANYC_MAX_VISITS];
     __device__ __forceinline__ const VisitListAny& at(unsigned) const { return *this; }
 };
+// The same list without the hash advances (the query computes them on the device, once per
+// wavefront, so that several rows' lists fit into the 4 KB of kernel arguments and share a launch).
+struct VisitGaps {
+    uint32_t K;
+    int32_t j;
+    uint64_t gmax;
+    uint64_t a, b, as, bs;
+    uint32_t omega, pc;
+    uint32_t gap[CS_ANYC_MAX_VISITS];
+};
+constexpr int kQueryRowsPerLaunch = 6;
+struct VisitGapsRows {
+    VisitGaps row[kQueryRowsPerLaunch];
+};
+static_assert(sizeof(VisitGapsRows) + 64 <= 4096, "the lists of a launch and its other arguments are kernel arguments");
 struct VisitWorkers {
     const float* g[kGroup];      // vectors of the workers of this group
     float* T;                    // the group's table, float[r][c][kGroup]; with `fold` one table float[r][c]
@@ -1065,12 +1080,21 @@ k_row_values_walk(KParams p, RowSegments segs, const float* __restrict__ S, int6
 // ---------------------------------------------------------------------------------------
 template <int RF, int NC>
 __global__ void __launch_bounds__(64)
-k_row_values_visits(VisitListAny v, const float* __restrict__ S, uint32_t c, int64_t d, int64_t i0,
+k_row_values_visits(VisitGapsRows vr, const float* __restrict__ S, uint32_t c, int64_t d, int64_t i0,
                     float* __restrict__ rows, float* __restrict__ est) {
     static_assert(kQRun == 4, "one 16-byte piece per lane");
     static_assert(NC == 2 || NC == 4, "omega = 1 or 2");
     const int lane = threadIdx.x;
+    const VisitGaps& v = vr.row[blockIdx.y];           // the rows of a launch run side by side
     const int j = v.j;
+    // hash advances of the visits, (a_j gap_k) mod p and (a'_j gap_k) mod p: computed here once
+    // per wavefront instead of travelling with the list
+    __shared__ uint64_t A_of[CS_ANYC_MAX_VISITS], As_of[CS_ANYC_MAX_VISITS];
+    for (uint32_t k = lane; k < v.K; k += 64) {
+        A_of[k] = mulmod_p(v.a, v.gap[k]);
+        As_of[k] = mulmod_p(v.as, v.gap[k]);
+    }
+    __syncthreads();
     const Columns col = columns_of<false>(c);
     const float* __restrict__ Sj = S + static_cast<size_t>(j) * c;
     float* __restrict__ out = rows + static_cast<size_t>(j) * d;
@@ -1176,8 +1200,8 @@ k_row_values_visits(VisitListAny v, const float* __restrict__ S, uint32_t c, int
                 }
             }
             s += gap;
-            yb = hash_advance(yb, v.A[k]);
-            ys = hash_advance(ys, v.As[k]);
+            yb = hash_advance(yb, A_of[k]);
+            ys = hash_advance(ys, As_of[k]);
         }
     }
 }
@@ -1200,7 +1224,20 @@ void fill_visit_list_any(const cs_params* p, uint32_t j, VisitListAny& v) {
 }  // namespace
 
 // The query along the rows' visit lists for any column count: rows 0 .. r-2 into the scratch,
-// one launch each, then the last row together with the median.
+// up to kQueryRowsPerLaunch rows per launch (one row's wavefronts alone fill a third to two
+// thirds of the chip, and every launch has the tail of its longest chain of visits), then the
+// last row together with the median.  The rows of a launch use the same number of cells.
+static void fill_visit_gaps(const cs_params* p, uint32_t j, VisitGaps& v) {
+    const cs_anyc_plan& vp = p->anyc[j];
+    v.K = vp.K;
+    v.j = static_cast<int32_t>(j);
+    v.gmax = vp.gmax;
+    v.a = p->a[j]; v.b = p->b[j]; v.as = p->as[j]; v.bs = p->bs[j];
+    v.omega = vp.omega;
+    v.pc = static_cast<uint32_t>(kP61 % p->c);
+    for (uint32_t k = 0; k < vp.K; ++k) v.gap[k] = vp.gap[k];
+}
+
 int launch_estimate_anyc(const cs_params* p, const float* S, int64_t d, int64_t i0, float* est,
                          float* rows, hipStream_t stream) {
     auto grid_x = [](uint64_t gmax) {
@@ -1210,18 +1247,32 @@ int launch_estimate_anyc(const cs_params* p, const float* S, int64_t d, int64_t 
         return static_cast<unsigned>((gx + 7) / 8 * 8);
     };
     const uint32_t last = p->r - 1;
-    VisitListAny v{};
-    for (uint32_t j = 0; j < last; ++j) {
-        fill_visit_list_any(p, j, v);
-        if (v.omega == 1) k_row_values_visits<0, 2><<<grid_x(v.gmax), 64, 0, stream>>>(v, S, p->c, d, i0, rows, est);
-        else k_row_values_visits<0, 4><<<grid_x(v.gmax), 64, 0, stream>>>(v, S, p->c, d, i0, rows, est);
+    VisitGapsRows vr{};
+    for (uint32_t omega = 1; omega <= 2; ++omega) {
+        int n = 0;
+        uint64_t most = 0;
+        for (uint32_t j = 0; j <= last; ++j) {
+            const bool mine = j < last && p->anyc[j].omega == omega;
+            if (mine) {
+                fill_visit_gaps(p, j, vr.row[n++]);
+                if (p->anyc[j].gmax > most) most = p->anyc[j].gmax;
+            }
+            if (n == kQueryRowsPerLaunch || (j == last && n > 0)) {
+                const dim3 grid(grid_x(most), static_cast<unsigned>(n));
+                if (omega == 1) k_row_values_visits<0, 2><<<grid, 64, 0, stream>>>(vr, S, p->c, d, i0, rows, est);
+                else k_row_values_visits<0, 4><<<grid, 64, 0, stream>>>(vr, S, p->c, d, i0, rows, est);
+                n = 0;
+                most = 0;
+            }
+        }
     }
-    fill_visit_list_any(p, last, v);
-    const unsigned gx = grid_x(v.gmax);
+    fill_visit_gaps(p, last, vr.row[0]);
+    const uint32_t omega_last = p->anyc[last].omega;
+    const unsigned gx = grid_x(p->anyc[last].gmax);
 #define CS_LASTR(R_)                                                                                 \
     case R_:                                                                                         \
-        if (v.omega == 1) k_row_values_visits<R_, 2><<<gx, 64, 0, stream>>>(v, S, p->c, d, i0, rows, est); \
-        else k_row_values_visits<R_, 4><<<gx, 64, 0, stream>>>(v, S, p->c, d, i0, rows, est);             \
+        if (omega_last == 1) k_row_values_visits<R_, 2><<<gx, 64, 0, stream>>>(vr, S, p->c, d, i0, rows, est); \
+        else k_row_values_visits<R_, 4><<<gx, 64, 0, stream>>>(vr, S, p->c, d, i0, rows, est);             \
         break;
     switch (p->r) {
         CS_LASTR(1) CS_LASTR(3) CS_LASTR(5) CS_LASTR(7) CS_LASTR(9) CS_LASTR(11) CS_LASTR(13) CS_LASTR(15)
