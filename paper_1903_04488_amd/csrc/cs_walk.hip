@@ -1090,9 +1090,13 @@ k_row_values_visits(VisitGapsRows vr, const float* __restrict__ S, uint32_t c, i
     // hash advances of the visits, (a_j gap_k) mod p and (a'_j gap_k) mod p: computed here once
     // per wavefront instead of travelling with the list
     __shared__ uint64_t A_of[CS_ANYC_MAX_VISITS], As_of[CS_ANYC_MAX_VISITS];
+    __shared__ uint32_t Ac_of[CS_ANYC_MAX_VISITS];     // A_of[k] mod c
+    const Columns colc = columns_of<false>(c);
     for (uint32_t k = lane; k < v.K; k += 64) {
-        A_of[k] = mulmod_p(v.a, v.gap[k]);
+        const uint64_t A = mulmod_p(v.a, v.gap[k]);
+        A_of[k] = A;
         As_of[k] = mulmod_p(v.as, v.gap[k]);
+        Ac_of[k] = bucket_of<false>(A + 1, colc);     // bucket_of takes the y form, x + 1
     }
     __syncthreads();
     const Columns col = columns_of<false>(c);
@@ -1110,6 +1114,20 @@ k_row_values_visits(VisitGapsRows vr, const float* __restrict__ S, uint32_t c, i
         const uint32_t x = static_cast<uint32_t>(q) < omega ? first + q : first + (q - omega) + (c - pc);
         return x >= c ? x - c : x;
     };
+    // The bucket x mod c is carried along with the hash value instead of being taken again by a
+    // 64-bit remainder at every coordinate: when x moves on by A (mod p), x mod c moves on by
+    // A mod c, less p mod c if x wrapped past p.  All terms are below c <= 2^31, so the sums
+    // stay below 2^32.  Exact, like the hash state itself.
+    const uint32_t Ajc = bucket_of<false>(Aj + 1, colc);          // a_j mod c
+    auto advance = [&](uint64_t& y, uint32_t& rem, uint64_t A, uint32_t Ac) {
+        const uint64_t t = y + A;
+        const bool wrapped = (t >> 61) != 0;
+        y = (t & kP61) + (t >> 61);
+        uint32_t u = rem + Ac;
+        u = u >= c ? u - c : u;
+        const uint32_t u2 = u + (c - pc);
+        rem = !wrapped ? u : (u2 >= c ? u2 - c : u2);
+    };
     const int64_t nwaves = (static_cast<int64_t>(v.gmax) + 64 * kQRun - 1) / (64 * kQRun);
     const int64_t per_xcd = (nwaves + 7) / 8;
     const int64_t xcd_first = static_cast<int64_t>(blockIdx.x & 7) * per_xcd;
@@ -1120,16 +1138,18 @@ k_row_values_visits(VisitGapsRows vr, const float* __restrict__ S, uint32_t c, i
         const int64_t my_res = wave_res + static_cast<int64_t>(lane) * kQRun;
         uint64_t yb = hash_state(v.a, v.b, static_cast<uint64_t>(i0 + my_res));
         uint64_t ys = hash_state(v.as, v.bs, static_cast<uint64_t>(i0 + my_res));
+        uint32_t rb = bucket_of<false>(yb, col);                    // bucket of my first coordinate
         uint32_t first_cell[kQRun];
         float cellv[kQRun][NC];
         {
             uint64_t tb = yb;
+            uint32_t tr = rb;
 #pragma unroll
             for (int m = 0; m < kQRun; ++m) {
-                first_cell[m] = bucket_of<false>(tb, col);
+                first_cell[m] = tr;
 #pragma unroll
                 for (int n = 0; n < NC; ++n) cellv[m][n] = Sj[cell_of_sum(first_cell[m], n)];
-                tb = hash_advance(tb, Aj);
+                advance(tb, tr, Aj, Ajc);
             }
         }
         int64_t s = 0;
@@ -1150,17 +1170,18 @@ k_row_values_visits(VisitGapsRows vr, const float* __restrict__ S, uint32_t c, i
                     }
                 }
                 uint64_t tb = yb, ts = ys;
+                uint32_t tr = rb;
                 float o[kQRun];
 #pragma unroll
                 for (int m = 0; m < kQRun; ++m) {
-                    const uint32_t cell = bucket_of<false>(tb, col);
+                    const uint32_t cell = tr;
                     const uint32_t rel = sum_of(cell, first_cell[m]);
                     float x = cellv[m][NC - 1];
 #pragma unroll
                     for (int n = NC - 2; n >= 0; --n) x = rel == static_cast<uint32_t>(n) ? cellv[m][n] : x;
                     if (rel >= static_cast<uint32_t>(NC) && m < my_len) x = Sj[cell];
                     o[m] = apply_sign(x, sign_flip_of(ts));
-                    tb = hash_advance(tb, Aj);
+                    advance(tb, tr, Aj, Ajc);
                     ts = hash_advance(ts, Asj);
                 }
                 if constexpr (RF > 0) {
@@ -1175,7 +1196,7 @@ k_row_values_visits(VisitGapsRows vr, const float* __restrict__ S, uint32_t c, i
                         vec4f u;
                         u.x = median_odd<RF>(vx); u.y = median_odd<RF>(vy);
                         u.z = median_odd<RF>(vz); u.w = median_odd<RF>(vw);
-                        *reinterpret_cast<vec4f_u*>(dst) = u;
+                        __builtin_nontemporal_store(u, reinterpret_cast<vec4f_u*>(dst));
                     } else {
                         for (int m = 0; m < kQRun; ++m) {
                             if (m >= my_len) break;
@@ -1200,7 +1221,7 @@ k_row_values_visits(VisitGapsRows vr, const float* __restrict__ S, uint32_t c, i
                 }
             }
             s += gap;
-            yb = hash_advance(yb, A_of[k]);
+            advance(yb, rb, A_of[k], Ac_of[k]);
             ys = hash_advance(ys, As_of[k]);
         }
     }
