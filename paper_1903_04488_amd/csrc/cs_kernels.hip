@@ -476,7 +476,7 @@ k_gather(GatherPtrs ptrs, int nw, const int64_t* __restrict__ idx, int64_t k, fl
     for (int64_t n = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; n < k; n += stride) {
         const int64_t i = idx[n];
         float s = first_chunk ? 0.0f : out[n];
-        for (int w = 0; w < nw; ++w) s += ptrs.vec[w][i];
+        for (int w = 0; w < nw; ++w) s += __builtin_nontemporal_load(ptrs.vec[w] + i);
         out[n] = last_chunk ? alpha * s : s;
     }
 }
