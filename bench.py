@@ -425,7 +425,8 @@ def main():
                             for name in ("accumulate", "dense_momentum", "estimate", "topk", "heavymix_select")
                             if stage_ms.get(name)},
         "roofline": {
-            "kernel": "k_accumulate_visits (all launches of cs_sketch_accumulate_bundle)",
+            "kernel": ("k_accumulate_visits (all launches of cs_sketch_accumulate_sum)" if variant == "fused-merge"
+                       else "k_accumulate_visits (all launches of cs_sketch_accumulate_bundle)"),
             "bound": "hbm",
             "achieved": achieved,
             "peak": HBM_PEAK_GBS,
