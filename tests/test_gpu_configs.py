@@ -342,8 +342,8 @@ def test_dense_momentum_unaligned_and_tail():
 
 
 # ----------------------------------------------------------------------------- HIP graph
-@pytest.mark.parametrize("stateful", [False, True])
-def test_step_replayed_from_a_hip_graph_matches_eager(stateful):
+@pytest.mark.parametrize("stateful,fold", [(False, False), (True, False), (True, True)])
+def test_step_replayed_from_a_hip_graph_matches_eager(stateful, fold):
     """A step recorded once as a HIP graph and replayed: three replays, with the program's own
     eager work (input generation, device-to-host copies, synchronisation) between them, each
     checked against the same step run eagerly on a second instance.  Sums in the tables may
@@ -352,8 +352,8 @@ def test_step_replayed_from_a_hip_graph_matches_eager(stateful):
     c = wl.scaled(4 if stateful else 1, d=(1 << 19) + 321, W=5, c=1 << 13, k=300, steps=3,
                   n_heavy=300 if not stateful else 0)
     work = wl.Workload(c, DEV)
-    eager = HotPath(c.d, c.W, c.r, c.c, c.k, c.hash_seed, rho=c.rho, device=DEV)
-    graphed = HotPath(c.d, c.W, c.r, c.c, c.k, c.hash_seed, rho=c.rho, device=DEV)
+    eager = HotPath(c.d, c.W, c.r, c.c, c.k, c.hash_seed, rho=c.rho, device=DEV, fold_workers=fold)
+    graphed = HotPath(c.d, c.W, c.r, c.c, c.k, c.hash_seed, rho=c.rho, device=DEV, fold_workers=fold)
     static = [torch.zeros(c.d, dtype=torch.float32, device=DEV) for _ in range(c.W)]
     for w in range(c.W):
         static[w].copy_(work.gradient(0, w))
