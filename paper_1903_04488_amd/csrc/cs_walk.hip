@@ -292,10 +292,11 @@ struct VisitRows {
     VisitArgs row[kRowsPerLaunch];
     __device__ __forceinline__ const VisitArgs& at(unsigned y) const { return row[y]; }
 };
-// The list of one row when the column count is not a power of two (cs_anyc_plan): gaps and hash
-// advances visit by visit.  One row per launch: with 144 visits the struct is 2.9 KB of the
-// 4 KB that kernel arguments may take.
-struct VisitListAny {
+// The list of one row when the column count is not a power of two (cs_anyc_plan): the gaps visit
+// by visit.  The hash advances (a_j gap_k) mod p and (a'_j gap_k) mod p do not travel with it:
+// every workgroup computes them once into LDS, so that several rows' lists fit into the 4 KB of
+// kernel arguments and share a launch.
+struct VisitGaps {
     uint32_t K;
     int32_t j;
     uint64_t gmax;
@@ -303,24 +304,13 @@ struct VisitListAny {
     uint32_t omega;              // running sums: omega cells from the first one, omega more after a wrap
     uint32_t pc;                 // p mod c: how far back a wrap past p sets the bucket
     uint32_t gap[CS_ANYC_MAX_VISITS];
-    uint64_t A[CS_ANYC_MAX_VISITS], As[CS_ANYC_MAX_VISITS];
-    __device__ __forceinline__ const VisitListAny& at(unsigned) const { return *this; }
 };
-// The same list without the hash advances (the query computes them on the device, once per
-// wavefront, so that several rows' lists fit into the 4 KB of kernel arguments and share a launch).
-struct VisitGaps {
-    uint32_t K;
-    int32_t j;
-    uint64_t gmax;
-    uint64_t a, b, as, bs;
-    uint32_t omega, pc;
-    uint32_t gap[CS_ANYC_MAX_VISITS];
-};
-constexpr int kQueryRowsPerLaunch = 6;
+constexpr int kAnycRowsPerLaunch = 6;
 struct VisitGapsRows {
-    VisitGaps row[kQueryRowsPerLaunch];
+    VisitGaps row[kAnycRowsPerLaunch];
+    __device__ __forceinline__ const VisitGaps& at(unsigned y) const { return row[y]; }
 };
-static_assert(sizeof(VisitGapsRows) + 64 <= 4096, "the lists of a launch and its other arguments are kernel arguments");
+static_assert(sizeof(VisitGapsRows) + 128 <= 4096, "the lists of a launch and its other arguments are kernel arguments");
 struct VisitWorkers {
     const float* g[kGroup];      // vectors of the workers of this group
     float* T;                    // the group's table, float[r][c][kGroup]; with `fold` one table float[r][c]
@@ -358,7 +348,7 @@ __device__ __forceinline__ void load_floats(gfloat_ptr src, float (&out)[N]) {
 }
 
 // LIST = VisitRows (power-of-two column counts: three gaps and 2-bit codes, the NC cells are
-// neighbours) or VisitListAny (any column count: gaps one by one, NC = 2 omega cells of which
+// neighbours) or VisitGapsRows (any column count: gaps one by one, NC = 2 omega cells of which
 // the second half lies p mod c cells back).
 template <int WL, int RUN, int NWAVE, int NC, typename LIST>
 __global__ void __launch_bounds__(64 * NWAVE)
@@ -461,13 +451,22 @@ k_accumulate_visits(LIST rows, VisitWorkers a) {
         if constexpr (POW2) return static_cast<int64_t>(pick(code, v.gap[0], v.gap[1], v.gap[2], v.gap[3]));
         else return static_cast<int64_t>(v.gap[code]);
     };
+    // hash advances of the visits of an any-c list: once per workgroup into LDS
+    __shared__ uint64_t adv_b[POW2 ? 1 : CS_ANYC_MAX_VISITS], adv_s[POW2 ? 1 : CS_ANYC_MAX_VISITS];
+    if constexpr (!POW2) {
+        for (uint32_t k = threadIdx.x; k < v.K; k += 64 * NWAVE) {
+            adv_b[k] = mulmod_p(v.a, v.gap[k]);
+            adv_s[k] = mulmod_p(v.as, v.gap[k]);
+        }
+        __syncthreads();
+    }
     auto A_of = [&](uint32_t code) -> uint64_t {
         if constexpr (POW2) return pick(code, v.A[0], v.A[1], v.A[2], v.A[3]);
-        else return v.A[code];
+        else return adv_b[code];
     };
     auto As_of = [&](uint32_t code) -> uint64_t {
         if constexpr (POW2) return pick(code, v.As[0], v.As[1], v.As[2], v.As[3]);
-        else return v.As[code];
+        else return adv_s[code];
     };
 
     // Walkers with small residues take part in every visit, those with large ones only in
@@ -723,24 +722,61 @@ bool visits_apply(const cs_params* p, uint32_t j, int64_t d, bool any_cost = fal
     return any_cost || vp.cost < vp.cost_walk;
 }
 
-void fill_visit_list_any(const cs_params* p, uint32_t j, VisitListAny& v);
-
-// one launch: row j of one group of workers along its list for any column count
-template <int WL, int RUN, int NWAVE>
-int launch_visits_anyc(const cs_params* p, const VisitWorkers& a, uint32_t j, hipStream_t stream) {
-    constexpr int WPW = 64 / WL;
+void fill_visit_gaps(const cs_params* p, uint32_t j, VisitGaps& v) {
     const cs_anyc_plan& vp = p->anyc[j];
-    VisitListAny v{};
-    fill_visit_list_any(p, j, v);
-    const int64_t chunks = (static_cast<int64_t>(vp.gmax) + RUN - 1) / RUN;
-    const int64_t nwaves = (chunks + WPW - 1) / WPW;
-    const int64_t ngroups = (nwaves + NWAVE - 1) / NWAVE;
+    v.K = vp.K;
+    v.j = static_cast<int32_t>(j);
+    v.gmax = vp.gmax;
+    v.a = p->a[j]; v.b = p->b[j]; v.as = p->as[j]; v.bs = p->bs[j];
+    v.omega = vp.omega;
+    v.pc = static_cast<uint32_t>(kP61 % p->c);
+    for (uint32_t k = 0; k < vp.K; ++k) v.gap[k] = vp.gap[k];
+}
+
+// The rows of an any-c sketch in the launches that take them: rows with the same number of
+// running sums (omega = 1 or 2) together, up to kAnycRowsPerLaunch per launch, the longest lists
+// first.  fn(rows, n, omega) is called per launch.
+template <typename FN>
+int for_each_anyc_launch(const cs_params* p, uint32_t nrows_of_sketch, FN fn) {
+    for (uint32_t omega = 1; omega <= 2; ++omega) {
+        uint32_t order[CS_MAX_R];
+        int n = 0;
+        for (uint32_t j = 0; j < nrows_of_sketch; ++j) {
+            if (p->anyc[j].omega != omega) continue;
+            int at = n++;
+            for (; at > 0 && p->anyc[order[at - 1]].K < p->anyc[j].K; --at) order[at] = order[at - 1];
+            order[at] = j;
+        }
+        for (int q0 = 0; q0 < n; q0 += kAnycRowsPerLaunch) {
+            const int m = n - q0 < kAnycRowsPerLaunch ? n - q0 : kAnycRowsPerLaunch;
+            const int rc = fn(order + q0, m, omega);
+            if (rc != CS_OK) return rc;
+        }
+    }
+    return CS_OK;
+}
+
+// one launch: rows js[0 .. n) (all with the same omega) of one group of workers, each along
+// its list for any column count
+template <int WL, int RUN, int NWAVE>
+int launch_visits_anyc(const cs_params* p, const VisitWorkers& a, const uint32_t* js, int n,
+                       uint32_t omega, hipStream_t stream) {
+    constexpr int WPW = 64 / WL;
+    VisitGapsRows rows{};
+    int64_t most = 1;
+    for (int q = 0; q < n; ++q) {
+        fill_visit_gaps(p, js[q], rows.row[q]);
+        const int64_t chunks = (static_cast<int64_t>(p->anyc[js[q]].gmax) + RUN - 1) / RUN;
+        const int64_t nwaves = (chunks + WPW - 1) / WPW;
+        const int64_t ngroups = (nwaves + NWAVE - 1) / NWAVE;
+        if (ngroups > most) most = ngroups;
+    }
     const int64_t cap = 256 * 64 / NWAVE;
-    int64_t gx = ngroups < cap ? ngroups : cap;
+    int64_t gx = most < cap ? most : cap;
     gx = (gx + 8 * kVisitSetBlock - 1) / (8 * kVisitSetBlock) * (8 * kVisitSetBlock);
-    const dim3 grid(static_cast<unsigned>(gx), 1), block(64 * NWAVE);
-    if (vp.omega == 1) k_accumulate_visits<WL, RUN, NWAVE, 2, VisitListAny><<<grid, block, 0, stream>>>(v, a);
-    else if (vp.omega == 2) k_accumulate_visits<WL, RUN, NWAVE, 4, VisitListAny><<<grid, block, 0, stream>>>(v, a);
+    const dim3 grid(static_cast<unsigned>(gx), static_cast<unsigned>(n)), block(64 * NWAVE);
+    if (omega == 1) k_accumulate_visits<WL, RUN, NWAVE, 2, VisitGapsRows><<<grid, block, 0, stream>>>(rows, a);
+    else if (omega == 2) k_accumulate_visits<WL, RUN, NWAVE, 4, VisitGapsRows><<<grid, block, 0, stream>>>(rows, a);
     else return CS_EINVAL;
     return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
 }
@@ -767,12 +803,15 @@ bool anyc_visits_serve_query(const cs_params* p, int64_t d) {
 }
 
 int count_accumulate_anyc_launches(const cs_params* p, int W) {
-    return static_cast<int>(p->r) * ((W + kGroup - 1) / kGroup);
+    int per_group = 0;
+    for_each_anyc_launch(p, p->r, [&](const uint32_t*, int, uint32_t) { ++per_group; return CS_OK; });
+    return per_group * ((W + kGroup - 1) / kGroup);
 }
 
-// One launch per row and group of 8 workers: every row has its own visiting order, so the
-// group's vectors are read once per row (where the direct form reads them once in all but
-// sends d requests per row to the atomic unit, which is what bounds it).
+// Per group of 8 workers one launch for up to kAnycRowsPerLaunch rows: every row has its own
+// visiting order, so the group's vectors are read once per row (where the direct form reads them
+// once in all but sends d requests per row to the atomic unit, which is what bounds it); rows
+// that share a launch overlap their serial chains of visits and have one tail.
 int launch_accumulate_anyc(const cs_params* p, float* T, int W, const float* const* g_w,
                            int64_t d, int64_t i0, float scale, bool fold, hipStream_t stream) {
     const size_t row_floats = static_cast<size_t>(p->c) * kGroup;
@@ -787,14 +826,13 @@ int launch_accumulate_anyc(const cs_params* p, float* T, int W, const float* con
         vw.nw = nw;
         vw.scale = scale;
         vw.fold = fold ? 1 : 0;
-        for (uint32_t j = 0; j < p->r; ++j) {
-            int rc;
-            if (nw > 4) rc = launch_visits_anyc<8, 16, kWavesPerGroupOf8>(p, vw, j, stream);
-            else if (nw > 2) rc = launch_visits_anyc<4, 16, 1>(p, vw, j, stream);
-            else if (nw > 1) rc = launch_visits_anyc<2, 16, 1>(p, vw, j, stream);
-            else rc = launch_visits_anyc<1, 16, 1>(p, vw, j, stream);
-            if (rc != CS_OK) return rc;
-        }
+        const int rc = for_each_anyc_launch(p, p->r, [&](const uint32_t* js, int n, uint32_t omega) {
+            if (nw > 4) return launch_visits_anyc<8, 16, kWavesPerGroupOf8>(p, vw, js, n, omega, stream);
+            if (nw > 2) return launch_visits_anyc<4, 16, 1>(p, vw, js, n, omega, stream);
+            if (nw > 1) return launch_visits_anyc<2, 16, 1>(p, vw, js, n, omega, stream);
+            return launch_visits_anyc<1, 16, 1>(p, vw, js, n, omega, stream);
+        });
+        if (rc != CS_OK) return rc;
     }
     return CS_OK;
 }
@@ -1227,38 +1265,12 @@ k_row_values_visits(VisitGapsRows vr, const float* __restrict__ S, uint32_t c, i
     }
 }
 
-void fill_visit_list_any(const cs_params* p, uint32_t j, VisitListAny& v) {
-    const cs_anyc_plan& vp = p->anyc[j];
-    v.K = vp.K;
-    v.j = static_cast<int32_t>(j);
-    v.gmax = vp.gmax;
-    v.a = p->a[j]; v.b = p->b[j]; v.as = p->as[j]; v.bs = p->bs[j];
-    v.omega = vp.omega;
-    v.pc = static_cast<uint32_t>(kP61 % p->c);
-    for (uint32_t k = 0; k < vp.K; ++k) {
-        v.gap[k] = vp.gap[k];
-        v.A[k] = static_cast<uint64_t>((static_cast<unsigned __int128>(p->a[j]) * vp.gap[k]) % kP61);
-        v.As[k] = static_cast<uint64_t>((static_cast<unsigned __int128>(p->as[j]) * vp.gap[k]) % kP61);
-    }
-}
-
 }  // namespace
 
 // The query along the rows' visit lists for any column count: rows 0 .. r-2 into the scratch,
-// up to kQueryRowsPerLaunch rows per launch (one row's wavefronts alone fill a third to two
+// up to kAnycRowsPerLaunch rows per launch (one row's wavefronts alone fill a third to two
 // thirds of the chip, and every launch has the tail of its longest chain of visits), then the
 // last row together with the median.  The rows of a launch use the same number of cells.
-static void fill_visit_gaps(const cs_params* p, uint32_t j, VisitGaps& v) {
-    const cs_anyc_plan& vp = p->anyc[j];
-    v.K = vp.K;
-    v.j = static_cast<int32_t>(j);
-    v.gmax = vp.gmax;
-    v.a = p->a[j]; v.b = p->b[j]; v.as = p->as[j]; v.bs = p->bs[j];
-    v.omega = vp.omega;
-    v.pc = static_cast<uint32_t>(kP61 % p->c);
-    for (uint32_t k = 0; k < vp.K; ++k) v.gap[k] = vp.gap[k];
-}
-
 int launch_estimate_anyc(const cs_params* p, const float* S, int64_t d, int64_t i0, float* est,
                          float* rows, hipStream_t stream) {
     auto grid_x = [](uint64_t gmax) {
@@ -1269,24 +1281,18 @@ int launch_estimate_anyc(const cs_params* p, const float* S, int64_t d, int64_t 
     };
     const uint32_t last = p->r - 1;
     VisitGapsRows vr{};
-    for (uint32_t omega = 1; omega <= 2; ++omega) {
-        int n = 0;
+    const int rc = for_each_anyc_launch(p, last, [&](const uint32_t* js, int n, uint32_t omega) {
         uint64_t most = 0;
-        for (uint32_t j = 0; j <= last; ++j) {
-            const bool mine = j < last && p->anyc[j].omega == omega;
-            if (mine) {
-                fill_visit_gaps(p, j, vr.row[n++]);
-                if (p->anyc[j].gmax > most) most = p->anyc[j].gmax;
-            }
-            if (n == kQueryRowsPerLaunch || (j == last && n > 0)) {
-                const dim3 grid(grid_x(most), static_cast<unsigned>(n));
-                if (omega == 1) k_row_values_visits<0, 2><<<grid, 64, 0, stream>>>(vr, S, p->c, d, i0, rows, est);
-                else k_row_values_visits<0, 4><<<grid, 64, 0, stream>>>(vr, S, p->c, d, i0, rows, est);
-                n = 0;
-                most = 0;
-            }
+        for (int q = 0; q < n; ++q) {
+            fill_visit_gaps(p, js[q], vr.row[q]);
+            if (p->anyc[js[q]].gmax > most) most = p->anyc[js[q]].gmax;
         }
-    }
+        const dim3 grid(grid_x(most), static_cast<unsigned>(n));
+        if (omega == 1) k_row_values_visits<0, 2><<<grid, 64, 0, stream>>>(vr, S, p->c, d, i0, rows, est);
+        else k_row_values_visits<0, 4><<<grid, 64, 0, stream>>>(vr, S, p->c, d, i0, rows, est);
+        return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
+    });
+    if (rc != CS_OK) return rc;
     fill_visit_gaps(p, last, vr.row[0]);
     const uint32_t omega_last = p->anyc[last].omega;
     const unsigned gx = grid_x(p->anyc[last].gmax);

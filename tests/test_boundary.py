@@ -213,8 +213,8 @@ def test_invalid_arguments_are_rejected_without_a_gpu(lib):
 def test_update_launch_count_follows_the_grouping(lib):
     """cs_bundle_update_launches: per group of 8 workers one launch for the rows with a visit list
     (8 rows at most per launch) and one for the rows walked by stride; for other column counts
-    one launch per row and group with visit lists, one per 32 workers without; none for an empty
-    vector."""
+    one launch per group and up to 6 rows of equal omega with visit lists, one per 32 workers
+    without; none for an empty vector."""
     for r, c, seed, d in [(5, 1 << 20, 190304492, 10**8), (5, 1 << 15, 190304489, 1 << 20),
                           (7, 1 << 19, 190304493, 25_000_000), (15, 1 << 12, 4, 3_000_000)]:
         p = cs.cs_params_init(r, c, seed, d)
@@ -226,12 +226,17 @@ def test_update_launch_count_follows_the_grouping(lib):
         walk = binding.CsParams.from_buffer_copy(p)
         walk.flags = binding.CS_FLAG_NO_VISIT_LIST
         assert cs.cs_bundle_update_launches(walk, 16, d) == 2
-    # a column count that is not a power of two: one launch per row and group of 8 workers along
-    # the rows' visit lists, one launch per 32 workers without them
+    # a column count that is not a power of two: per group of 8 workers one launch for up to 6 rows
+    # that keep the same number of running sums (omega), along the rows' visit lists; one launch
+    # per 32 workers without them
+    for r in (5, 15):
+        p = cs.cs_params_init(r, 180_000, 1, 6_500_000)
+        assert all(p.anyc[j].K > 0 for j in range(r))
+        per_group = sum(-(-sum(1 for j in range(r) if p.anyc[j].omega == omega) // 6) for omega in (1, 2))
+        assert 1 <= per_group <= (2 if r == 5 else 4)
+        for W, groups in ((1, 1), (8, 1), (9, 2), (100, 13)):
+            assert cs.cs_bundle_update_launches(p, W, 6_500_000) == per_group * groups
     p = cs.cs_params_init(5, 180_000, 1, 6_500_000)
-    assert all(p.anyc[j].K > 0 for j in range(5))
-    for W, n in ((1, 5), (8, 5), (9, 10), (100, 65)):
-        assert cs.cs_bundle_update_launches(p, W, 6_500_000) == n
     p.flags = binding.CS_FLAG_NO_VISIT_LIST
     for W, n in ((1, 1), (32, 1), (33, 2), (100, 4)):
         assert cs.cs_bundle_update_launches(p, W, 6_500_000) == n

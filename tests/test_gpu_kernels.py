@@ -232,7 +232,9 @@ def test_accumulate_bundle_visit_lists_for_any_column_count(r, c, seed, d, d_hin
     worker's table against the reference, and the same call with the lists switched off."""
     p = cs.cs_params_init(r, c, seed, d_hint)
     assert all(p.anyc[j].K > 0 for j in range(r)), "no list was planned for this shape"
-    assert cs.cs_bundle_update_launches(p, W, d) == r * -(-W // cs.CS_BUNDLE_GROUP)
+    # per group of 8 workers, one launch per 6 rows that keep the same number of running sums
+    per_group = sum(-(-sum(1 for j in range(r) if p.anyc[j].omega == omega) // 6) for omega in (1, 2))
+    assert cs.cs_bundle_update_launches(p, W, d) == per_group * -(-W // cs.CS_BUNDLE_GROUP)
     sk = orc.SketchOracle(r, c, seed)
     rng = np.random.default_rng(seed)
     gs = [(rng.standard_normal(d) * 0.01).astype(np.float32) for _ in range(W)]
