@@ -1119,7 +1119,7 @@ k_row_values_walk(KParams p, RowSegments segs, const float* __restrict__ S, int6
 template <int RF, int NC>
 __global__ void __launch_bounds__(64)
 k_row_values_visits(VisitGapsRows vr, const float* __restrict__ S, uint32_t c, int64_t d, int64_t i0,
-                    float* __restrict__ rows, float* __restrict__ est) {
+                    float* __restrict__ rows, float* __restrict__ est, int nseg) {
     static_assert(kQRun == 4, "one 16-byte piece per lane");
     static_assert(NC == 2 || NC == 4, "omega = 1 or 2");
     const int lane = threadIdx.x;
@@ -1190,8 +1190,19 @@ k_row_values_visits(VisitGapsRows vr, const float* __restrict__ S, uint32_t c, i
                 advance(tb, tr, Aj, Ajc);
             }
         }
+        // A launch with few rows leaves the chip half empty and waits on its longest chain of
+        // visits, so the chains are cut into nseg pieces walked by separate wavefronts
+        // (blockIdx.z); a piece that does not start at visit 0 takes its hash state from the
+        // definition at its first coordinate (the cells it can meet are still those of visit 0).
+        const uint32_t k0 = v.K * blockIdx.z / nseg, k1 = v.K * (blockIdx.z + 1) / nseg;
         int64_t s = 0;
-        for (uint32_t k = 0; k < v.K; ++k) {
+        if (k0 > 0) {
+            for (uint32_t k = 0; k < k0; ++k) s += static_cast<int64_t>(v.gap[k]);
+            yb = hash_state(v.a, v.b, static_cast<uint64_t>(i0 + my_res + s));
+            ys = hash_state(v.as, v.bs, static_cast<uint64_t>(i0 + my_res + s));
+            rb = bucket_of<false>(yb, col);
+        }
+        for (uint32_t k = k0; k < k1; ++k) {
             const int64_t gap = static_cast<int64_t>(v.gap[k]);
             // residues from wave_res on that take part in this visit and exist in the vector
             const int64_t in_gap = gap - wave_res, in_vec = d - s - wave_res;
@@ -1279,27 +1290,41 @@ int launch_estimate_anyc(const cs_params* p, const float* S, int64_t d, int64_t 
         const int64_t gx = nwaves < cap ? nwaves : cap;
         return static_cast<unsigned>((gx + 7) / 8 * 8);
     };
+    // pieces per chain of a launch: enough wavefronts for about two per SIMD slot of the chip,
+    // at least 8 visits per piece
+    auto pieces = [](uint64_t waves, uint32_t shortest_list) {
+        int64_t n = static_cast<int64_t>((16384 + waves - 1) / (waves > 0 ? waves : 1));
+        if (n > shortest_list / 8) n = shortest_list / 8;
+        if (n > 16) n = 16;
+        return static_cast<unsigned>(n < 1 ? 1 : n);
+    };
     const uint32_t last = p->r - 1;
     VisitGapsRows vr{};
     const int rc = for_each_anyc_launch(p, last, [&](const uint32_t* js, int n, uint32_t omega) {
-        uint64_t most = 0;
+        uint64_t most = 0, waves = 0;
+        uint32_t shortest = CS_ANYC_MAX_VISITS;
         for (int q = 0; q < n; ++q) {
             fill_visit_gaps(p, js[q], vr.row[q]);
-            if (p->anyc[js[q]].gmax > most) most = p->anyc[js[q]].gmax;
+            const cs_anyc_plan& vp = p->anyc[js[q]];
+            if (vp.gmax > most) most = vp.gmax;
+            waves += (vp.gmax + 64 * kQRun - 1) / (64 * kQRun);
+            if (vp.K < shortest) shortest = vp.K;
         }
-        const dim3 grid(grid_x(most), static_cast<unsigned>(n));
-        if (omega == 1) k_row_values_visits<0, 2><<<grid, 64, 0, stream>>>(vr, S, p->c, d, i0, rows, est);
-        else k_row_values_visits<0, 4><<<grid, 64, 0, stream>>>(vr, S, p->c, d, i0, rows, est);
+        const unsigned nseg = pieces(waves, shortest);
+        const dim3 grid(grid_x(most), static_cast<unsigned>(n), nseg);
+        if (omega == 1) k_row_values_visits<0, 2><<<grid, 64, 0, stream>>>(vr, S, p->c, d, i0, rows, est, static_cast<int>(nseg));
+        else k_row_values_visits<0, 4><<<grid, 64, 0, stream>>>(vr, S, p->c, d, i0, rows, est, static_cast<int>(nseg));
         return hipGetLastError() == hipSuccess ? CS_OK : CS_EHIP;
     });
     if (rc != CS_OK) return rc;
     fill_visit_gaps(p, last, vr.row[0]);
     const uint32_t omega_last = p->anyc[last].omega;
-    const unsigned gx = grid_x(p->anyc[last].gmax);
+    const unsigned nseg_last = pieces((p->anyc[last].gmax + 64 * kQRun - 1) / (64 * kQRun), p->anyc[last].K);
+    const dim3 gx(grid_x(p->anyc[last].gmax), 1, nseg_last);
 #define CS_LASTR(R_)                                                                                 \
     case R_:                                                                                         \
-        if (omega_last == 1) k_row_values_visits<R_, 2><<<gx, 64, 0, stream>>>(vr, S, p->c, d, i0, rows, est); \
-        else k_row_values_visits<R_, 4><<<gx, 64, 0, stream>>>(vr, S, p->c, d, i0, rows, est);             \
+        if (omega_last == 1) k_row_values_visits<R_, 2><<<gx, 64, 0, stream>>>(vr, S, p->c, d, i0, rows, est, static_cast<int>(nseg_last)); \
+        else k_row_values_visits<R_, 4><<<gx, 64, 0, stream>>>(vr, S, p->c, d, i0, rows, est, static_cast<int>(nseg_last));             \
         break;
     switch (p->r) {
         CS_LASTR(1) CS_LASTR(3) CS_LASTR(5) CS_LASTR(7) CS_LASTR(9) CS_LASTR(11) CS_LASTR(13) CS_LASTR(15)
