@@ -54,10 +54,16 @@ struct TopkWs {
 };
 constexpr size_t kCandBytes = sizeof(int64_t) + sizeof(float);   // index and value of a candidate
 
-// candidates worth providing for: a few times k, never a large part of d
+// candidates worth providing for: a few times k, never a large part of d.  When k itself is a
+// few per cent of d (the P k candidates of Alg. 3 with P in the tens) the list is sized more
+// tightly: the entries of the k-th largest key's bin and above are k plus that bin's own
+// population, at most a few tenths of k for magnitudes that fall off smoothly (a bin is an
+// eighth of a binade wide); should they not fit, the five-pass form takes over on the device.
 __host__ inline int64_t candidate_capacity_for(int64_t d, int64_t k) {
-    const int64_t want = 8 * k + 65536;
-    return want <= d / 4 ? want : 0;
+    const int64_t roomy = 8 * k + 65536;
+    if (roomy <= d / 4) return roomy;
+    const int64_t tight = 3 * k + 65536;
+    return tight <= d / 5 ? tight : 0;
 }
 
 // Selection keys (31 bits, larger = selected first; equal keys: lower index first).

@@ -646,7 +646,8 @@ def test_topk_exact(d, k, kind):
     np.testing.assert_array_equal(val.view(np.uint32), est[want].view(np.uint32))
 
 
-@pytest.mark.parametrize("case", ["spread", "one block full of heavy entries", "unaligned", "all in one bin"])
+@pytest.mark.parametrize("case", ["spread", "one block full of heavy entries", "unaligned", "all in one bin",
+                                  "k a few per cent of d", "k a few per cent of d, heavy tail"])
 def test_topk_candidate_list_and_five_pass_form_agree(case):
     """With room for a candidate list in the workspace the selection reads est twice, without it
     five times; both must return the reference's selection.  Covered: the ordinary case, a
@@ -663,6 +664,10 @@ def test_topk_candidate_list_and_five_pass_form_agree(case):
     elif case == "unaligned":
         d, k = 700_001, 500
         est = est[:d].copy()
+    elif case.startswith("k a few per cent of d"):
+        k = 1_200_000                                  # 6 % of d: the tightly sized list (3 k + 65 536 entries)
+        if case.endswith("heavy tail"):
+            est = (rng.standard_t(2.5, size=d) * 0.01).astype(np.float32)
     want = orc.topk_threshold(est, k)
     base = torch.empty(d + 1, dtype=torch.float32, device=DEV)
     off = 1 if case == "unaligned" else 0
