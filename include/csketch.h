@@ -322,8 +322,9 @@ int cs_sketch_estimate_sparse(const cs_params* p, const float* S, const int64_t*
  * selection.
  * workspace: device, 8-byte aligned, contents irrelevant on entry.  cs_topk_workspace_bytes(d, k)
  * is what makes the call fastest: about 114 KiB of histograms and counters plus, when k is
- * small against d, room for a list of 8 k + 65 536 candidates (12 bytes each), with which est
- * is read twice (once with hist_or_null) instead of five times.  Any size from cs_topk_workspace_bytes(1, 1) (the fixed
+ * small against d, room for a list of 8 k + 65 536 candidates (12 bytes each; 3 k + 65 536
+ * when k is a few per cent of d), with which est is read twice (once with hist_or_null)
+ * instead of five times.  Any size from cs_topk_workspace_bytes(1, 1) (the fixed
  * part alone) upwards is accepted and gives the same result; below that CS_EWORKSPACE.
  * 1 <= k <= d. */
 int cs_topk_workspace_bytes(int64_t d, int64_t k, size_t* bytes);
